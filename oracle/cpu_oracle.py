@@ -1,0 +1,246 @@
+"""ctypes front end of the CPU oracle (``flexgemm_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by the tests, by the smoke check and by the
+CPU-baseline leg of the benchmark.  The product package never imports this
+module, and this module never imports the product package.
+
+Every function takes numpy arrays (float16 for A and B, float32 for C and the
+bias), hands their buffers to the C code unchanged and returns float64 arrays.
+No arithmetic of the method happens in this file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "flexgemm_oracle.c")
+_LIB = os.path.join(_HERE, "libflexgemm_oracle.so")
+
+COL, ROW, DIAG = 0, 1, 2
+ACT_NONE, ACT_RELU = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, no fast-math) and return the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-Wall", "-Wextra",
+             "-o", tmp, _SRC, "-lm", "-lpthread"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _GemmProblem(C.Structure):
+    _fields_ = [
+        ("M", C.c_int64), ("N", C.c_int64), ("K", C.c_int64),
+        ("alpha", C.c_double), ("beta", C.c_double),
+        ("A_re", C.c_void_p), ("A_im", C.c_void_p), ("layoutA", C.c_int32), ("lda", C.c_int64),
+        ("B_re", C.c_void_p), ("B_im", C.c_void_p), ("layoutB", C.c_int32), ("ldb", C.c_int64),
+        ("C_re", C.c_void_p), ("C_im", C.c_void_p), ("layoutC", C.c_int32), ("ldc", C.c_int64),
+        ("bias", C.c_void_p), ("bias_dim", C.c_int32), ("act", C.c_int32),
+    ]
+
+
+class _ContractProblem(C.Structure):
+    _fields_ = [
+        ("n_modes", C.c_int32), ("labels", C.c_void_p), ("extents", C.c_void_p),
+        ("nA", C.c_int32), ("modesA", C.c_void_p), ("stridesA", C.c_void_p), ("A", C.c_void_p),
+        ("nB", C.c_int32), ("modesB", C.c_void_p), ("stridesB", C.c_void_p), ("B", C.c_void_p),
+        ("nC", C.c_int32), ("modesC", C.c_void_p), ("stridesC", C.c_void_p), ("Cin", C.c_void_p),
+        ("alpha", C.c_double), ("beta", C.c_double),
+    ]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        l = C.CDLL(build())
+        l.oracle_half_to_double.restype = C.c_double
+        l.oracle_half_to_double.argtypes = [C.c_uint16]
+        pd = C.c_void_p
+        l.oracle_gemm_full.restype = C.c_int
+        l.oracle_gemm_full.argtypes = [C.POINTER(_GemmProblem), pd, pd, pd, pd, C.c_int]
+        l.oracle_gemm_at.restype = C.c_int
+        l.oracle_gemm_at.argtypes = [C.POINTER(_GemmProblem), C.c_int64, pd, pd, pd, pd, pd, pd, C.c_int]
+        l.oracle_contract_full.restype = C.c_int
+        l.oracle_contract_full.argtypes = [C.POINTER(_ContractProblem), pd, pd, C.c_int]
+        l.oracle_contract_at.restype = C.c_int
+        l.oracle_contract_at.argtypes = [C.POINTER(_ContractProblem), C.c_int64, pd, pd, pd, C.c_int]
+        _lib = l
+    return _lib
+
+
+def default_threads() -> int:
+    try:
+        return max(1, len(os.sched_getaffinity(0)))
+    except AttributeError:  # pragma: no cover
+        return max(1, os.cpu_count() or 1)
+
+
+def half_to_double(bits: int) -> float:
+    return float(lib().oracle_half_to_double(int(bits) & 0xFFFF))
+
+
+@dataclass
+class Operand:
+    """A stored FP16 operand: ``re`` (and ``im`` for planar complex) are flat or 2-D float16
+    arrays whose memory is read as-is; ``layout`` and ``ld`` say how element (r, c) is found."""
+    re: np.ndarray
+    layout: int = COL
+    ld: int = 0
+    im: Optional[np.ndarray] = None
+
+
+def _ptr(a: Optional[np.ndarray], dtype) -> Optional[int]:
+    if a is None:
+        return None
+    if a.dtype != dtype or not a.flags["C_CONTIGUOUS"] and not a.flags["F_CONTIGUOUS"]:
+        raise ValueError("oracle buffers must be contiguous %s arrays" % np.dtype(dtype).name)
+    return a.ctypes.data
+
+
+def _check_span(a: Optional[np.ndarray], need: int, what: str):
+    if a is not None and a.size < need:
+        raise ValueError("%s holds %d elements, the described operand needs %d" % (what, a.size, need))
+
+
+def _gemm_problem(M, N, K, alpha, A: Operand, B: Operand, beta, Cre, Cim, layoutC, ldc, bias, bias_dim, act):
+    q = _GemmProblem()
+    q.M, q.N, q.K, q.alpha, q.beta = M, N, K, float(alpha), float(beta)
+
+    def span(layout, ld, rows, cols):
+        if rows == 0 or cols == 0:
+            return 0
+        if layout == COL:
+            return (cols - 1) * ld + rows
+        if layout == ROW:
+            return (rows - 1) * ld + cols
+        return min(rows, cols)
+
+    for name, op, rows, cols in (("A", A, M, K), ("B", B, K, N)):
+        if op.layout == COL and op.ld < rows or op.layout == ROW and op.ld < cols:
+            raise ValueError("leading dimension of %s too small" % name)
+        need = span(op.layout, op.ld, rows, cols)
+        _check_span(op.re, need, name + ".re")
+        _check_span(op.im, need, name + ".im")
+    q.A_re, q.A_im, q.layoutA, q.lda = _ptr(A.re, np.float16), _ptr(A.im, np.float16), A.layout, A.ld
+    q.B_re, q.B_im, q.layoutB, q.ldb = _ptr(B.re, np.float16), _ptr(B.im, np.float16), B.layout, B.ld
+    if Cre is not None:
+        need = span(layoutC, ldc, M, N)
+        _check_span(Cre, need, "C.re")
+        _check_span(Cim, need, "C.im")
+    q.C_re, q.C_im, q.layoutC, q.ldc = _ptr(Cre, np.float32), _ptr(Cim, np.float32), layoutC, ldc
+    if bias is not None:
+        _check_span(bias, M if bias_dim == 0 else N, "bias")
+    q.bias, q.bias_dim, q.act = _ptr(bias, np.float32), bias_dim, act
+    return q
+
+
+def gemm(M: int, N: int, K: int, alpha: float, A: Operand, B: Operand, beta: float = 0.0,
+         C_re: Optional[np.ndarray] = None, C_im: Optional[np.ndarray] = None, layoutC: int = COL, ldc: int = 0,
+         bias: Optional[np.ndarray] = None, bias_dim: int = 0, act: int = ACT_NONE,
+         at: Optional[Sequence[np.ndarray]] = None, threads: Optional[int] = None):
+    """Evaluate the GEMM definition.
+
+    Returns a dict with ``D`` and ``G`` (float64; complex problems also ``D_im`` and ``G_im``).
+    Without ``at`` the arrays are (M, N); with ``at=(I, J)`` they are 1-D, one value per listed
+    position.
+    """
+    threads = threads or default_threads()
+    q = _gemm_problem(M, N, K, alpha, A, B, beta, C_re, C_im, layoutC, ldc, bias, bias_dim, act)
+    is_complex = A.im is not None or B.im is not None
+    if at is None:
+        shape, order = (M, N), "F"
+    else:
+        I = np.ascontiguousarray(at[0], dtype=np.int64)
+        J = np.ascontiguousarray(at[1], dtype=np.int64)
+        if I.shape != J.shape or I.ndim != 1:
+            raise ValueError("at=(I, J) must be two 1-D arrays of equal length")
+        shape, order = (I.size,), "C"
+    out = {"D": np.zeros(shape, np.float64, order=order), "G": np.zeros(shape, np.float64, order=order)}
+    if is_complex:
+        out["D_im"] = np.zeros(shape, np.float64, order=order)
+        out["G_im"] = np.zeros(shape, np.float64, order=order)
+    p = lambda k: out[k].ctypes.data if k in out else None
+    if at is None:
+        rc = lib().oracle_gemm_full(C.byref(q), p("D"), p("D_im"), p("G"), p("G_im"), threads)
+    else:
+        rc = lib().oracle_gemm_at(C.byref(q), I.size, I.ctypes.data, J.ctypes.data,
+                                  p("D"), p("D_im"), p("G"), p("G_im"), threads)
+    if rc != 0:
+        raise ValueError("oracle rejected the GEMM description (code %d)" % rc)
+    return out
+
+
+def contract(extents: dict, modesA: Sequence[int], stridesA: Sequence[int], A: np.ndarray,
+             modesB: Sequence[int], stridesB: Sequence[int], B: np.ndarray,
+             modesC: Sequence[int], stridesC: Sequence[int], Cin: Optional[np.ndarray] = None,
+             alpha: float = 1.0, beta: float = 0.0, at: Optional[np.ndarray] = None,
+             threads: Optional[int] = None):
+    """Evaluate the contraction definition.
+
+    ``extents`` maps an integer mode label to its extent.  Without ``at`` returns ``D`` and ``G``
+    as flat float64 arrays indexed by C's own element offsets (length = span of C); with ``at``
+    (count x len(modesC) indices) returns one value per listed position.
+    """
+    threads = threads or default_threads()
+    labels = np.array(list(extents.keys()), dtype=np.int32)
+    exts = np.array([extents[k] for k in extents], dtype=np.int64)
+    keep = []
+
+    def arr(x, dt):
+        a = np.ascontiguousarray(np.array(list(x), dtype=dt))
+        keep.append(a)
+        return a
+
+    mA, sA = arr(modesA, np.int32), arr(stridesA, np.int64)
+    mB, sB = arr(modesB, np.int32), arr(stridesB, np.int64)
+    mC, sC = arr(modesC, np.int32), arr(stridesC, np.int64)
+    if len(mA) != len(sA) or len(mB) != len(sB) or len(mC) != len(sC):
+        raise ValueError("one stride per mode is required")
+
+    def span(modes, strides):
+        s = 1
+        for m, st in zip(modes, strides):
+            if int(m) not in extents:
+                raise ValueError("mode label %d has no extent" % int(m))
+            e = extents[int(m)]
+            if e == 0:
+                return 0
+            s += (e - 1) * int(st)
+        return s
+
+    _check_span(A, span(mA, sA), "A")
+    _check_span(B, span(mB, sB), "B")
+    spanC = span(mC, sC)
+    _check_span(Cin, spanC, "Cin")
+    q = _ContractProblem()
+    q.n_modes, q.labels, q.extents = len(labels), labels.ctypes.data, exts.ctypes.data
+    q.nA, q.modesA, q.stridesA, q.A = len(mA), mA.ctypes.data, sA.ctypes.data, _ptr(A, np.float16)
+    q.nB, q.modesB, q.stridesB, q.B = len(mB), mB.ctypes.data, sB.ctypes.data, _ptr(B, np.float16)
+    q.nC, q.modesC, q.stridesC, q.Cin = len(mC), mC.ctypes.data, sC.ctypes.data, _ptr(Cin, np.float32)
+    q.alpha, q.beta = float(alpha), float(beta)
+    if at is None:
+        D = np.zeros(spanC, np.float64)
+        G = np.zeros(spanC, np.float64)
+        rc = lib().oracle_contract_full(C.byref(q), D.ctypes.data, G.ctypes.data, threads)
+    else:
+        idx = np.ascontiguousarray(at, dtype=np.int64)
+        if idx.ndim != 2 or idx.shape[1] != len(mC):
+            raise ValueError("at must be count x len(modesC)")
+        D = np.zeros(idx.shape[0], np.float64)
+        G = np.zeros(idx.shape[0], np.float64)
+        rc = lib().oracle_contract_at(C.byref(q), idx.shape[0], idx.ctypes.data, D.ctypes.data, G.ctypes.data, threads)
+    if rc != 0:
+        raise ValueError("oracle rejected the contraction description (code %d)" % rc)
+    return {"D": D, "G": G}

@@ -1,0 +1,345 @@
+"""Pins for the CPU oracle: closed forms, identities, brute force and independent library
+routines.  None of these tests touches the GPU library.
+
+Each pin is aimed at a different plausible mistake: a transposed operand or leading dimension,
+a dropped or mis-signed term, a wrong broadcast direction of the bias, a wrong merged-index
+order in a contraction, a bad FP16 decode.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import cpu_oracle as O
+from oracle.cpu_oracle import Operand, COL, ROW, DIAG, ACT_NONE, ACT_RELU
+
+RNG = np.random.default_rng(20091226)
+
+
+def store(mat: np.ndarray, layout: int, pad: int = 0):
+    """Store a logical rows x cols float matrix as FP16 in the given layout with ``pad`` extra
+    elements per leading dimension; returns (flat float16 buffer, ld, fp16-rounded logical matrix)."""
+    rows, cols = mat.shape
+    h = mat.astype(np.float16)
+    if layout == COL:
+        ld = rows + pad
+        buf = np.full((cols, ld), np.float16(7.0))     # poison in the padding
+        buf[:, :rows] = h.T
+    else:
+        ld = cols + pad
+        buf = np.full((rows, ld), np.float16(7.0))
+        buf[:, :cols] = h
+    return np.ascontiguousarray(buf).reshape(-1), ld, h.astype(np.float64)
+
+
+def rand_mat(r, c):
+    return RNG.uniform(-1, 1, size=(r, c))
+
+
+# ---------------------------------------------------------------- FP16 decode
+def test_half_decode_matches_numpy_for_every_bit_pattern():
+    bits = np.arange(65536, dtype=np.uint16)
+    want = bits.view(np.float16).astype(np.float64)
+    got = np.array([O.half_to_double(int(b)) for b in bits])
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+
+
+# ---------------------------------------------------------------- real GEMM
+@pytest.mark.parametrize("la,lb", list(itertools.product([COL, ROW], [COL, ROW])))
+@pytest.mark.parametrize("lc", [COL, ROW])
+def test_gemm_matches_float64_matmul_all_layouts(la, lb, lc):
+    M, N, K = 13, 9, 21
+    A, lda, Ah = store(rand_mat(M, K), la, pad=3)
+    B, ldb, Bh = store(rand_mat(K, N), lb, pad=5)
+    Cm = rand_mat(M, N).astype(np.float32)
+    Cbuf = np.ascontiguousarray(Cm.T if lc == COL else Cm).reshape(-1)
+    ldc = M if lc == COL else N
+    alpha, beta = 0.75, -1.5
+    r = O.gemm(M, N, K, alpha, Operand(A, la, lda), Operand(B, lb, ldb), beta, Cbuf, None, lc, ldc, threads=3)
+    want = alpha * (Ah @ Bh) + beta * Cm.astype(np.float64)
+    assert np.allclose(r["D"], want, rtol=0, atol=1e-12)
+    wantG = abs(alpha) * (np.abs(Ah) @ np.abs(Bh)) + abs(beta) * np.abs(Cm.astype(np.float64))
+    assert np.allclose(r["G"], wantG, rtol=0, atol=1e-12)
+
+
+def test_non_square_transposed_operand_is_not_confused_with_its_transpose():
+    # A is 2x3 with distinct entries; a swapped (rows, cols) or ld reading gives a different product
+    Am = np.array([[1., 2., 3.], [4., 5., 6.]])
+    Bm = np.array([[1., 0.], [0., 1.], [2., -1.]])
+    want = Am @ Bm
+    for la, lb in itertools.product([COL, ROW], repeat=2):
+        A, lda, _ = store(Am, la, pad=1)
+        B, ldb, _ = store(Bm, lb, pad=2)
+        r = O.gemm(2, 2, 3, 1.0, Operand(A, la, lda), Operand(B, lb, ldb))
+        assert np.array_equal(r["D"], want), (la, lb)
+
+
+@pytest.mark.parametrize("la,lb", list(itertools.product([COL, ROW], [COL, ROW])))
+def test_identity_and_permutation(la, lb):
+    n = 8
+    Bm = RNG.integers(-5, 6, size=(n, n)).astype(np.float64)
+    Cm = RNG.integers(-5, 6, size=(n, n)).astype(np.float32)
+    perm = RNG.permutation(n)
+    P = np.zeros((n, n)); P[np.arange(n), perm] = 1.0       # (P B)[i, :] = B[perm[i], :]
+    B, ldb, _ = store(Bm, lb)
+    for Amat, want_prod in ((np.eye(n), Bm), (P, Bm[perm, :])):
+        A, lda, _ = store(Amat, la)
+        r = O.gemm(n, n, n, 2.0, Operand(A, la, lda), Operand(B, lb, ldb), 3.0, Cm.T.copy().reshape(-1), None, COL, n)
+        assert np.array_equal(r["D"], 2.0 * want_prod + 3.0 * Cm)
+    # identity on the B side: A I = A
+    A, lda, _ = store(Bm, la)
+    I, ldi, _ = store(np.eye(n), lb)
+    r = O.gemm(n, n, n, 1.0, Operand(A, la, lda), Operand(I, lb, ldi))
+    assert np.array_equal(r["D"], Bm)
+
+
+def test_rank_one_closed_form_is_exact():
+    M, N, K = 6, 5, 37
+    u = RNG.integers(-4, 5, size=M).astype(np.float64)
+    v = RNG.integers(-4, 5, size=N).astype(np.float64)
+    A, lda, _ = store(np.repeat(u[:, None], K, axis=1), COL)
+    B, ldb, _ = store(np.repeat(v[None, :], K, axis=0), COL)
+    r = O.gemm(M, N, K, 1.0, Operand(A, COL, lda), Operand(B, COL, ldb))
+    assert np.array_equal(r["D"], K * np.outer(u, v))
+    assert np.array_equal(r["G"], K * np.outer(np.abs(u), np.abs(v)))
+
+
+def test_alpha_beta_linearity():
+    M, N, K = 7, 6, 11
+    A, lda, _ = store(rand_mat(M, K), ROW)
+    B, ldb, _ = store(rand_mat(K, N), COL)
+    Cb = rand_mat(M, N).astype(np.float32).T.copy().reshape(-1)
+    a, b = 1.25, -0.5
+    f = lambda al, be: O.gemm(M, N, K, al, Operand(A, ROW, lda), Operand(B, COL, ldb), be, Cb, None, COL, M)["D"]
+    assert np.allclose(f(a, b), a * f(1, 0) + b * f(0, 1), rtol=0, atol=1e-13)
+    assert np.array_equal(f(0, 1), Cb.reshape(N, M).T.astype(np.float64))
+
+
+def test_transpose_consistency():
+    # the same memory read as row-major rows x cols or as column-major cols x rows: A^T
+    M, N, K = 5, 4, 6
+    Am = rand_mat(M, K)
+    A_row, ld_row, Ah = store(Am, ROW, pad=2)              # M x K row-major, ld = K + 2
+    B, ldb, Bh = store(rand_mat(K, N), COL)
+    r1 = O.gemm(M, N, K, 1.0, Operand(A_row, ROW, ld_row), Operand(B, COL, ldb))["D"]
+    # explicit transpose stored column-major is the same buffer
+    A_col, ld_col, _ = store(Am.T, COL, pad=2)             # K x M col-major, ld = K + 2
+    assert np.array_equal(A_row, A_col) and ld_row == ld_col
+    # and A^T used as the left operand of a (K x M)(M x N') product needs M x N' right operand
+    Bm2 = rand_mat(M, 3); B2, ldb2, B2h = store(Bm2, COL)
+    r2 = O.gemm(K, 3, M, 1.0, Operand(A_col, COL, ld_col), Operand(B2, COL, ldb2))["D"]
+    assert np.allclose(r1, Ah @ Bh, atol=1e-13) and np.allclose(r2, Ah.T @ B2h, atol=1e-13)
+
+
+def test_at_mode_equals_full_mode():
+    M, N, K = 10, 12, 9
+    A, lda, _ = store(rand_mat(M, K), COL, 1); B, ldb, _ = store(rand_mat(K, N), ROW, 1)
+    bias = rand_mat(1, M).astype(np.float32).reshape(-1)
+    kw = dict(bias=bias, bias_dim=0, act=ACT_RELU)
+    full = O.gemm(M, N, K, 1.0, Operand(A, COL, lda), Operand(B, ROW, ldb), **kw)
+    I = RNG.integers(0, M, size=40); J = RNG.integers(0, N, size=40)
+    part = O.gemm(M, N, K, 1.0, Operand(A, COL, lda), Operand(B, ROW, ldb), at=(I, J), **kw)
+    assert np.array_equal(part["D"], full["D"][I, J]) and np.array_equal(part["G"], full["G"][I, J])
+
+
+def test_thread_count_does_not_change_results():
+    M, N, K = 17, 19, 23
+    A, lda, _ = store(rand_mat(M, K), COL); B, ldb, _ = store(rand_mat(K, N), COL)
+    r1 = O.gemm(M, N, K, 1.0, Operand(A, COL, lda), Operand(B, COL, ldb), threads=1)["D"]
+    r8 = O.gemm(M, N, K, 1.0, Operand(A, COL, lda), Operand(B, COL, ldb), threads=8)["D"]
+    assert np.array_equal(r1, r8)
+
+
+# ---------------------------------------------------------------- epilogues
+def test_bias_direction_and_relu_by_brute_force():
+    M, N, K = 4, 3, 5
+    Am = RNG.integers(-3, 4, size=(M, K)).astype(np.float64)
+    Bm = RNG.integers(-3, 4, size=(K, N)).astype(np.float64)
+    A, lda, _ = store(Am, COL); B, ldb, _ = store(Bm, COL)
+    bias_m = np.array([100., 200., 300., 400.], np.float32)       # per row i
+    bias_n = np.array([1000., 2000., 3000.], np.float32)          # per column j
+    for dim, bias in ((0, bias_m), (1, bias_n)):
+        for act in (ACT_NONE, ACT_RELU):
+            r = O.gemm(M, N, K, -1.0, Operand(A, COL, lda), Operand(B, COL, ldb), bias=bias, bias_dim=dim, act=act)["D"]
+            for i in range(M):
+                for j in range(N):
+                    y = -sum(Am[i, k] * Bm[k, j] for k in range(K)) + float(bias[i] if dim == 0 else bias[j])
+                    assert r[i, j] == (max(y, 0.0) if act == ACT_RELU else y)
+
+
+def test_relu_properties_and_order_of_operations():
+    M = N = K = 16
+    A, lda, _ = store(rand_mat(M, K), COL); B, ldb, _ = store(rand_mat(K, N), COL)
+    Cb = (4 * rand_mat(M, N)).astype(np.float32).T.copy().reshape(-1)
+    bias = (2 * rand_mat(1, M)).astype(np.float32).reshape(-1)
+    kw = dict(beta=0.5, C_re=Cb, ldc=M, bias=bias, bias_dim=0)
+    y = O.gemm(M, N, K, 1.0, Operand(A, COL, lda), Operand(B, COL, ldb), **kw)["D"]
+    d = O.gemm(M, N, K, 1.0, Operand(A, COL, lda), Operand(B, COL, ldb), act=ACT_RELU, **kw)["D"]
+    assert (y < 0).any() and (y > 0).any()
+    assert (d >= 0).all() and np.array_equal(d[y > 0], y[y > 0]) and (d[y <= 0] == 0).all()
+
+
+# ---------------------------------------------------------------- diagonal operands
+def test_diagonal_equals_materialised_dense_and_closed_form():
+    n = 12
+    d = RNG.uniform(-1, 1, n).astype(np.float16)
+    Bm = rand_mat(n, n); B, ldb, Bh = store(Bm, COL)
+    Cm = rand_mat(n, n).astype(np.float32); Cb = Cm.T.copy().reshape(-1)
+    dense, ldd, _ = store(np.diag(d.astype(np.float64)), COL)
+    r_diag = O.gemm(n, n, n, 1.0, Operand(d, DIAG, 0), Operand(B, COL, ldb), 1.0, Cb, None, COL, n)
+    r_dense = O.gemm(n, n, n, 1.0, Operand(dense, COL, ldd), Operand(B, COL, ldb), 1.0, Cb, None, COL, n)
+    assert np.array_equal(r_diag["D"], r_dense["D"]) and np.array_equal(r_diag["G"], r_dense["G"])
+    assert np.allclose(r_diag["D"], d.astype(np.float64)[:, None] * Bh + Cm, atol=1e-14)
+    # diagonal on the right: column scaling
+    A, lda, Ah = store(rand_mat(n, n), ROW)
+    r = O.gemm(n, n, n, 1.0, Operand(A, ROW, lda), Operand(d, DIAG, 0))
+    assert np.allclose(r["D"], Ah * d.astype(np.float64)[None, :], atol=1e-14)
+
+
+# ---------------------------------------------------------------- planar complex
+def test_complex_matches_complex128_product():
+    M, N, K = 7, 5, 9
+    Ar, lda, Arh = store(rand_mat(M, K), COL, 1); Ai, _, Aih = store(rand_mat(M, K), COL, 1)
+    Br, ldb, Brh = store(rand_mat(K, N), ROW, 2); Bi, _, Bih = store(rand_mat(K, N), ROW, 2)
+    Cr = rand_mat(M, N).astype(np.float32); Ci = rand_mat(M, N).astype(np.float32)
+    r = O.gemm(M, N, K, 1.0, Operand(Ar, COL, lda, Ai), Operand(Br, ROW, ldb, Bi), 1.0,
+               Cr.T.copy().reshape(-1), Ci.T.copy().reshape(-1), COL, M)
+    want = (Arh + 1j * Aih) @ (Brh + 1j * Bih) + (Cr + 1j * Ci)
+    assert np.allclose(r["D"], want.real, atol=1e-13) and np.allclose(r["D_im"], want.imag, atol=1e-13)
+    Gr = np.abs(Arh) @ np.abs(Brh) + np.abs(Aih) @ np.abs(Bih) + np.abs(Cr)
+    Gi = np.abs(Arh) @ np.abs(Bih) + np.abs(Aih) @ np.abs(Brh) + np.abs(Ci)
+    assert np.allclose(r["G"], Gr, atol=1e-13) and np.allclose(r["G_im"], Gi, atol=1e-13)
+
+
+def test_complex_closed_form_i_times_identity():
+    n = 6
+    Z, ldz, _ = store(np.zeros((n, n)), COL); I, _, _ = store(np.eye(n), COL)
+    Br, ldb, Brh = store(RNG.integers(-4, 5, (n, n)).astype(float), COL)
+    Bi, _, Bih = store(RNG.integers(-4, 5, (n, n)).astype(float), COL)
+    r = O.gemm(n, n, n, 1.0, Operand(Z, COL, ldz, I), Operand(Br, COL, ldb, Bi))    # A = i * I
+    assert np.array_equal(r["D"], -Bih) and np.array_equal(r["D_im"], Brh)          # i (Br + i Bi) = -Bi + i Br
+
+
+# ---------------------------------------------------------------- contractions
+def brute_contract(ext, mA, sA, A, mB, sB, B, mC, sC, alpha=1.0, beta=0.0, Cin=None):
+    """Independent brute force: enumerate every assignment of every mode with itertools.product."""
+    labels = sorted(set(mA) | set(mB) | set(mC))
+    out = {}
+    for assign in itertools.product(*[range(ext[l]) for l in labels]):
+        ix = dict(zip(labels, assign))
+        oa = sum(ix[m] * s for m, s in zip(mA, sA)); ob = sum(ix[m] * s for m, s in zip(mB, sB))
+        oc = sum(ix[m] * s for m, s in zip(mC, sC))
+        out[oc] = out.get(oc, 0.0) + float(A[oa]) * float(B[ob])
+    res = {}
+    for oc, v in out.items():
+        res[oc] = alpha * v + (beta * float(Cin[oc]) if Cin is not None else 0.0)
+    return res
+
+
+def dense(ext, modes):
+    return O_col_strides([ext[m] for m in modes])
+
+
+def O_col_strides(e):
+    st, s = [], 1
+    for x in e:
+        st.append(s); s *= x
+    return st
+
+
+CASES = [
+    # (extents, modesA, modesB, modesC): labels are small integers
+    ({0: 4, 1: 3, 2: 2, 3: 5}, [0, 3, 2], [3, 1], [0, 1, 2]),              # C[a,b,c] = sum_d A[a,d,c] B[d,b]
+    ({0: 2, 1: 3, 2: 2, 3: 3, 4: 4, 5: 2}, [0, 4, 1, 5], [3, 5, 2, 4], [0, 1, 2, 3]),  # two contracted modes
+    ({0: 3, 1: 2, 2: 4, 3: 3}, [1, 3, 0], [3, 2], [0, 1, 2]),              # D_abc = A_bda B_dc (Section 5.5)
+    ({0: 3, 1: 4}, [0, 1], [1], [0]),                                       # matrix-vector
+]
+
+
+@pytest.mark.parametrize("ext,mA,mB,mC", CASES)
+def test_contraction_matches_brute_force_and_einsum(ext, mA, mB, mC):
+    sA, sB, sC = dense(ext, mA), dense(ext, mB), dense(ext, mC)
+    nA = int(np.prod([ext[m] for m in mA])); nB = int(np.prod([ext[m] for m in mB])); nC = int(np.prod([ext[m] for m in mC]))
+    A = RNG.integers(-4, 5, nA).astype(np.float16); B = RNG.integers(-4, 5, nB).astype(np.float16)
+    Cin = RNG.integers(-4, 5, nC).astype(np.float32)
+    r = O.contract(ext, mA, sA, A, mB, sB, B, mC, sC, Cin, alpha=2.0, beta=-1.0, threads=2)
+    want = brute_contract(ext, mA, sA, A, mB, sB, B, mC, sC, 2.0, -1.0, Cin)
+    assert len(want) == nC
+    for oc, v in want.items():
+        assert r["D"][oc] == v
+    # numpy.einsum on Fortran-ordered views (first listed mode fastest)
+    letters = "abcdefgh"
+    sub = lambda ms: "".join(letters[m] for m in ms)
+    At = A.astype(np.float64).reshape([ext[m] for m in mA], order="F")
+    Bt = B.astype(np.float64).reshape([ext[m] for m in mB], order="F")
+    Ct = Cin.astype(np.float64).reshape([ext[m] for m in mC], order="F")
+    E = 2.0 * np.einsum(f"{sub(mA)},{sub(mB)}->{sub(mC)}", At, Bt) - Ct
+    assert np.array_equal(r["D"].reshape(E.shape, order="F"), E)
+    G = 2.0 * np.einsum(f"{sub(mA)},{sub(mB)}->{sub(mC)}", np.abs(At), np.abs(Bt)) + np.abs(Ct)
+    assert np.array_equal(r["G"].reshape(E.shape, order="F"), G)
+
+
+def test_contraction_non_dense_strides_and_at_mode():
+    ext = {0: 3, 1: 2, 2: 4}
+    mA, mB, mC = [0, 2], [2, 1], [1, 0]            # C[b,a] = sum_c A[a,c] B[c,b], C stored transposed
+    sA, sB, sC = [1, 5], [2, 9], [1, 4]            # padded / strided storage
+    A = RNG.integers(-4, 5, 1 + 2 * 1 + 3 * 5).astype(np.float16)
+    B = RNG.integers(-4, 5, 1 + 3 * 2 + 1 * 9).astype(np.float16)
+    r = O.contract(ext, mA, sA, A, mB, sB, B, mC, sC)
+    want = brute_contract(ext, mA, sA, A, mB, sB, B, mC, sC)
+    for oc, v in want.items():
+        assert r["D"][oc] == v
+    at = np.array([[1, 2], [0, 0], [1, 1]])          # (b, a) pairs
+    ra = O.contract(ext, mA, sA, A, mB, sB, B, mC, sC, at=at)
+    for (b, a), v in zip(at, ra["D"]):
+        assert v == want[b * 1 + a * 4]
+
+
+def test_contraction_with_delta_is_a_mode_permutation():
+    # C[a,b,c] = sum_d A[a,d,c] delta[d,b]  =>  C[a,b,c] = A[a,b,c]
+    n = 4
+    ext = {0: n, 1: n, 2: n, 3: n}
+    A = RNG.integers(-8, 9, n ** 3).astype(np.float16)
+    delta = np.eye(n, dtype=np.float16).reshape(-1)
+    st3 = O_col_strides([n, n, n])
+    r = O.contract(ext, [0, 3, 2], st3, A, [3, 1], [1, n], delta, [0, 1, 2], st3)
+    assert np.array_equal(r["D"], A.astype(np.float64))
+
+
+def test_merged_index_convention_of_the_gett_layout():
+    """Section 5.5 maps A_bda to a matrix A_mk with m = (b a), k = d, and gives the element
+    position as b + d*Nb + a*Nb*Nd (zero-based) with a = m div Nb, b = m mod Nb: the first
+    written mode of a merged index is the fastest.  The GEMM oracle on matrices built with that
+    formula must reproduce the contraction oracle, with D_(ba),c unshuffled to D_abc."""
+    Na, Nb, Nc, Nd = 3, 4, 5, 6
+    ext = {0: Na, 1: Nb, 2: Nc, 3: Nd}
+    A = RNG.integers(-4, 5, Nb * Nd * Na).astype(np.float16)     # A[b,d,a], b fastest
+    B = RNG.integers(-4, 5, Nd * Nc).astype(np.float16)          # B[d,c]
+    r = O.contract(ext, [1, 3, 0], [1, Nb, Nb * Nd], A, [3, 2], [1, Nd], B, [0, 1, 2], [1, Na, Na * Nb])
+    M, K, N = Na * Nb, Nd, Nc
+    Amat = np.zeros((M, K), np.float64)
+    for m in range(M):
+        a, b = m // Nb, m % Nb
+        for k in range(K):
+            Amat[m, k] = float(A[b + k * Nb + a * Nb * Nd])
+    Am, lda, _ = store(Amat, COL)
+    g = O.gemm(M, N, K, 1.0, Operand(Am, COL, lda), Operand(B, COL, Nd))["D"]        # rows m = (b a)
+    D = r["D"].reshape((Na, Nb, Nc), order="F")
+    for a in range(Na):
+        for b in range(Nb):
+            assert np.array_equal(D[a, b, :], g[b + a * Nb, :])
+
+
+def test_bad_descriptions_are_rejected():
+    A = np.zeros(4, np.float16)
+    with pytest.raises(ValueError):
+        O.gemm(2, 2, 2, 1.0, Operand(A, COL, 1), Operand(A, COL, 2))          # ld too small
+    with pytest.raises(ValueError):
+        O.gemm(2, 2, 3, 1.0, Operand(A, COL, 2), Operand(A, COL, 3))          # buffer too short
+    with pytest.raises(ValueError):
+        O.contract({0: 2, 1: 2}, [0, 1], [1, 2], A, [1], [1], A[:2], [0, 5], [1, 2])  # unknown mode in C
+    with pytest.raises(ValueError):
+        O.gemm(2, 2, 2, 1.0, Operand(A, COL, 2, A), Operand(A, COL, 2), act=ACT_RELU)  # ReLU of a complex value
