@@ -1,0 +1,140 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: one fg_gemm call
+computing D = A.B + C at M = N = K = 8192 (FP16 A and B, column-major; FP32 C and D; FP32
+accumulation; alpha = beta = 1) with the inputs already resident in HBM.  The line printed at
+the end is the contract with the build driver:
+
+    value      whole-job TFLOP/s (2 M N K flops per step)
+    roofline   the GEMM kernel against the dense FP16 MFMA peak of the chip; `achieved` uses the
+               kernel's average launch duration measured with HIP events on the launch stream
+               over the timed region
+    cpu_baseline  the FP64 CPU oracle as it stands, timed on this machine's host cores on a bounded
+               sample of output entries of the same problem (each a full K-long dot product)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "TFLOP/s and % of FP16 MFMA peak, mixed-precision GEMM N=8192 and GETT"
+MFMA_FP16_PEAK_TFLOPS = 2500.0     # MI355X dense FP16 MFMA, published (2.5 PFLOP/s)
+# HBM bytes per launch of the 8192^3 kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (profiles/gemm_nn_8192_pmc.txt); None until that profile has been taken.
+MEASURED_HBM_TRAFFIC_BYTES = None
+
+
+def cpu_baseline(M, N, K, A, lda, B, ldb, C, ldc, budget_s=15.0):
+    """Time the oracle on a sample of output entries of the same workload, sized to ~budget_s."""
+    import numpy as np
+    from oracle import cpu_oracle as O
+    threads = O.default_threads()
+    rng = np.random.default_rng(1)
+
+    def run(count):
+        I = rng.integers(0, M, count); J = rng.integers(0, N, count)
+        t0 = time.perf_counter()
+        O.gemm(M, N, K, 1.0, O.Operand(A, O.COL, lda), O.Operand(B, O.COL, ldb), 1.0, C, None, O.COL, ldc,
+               at=(I, J), threads=threads)
+        return time.perf_counter() - t0
+
+    probe = 20000
+    t = run(probe)
+    count = int(min(max(probe, probe * budget_s / max(t, 1e-6)), 4_000_000))
+    t = run(count)
+    flops = 2.0 * K * count
+    return {"value": flops / t * 1e-12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": "%d of %d output entries of the same %dx%dx%d problem, each a full K=%d FP64 dot product; %.1f s"
+                      % (count, M * N, M, N, K, K, t)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--size", type=int, default=8192, help="M = N = K of the timed GEMM")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", action="store_true", help="also time the other layouts and configs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path shards without any exchange; "
+                 "see DESIGN.md); run with --gpus 1")
+
+    import torch
+    from paper_2009_12263_amd import binding as fg
+    from paper_2009_12263_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    n = args.size
+    M = N = K = n
+    A = W.uniform_pm1(M * K, W.stream_id(2, "A"), device=dev)
+    B = W.uniform_pm1(K * N, W.stream_id(2, "B"), device=dev)
+    C = W.uniform_pm1(M * N, W.stream_id(2, "C"), device=dev, dtype=torch.float32)
+    D = torch.empty_like(C)
+    mA, mB = fg.Matrix(A, fg.FG_COL, M), fg.Matrix(B, fg.FG_COL, K)
+    mC, mD = fg.Matrix(C, fg.FG_COL, M), fg.Matrix(D, fg.FG_COL, M)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        fg.fg_gemm(M, N, K, 1.0, mA, mB, 1.0, mC, mD, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    kern_ms = e0.elapsed_time(e1) / args.steps
+    flops = 2.0 * M * N * K
+    value = flops / (wall_ms * 1e-3) * 1e-12
+    achieved = flops / (kern_ms * 1e-3) * 1e-12
+
+    out = {
+        "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 in / f32 accumulate", "data": "synthetic",
+        "config": {"workload": "configs[1]: square mixed-precision GEMM D = A.B + C, M=N=K=%d, A,B FP16 column-major (NN), "
+                               "C,D FP32, uniform[-1,1), alpha=beta=1" % n,
+                   "kernel": fg.fg_gemm_plan(M, N, K)},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_FP16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_FP16_PEAK_TFLOPS, "traffic": MEASURED_HBM_TRAFFIC_BYTES,
+                     "kernel_ms": kern_ms},
+    }
+
+    if args.extras:
+        extras = {}
+        for name, la, lb in (("NT", fg.FG_COL, fg.FG_ROW), ("TN", fg.FG_ROW, fg.FG_COL), ("TT", fg.FG_ROW, fg.FG_ROW)):
+            a2, b2 = fg.Matrix(A, la, M), fg.Matrix(B, lb, K)
+            for _ in range(3):
+                fg.fg_gemm(M, N, K, 1.0, a2, b2, 1.0, mC, mD, stream=stream)
+            e0.record(stream)
+            for _ in range(10):
+                fg.fg_gemm(M, N, K, 1.0, a2, b2, 1.0, mC, mD, stream=stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            extras["gemm_%s_%d_TFLOPs" % (name, n)] = flops / (e0.elapsed_time(e1) / 10 * 1e-3) * 1e-12
+        out["extras"] = extras
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(M, N, K, A.cpu().numpy(), M, B.cpu().numpy(), K, C.cpu().numpy(), M)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

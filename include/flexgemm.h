@@ -1,0 +1,145 @@
+/*
+ * flexgemm -- flexible mixed-precision GEMM and GETT-style tensor contraction for AMD MI355X
+ * (gfx950).  C ABI of the shared library libflexgemm.so.
+ *
+ * The operations follow "Flexible Performant GEMM Kernels on GPUs" (arXiv 2009.12263):
+ *   - Section 2.2:   the matrix unit computes D = A.B + C with FP16 A, B and FP32 C, D;
+ *   - Section 4.3.2: the BLAS-like form C := alpha.A.B + beta.C with 'N'/'T' operands;
+ *   - Section 5.1:   'N' = column-major, 'T' = row-major storage of an operand;
+ *   - Section 5.2:   diagonal operands (only the diagonal is stored, zeros are never read,
+ *                    inner-loop iterations off the diagonal are skipped);
+ *   - Section 5.3:   fused elementwise operations and a bias vector (epilogue);
+ *   - Section 5.4:   complex operands as four real products on split (planar) storage;
+ *   - Section 5.5:   tensor contractions whose modes are mapped to GEMM tile coordinates
+ *                    while tiles are loaded (GETT), never by separate transposition.
+ *
+ * General conventions
+ *   - Every data pointer (matrix/tensor elements, bias) is a DEVICE pointer to memory the
+ *     caller owns.  The library never allocates, frees, retains or copies caller memory.
+ *   - Every descriptor pointer (fg_matrix, fg_epilogue, mode/extent/stride arrays) is a HOST
+ *     pointer, read only during the call.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t, NULL = the default stream) and the call
+ *     returns without synchronising.  Calls on one stream execute in order.
+ *   - Errors are reported by the return value only; nothing is launched when a call fails, and
+ *     nothing is thrown or aborted across this boundary.  fg_last_error() gives a message.
+ *   - Leading dimensions and strides are in ELEMENTS.
+ *   - Alignment: element base pointers must be 16-byte aligned; leading dimensions of FP16
+ *     operands must be multiples of 8 and of FP32 operands multiples of 4 (Section 4.2.2:
+ *     the aligned layouts that permit 128-bit accesses).  Otherwise FG_ERR_ALIGN.
+ *   - Sizes: M, N multiples of 64 and K a multiple of 64 (the paper requires inputs padded to
+ *     the tile sizes, Section 7).  Otherwise FG_ERR_UNSUPPORTED.  M, N or K equal to zero is
+ *     accepted: with M == 0 or N == 0 nothing is done; with K == 0 the product term is zero.
+ *   - D may alias C exactly (same pointer, layout and ld: the in-place BLAS form).  A and B
+ *     must not overlap D.
+ */
+#ifndef FLEXGEMM_H
+#define FLEXGEMM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FG_OK = 0,
+    FG_ERR_NULL = 1,         /* a required pointer is NULL                                   */
+    FG_ERR_SHAPE = 2,        /* negative size, leading dimension smaller than the extent     */
+    FG_ERR_LAYOUT = 3,       /* layout / dtype value not valid for that operand              */
+    FG_ERR_ALIGN = 4,        /* pointer or leading dimension not aligned as required         */
+    FG_ERR_UNSUPPORTED = 5,  /* valid request that this version does not implement           */
+    FG_ERR_MODES = 6,        /* inconsistent contraction description                         */
+    FG_ERR_LAUNCH = 7        /* the HIP runtime refused the launch (no device, bad stream)   */
+} fg_status;
+
+typedef enum { FG_F16 = 0, FG_BF16 = 1, FG_F32 = 2 } fg_dtype;   /* A, B: FG_F16.  C, D: FG_F32 */
+
+typedef enum {
+    FG_COL = 0,   /* column-major ('N'): element (r, c) at r + c*ld                            */
+    FG_ROW = 1,   /* row-major ('T'):    element (r, c) at c + r*ld                            */
+    FG_DIAG = 2,  /* diagonal: `re` points at the min(rows, cols) diagonal entries; every other
+                     element is zero and is never read; ld is ignored (A or B only)            */
+    FG_ZERO = 3   /* all-zero matrix that is never read (C only; same as passing C == NULL)    */
+} fg_layout;
+
+typedef enum { FG_ACT_NONE = 0, FG_ACT_RELU = 1 } fg_act;       /* relu(y) = max(y, 0)         */
+
+/* A matrix operand.  `im == NULL`: real matrix.  `im != NULL`: complex matrix in planar-split
+ * storage, real parts at `re` and imaginary parts at `im`, both with the same layout and ld. */
+typedef struct {
+    void   *re;
+    void   *im;
+    int32_t dtype;    /* fg_dtype  */
+    int32_t layout;   /* fg_layout */
+    int64_t ld;
+} fg_matrix;
+
+/* Operations fused into the store of D (Section 5.3): D = act(alpha.A.B + beta.C + bias). */
+typedef struct {
+    const float *bias;      /* device pointer or NULL                                           */
+    int32_t      bias_dim;  /* 0: length M, bias[i] added to row i; 1: length N, bias[j] added
+                               to column j                                                      */
+    int32_t      act;       /* fg_act */
+} fg_epilogue;
+
+/*
+ * D = act(alpha * op(A) * op(B) + beta * C + bias)       (Sections 2.2, 4.3.2, 5.1-5.4)
+ *
+ * op(A) is the logical M x K matrix and op(B) the logical K x N matrix described by A and B;
+ * C and D are M x N.  FP16 elements are multiplied exactly and accumulated in FP32.
+ *   A, B : FG_F16; layout FG_COL, FG_ROW or FG_DIAG (at most one of A, B diagonal).
+ *   C    : FG_F32, FG_COL or FG_ROW with the same layout as D; NULL or FG_ZERO means no C term
+ *          (beta is then ignored).
+ *   D    : FG_F32, FG_COL or FG_ROW; written.
+ *   ep   : NULL means no bias and no activation.
+ * Complex: if A or B has `im`, the product is complex (a missing `im` is zero), D must have
+ * `im`, C (if given) must have `im`, alpha and beta are real, and `ep` must be NULL or empty.
+ */
+fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha,
+                  const fg_matrix *A, const fg_matrix *B,
+                  float beta, const fg_matrix *C,
+                  const fg_matrix *D, const fg_epilogue *ep,
+                  void *hip_stream);
+
+/*
+ * Cout[modesC] = alpha * sum over contracted modes of A[modesA] * B[modesB] + beta * Cin[modesC]
+ *                                                                     (Sections 4.1 and 5.5)
+ * A mode is an integer label; `mode_labels[n_modes]` lists the distinct labels and
+ * `mode_extents[n_modes]` their extents.  modesX[nX] / stridesX[nX] give, for tensor X, its
+ * modes in storage order and the element stride of each.  Every label must appear in exactly
+ * two of {A, B, C}: modes shared by A and C become GEMM rows, modes shared by B and C become
+ * GEMM columns, modes shared by A and B are summed over (no batch and no trace modes:
+ * FG_ERR_MODES).  A, B are FP16 device tensors, Cin (NULL iff beta term absent) and Cout FP32;
+ * Cout may equal Cin.  The tensors are never transposed in memory: the mode-to-tile mapping
+ * happens while tiles are loaded and while the result is stored.
+ * Requirements of this version (else FG_ERR_UNSUPPORTED): in each of A and B some mode has
+ * stride 1 and an extent that is a multiple of 8; the products of the row, column and summed
+ * extents are multiples of 64; at most 4 modes per group.
+ */
+fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA, const void *A,
+                      int32_t nB, const int32_t *modesB, const int64_t *stridesB, const void *B,
+                      int32_t nC, const int32_t *modesC, const int64_t *stridesC,
+                      const float *Cin, float *Cout,
+                      int32_t n_modes, const int32_t *mode_labels, const int64_t *mode_extents,
+                      float alpha, float beta, void *hip_stream);
+
+/* Message for the most recent failing call on this thread ("" if none).  The pointer refers to
+ * thread-local static storage: valid until the next library call on the same thread. */
+const char *fg_last_error(void);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int32_t fg_version(void);
+
+/*
+ * Name of the kernel variant and block tile that fg_gemm would use for this problem, written as
+ * a NUL-terminated string into `buf` (at most `buf_len` bytes).  This is the "params" choice of
+ * Section 4.2.1: the largest (nearly) square block tile that divides the problem and fills the
+ * GPU.  Returns FG_OK, or the status fg_gemm would return for these sizes and layouts.
+ */
+fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t layoutB,
+                       int32_t layoutD, int32_t is_complex, char *buf, int32_t buf_len);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXGEMM_H */

@@ -1,0 +1,153 @@
+"""Thin ctypes binding of libflexgemm.so: argument marshalling only.
+
+The functions have the names and arguments of the C ABI (include/flexgemm.h).  Torch is used
+for device memory and streams; every step of the computation runs in the library's kernels.
+There is no fallback: if the shared library is missing, importing the entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libflexgemm.so")
+
+FG_OK = 0
+FG_ERR_NULL, FG_ERR_SHAPE, FG_ERR_LAYOUT, FG_ERR_ALIGN, FG_ERR_UNSUPPORTED, FG_ERR_MODES, FG_ERR_LAUNCH = range(1, 8)
+FG_F16, FG_BF16, FG_F32 = 0, 1, 2
+FG_COL, FG_ROW, FG_DIAG, FG_ZERO = 0, 1, 2, 3
+FG_ACT_NONE, FG_ACT_RELU = 0, 1
+
+EXPORTS = ("fg_gemm", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan")
+
+
+class fg_matrix(C.Structure):
+    _fields_ = [("re", C.c_void_p), ("im", C.c_void_p), ("dtype", C.c_int32), ("layout", C.c_int32), ("ld", C.c_int64)]
+
+
+class fg_epilogue(C.Structure):
+    _fields_ = [("bias", C.c_void_p), ("bias_dim", C.c_int32), ("act", C.c_int32)]
+
+
+class FlexGemmError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("flexgemm status %d: %s" % (status, message))
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load libflexgemm.so (built in-tree by ``paper_2009_12263_amd.build``).  Fails loudly."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libflexgemm.so is not built: run `python -m paper_2009_12263_amd.build` "
+                              "(there is no CPU or PyTorch fallback)")
+        lib = C.CDLL(LIB_PATH)
+        i32, i64, f32, vp = C.c_int32, C.c_int64, C.c_float, C.c_void_p
+        lib.fg_gemm.restype = C.c_int
+        lib.fg_gemm.argtypes = [i64, i64, i64, f32, C.POINTER(fg_matrix), C.POINTER(fg_matrix), f32,
+                                C.POINTER(fg_matrix), C.POINTER(fg_matrix), C.POINTER(fg_epilogue), vp]
+        lib.fg_contract.restype = C.c_int
+        lib.fg_contract.argtypes = [i32, vp, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, f32, f32, vp]
+        lib.fg_last_error.restype = C.c_char_p
+        lib.fg_last_error.argtypes = []
+        lib.fg_version.restype = i32
+        lib.fg_version.argtypes = []
+        lib.fg_gemm_plan.restype = C.c_int
+        lib.fg_gemm_plan.argtypes = [i64, i64, i64, i32, i32, i32, i32, C.c_char_p, i32]
+        _lib = lib
+    return _lib
+
+
+@dataclass
+class Matrix:
+    """Host-side description of a device matrix: the tensors only provide the pointers."""
+    re: Optional[torch.Tensor]
+    layout: int = FG_COL
+    ld: int = 0
+    im: Optional[torch.Tensor] = None
+    dtype: Optional[int] = None
+
+    def _struct(self) -> fg_matrix:
+        m = fg_matrix()
+        m.re = self.re.data_ptr() if self.re is not None else None
+        m.im = self.im.data_ptr() if self.im is not None else None
+        if self.dtype is not None:
+            m.dtype = self.dtype
+        else:
+            t = self.re if self.re is not None else self.im
+            m.dtype = {torch.float16: FG_F16, torch.bfloat16: FG_BF16, torch.float32: FG_F32}.get(
+                t.dtype if t is not None else torch.float32, -1)
+        m.layout, m.ld = self.layout, self.ld
+        return m
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def fg_last_error() -> str:
+    return load_library().fg_last_error().decode()
+
+
+def fg_version() -> int:
+    return int(load_library().fg_version())
+
+
+def _check(status: int, raise_on_error: bool) -> int:
+    if status != FG_OK and raise_on_error:
+        raise FlexGemmError(status, fg_last_error())
+    return status
+
+
+def fg_gemm(M: int, N: int, K: int, alpha: float, A: Optional[Matrix], B: Optional[Matrix], beta: float,
+            C_: Optional[Matrix], D: Optional[Matrix], bias: Optional[torch.Tensor] = None, bias_dim: int = 0,
+            act: int = FG_ACT_NONE, stream=None, raise_on_error: bool = True) -> int:
+    """D = act(alpha * op(A) * op(B) + beta * C + bias); see fg_gemm in include/flexgemm.h."""
+    lib = load_library()
+    sa = A._struct() if A is not None else None
+    sb = B._struct() if B is not None else None
+    sc = C_._struct() if C_ is not None else None
+    sd = D._struct() if D is not None else None
+    ep = None
+    if bias is not None or act != FG_ACT_NONE:
+        ep = fg_epilogue()
+        ep.bias = bias.data_ptr() if bias is not None else None
+        ep.bias_dim, ep.act = bias_dim, act
+    ref = lambda s: C.byref(s) if s is not None else None
+    st = lib.fg_gemm(M, N, K, alpha, ref(sa), ref(sb), beta, ref(sc), ref(sd), ref(ep), _stream_handle(stream))
+    return _check(st, raise_on_error)
+
+
+def fg_gemm_plan(M: int, N: int, K: int, layoutA: int = FG_COL, layoutB: int = FG_COL, layoutD: int = FG_COL,
+                 is_complex: bool = False) -> str:
+    buf = C.create_string_buffer(128)
+    st = load_library().fg_gemm_plan(M, N, K, layoutA, layoutB, layoutD, int(is_complex), buf, 128)
+    _check(st, True)
+    return buf.value.decode()
+
+
+def fg_contract(modesA: Sequence[int], stridesA: Sequence[int], A: torch.Tensor,
+                modesB: Sequence[int], stridesB: Sequence[int], B: torch.Tensor,
+                modesC: Sequence[int], stridesC: Sequence[int], Cin: Optional[torch.Tensor], Cout: torch.Tensor,
+                extents: dict, alpha: float = 1.0, beta: float = 0.0, stream=None, raise_on_error: bool = True) -> int:
+    """Cout = alpha * contraction(A, B) + beta * Cin; see fg_contract in include/flexgemm.h.
+    ``extents`` maps each integer mode label to its extent."""
+    lib = load_library()
+    i32 = lambda xs: (C.c_int32 * len(xs))(*[int(x) for x in xs])
+    i64 = lambda xs: (C.c_int64 * len(xs))(*[int(x) for x in xs])
+    mA, sA, mB, sB, mC, sC = i32(modesA), i64(stridesA), i32(modesB), i64(stridesB), i32(modesC), i64(stridesC)
+    labels, exts = i32(list(extents.keys())), i64([extents[k] for k in extents])
+    ptr = lambda t: t.data_ptr() if t is not None else None
+    st = lib.fg_contract(len(mA), mA, sA, ptr(A), len(mB), mB, sB, ptr(B), len(mC), mC, sC, ptr(Cin), ptr(Cout),
+                         len(labels), labels, exts, alpha, beta, _stream_handle(stream))
+    return _check(st, raise_on_error)

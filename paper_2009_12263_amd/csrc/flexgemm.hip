@@ -1,0 +1,245 @@
+// C ABI of libflexgemm.so: argument validation, the "params" choice (Section 4.2.1: which block
+// tile and kernel variant serve a problem) and the launch.  All arithmetic of the method runs in
+// the kernels of gemm_kernel.hpp; this file only describes problems to them.
+#include "../../include/flexgemm.h"
+
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+
+#include "kernel_table.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+fg_status fail(fg_status st, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+constexpr int kNumCU = 256;   // MI355X: 8 XCDs x 32 compute units
+
+// ---- description of one GEMM after normalisation to "column-major D" ------------------------
+struct Problem {
+    int64_t M, N, K;
+    const void *A, *A_im, *B, *B_im;
+    bool a_kc, b_kc;         // operand is K-contiguous
+    bool a_diag, b_diag;
+    int64_t lda, ldb;
+    const float *C, *C_im;
+    float *D, *D_im;
+    int64_t ldc, ldd;
+    const float *bias;
+    int bias_dim, act;
+    float alpha, beta;
+    bool cplx;
+};
+
+const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
+    if (!a_kc && b_kc) return fg::kernel_table_nn();
+    if (!a_kc && !b_kc) return fg::kernel_table_nt();
+    if (a_kc && b_kc) return fg::kernel_table_tn();
+    return fg::kernel_table_tt();
+}
+
+// The params heuristic: the largest block tile that divides the problem and still gives every
+// compute unit a workgroup; if none fills the GPU, the smallest tile that divides the problem.
+int choose_tile(int64_t M, int64_t N) {
+    static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64};
+    static const int bn[fg::TILE_COUNT] = {256, 128, 128, 64};
+    int last_fit = -1;
+    for (int t = 0; t < fg::TILE_COUNT; ++t) {
+        if (M % bm[t] || N % bn[t]) continue;
+        last_fit = t;
+        if ((M / bm[t]) * (N / bn[t]) >= kNumCU) return t;
+    }
+    return last_fit;
+}
+
+
+fg_status launch(const fg::KernelEntry &k, const fg::GemmParams &p, hipStream_t stream) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(FG_ERR_LAUNCH, "no HIP device is current");
+    // Raise the dynamic LDS limit once per (kernel, device).
+    {
+        static std::mutex m;
+        static struct { const void *fn; int dev; } done[256];
+        static int n_done = 0;
+        std::lock_guard<std::mutex> lock(m);
+        bool found = false;
+        for (int i = 0; i < n_done; ++i) found |= (done[i].fn == (const void *)k.fn && done[i].dev == dev);
+        if (!found) {
+            hipError_t e = hipFuncSetAttribute((const void *)k.fn, hipFuncAttributeMaxDynamicSharedMemorySize, k.lds_bytes);
+            if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "hipFuncSetAttribute(%s): %s", k.name, hipGetErrorString(e));
+            if (n_done < 256) { done[n_done].fn = (const void *)k.fn; done[n_done].dev = dev; ++n_done; }
+        }
+    }
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block((unsigned)k.threads);
+    hipLaunchKernelGGL(k.fn, grid, block, (size_t)k.lds_bytes, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "launch of %s failed: %s", k.name, hipGetErrorString(e));
+    return FG_OK;
+}
+
+fg_status check_sizes(int64_t M, int64_t N, int64_t K) {
+    if (M < 0 || N < 0 || K < 0) return fail(FG_ERR_SHAPE, "negative size M=%lld N=%lld K=%lld", (long long)M, (long long)N, (long long)K);
+    if (M % 64 || N % 64 || K % 64)
+        return fail(FG_ERR_UNSUPPORTED, "M, N and K must be multiples of 64 (got %lld, %lld, %lld)", (long long)M, (long long)N, (long long)K);
+    if (M > (1 << 30) || N > (1 << 30) || K > (1 << 30)) return fail(FG_ERR_UNSUPPORTED, "sizes above 2^30 are not supported");
+    return FG_OK;
+}
+
+fg_status check_input_matrix(const char *name, const fg_matrix *X, int64_t rows, int64_t cols) {
+    if (!X) return fail(FG_ERR_NULL, "%s is NULL", name);
+    if (X->dtype != FG_F16) return fail(X->dtype == FG_BF16 ? FG_ERR_UNSUPPORTED : FG_ERR_LAYOUT, "%s must be FG_F16", name);
+    if (X->layout != FG_COL && X->layout != FG_ROW && X->layout != FG_DIAG) return fail(FG_ERR_LAYOUT, "%s: layout %d is not valid for an input", name, X->layout);
+    if (rows > 0 && cols > 0) {
+        if (!X->re) return fail(FG_ERR_NULL, "%s->re is NULL", name);
+        if (!aligned16(X->re) || (X->im && !aligned16(X->im))) return fail(FG_ERR_ALIGN, "%s: element pointers must be 16-byte aligned", name);
+        if (X->layout != FG_DIAG) {
+            int64_t need = X->layout == FG_COL ? rows : cols;
+            if (X->ld < need) return fail(FG_ERR_SHAPE, "%s: ld=%lld is smaller than %lld", name, (long long)X->ld, (long long)need);
+            if (X->ld % 8) return fail(FG_ERR_ALIGN, "%s: ld=%lld must be a multiple of 8", name, (long long)X->ld);
+        }
+    }
+    return FG_OK;
+}
+
+fg_status check_output_matrix(const char *name, const fg_matrix *X, int64_t rows, int64_t cols, bool need_im) {
+    if (X->dtype != FG_F32) return fail(FG_ERR_LAYOUT, "%s must be FG_F32", name);
+    if (X->layout != FG_COL && X->layout != FG_ROW) return fail(FG_ERR_LAYOUT, "%s: layout %d is not valid here", name, X->layout);
+    if (rows > 0 && cols > 0) {
+        if (!X->re) return fail(FG_ERR_NULL, "%s->re is NULL", name);
+        if (need_im && !X->im) return fail(FG_ERR_NULL, "%s->im is NULL but the product is complex", name);
+        if (!aligned16(X->re) || (X->im && !aligned16(X->im))) return fail(FG_ERR_ALIGN, "%s: element pointers must be 16-byte aligned", name);
+        int64_t need = X->layout == FG_COL ? rows : cols;
+        if (X->ld < need) return fail(FG_ERR_SHAPE, "%s: ld=%lld is smaller than %lld", name, (long long)X->ld, (long long)need);
+        if (X->ld % 4) return fail(FG_ERR_ALIGN, "%s: ld=%lld must be a multiple of 4", name, (long long)X->ld);
+    }
+    return FG_OK;
+}
+
+// Validate an fg_gemm call and normalise it so that D is column-major: a row-major D is the
+// column-major D^T = op(B)^T op(A)^T, i.e. the same kernel with the operands exchanged.
+fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
+                    float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, Problem &q) {
+    if (fg_status st = check_sizes(M, N, K)) return st;
+    if (fg_status st = check_input_matrix("A", A, M, K)) return st;
+    if (fg_status st = check_input_matrix("B", B, K, N)) return st;
+    if (!D) return fail(FG_ERR_NULL, "D is NULL");
+    const bool cplx = (A->im != nullptr) || (B->im != nullptr);
+    if (fg_status st = check_output_matrix("D", D, M, N, cplx)) return st;
+    const bool has_c = C && C->layout != FG_ZERO && C->re != nullptr;
+    if (C && C->layout != FG_ZERO && !C->re && M > 0 && N > 0) return fail(FG_ERR_NULL, "C->re is NULL (pass C == NULL or FG_ZERO for no C term)");
+    if (has_c) {
+        if (fg_status st = check_output_matrix("C", C, M, N, cplx)) return st;
+        if (C->layout != D->layout) return fail(FG_ERR_LAYOUT, "C and D must have the same layout");
+    }
+    if (A->layout == FG_DIAG && B->layout == FG_DIAG) return fail(FG_ERR_UNSUPPORTED, "at most one of A and B may be diagonal");
+    const bool has_ep = ep && (ep->bias || ep->act != FG_ACT_NONE);
+    if (ep) {
+        if (ep->act != FG_ACT_NONE && ep->act != FG_ACT_RELU) return fail(FG_ERR_LAYOUT, "unknown activation %d", ep->act);
+        if (ep->bias && ep->bias_dim != 0 && ep->bias_dim != 1) return fail(FG_ERR_LAYOUT, "bias_dim must be 0 or 1");
+        if (ep->bias && !aligned16(ep->bias)) return fail(FG_ERR_ALIGN, "bias must be 16-byte aligned");
+    }
+    if (cplx && has_ep) return fail(FG_ERR_UNSUPPORTED, "bias and activation are not defined for complex products");
+
+    const bool swap = (D->layout == FG_ROW);
+    q.cplx = cplx;
+    q.alpha = alpha;
+    q.beta = has_c ? beta : 0.f;
+    q.C = has_c ? (const float *)C->re : nullptr;
+    q.C_im = has_c ? (const float *)C->im : nullptr;
+    q.ldc = has_c ? C->ld : 0;
+    q.D = (float *)D->re;
+    q.D_im = (float *)D->im;
+    q.ldd = D->ld;
+    q.bias = (ep && ep->bias) ? ep->bias : nullptr;
+    q.bias_dim = ep ? ep->bias_dim : 0;
+    q.act = ep ? ep->act : FG_ACT_NONE;
+    if (!swap) {
+        q.M = M; q.N = N; q.K = K;
+        q.A = A->re; q.A_im = A->im; q.lda = A->ld; q.a_diag = A->layout == FG_DIAG; q.a_kc = (A->layout == FG_ROW);
+        q.B = B->re; q.B_im = B->im; q.ldb = B->ld; q.b_diag = B->layout == FG_DIAG; q.b_kc = (B->layout == FG_COL);
+    } else {
+        // D^T (N x M, column-major) = B^T (N x K) . A^T (K x M)
+        q.M = N; q.N = M; q.K = K;
+        q.A = B->re; q.A_im = B->im; q.lda = B->ld; q.a_diag = B->layout == FG_DIAG; q.a_kc = (B->layout == FG_COL);
+        q.B = A->re; q.B_im = A->im; q.ldb = A->ld; q.b_diag = A->layout == FG_DIAG; q.b_kc = (A->layout == FG_ROW);
+        q.bias_dim = 1 - q.bias_dim;
+    }
+    return FG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *fg_last_error(void) { return g_err; }
+
+int32_t fg_version(void) { return 100; }   // 0.1.0
+
+fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
+                  float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, void *hip_stream) {
+    Problem q;
+    if (fg_status st = normalise(M, N, K, alpha, A, B, beta, C, D, ep, q)) return st;
+    if (q.M == 0 || q.N == 0) return FG_OK;
+    if (q.cplx) return fail(FG_ERR_UNSUPPORTED, "complex products are not implemented yet");
+    if (q.a_diag || q.b_diag) return fail(FG_ERR_UNSUPPORTED, "diagonal operands are not implemented yet");
+
+    const int tile = choose_tile(q.M, q.N);
+    if (tile < 0) return fail(FG_ERR_UNSUPPORTED, "no block tile divides M=%lld, N=%lld", (long long)q.M, (long long)q.N);
+    const fg::KernelEntry &k = table_for(q.a_kc, q.b_kc)[fg::entry_index(tile, false)];
+
+    fg::GemmParams p;
+    memset(&p, 0, sizeof p);
+    p.M = (int32_t)q.M; p.N = (int32_t)q.N; p.K = (int32_t)q.K;
+    p.tiles_m = (int32_t)(q.M / k.bm); p.tiles_n = (int32_t)(q.N / k.bn);
+    p.A = (const _Float16 *)q.A; p.B = (const _Float16 *)q.B;
+    p.a_rs = q.a_kc ? q.lda : 1; p.a_ks = q.a_kc ? 1 : q.lda;
+    p.b_rs = q.b_kc ? q.ldb : 1; p.b_ks = q.b_kc ? 1 : q.ldb;
+    p.C = q.C; p.D = q.D; p.ldc = q.ldc; p.ldd = q.ldd;
+    p.bias = q.bias; p.bias_dim = q.bias_dim; p.act = q.act; p.has_c = q.C != nullptr;
+    p.alpha = q.alpha; p.beta = q.beta;
+    return launch(k, p, (hipStream_t)hip_stream);
+}
+
+fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t layoutB, int32_t layoutD,
+                       int32_t is_complex, char *buf, int32_t buf_len) {
+    if (!buf || buf_len <= 0) return fail(FG_ERR_NULL, "buf is NULL or empty");
+    buf[0] = 0;
+    if (fg_status st = check_sizes(M, N, K)) return st;
+    if ((layoutA != FG_COL && layoutA != FG_ROW) || (layoutB != FG_COL && layoutB != FG_ROW) || (layoutD != FG_COL && layoutD != FG_ROW))
+        return fail(FG_ERR_LAYOUT, "plan query takes FG_COL / FG_ROW layouts");
+    if (is_complex) return fail(FG_ERR_UNSUPPORTED, "complex products are not implemented yet");
+    bool a_kc = layoutA == FG_ROW, b_kc = layoutB == FG_COL;
+    int64_t m = M, n = N;
+    if (layoutD == FG_ROW) { bool t = a_kc; a_kc = b_kc; b_kc = t; m = N; n = M; }
+    const int tile = choose_tile(m, n);
+    if (tile < 0) return fail(FG_ERR_UNSUPPORTED, "no block tile divides the problem");
+    snprintf(buf, (size_t)buf_len, "%s", table_for(a_kc, b_kc)[fg::entry_index(tile, false)].name);
+    return FG_OK;
+}
+
+fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA, const void *A,
+                      int32_t nB, const int32_t *modesB, const int64_t *stridesB, const void *B,
+                      int32_t nC, const int32_t *modesC, const int64_t *stridesC, const float *Cin, float *Cout,
+                      int32_t n_modes, const int32_t *mode_labels, const int64_t *mode_extents,
+                      float alpha, float beta, void *hip_stream) {
+    (void)nA; (void)modesA; (void)stridesA; (void)A; (void)nB; (void)modesB; (void)stridesB; (void)B;
+    (void)nC; (void)modesC; (void)stridesC; (void)Cin; (void)Cout; (void)n_modes; (void)mode_labels;
+    (void)mode_extents; (void)alpha; (void)beta; (void)hip_stream;
+    return fail(FG_ERR_UNSUPPORTED, "fg_contract is not implemented yet");
+}
+
+}  // extern "C"

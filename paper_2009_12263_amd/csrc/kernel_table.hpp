@@ -1,0 +1,44 @@
+// Registry of the compiled kernel variants.  A variant is chosen by
+// (tile shape, A K-contiguous?, B K-contiguous?, strided tensor addressing?, operator).
+#pragma once
+#include "gemm_kernel.hpp"
+
+namespace fg {
+
+enum TileId { TILE_256x256 = 0, TILE_256x128 = 1, TILE_128x128 = 2, TILE_64x64 = 3, TILE_COUNT = 4 };
+
+struct KernelEntry {
+    void (*fn)(const GemmParams);
+    const char *name;
+    int bm, bn, threads, lds_bytes;
+};
+
+// Defined by the instantiation files (one per layout pair).
+const KernelEntry *kernel_table_nn();   // A M-contiguous, B K-contiguous  (A 'N', B 'N')
+const KernelEntry *kernel_table_nt();   // A M-contiguous, B N-contiguous  (A 'N', B 'T')
+const KernelEntry *kernel_table_tn();   // A K-contiguous, B K-contiguous  (A 'T', B 'N')
+const KernelEntry *kernel_table_tt();   // A K-contiguous, B N-contiguous  (A 'T', B 'T')
+
+// Entry index inside one table: tile * 2 + strided.
+inline int entry_index(int tile, bool strided) { return tile * 2 + (strided ? 1 : 0); }
+
+#define FG_ENTRY(BM, BN, WGM, WGN, AKC, BKC, STR, NAME)                                            \
+    { gemm_kernel<TileCfg<BM, BN, WGM, WGN, AKC, BKC, STR>>, NAME, BM, BN,                         \
+      TileCfg<BM, BN, WGM, WGN, AKC, BKC, STR>::NTHREADS, TileCfg<BM, BN, WGM, WGN, AKC, BKC, STR>::LDS_BYTES }
+
+#define FG_DEFINE_TABLE(FUNC, AKC, BKC, TAG)                                                       \
+    const KernelEntry *FUNC() {                                                                    \
+        static const KernelEntry t[TILE_COUNT * 2] = {                                             \
+            FG_ENTRY(256, 256, 2, 4, AKC, BKC, false, "gemm_" TAG "_256x256x64"),                  \
+            FG_ENTRY(256, 256, 2, 4, AKC, BKC, true, "gett_" TAG "_256x256x64"),                   \
+            FG_ENTRY(256, 128, 4, 2, AKC, BKC, false, "gemm_" TAG "_256x128x64"),                  \
+            FG_ENTRY(256, 128, 4, 2, AKC, BKC, true, "gett_" TAG "_256x128x64"),                   \
+            FG_ENTRY(128, 128, 2, 2, AKC, BKC, false, "gemm_" TAG "_128x128x64"),                  \
+            FG_ENTRY(128, 128, 2, 2, AKC, BKC, true, "gett_" TAG "_128x128x64"),                   \
+            FG_ENTRY(64, 64, 2, 2, AKC, BKC, false, "gemm_" TAG "_64x64x64"),                      \
+            FG_ENTRY(64, 64, 2, 2, AKC, BKC, true, "gett_" TAG "_64x64x64"),                       \
+        };                                                                                         \
+        return t;                                                                                  \
+    }
+
+}  // namespace fg

@@ -1,0 +1,113 @@
+"""Helpers shared by the GPU parity tests: build seeded inputs, call the library through its
+C ABI binding, evaluate the oracle (all entries, or a sample) and compare.
+
+Tolerances (written here once, used by every test):
+  * official bar (the benchmark spec of this build):
+        |D - D_ref| <= 2e-3 * (|alpha| (|A||B|)_ij + |beta| |C_ij|)            elementwise;
+  * tight bar, derived from the arithmetic: FP16 x FP16 products are exact in FP32, so the only
+    error is FP32 accumulation, at worst K * 2^-24 * G and in practice ~sqrt(K) * 2^-24 * G;
+    results must also satisfy  |D - D_ref| <= 4 * sqrt(K) * 2^-24 * G + 2^-22 * |D_ref|
+    (the second term covers the final alpha/beta/bias roundings).  A dropped or duplicated
+    16-wide k slice changes an entry by ~16/K of |A||B|, far above this bar;
+  * integer-valued inputs (|a|, |b| <= 8): every partial sum is an integer below 2^24, the
+    result is unique, and the comparison is bit-exact.
+"""
+from __future__ import annotations
+
+import math
+from typing import Optional
+
+import numpy as np
+import torch
+
+from oracle import cpu_oracle as O
+from paper_2009_12263_amd import binding as fg
+from paper_2009_12263_amd import workloads as W
+
+OFFICIAL_RTOL = 2e-3
+
+
+def make_operand(rows: int, cols: int, layout: int, stream: int, device, ints: bool, pad: int = 0, seed=W.DEFAULT_SEED):
+    """A stored rows x cols FP16 operand in FG_COL / FG_ROW layout with ld = extent + pad.
+    Returns (device tensor, ld)."""
+    lead = rows if layout == fg.FG_COL else cols
+    other = cols if layout == fg.FG_COL else rows
+    ld = lead + pad
+    gen = W.small_ints if ints else W.uniform_pm1
+    t = gen(ld * other, stream, seed=seed, device=device, dtype=torch.float16)
+    return t, ld
+
+
+def make_f32(numel: int, stream: int, device, ints: bool, seed=W.DEFAULT_SEED):
+    gen = W.small_ints if ints else W.uniform_pm1
+    return gen(numel, stream, seed=seed, device=device, dtype=torch.float32)
+
+
+def np16(t: Optional[torch.Tensor]):
+    return None if t is None else t.detach().cpu().numpy()
+
+
+def sample_positions(M: int, N: int, count: int, seed: int, tile: int = 256):
+    """Random positions plus the corners, the last row/column and both sides of block-tile seams."""
+    rng = np.random.default_rng(seed)
+    I = list(rng.integers(0, M, count)); J = list(rng.integers(0, N, count))
+    edges_m = sorted({0, M - 1} | {x for b in range(tile, M, tile) for x in (b - 1, b)} )
+    edges_n = sorted({0, N - 1} | {x for b in range(tile, N, tile) for x in (b - 1, b)} )
+    pick_m = edges_m if len(edges_m) <= 24 else list(rng.choice(edges_m, 24, replace=False)) + [0, M - 1]
+    pick_n = edges_n if len(edges_n) <= 24 else list(rng.choice(edges_n, 24, replace=False)) + [0, N - 1]
+    for i in pick_m:
+        for j in pick_n:
+            I.append(i); J.append(j)
+    return np.array(I, np.int64), np.array(J, np.int64)
+
+
+def compare(got: np.ndarray, ref: np.ndarray, G: np.ndarray, K: int, exact: bool, what: str):
+    got = got.astype(np.float64)
+    assert np.isfinite(got).all(), what + ": non-finite output"
+    err = np.abs(got - ref)
+    if exact:
+        bad = np.flatnonzero(err.reshape(-1) != 0)
+        assert bad.size == 0, "%s: %d entries differ from the exact result (first at flat index %d: got %r want %r)" % (
+            what, bad.size, bad[0], got.reshape(-1)[bad[0]], ref.reshape(-1)[bad[0]])
+        return 0.0
+    official = OFFICIAL_RTOL * G
+    tiny = np.finfo(np.float32).tiny
+    worst = float(np.max(err / np.maximum(G, tiny))) if err.size else 0.0
+    assert (err <= official + tiny).all(), "%s: official tolerance exceeded, max err/G = %g" % (what, worst)
+    tight = 4.0 * math.sqrt(max(K, 1)) * 2.0 ** -24 * G + 2.0 ** -22 * np.abs(ref) + tiny
+    assert (err <= tight).all(), "%s: tight tolerance exceeded, max err/G = %g" % (what, worst)
+    return worst
+
+
+def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alpha=1.0, beta=1.0, with_c=True,
+                  bias_dim=None, act=fg.FG_ACT_NONE, ints=False, pad=0, config=1, samples: Optional[int] = None,
+                  inplace=False, device="cuda", seed=W.DEFAULT_SEED):
+    """Run fg_gemm on seeded inputs and compare with the oracle.  ``samples`` None: every entry."""
+    A, lda = make_operand(M, K, la, W.stream_id(config, "A"), device, ints, pad, seed)
+    B, ldb = make_operand(K, N, lb, W.stream_id(config, "B"), device, ints, pad, seed)
+    lead, other = (M, N) if ld_layout == fg.FG_COL else (N, M)
+    ldc = lead + (4 if pad else 0)
+    Cbuf = make_f32(ldc * other, W.stream_id(config, "C"), device, ints, seed) if with_c else None
+    bias = None
+    if bias_dim is not None:
+        bias = make_f32(M if bias_dim == 0 else N, W.stream_id(config, "bias"), device, ints, seed)
+    Dbuf = Cbuf if (inplace and with_c) else torch.full((ldc * other,), float("nan"), dtype=torch.float32, device=device)
+    C_host = np16(Cbuf).copy() if with_c else None
+    fg.fg_gemm(M, N, K, alpha, fg.Matrix(A, la, lda), fg.Matrix(B, lb, ldb), beta,
+               fg.Matrix(Cbuf, ld_layout, ldc) if with_c else None, fg.Matrix(Dbuf, ld_layout, ldc),
+               bias=bias, bias_dim=bias_dim or 0, act=act)
+    torch.cuda.synchronize()
+    D_host = np16(Dbuf)
+    # padding of D must be untouched
+    Dm = D_host.reshape(other, ldc)
+    if ldc > lead and not inplace:
+        assert np.isnan(Dm[:, lead:]).all(), "padding of D was written"
+    Dlog = Dm[:, :lead].T if ld_layout == fg.FG_COL else Dm[:, :lead]       # logical M x N view
+    at = None
+    if samples is not None:
+        at = sample_positions(M, N, samples, seed=M * 31 + N * 17 + K)
+    r = O.gemm(M, N, K, alpha, O.Operand(np16(A), la, lda), O.Operand(np16(B), lb, ldb), beta,
+               C_host, None, ld_layout, ldc, bias=np16(bias), bias_dim=bias_dim or 0, act=act, at=at)
+    got = Dlog if at is None else Dlog[at[0], at[1]]
+    what = "gemm M=%d N=%d K=%d A=%d B=%d D=%d alpha=%g beta=%g ints=%s" % (M, N, K, la, lb, ld_layout, alpha, beta, ints)
+    return compare(got, r["D"], r["G"], K, ints, what)

@@ -1,0 +1,78 @@
+"""GPU parity tests of fg_gemm against the CPU oracle (run with -m gpu on an MI355X)."""
+import itertools
+
+import pytest
+import torch
+
+from paper_2009_12263_amd import binding as fg
+from tests.parity import run_gemm_case
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = [fg.FG_COL, fg.FG_ROW]
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def test_config1_256_cube_colmajor():
+    """BASELINE config 1: D = A.B + C, 256^3, A, B column-major, alpha = beta = 1; every entry."""
+    say("256^3 NN floats"); run_gemm_case(256, 256, 256, config=1)
+    say("256^3 NN ints"); run_gemm_case(256, 256, 256, config=1, ints=True)
+
+
+@pytest.mark.parametrize("la,lb", list(itertools.product(LAYOUTS, LAYOUTS)))
+def test_index_mapping_is_bit_exact_all_layouts(la, lb):
+    """Integer-valued inputs: the result is unique, so every entry must match bit for bit.
+    Sizes span several block tiles of every tile shape and use padded leading dimensions."""
+    for (M, N, K) in [(64, 64, 64), (128, 192, 256), (512, 256, 128), (768, 1280, 320)]:
+        say("ints M=%d N=%d K=%d la=%d lb=%d" % (M, N, K, la, lb))
+        run_gemm_case(M, N, K, la, lb, ints=True, pad=8, config=2)
+
+
+@pytest.mark.parametrize("la,lb", list(itertools.product(LAYOUTS, LAYOUTS)))
+def test_float_parity_1024_all_layouts(la, lb):
+    say("1024^3 la=%d lb=%d" % (la, lb))
+    run_gemm_case(1024, 1024, 1024, la, lb, config=2)
+
+
+@pytest.mark.parametrize("ldl", LAYOUTS)
+def test_row_major_output_alpha_beta_inplace(ldl):
+    say("D layout %d alpha=-1.5 beta=0.25 in place" % ldl)
+    run_gemm_case(384, 256, 192, fg.FG_COL, fg.FG_ROW, ldl, alpha=-1.5, beta=0.25, pad=8, inplace=True, config=2)
+    say("D layout %d ints" % ldl)
+    run_gemm_case(256, 384, 128, fg.FG_ROW, fg.FG_ROW, ldl, alpha=2.0, beta=-1.0, ints=True, config=2)
+
+
+@pytest.mark.parametrize("bias_dim", [0, 1])
+@pytest.mark.parametrize("ldl", LAYOUTS)
+def test_bias_and_relu_epilogue(bias_dim, ldl):
+    say("bias_dim=%d D layout=%d relu" % (bias_dim, ldl))
+    run_gemm_case(256, 320, 128, ld_layout=ldl, with_c=False, bias_dim=bias_dim, act=fg.FG_ACT_RELU, config=3)
+    run_gemm_case(256, 320, 128, ld_layout=ldl, with_c=False, bias_dim=bias_dim, act=fg.FG_ACT_RELU, ints=True, config=3)
+    run_gemm_case(128, 128, 64, ld_layout=ldl, with_c=True, beta=0.5, bias_dim=bias_dim, act=fg.FG_ACT_NONE, config=3)
+
+
+def test_k_zero_and_empty():
+    # K = 0: D = beta*C; M = 0: nothing happens
+    say("K=0"); run_gemm_case(128, 128, 0, beta=2.0, ints=True, config=1)
+    A = torch.zeros(64, dtype=torch.float16, device="cuda"); D = torch.zeros(64, dtype=torch.float32, device="cuda")
+    assert fg.fg_gemm(0, 64, 64, 1.0, fg.Matrix(A, fg.FG_COL, 8), fg.Matrix(A, fg.FG_COL, 64), 0.0, None, fg.Matrix(D, fg.FG_COL, 8)) == fg.FG_OK
+
+
+@pytest.mark.parametrize("la,lb", list(itertools.product(LAYOUTS, LAYOUTS)))
+def test_full_size_8192_sampled(la, lb):
+    """BASELINE config 2 at its headline size, in the launch configuration bench.py times:
+    sampled entries (each an exact K-long FP64 dot product in the oracle) incl. every tile seam."""
+    say("8192^3 la=%d lb=%d sampled" % (la, lb))
+    run_gemm_case(8192, 8192, 8192, la, lb, config=2, samples=4096)
+
+
+def test_full_size_4096_ints_sampled():
+    say("4096^3 ints sampled"); run_gemm_case(4096, 4096, 4096, ints=True, config=2, samples=8192)
+
+
+def test_config3_relu_bias_shapes():
+    say("config 3: 4096^3 relu+bias"); run_gemm_case(4096, 4096, 4096, with_c=False, bias_dim=0, act=fg.FG_ACT_RELU, config=3, samples=4096)
+    say("config 3: 8192x1024x4096 relu+bias"); run_gemm_case(8192, 1024, 4096, with_c=False, bias_dim=0, act=fg.FG_ACT_RELU, config=3, samples=4096)
