@@ -70,21 +70,28 @@ int choose_tile(int64_t M, int64_t N) {
 fg_status launch(const fg::KernelEntry &k, const fg::GemmParams &p, hipStream_t stream) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return fail(FG_ERR_LAUNCH, "no HIP device is current");
-    // Raise the dynamic LDS limit once per (kernel, device).
+    // Once per (kernel, device): raise the dynamic LDS limit and ask how many workgroups of this
+    // kernel fit on a compute unit.
+    int per_cu = 0;
     {
         static std::mutex m;
-        static struct { const void *fn; int dev; } done[256];
+        static struct { const void *fn; int dev; int per_cu; } done[256];
         static int n_done = 0;
         std::lock_guard<std::mutex> lock(m);
-        bool found = false;
-        for (int i = 0; i < n_done; ++i) found |= (done[i].fn == (const void *)k.fn && done[i].dev == dev);
-        if (!found) {
+        for (int i = 0; i < n_done; ++i)
+            if (done[i].fn == (const void *)k.fn && done[i].dev == dev) per_cu = done[i].per_cu;
+        if (per_cu == 0) {
             hipError_t e = hipFuncSetAttribute((const void *)k.fn, hipFuncAttributeMaxDynamicSharedMemorySize, k.lds_bytes);
             if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "hipFuncSetAttribute(%s): %s", k.name, hipGetErrorString(e));
-            if (n_done < 256) { done[n_done].fn = (const void *)k.fn; done[n_done].dev = dev; ++n_done; }
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)k.fn, k.threads, (size_t)k.lds_bytes);
+            if (e != hipSuccess || per_cu < 1) return fail(FG_ERR_LAUNCH, "occupancy query for %s failed: %s", k.name, hipGetErrorString(e));
+            if (n_done < 256) { done[n_done].fn = (const void *)k.fn; done[n_done].dev = dev; done[n_done].per_cu = per_cu; ++n_done; }
         }
     }
-    dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block((unsigned)k.threads);
+    // Persistent workgroups: as many as the GPU holds at once; each walks tiles b, b + grid, ...
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int resident = per_cu * kNumCU;
+    dim3 grid((unsigned)(ntiles < resident ? ntiles : resident)), block((unsigned)k.threads);
     hipLaunchKernelGGL(k.fn, grid, block, (size_t)k.lds_bytes, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "launch of %s failed: %s", k.name, hipGetErrorString(e));

@@ -23,6 +23,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace fg {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -62,33 +64,42 @@ struct GemmParams {
 // ---- tile configuration ---------------------------------------------------------------------
 // BM x BN x BK block tile, WGM x WGN waves, each wave owns a (32*TI) x (32*TJ) sub-tile made of
 // 32x32 MFMA accumulators.  A_KC / B_KC: operand is K-contiguous in memory (A row-major,
-// B column-major) rather than M/N-contiguous.
-template <int BM_, int BN_, int WGM_, int WGN_, bool A_KC_, bool B_KC_, bool STRIDED_, bool CPLX_ = false>
+// B column-major) rather than M/N-contiguous.  STAGES LDS buffers per operand form a ring over K.
+template <int BM_, int BN_, int BK_, int STAGES_, int WGM_, int WGN_, bool A_KC_, bool B_KC_, bool STRIDED_,
+          bool CPLX_ = false>
 struct TileCfg {
-    static constexpr int BM = BM_, BN = BN_, BK = 64;
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_;
+    static constexpr int KSTEPS = BK / 16;                          // MFMA k-slices per tile
     static constexpr int WGM = WGM_, WGN = WGN_;
     static constexpr int NWAVES = WGM * WGN, NTHREADS = 64 * NWAVES;
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;
     static constexpr int TI = WTM / 32, TJ = WTN / 32;
     static constexpr bool A_KC = A_KC_, B_KC = B_KC_, STRIDED = STRIDED_, CPLX = CPLX_;
-    static constexpr int PLANES = CPLX ? 2 : 1;
     static constexpr int A_TILE_BYTES = BM * BK * 2, B_TILE_BYTES = BN * BK * 2;
     static constexpr int A_SLABS = A_TILE_BYTES / 1024 / NWAVES;   // 1 KB direct-to-LDS writes per wave
     static constexpr int B_SLABS = B_TILE_BYTES / 1024 / NWAVES;
-    static constexpr int STAGES = 2;
-    // LDS map: [A plane0 stage0 | A plane0 stage1 | (A plane1 ...) | B ...]
-    static constexpr int A_BYTES = A_TILE_BYTES * STAGES * PLANES;
-    static constexpr int LDS_BYTES = A_BYTES + B_TILE_BYTES * STAGES * PLANES;
+    static constexpr int LOADS_PER_TILE = A_SLABS + B_SLABS;       // per wave and K step
+    // LDS map: [A stage 0 .. A stage S-1 | B stage 0 .. B stage S-1]
+    static constexpr int A_BYTES = A_TILE_BYTES * STAGES;
+    static constexpr int LDS_BYTES = A_BYTES + B_TILE_BYTES * STAGES;
+    static_assert(BK == 32 || BK == 64, "BK must be 32 or 64");
+    static_assert((STAGES & (STAGES - 1)) == 0 && STAGES >= 2, "STAGES must be a power of two");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 accumulators");
     static_assert(A_SLABS >= 1 && B_SLABS >= 1, "tile too small for this many waves");
     static_assert(A_TILE_BYTES % (1024 * NWAVES) == 0 && B_TILE_BYTES % (1024 * NWAVES) == 0, "");
+    static_assert((STAGES - 1) * LOADS_PER_TILE <= 63, "vmcnt is a 6-bit counter");
+    static_assert(LDS_BYTES <= 160 * 1024, "tile ring exceeds the 160 KB LDS of a compute unit");
 };
 
 // ---- swizzles -------------------------------------------------------------------------------
-// K-contiguous tile: rows of 128 bytes (64 halves) = 8 chunks of 16 bytes.  Logical chunk c of
-// row r is stored at chunk position c ^ ((r >> 1) & 7): sixteen consecutive rows reading the
-// same logical chunk then touch sixteen different 16-byte bank groups of the 64-bank LDS.
-__device__ __forceinline__ int kc_swz(int row) { return (row >> 1) & 7; }
+// The LDS has 64 banks of 4 bytes: addresses 256 bytes apart share a bank.
+//
+// K-contiguous tile: rows of BK halves (BK/8 chunks of 16 bytes).  Logical chunk c of row r is
+// stored at chunk position c ^ swz(r), where swz counts 256-byte bank lines: sixteen consecutive
+// rows reading the same logical chunk (one quarter of a ds_read_b128) then touch sixteen
+// different 16-byte bank groups.
+template <int BK>
+__device__ __forceinline__ int kc_swz(int row) { return (row / (128 / BK)) & (BK / 8 - 1); }
 
 // M/N-contiguous tile: k-rows of R halves.  The 64-byte chunk index of a k-row is XORed with
 // (krow & 3) so that the four k-rows one transposing read touches fall into different banks.
@@ -110,15 +121,22 @@ __device__ __forceinline__ u32x4 make_rsrc(const void *p) {
 
 // 64 lanes x 16 bytes from global memory straight into LDS: lane l's 16 bytes land at
 // lds_addr + 16*l.  lds_addr is wave-uniform (it goes to M0).  The load is tracked by vmcnt only;
-// the compiler does not see it, so the caller waits with s_waitcnt vmcnt(0) before the barrier
-// that publishes the tile.  (Written as assembly because the compiler, not knowing which LDS
-// bytes a direct load writes, otherwise drains every outstanding load before any LDS read, which
-// would serialise the prefetch of the next tile with the product of the current one.)
+// the compiler does not see it, so the kernel waits explicitly (wait_tile) before the barrier that
+// publishes a tile.  (Written as assembly because the compiler, not knowing which LDS bytes a
+// direct load writes, otherwise drains every outstanding load before any LDS read, which would
+// serialise the prefetch of later tiles with the product of the current one.)
 __device__ __forceinline__ void load16_to_lds(u32x4 rsrc, uint32_t lds_addr, uint32_t voff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(rsrc)
                  : "memory", "m0");
+}
+
+// Wait until at most NEWER of this wave's direct loads are still in flight (loads complete in
+// order) and until every LDS read this wave issued has returned.
+template <int NEWER>
+__device__ __forceinline__ void wait_tile() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NEWER) : "memory");
 }
 
 __device__ __forceinline__ int64_t group_offset(const ModeGroup &g, int idx) {
@@ -136,10 +154,10 @@ __device__ __forceinline__ int64_t group_offset(const ModeGroup &g, int idx) {
 }
 
 // ---- global -> LDS tile loader ----------------------------------------------------------------
-// One operand tile: R rows (M or N index) x 64 k.  Each wave issues SLABS direct-to-LDS loads per
+// One operand tile: R rows (M or N index) x BK k.  Each wave issues SLABS direct-to-LDS loads per
 // K step; a load writes 1024 consecutive LDS bytes (lane l writes bytes 16*l .. 16*l+15), so the
 // swizzle is applied by choosing which global chunk each lane fetches.
-template <int R, bool KC, int SLABS, int NWAVES, bool STRIDED>
+template <int R, int BK, bool KC, int SLABS, bool STRIDED>
 struct TileLoader {
     uint32_t voff[SLABS];    // per-lane byte offset from the moving base (per slab)
     const char *base;        // uniform: start of this block's panel at the current K step
@@ -152,7 +170,7 @@ struct TileLoader {
         ktile = 0;
         if constexpr (!STRIDED) {
             base = (const char *)(ptr + (int64_t)row0 * rs);
-            kstep_bytes = 64 * ks * 2;
+            kstep_bytes = BK * ks * 2;
         } else {
             base = (const char *)ptr;
             kg = kgrp;
@@ -163,9 +181,11 @@ struct TileLoader {
             int slab = wave * SLABS + s;
             int64_t off;
             if constexpr (KC) {
-                // slab = 8 rows x 8 chunks; lane -> physical (row, chunk); fetch the logical chunk
-                int r = slab * 8 + (lane >> 3);
-                int c = (lane & 7) ^ kc_swz(r);
+                // slab = (512/BK) rows x BK/8 chunks; lane -> physical (row, chunk); fetch the
+                // logical chunk that the swizzle stores there
+                constexpr int CPR = BK / 8;
+                int r = slab * (64 / CPR) + lane / CPR;
+                int c = (lane % CPR) ^ kc_swz<BK>(r);
                 if constexpr (!STRIDED) off = (int64_t)r * rs + c * 8;
                 else off = group_offset(rg, row0 + r) + c * 8;     // leading K mode has stride 1
             } else {
@@ -184,7 +204,7 @@ struct TileLoader {
     // issue the loads of the current K step into the LDS tile at `lds_tile`, then advance
     __device__ __forceinline__ void issue(FG_LDS char *lds_tile, int wave) {
         const char *b = base;
-        if constexpr (STRIDED) b += group_offset(kg, ktile * 64) * 2;
+        if constexpr (STRIDED) b += group_offset(kg, ktile * BK) * 2;
         u32x4 rsrc = make_rsrc(b);
         uint32_t dst = (uint32_t)(uintptr_t)lds_tile + (uint32_t)(wave * SLABS) * 1024u;
 #pragma unroll
@@ -194,26 +214,24 @@ struct TileLoader {
     }
 };
 
-// Wait until every direct-to-LDS load this wave issued has written its bytes.
-__device__ __forceinline__ void wait_direct_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
 // ---- LDS -> register fragment reads -----------------------------------------------------------
 // Fragment of 32 rows x 16 k for v_mfma_f32_32x32x16_f16: lane l holds row l%32, k = 8*(l/32)+0..7.
-template <int R, bool KC, int NT>
+template <int R, int BK, bool KC, int NT>
 struct FragReader {
     // KC: one address per 16-wide k slice (the swizzle mixes the slice index into the chunk);
-    //     sub-tiles are 32 rows = 4096 bytes apart.
+    //     sub-tiles are 32 rows apart.
     // MC: one address per 32-row sub-tile; k slices are 16 k-rows apart, the two halves of a
     //     fragment 4 k-rows apart.
-    uint32_t addr[KC ? 4 : NT];
+    static constexpr int KSTEPS = BK / 16;
+    uint32_t addr[KC ? KSTEPS : NT];
 
     __device__ __forceinline__ void init(int row_base, int lane) {
         if constexpr (KC) {
             int r = row_base + (lane & 31);
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                int c = (2 * ks + (lane >> 5)) ^ kc_swz(r);
-                addr[ks] = r * 128 + c * 16;
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                int c = (2 * ks + (lane >> 5)) ^ kc_swz<BK>(r);
+                addr[ks] = r * (BK * 2) + c * 16;
             }
         } else {
             int g = lane >> 4, i16 = lane & 15;
@@ -229,7 +247,7 @@ struct FragReader {
 
     __device__ __forceinline__ half8 read(FG_LDS const char *tile, int t, int ks) const {
         if constexpr (KC) {
-            return *(FG_LDS const half8 *)(tile + addr[ks] + t * 4096);
+            return *(FG_LDS const half8 *)(tile + addr[ks] + t * (32 * BK * 2));
         } else {
             FG_LDS const char *p = tile + addr[t] + ks * 16 * (R * 2);
             short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FG_LDS short4v *)(p));
@@ -257,104 +275,236 @@ __device__ __forceinline__ void block_to_tile(int bid, int tiles_m, int tiles_n,
     tn = within / rows;
 }
 
+// ---- epilogue fused into the register -> global store -------------------------------------------
+// D = act(alpha*acc + beta*C + bias) (Sections 4.2.3, 4.2.5, 5.3).  Accumulator (i, j), register r
+// of lane l holds D[m][n] with m = 32 i + l % 32 and n = 32 j + 8 (r / 4) + 4 (l / 32) + r % 4: one
+// store instruction writes two runs of 32 consecutive m, i.e. two full 128-byte lines of a
+// column-major D.  The sixteen C values of an accumulator are fetched as one batch of independent
+// loads before any of them is used.
+template <class Cfg, bool HAS_C>
+__device__ __forceinline__ void epilogue(const GemmParams &p, floatx16 (&acc)[Cfg::TI][Cfg::TJ], int m_base, int n_base,
+                                         int lane) {
+    const int lm = lane & 31, lh = lane >> 5;
+    const bool bias_m_on = p.bias && p.bias_dim == 0, bias_n_on = p.bias && p.bias_dim != 0;
+    const float floor_v = p.act == 1 ? 0.f : -__builtin_inff();
+    if constexpr (!Cfg::STRIDED) {
+        // (m, n) at m + n*ld.  All accesses are buffer operations on a descriptor whose base is this
+        // wave's corner of the tile: the per-lane part of the address is one register for all of
+        // them, the rest is a scalar offset.  The C values of accumulator b+1 are requested before
+        // accumulator b is stored, so a batch of loads never queues behind the previous stores.
+        const int voff_c = (lm + 4 * lh * (int)p.ldc) * 4;
+        const int voff_d = (lm + 4 * lh * (int)p.ldd) * 4;
+        const int ldc4 = (int)p.ldc * 4, ldd4 = (int)p.ldd * 4;
+        __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(HAS_C ? p.C + m_base + (int64_t)n_base * p.ldc : p.D), 0, 0x7fffffff, 0x00020000);
+        __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(p.D + m_base + (int64_t)n_base * p.ldd, 0, 0x7fffffff, 0x00020000);
+        constexpr int NB = Cfg::TI * Cfg::TJ;
+        float cv[2][16];
+        auto load_c = [&](int b, float (&dst)[16]) {
+            const int i = b / Cfg::TJ, j = b % Cfg::TJ;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                dst[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                             rc, voff_c, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, 0));
+        };
+        float bias_m[Cfg::TI];
+#pragma unroll
+        for (int i = 0; i < Cfg::TI; ++i) bias_m[i] = bias_m_on ? p.bias[m_base + 32 * i + lm] : 0.f;
+        if constexpr (HAS_C) load_c(0, cv[0]);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int i = b / Cfg::TJ, j = b % Cfg::TJ;
+            if constexpr (HAS_C) {
+                if (b + 1 < NB) load_c(b + 1, cv[(b + 1) & 1]);
+            }
+            float bv[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) bv[r] = bias_m[i];
+            if (bias_n_on) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) bv[r] = p.bias[n_base + 32 * j + 8 * (r >> 2) + 4 * lh + (r & 3)];
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float y = p.alpha * acc[i][j][r] + bv[r];
+                if constexpr (HAS_C) y += p.beta * cv[b & 1][r];
+                y = y > floor_v ? y : floor_v;
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, voff_d,
+                                                      128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, 0);
+            }
+        }
+    } else {
+        // tensor contraction: element offsets are mixed-radix sums over C's row and column modes
+#pragma unroll
+        for (int i = 0; i < Cfg::TI; ++i) {
+            const int m = m_base + 32 * i + lm;
+            const int64_t row_off = group_offset(p.c_m, m);
+#pragma unroll
+            for (int j = 0; j < Cfg::TJ; ++j) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    int64_t off[4];
+                    float cv[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) off[t] = row_off + group_offset(p.c_n, n_base + 32 * j + 8 * q + 4 * lh + t);
+                    if constexpr (HAS_C) {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) cv[t] = p.C[off[t]];
+                    }
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        float y = p.alpha * acc[i][j][4 * q + t];
+                        if constexpr (HAS_C) y += p.beta * cv[t];
+                        p.D[off[t]] = y > floor_v ? y : floor_v;
+                    }
+                }
+            }
+        }
+    }
+}
+
 // ---- the kernel -----------------------------------------------------------------------------------
+// Workgroups are persistent: workgroup b computes tiles b, b + gridDim.x, ... so that the first
+// loads of the next tile are in flight while the current tile is stored.
+//
+// C is not staged through the accumulators (stages 1-2 of Section 3.1): beta*C is added when D
+// is stored, which measured faster here than starting the accumulators from C.
+//
+// K loop, software pipelined at two levels:
+//   * tiles: STAGES LDS buffers; the direct loads of tile kt+STAGES are issued as soon as the
+//     buffer of tile kt is free, so STAGES-1 tiles are in flight or ready ahead of the product;
+//   * fragments: the registers of k-slice s+1 are read from LDS while the MFMAs of slice s run.
+//     The barrier that publishes tile kt+1 (and retires tile kt) sits before the LAST slice of
+//     tile kt, whose fragments are already in registers, so the first reads of tile kt+1 are
+//     covered by that slice's MFMAs instead of stalling the matrix unit.
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p) {
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     FG_LDS char *smem = (FG_LDS char *)smem_generic;
-    constexpr int BM = Cfg::BM, BN = Cfg::BN, TI = Cfg::TI, TJ = Cfg::TJ;
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, TI = Cfg::TI, TJ = Cfg::TJ;
+    constexpr int S = Cfg::STAGES, KS = Cfg::KSTEPS, L = Cfg::LOADS_PER_TILE;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % Cfg::WGM, wn = wave / Cfg::WGM;
-
-    int tm, tn;
-    block_to_tile(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
-    const int m0 = tm * BM, n0 = tn * BN;
-
-    TileLoader<BM, Cfg::A_KC, Cfg::A_SLABS, Cfg::NWAVES, Cfg::STRIDED> la;
-    TileLoader<BN, Cfg::B_KC, Cfg::B_SLABS, Cfg::NWAVES, Cfg::STRIDED> lb;
-    la.init(p.A, m0, wave, lane, p.a_rs, p.a_ks, p.a_m, p.a_k);
-    lb.init(p.B, n0, wave, lane, p.b_rs, p.b_ks, p.b_n, p.b_k);
-
-    FragReader<BM, Cfg::A_KC, TI> fa;
-    FragReader<BN, Cfg::B_KC, TJ> fb;
-    fa.init(wm * Cfg::WTM, lane);
-    fb.init(wn * Cfg::WTN, lane);
-
-    floatx16 acc[TI][TJ];
-#pragma unroll
-    for (int i = 0; i < TI; ++i)
-#pragma unroll
-        for (int j = 0; j < TJ; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int nk = p.K / BK;
 
     FG_LDS char *lds_a = smem;
     FG_LDS char *lds_b = smem + Cfg::A_BYTES;
-    const int nk = p.K / 64;
 
-    if (nk > 0) {
-        la.issue(lds_a, wave);
-        lb.issue(lds_b, wave);
-    }
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        // the loads of step kt (issued one step ago) have landed, for every wave, and every wave
-        // is done reading the other buffer
-        wait_direct_loads();
-        __builtin_amdgcn_s_barrier();
-        if (kt + 1 < nk) {
-            la.issue(lds_a + (cur ^ 1) * Cfg::A_TILE_BYTES, wave);
-            lb.issue(lds_b + (cur ^ 1) * Cfg::B_TILE_BYTES, wave);
-        }
-        FG_LDS const char *ta = lds_a + cur * Cfg::A_TILE_BYTES;
-        FG_LDS const char *tb = lds_b + cur * Cfg::B_TILE_BYTES;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            half8 af[TI], bf[TJ];
-#pragma unroll
-            for (int i = 0; i < TI; ++i) af[i] = fa.read(ta, i, ks);
-#pragma unroll
-            for (int j = 0; j < TJ; ++j) bf[j] = fb.read(tb, j, ks);
-#pragma unroll
-            for (int i = 0; i < TI; ++i)
-#pragma unroll
-                for (int j = 0; j < TJ; ++j)
-                    // MFMA rows <- our N index, MFMA columns <- our M index: lanes of the
-                    // accumulator then run along M, the contiguous direction of D
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[j], af[i], acc[i][j], 0, 0, 0);
-        }
-    }
+    TileLoader<BM, BK, Cfg::A_KC, Cfg::A_SLABS, Cfg::STRIDED> la;
+    TileLoader<BN, BK, Cfg::B_KC, Cfg::B_SLABS, Cfg::STRIDED> lb;
+    FragReader<BM, BK, Cfg::A_KC, TI> fa;
+    FragReader<BN, BK, Cfg::B_KC, TJ> fb;
+    fa.init(wm * Cfg::WTM, lane);
+    fb.init(wn * Cfg::WTN, lane);
 
-    // ---- epilogue fused into the register -> global store ----
-    // Accumulator (i, j), register r of lane l holds D[m][n] with m = 32 i + l % 32 and
-    // n = 32 j + 8 (r / 4) + 4 (l / 32) + r % 4: a store instruction writes two runs of 32
-    // consecutive m, i.e. two full 128-byte lines of a column-major D.
-    const int lm = lane & 31, lh = lane >> 5;
+    // start the loads of a tile: point the loaders at its panels and fill the ring
+    auto start_tile = [&](int tile_id, int &m0, int &n0) {
+        int tm, tn;
+        block_to_tile(tile_id, p.tiles_m, p.tiles_n, tm, tn);
+        m0 = tm * BM;
+        n0 = tn * BN;
+        la.init(p.A, m0, wave, lane, p.a_rs, p.a_ks, p.a_m, p.a_k);
+        lb.init(p.B, n0, wave, lane, p.b_rs, p.b_ks, p.b_n, p.b_k);
 #pragma unroll
-    for (int i = 0; i < TI; ++i) {
-        const int m = m0 + wm * Cfg::WTM + 32 * i + lm;
-        float bias_m = 0.f;
-        if (p.bias && p.bias_dim == 0) bias_m = p.bias[m];
-        int64_t c_row, d_row;
-        if constexpr (Cfg::STRIDED) c_row = d_row = group_offset(p.c_m, m);
-        else { c_row = m; d_row = m; }
-#pragma unroll
-        for (int j = 0; j < TJ; ++j) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int n = n0 + wn * Cfg::WTN + 32 * j + 8 * (r >> 2) + 4 * lh + (r & 3);
-                int64_t c_off, d_off;
-                if constexpr (Cfg::STRIDED) c_off = d_off = c_row + group_offset(p.c_n, n);
-                else { c_off = c_row + (int64_t)n * p.ldc; d_off = d_row + (int64_t)n * p.ldd; }
-                float y = p.alpha * acc[i][j][r];
-                if (p.has_c) y += p.beta * p.C[c_off];
-                if (p.bias) y += (p.bias_dim == 0) ? bias_m : p.bias[n];
-                if (p.act == 1) y = y > 0.f ? y : 0.f;
-                p.D[d_off] = y;
+        for (int s = 0; s < S; ++s)
+            if (s < nk) {
+                la.issue(lds_a + s * Cfg::A_TILE_BYTES, wave);
+                lb.issue(lds_b + s * Cfg::B_TILE_BYTES, wave);
             }
+    };
+
+    int tile = blockIdx.x;
+    if (tile >= ntiles) return;
+    int m0, n0;
+    start_tile(tile, m0, n0);
+
+    while (true) {
+        const int m_base = m0 + wm * Cfg::WTM, n_base = n0 + wn * Cfg::WTN;
+        floatx16 acc[TI][TJ];
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+            for (int j = 0; j < TJ; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        if (nk > 0) {
+            if (nk >= S) wait_tile<(S - 1) * L>(); else wait_tile<0>();
+            __builtin_amdgcn_s_barrier();
+
+            // A fragments are reloaded in place (the registers of sub-tile i are free once its
+            // MFMAs of this slice are issued); B fragments, used by every sub-tile row, are double
+            // buffered.
+            half8 af[TI], bf[2][TJ];
+#pragma unroll
+            for (int i = 0; i < TI; ++i) af[i] = fa.read(lds_a, i, 0);
+#pragma unroll
+            for (int j = 0; j < TJ; ++j) bf[0][j] = fb.read(lds_b, j, 0);
+
+            // one K tile; MORE: another tile follows (publish it, refill the ring, prefetch its
+            // first fragments)
+            auto tile_body = [&](int kt, auto more_tag) {
+                constexpr bool MORE = decltype(more_tag)::value;
+                const int cur = kt & (S - 1);
+                const int nxt = (kt + 1) & (S - 1);
+                FG_LDS const char *ta = lds_a + cur * Cfg::A_TILE_BYTES;
+                FG_LDS const char *tb = lds_b + cur * Cfg::B_TILE_BYTES;
+                FG_LDS const char *na = lds_a + nxt * Cfg::A_TILE_BYTES;
+                FG_LDS const char *nb = lds_b + nxt * Cfg::B_TILE_BYTES;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const int rb = ks & 1, wb = rb ^ 1;     // KS is even: slice 0 always uses buffer 0
+                    const bool last = (ks + 1 == KS);
+                    if (last && MORE) {
+                        // tile kt+1 has landed (for this wave) and all of this wave's reads of tile
+                        // kt have returned; after the barrier both hold for every wave
+                        if (kt + S < nk) wait_tile<(S - 2) * L>(); else wait_tile<0>();
+                        __builtin_amdgcn_s_barrier();
+                        if (kt + S < nk) {
+                            la.issue(lds_a + cur * Cfg::A_TILE_BYTES, wave);
+                            lb.issue(lds_b + cur * Cfg::B_TILE_BYTES, wave);
+                        }
+                    }
+                    if (!last || MORE) {
+#pragma unroll
+                        for (int j = 0; j < TJ; ++j) bf[wb][j] = last ? fb.read(nb, j, 0) : fb.read(tb, j, ks + 1);
+                    }
+#pragma unroll
+                    for (int i = 0; i < TI; ++i) {
+#pragma unroll
+                        for (int j = 0; j < TJ; ++j)
+                            // MFMA rows <- our N index, MFMA columns <- our M index: lanes of the
+                            // accumulator then run along M, the contiguous direction of D
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[rb][j], af[i], acc[i][j], 0, 0, 0);
+                        if (!last || MORE) af[i] = last ? fa.read(na, i, 0) : fa.read(ta, i, ks + 1);
+                    }
+                }
+            };
+            for (int kt = 0; kt + 1 < nk; ++kt) tile_body(kt, std::true_type{});
+            tile_body(nk - 1, std::false_type{});
         }
+
+        // next tile of this workgroup: once every wave has read its last fragments the LDS ring is
+        // free, so its first loads go out before this tile's results are stored
+        const int next = tile + (int)gridDim.x;
+        const bool more_tiles = next < ntiles;
+        int m1 = 0, n1 = 0;
+        if (more_tiles) {
+            wait_tile<0>();
+            __builtin_amdgcn_s_barrier();
+            start_tile(next, m1, n1);
+        }
+
+        if (p.has_c) epilogue<Cfg, true>(p, acc, m_base, n_base, lane);
+        else epilogue<Cfg, false>(p, acc, m_base, n_base, lane);
+
+        if (!more_tiles) break;
+        tile = next;
+        m0 = m1;
+        n0 = n1;
     }
 }
 

@@ -22,21 +22,23 @@ const KernelEntry *kernel_table_tt();   // A K-contiguous, B N-contiguous  (A 'T
 // Entry index inside one table: tile * 2 + strided.
 inline int entry_index(int tile, bool strided) { return tile * 2 + (strided ? 1 : 0); }
 
-#define FG_ENTRY(BM, BN, WGM, WGN, AKC, BKC, STR, NAME)                                            \
-    { gemm_kernel<TileCfg<BM, BN, WGM, WGN, AKC, BKC, STR>>, NAME, BM, BN,                         \
-      TileCfg<BM, BN, WGM, WGN, AKC, BKC, STR>::NTHREADS, TileCfg<BM, BN, WGM, WGN, AKC, BKC, STR>::LDS_BYTES }
+#define FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR) TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR>
+#define FG_ENTRY(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR, NAME)                                    \
+    { gemm_kernel<FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)>, NAME, BM, BN,                  \
+      FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)::NTHREADS,                                   \
+      FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)::LDS_BYTES }
 
 #define FG_DEFINE_TABLE(FUNC, AKC, BKC, TAG)                                                       \
     const KernelEntry *FUNC() {                                                                    \
         static const KernelEntry t[TILE_COUNT * 2] = {                                             \
-            FG_ENTRY(256, 256, 2, 4, AKC, BKC, false, "gemm_" TAG "_256x256x64"),                  \
-            FG_ENTRY(256, 256, 2, 4, AKC, BKC, true, "gett_" TAG "_256x256x64"),                   \
-            FG_ENTRY(256, 128, 4, 2, AKC, BKC, false, "gemm_" TAG "_256x128x64"),                  \
-            FG_ENTRY(256, 128, 4, 2, AKC, BKC, true, "gett_" TAG "_256x128x64"),                   \
-            FG_ENTRY(128, 128, 2, 2, AKC, BKC, false, "gemm_" TAG "_128x128x64"),                  \
-            FG_ENTRY(128, 128, 2, 2, AKC, BKC, true, "gett_" TAG "_128x128x64"),                   \
-            FG_ENTRY(64, 64, 2, 2, AKC, BKC, false, "gemm_" TAG "_64x64x64"),                      \
-            FG_ENTRY(64, 64, 2, 2, AKC, BKC, true, "gett_" TAG "_64x64x64"),                       \
+            FG_ENTRY(256, 256, 64, 2, 2, 4, AKC, BKC, false, "gemm_" TAG "_256x256x64"),                  \
+            FG_ENTRY(256, 256, 64, 2, 2, 4, AKC, BKC, true, "gett_" TAG "_256x256x64"),                   \
+            FG_ENTRY(256, 128, 64, 2, 4, 2, AKC, BKC, false, "gemm_" TAG "_256x128x64"),                  \
+            FG_ENTRY(256, 128, 64, 2, 4, 2, AKC, BKC, true, "gett_" TAG "_256x128x64"),                   \
+            FG_ENTRY(128, 128, 64, 2, 2, 2, AKC, BKC, false, "gemm_" TAG "_128x128x64"),                  \
+            FG_ENTRY(128, 128, 64, 2, 2, 2, AKC, BKC, true, "gett_" TAG "_128x128x64"),                   \
+            FG_ENTRY(64, 64, 64, 2, 2, 2, AKC, BKC, false, "gemm_" TAG "_64x64x64"),                      \
+            FG_ENTRY(64, 64, 64, 2, 2, 2, AKC, BKC, true, "gett_" TAG "_64x64x64"),                       \
         };                                                                                         \
         return t;                                                                                  \
     }
