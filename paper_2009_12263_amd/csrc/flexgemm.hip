@@ -188,6 +188,140 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
     return FG_OK;
 }
 
+
+// ---- tensor contraction -> GEMM description (Section 5.5) -----------------------------------------
+// Modes shared by A and C become GEMM rows (M), modes shared by B and C columns (N), modes
+// shared by A and B the summed index (K).  Inside a merged index the first mode is the fastest
+// (the (ba) -> m convention of the paper's layout listing).  No data moves: the kernel computes
+// element offsets from these groups while it loads tiles and stores results.
+struct Contraction {
+    int64_t M, N, K;
+    const void *A, *B;
+    bool a_kc, b_kc;
+    fg::ModeGroup a_m, a_k, b_n, b_k, c_m, c_n;
+};
+
+struct TensorView { int32_t n; const int32_t *modes; const int64_t *strides; };
+
+int find_mode(const TensorView &t, int32_t label) {
+    for (int i = 0; i < t.n; ++i) if (t.modes[i] == label) return i;
+    return -1;
+}
+
+fg_status plan_contraction(int32_t nA, const int32_t *modesA, const int64_t *stridesA, const void *A,
+                           int32_t nB, const int32_t *modesB, const int64_t *stridesB, const void *B,
+                           int32_t nC, const int32_t *modesC, const int64_t *stridesC, const float *Cin, float *Cout,
+                           int32_t n_modes, const int32_t *labels, const int64_t *extents, Contraction &c) {
+    (void)Cin;
+    if (nA < 0 || nB < 0 || nC < 0 || n_modes < 0) return fail(FG_ERR_SHAPE, "negative mode count");
+    if ((nA && (!modesA || !stridesA)) || (nB && (!modesB || !stridesB)) || (nC && (!modesC || !stridesC)) || (n_modes && (!labels || !extents)))
+        return fail(FG_ERR_NULL, "a mode, stride, label or extent array is NULL");
+    if (nA > 12 || nB > 12 || nC > 12 || n_modes > 24) return fail(FG_ERR_UNSUPPORTED, "too many modes");
+    TensorView ta{nA, modesA, stridesA}, tb{nB, modesB, stridesB}, tc{nC, modesC, stridesC};
+    auto extent_of = [&](int32_t label, int64_t &e) {
+        for (int i = 0; i < n_modes; ++i) if (labels[i] == label) { e = extents[i]; return true; }
+        return false;
+    };
+    for (int i = 0; i < n_modes; ++i) {
+        if (extents[i] < 0) return fail(FG_ERR_SHAPE, "mode %d has a negative extent", labels[i]);
+        for (int j = i + 1; j < n_modes; ++j) if (labels[i] == labels[j]) return fail(FG_ERR_MODES, "mode label %d is listed twice", labels[i]);
+    }
+    const TensorView *views[3] = {&ta, &tb, &tc};
+    const char *names = "ABC";
+    for (int v = 0; v < 3; ++v)
+        for (int i = 0; i < views[v]->n; ++i) {
+            int64_t e;
+            if (!extent_of(views[v]->modes[i], e)) return fail(FG_ERR_MODES, "%c uses mode %d, which has no extent", names[v], views[v]->modes[i]);
+            for (int j = i + 1; j < views[v]->n; ++j)
+                if (views[v]->modes[i] == views[v]->modes[j]) return fail(FG_ERR_MODES, "%c lists mode %d twice (trace modes are not supported)", names[v], views[v]->modes[i]);
+        }
+    // every used label must sit in exactly two tensors
+    bool any_zero = false;
+    for (int i = 0; i < n_modes; ++i) {
+        int cnt = (find_mode(ta, labels[i]) >= 0) + (find_mode(tb, labels[i]) >= 0) + (find_mode(tc, labels[i]) >= 0);
+        if (cnt == 0) continue;
+        if (cnt != 2) return fail(FG_ERR_MODES, "mode %d appears in %d of A, B, C; exactly two are required (no batch or reduction modes)", labels[i], cnt);
+        if (extents[i] == 0) any_zero = true;
+    }
+    c.M = c.N = 0; c.K = 0;
+    if (any_zero) return FG_OK;               // an empty tensor: nothing to compute
+    if (!A || !B || !Cout) return fail(FG_ERR_NULL, "A, B or Cout is NULL");
+    if (!aligned16(A) || !aligned16(B) || !aligned16(Cout) || (Cin && !aligned16(Cin))) return fail(FG_ERR_ALIGN, "tensor base pointers must be 16-byte aligned");
+
+    // Lanes of the result run along GEMM rows, so C's unit-stride mode should be a row mode:
+    // exchange the roles of A and B when it belongs to B.
+    int c_unit = -1;
+    for (int i = 0; i < nC; ++i) { int64_t e; extent_of(modesC[i], e); if (stridesC[i] == 1 && e > 1) { c_unit = modesC[i]; break; } }
+    if (c_unit >= 0 && find_mode(tb, c_unit) >= 0) { TensorView t = ta; ta = tb; tb = t; const void *q = A; A = B; B = q; }
+    c.A = A; c.B = B;
+
+    auto unit_mode = [&](const TensorView &t) {
+        int best = -1;
+        for (int i = 0; i < t.n; ++i) {
+            int64_t e; extent_of(t.modes[i], e);
+            if (t.strides[i] == 1 && e % 8 == 0 && e > 0) { best = t.modes[i]; break; }
+        }
+        return best;
+    };
+    const int ua = unit_mode(ta), ub = unit_mode(tb);
+    if (ua < 0 || ub < 0) return fail(FG_ERR_UNSUPPORTED, "A and B each need a mode with stride 1 and an extent that is a multiple of 8");
+    c.a_kc = find_mode(tb, ua) >= 0;          // A's contiguous mode is summed over
+    c.b_kc = find_mode(ta, ub) >= 0;
+    if (c.a_kc && c.b_kc && ua != ub) return fail(FG_ERR_UNSUPPORTED, "A and B are contiguous along different summed modes (%d and %d)", ua, ub);
+
+    // order of the modes inside each merged index
+    int32_t m_modes[16], n_modes_[16], k_modes[16];
+    int nm = 0, nn = 0, nkk = 0;
+    auto push_unique = [](int32_t *arr, int &n, int32_t label) { for (int i = 0; i < n; ++i) if (arr[i] == label) return; arr[n++] = label; };
+    if (!c.a_kc) push_unique(m_modes, nm, ua);
+    else if (c_unit >= 0 && find_mode(ta, c_unit) >= 0) push_unique(m_modes, nm, c_unit);
+    for (int i = 0; i < tc.n; ++i) if (find_mode(ta, tc.modes[i]) >= 0) push_unique(m_modes, nm, tc.modes[i]);
+    if (!c.b_kc) push_unique(n_modes_, nn, ub);
+    for (int i = 0; i < tc.n; ++i) if (find_mode(tb, tc.modes[i]) >= 0) push_unique(n_modes_, nn, tc.modes[i]);
+    if (c.a_kc) push_unique(k_modes, nkk, ua);
+    else if (c.b_kc) push_unique(k_modes, nkk, ub);
+    for (int i = 0; i < ta.n; ++i) if (find_mode(tb, ta.modes[i]) >= 0) push_unique(k_modes, nkk, ta.modes[i]);
+    if (nm > fg::kMaxGroupModes || nn > fg::kMaxGroupModes || nkk > fg::kMaxGroupModes)
+        return fail(FG_ERR_UNSUPPORTED, "at most %d modes per merged index", fg::kMaxGroupModes);
+    if (nkk == 0) return fail(FG_ERR_UNSUPPORTED, "an outer product (no summed mode) is not supported");
+
+    auto fill = [&](fg::ModeGroup &g, const int32_t *modes, int n, const TensorView &t, int64_t &total) {
+        g.n = n; total = 1;
+        for (int i = 0; i < n; ++i) {
+            int64_t e; extent_of(modes[i], e);
+            g.extent[i] = (int32_t)e;
+            g.stride[i] = t.strides[find_mode(t, modes[i])];
+            total *= e;
+        }
+        for (int i = n; i < fg::kMaxGroupModes; ++i) { g.extent[i] = 1; g.stride[i] = 0; }
+    };
+    int64_t t1, t2;
+    fill(c.a_m, m_modes, nm, ta, c.M); fill(c.c_m, m_modes, nm, tc, t1);
+    fill(c.b_n, n_modes_, nn, tb, c.N); fill(c.c_n, n_modes_, nn, tc, t2);
+    fill(c.a_k, k_modes, nkk, ta, c.K); fill(c.b_k, k_modes, nkk, tb, t1);
+    if (nm == 0) c.M = 1;
+    if (nn == 0) c.N = 1;
+
+    if (c.M % 64 || c.N % 64 || c.K % 64) return fail(FG_ERR_UNSUPPORTED, "merged extents must be multiples of 64 (rows %lld, columns %lld, summed %lld)", (long long)c.M, (long long)c.N, (long long)c.K);
+    if (c.a_k.extent[0] % 64) return fail(FG_ERR_UNSUPPORTED, "the leading summed mode (%d) must have an extent that is a multiple of 64", k_modes[0]);
+    if (c.a_kc && c.a_k.stride[0] != 1) return fail(FG_ERR_UNSUPPORTED, "internal: leading summed mode is not contiguous in A");
+    if (c.b_kc && c.b_k.stride[0] != 1) return fail(FG_ERR_UNSUPPORTED, "leading summed mode %d is contiguous in A but not in B", k_modes[0]);
+    if (!c.a_kc && (c.a_m.stride[0] != 1 || c.a_m.extent[0] % 8)) return fail(FG_ERR_UNSUPPORTED, "A's contiguous row mode must have an extent that is a multiple of 8");
+    if (!c.b_kc && (c.b_n.stride[0] != 1 || c.b_n.extent[0] % 8)) return fail(FG_ERR_UNSUPPORTED, "B's contiguous column mode must have an extent that is a multiple of 8");
+    // the kernel addresses A and B with 32-bit byte offsets inside a 2 GiB window
+    auto span = [&](const TensorView &t) {
+        int64_t sp = 1;
+        for (int i = 0; i < t.n; ++i) { int64_t e; extent_of(t.modes[i], e); int64_t st = t.strides[i] < 0 ? -t.strides[i] : t.strides[i]; sp += (e - 1) * st; }
+        return sp;
+    };
+    for (int i = 0; i < ta.n; ++i) if (ta.strides[i] < 0) return fail(FG_ERR_UNSUPPORTED, "negative strides are not supported");
+    for (int i = 0; i < tb.n; ++i) if (tb.strides[i] < 0) return fail(FG_ERR_UNSUPPORTED, "negative strides are not supported");
+    for (int i = 0; i < tc.n; ++i) if (tc.strides[i] < 0) return fail(FG_ERR_UNSUPPORTED, "negative strides are not supported");
+    if (span(ta) * 2 >= (1ll << 31) || span(tb) * 2 >= (1ll << 31)) return fail(FG_ERR_UNSUPPORTED, "A and B must each span less than 2 GiB");
+    if (c.M > (1 << 30) || c.N > (1 << 30) || c.K > (1 << 30)) return fail(FG_ERR_UNSUPPORTED, "merged extents above 2^30 are not supported");
+    return FG_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -243,10 +377,24 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
                       int32_t nC, const int32_t *modesC, const int64_t *stridesC, const float *Cin, float *Cout,
                       int32_t n_modes, const int32_t *mode_labels, const int64_t *mode_extents,
                       float alpha, float beta, void *hip_stream) {
-    (void)nA; (void)modesA; (void)stridesA; (void)A; (void)nB; (void)modesB; (void)stridesB; (void)B;
-    (void)nC; (void)modesC; (void)stridesC; (void)Cin; (void)Cout; (void)n_modes; (void)mode_labels;
-    (void)mode_extents; (void)alpha; (void)beta; (void)hip_stream;
-    return fail(FG_ERR_UNSUPPORTED, "fg_contract is not implemented yet");
+    Contraction c;
+    if (fg_status st = plan_contraction(nA, modesA, stridesA, A, nB, modesB, stridesB, B, nC, modesC, stridesC,
+                                        Cin, Cout, n_modes, mode_labels, mode_extents, c))
+        return st;
+    if (c.M == 0 || c.N == 0) return FG_OK;
+    const int tile = choose_tile(c.M, c.N);
+    if (tile < 0) return fail(FG_ERR_UNSUPPORTED, "no block tile divides the merged extents M=%lld, N=%lld", (long long)c.M, (long long)c.N);
+    const fg::KernelEntry &k = table_for(c.a_kc, c.b_kc)[fg::entry_index(tile, true)];
+    fg::GemmParams p;
+    memset(&p, 0, sizeof p);
+    p.M = (int32_t)c.M; p.N = (int32_t)c.N; p.K = (int32_t)c.K;
+    p.tiles_m = (int32_t)(c.M / k.bm); p.tiles_n = (int32_t)(c.N / k.bn);
+    p.A = (const _Float16 *)c.A; p.B = (const _Float16 *)c.B;
+    p.C = Cin; p.D = Cout;
+    p.has_c = (Cin != nullptr);
+    p.alpha = alpha; p.beta = Cin ? beta : 0.f;
+    p.a_m = c.a_m; p.a_k = c.a_k; p.b_n = c.b_n; p.b_k = c.b_k; p.c_m = c.c_m; p.c_n = c.c_n;
+    return launch(k, p, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

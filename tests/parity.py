@@ -111,3 +111,48 @@ def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alph
     got = Dlog if at is None else Dlog[at[0], at[1]]
     what = "gemm M=%d N=%d K=%d A=%d B=%d D=%d alpha=%g beta=%g ints=%s" % (M, N, K, la, lb, ld_layout, alpha, beta, ints)
     return compare(got, r["D"], r["G"], K, ints, what)
+
+
+def run_contract_case(extents, modesA, modesB, modesC, alpha=1.0, beta=0.0, ints=False, samples: Optional[int] = None,
+                      stridesA=None, stridesB=None, stridesC=None, inplace=False, config=5, device="cuda",
+                      seed=W.DEFAULT_SEED, B_override=None):
+    """Run fg_contract on seeded dense (or explicitly strided) tensors and compare with the oracle."""
+    ext = lambda ms: [extents[m] for m in ms]
+    sA = list(stridesA) if stridesA else list(W.col_major_strides(tuple(ext(modesA))))
+    sB = list(stridesB) if stridesB else list(W.col_major_strides(tuple(ext(modesB))))
+    sC = list(stridesC) if stridesC else list(W.col_major_strides(tuple(ext(modesC))))
+    span = lambda ms, st: 1 + sum((extents[m] - 1) * s for m, s in zip(ms, st))
+    gen = W.small_ints if ints else W.uniform_pm1
+    A = gen(span(modesA, sA), W.stream_id(config, "A"), seed=seed, device=device, dtype=torch.float16)
+    B = gen(span(modesB, sB), W.stream_id(config, "B"), seed=seed, device=device, dtype=torch.float16)
+    if B_override is not None:
+        B = B_override.to(device)
+    nC = span(modesC, sC)
+    Cin = gen(nC, W.stream_id(config, "C"), seed=seed, device=device, dtype=torch.float32) if beta != 0.0 else None
+    Cout = Cin if (inplace and Cin is not None) else torch.full((nC,), float("nan"), dtype=torch.float32, device=device)
+    Cin_host = np16(Cin).copy() if Cin is not None else None
+    fg.fg_contract(modesA, sA, A, modesB, sB, B, modesC, sC, Cin, Cout, extents, alpha=alpha, beta=beta)
+    torch.cuda.synchronize()
+    got_all = np16(Cout)
+    K = 1
+    for m in modesA:
+        if m in modesB:
+            K *= extents[m]
+    what = "contract A%s B%s -> C%s extents=%s ints=%s" % (modesA, modesB, modesC, extents, ints)
+    if samples is None:
+        r = O.contract(extents, modesA, sA, np16(A), modesB, sB, np16(B), modesC, sC, Cin_host, alpha=alpha, beta=beta)
+        # compare only the positions the tensor reaches (others must stay untouched)
+        idx = np.zeros(1, np.int64)
+        for m, s in zip(modesC, sC):
+            idx = (idx[:, None] + np.arange(extents[m], dtype=np.int64)[None, :] * s).reshape(-1)
+        reached = np.zeros(nC, bool); reached[idx] = True
+        if not inplace:
+            assert np.isnan(got_all[~reached]).all(), what + ": wrote outside the tensor"
+        return compare(got_all[idx], r["D"][idx], r["G"][idx], K, ints, what)
+    rng = np.random.default_rng(12345)
+    at = np.stack([rng.integers(0, extents[m], samples) for m in modesC], axis=1)
+    corners = np.array([[0] * len(modesC), [extents[m] - 1 for m in modesC]])
+    at = np.concatenate([at, corners], axis=0)
+    r = O.contract(extents, modesA, sA, np16(A), modesB, sB, np16(B), modesC, sC, Cin_host, alpha=alpha, beta=beta, at=at)
+    off = (at * np.array(sC, np.int64)[None, :]).sum(axis=1)
+    return compare(got_all[off], r["D"], r["G"], K, ints, what)

@@ -1,0 +1,113 @@
+"""CPU-only tests of the C ABI: the library loads, exports every declared symbol, and rejects
+bad descriptions with the documented status codes before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2009_12263_amd import binding as fg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "flexgemm.h")).read()
+    declared = set(re.findall(r"\b(fg_[a-z_]+)\s*\(", header))
+    assert declared == set(fg.EXPORTS)
+    lib = fg.load_library()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert fg.fg_version() >= 100
+
+
+class FakeTensor:
+    """Stands in for a device tensor: the library only looks at the pointer value before launch."""
+    def __init__(self, ptr, dtype):
+        self._p, self.dtype = ptr, dtype
+
+    def data_ptr(self):
+        return self._p
+
+
+def mats(M=256, N=256, K=256, la=fg.FG_COL, lb=fg.FG_COL, ld=fg.FG_COL, lda=None, ldb=None, ldd=None, pa=0x1000, pb=0x2000, pd=0x3000):
+    import torch
+    A = fg.Matrix(FakeTensor(pa, torch.float16), la, lda if lda is not None else (M if la == fg.FG_COL else K))
+    B = fg.Matrix(FakeTensor(pb, torch.float16), lb, ldb if ldb is not None else (K if lb == fg.FG_COL else N))
+    D = fg.Matrix(FakeTensor(pd, torch.float32), ld, ldd if ldd is not None else (M if ld == fg.FG_COL else N))
+    return A, B, D
+
+
+def status(*args, **kw):
+    return fg.fg_gemm(*args, raise_on_error=False, **kw)
+
+
+def test_gemm_argument_errors():
+    A, B, D = mats()
+    assert status(256, 256, 256, 1.0, None, B, 0.0, None, D) == fg.FG_ERR_NULL
+    assert status(256, 256, 256, 1.0, A, B, 0.0, None, None) == fg.FG_ERR_NULL
+    assert status(-1, 256, 256, 1.0, A, B, 0.0, None, D) == fg.FG_ERR_SHAPE
+    assert status(250, 256, 256, 1.0, A, B, 0.0, None, D) == fg.FG_ERR_UNSUPPORTED
+    assert "multiples of 64" in fg.fg_last_error()
+    A2, B2, D2 = mats(lda=128)
+    assert status(256, 256, 256, 1.0, A2, B2, 0.0, None, D2) == fg.FG_ERR_SHAPE
+    A3, B3, D3 = mats(lda=260)
+    assert status(256, 256, 256, 1.0, A3, B3, 0.0, None, D3) == fg.FG_ERR_ALIGN
+    A4, B4, D4 = mats(pa=0x1008)
+    assert status(256, 256, 256, 1.0, A4, B4, 0.0, None, D4) == fg.FG_ERR_ALIGN
+    A5, B5, D5 = mats()
+    A5.layout = 7
+    assert status(256, 256, 256, 1.0, A5, B5, 0.0, None, D5) == fg.FG_ERR_LAYOUT
+    A6, B6, D6 = mats()
+    A6.dtype = fg.FG_F32
+    assert status(256, 256, 256, 1.0, A6, B6, 0.0, None, D6) == fg.FG_ERR_LAYOUT
+    A7, B7, D7 = mats()
+    C7 = fg.Matrix(D7.re, fg.FG_ROW, 256)
+    assert status(256, 256, 256, 1.0, A7, B7, 1.0, C7, D7) == fg.FG_ERR_LAYOUT      # C and D layouts differ
+    import torch
+    assert status(256, 256, 256, 1.0, A, B, 0.0, None, D, bias=FakeTensor(0x5000, torch.float32), bias_dim=3) == fg.FG_ERR_LAYOUT
+    assert status(256, 256, 256, 1.0, A, B, 0.0, None, D, act=9) == fg.FG_ERR_LAYOUT
+
+
+def test_empty_problem_is_ok_without_a_gpu():
+    A, B, D = mats(M=0)
+    assert status(0, 256, 256, 1.0, A, B, 0.0, None, D) == fg.FG_OK
+
+
+def test_plan_names_follow_sizes_and_layouts():
+    assert fg.fg_gemm_plan(8192, 8192, 8192) == "gemm_nn_256x256x64"
+    assert fg.fg_gemm_plan(8192, 1024, 4096) == "gemm_nn_256x128x64"
+    assert fg.fg_gemm_plan(2048, 2048, 2048, fg.FG_ROW, fg.FG_COL) == "gemm_tn_128x128x64"
+    assert fg.fg_gemm_plan(256, 256, 256, fg.FG_COL, fg.FG_ROW) == "gemm_nt_64x64x64"
+    # a row-major D is computed as the transposed problem: the operands swap roles
+    assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_ROW, fg.FG_ROW, fg.FG_ROW) == "gemm_nn_256x256x64"
+    with pytest.raises(fg.FlexGemmError):
+        fg.fg_gemm_plan(100, 64, 64)
+
+
+def contract_status(mA, sA, mB, sB, mC, sC, ext, pa=0x1000, pb=0x2000, pc=0x3000):
+    import torch
+    return fg.fg_contract(mA, sA, FakeTensor(pa, torch.float16), mB, sB, FakeTensor(pb, torch.float16), mC, sC, None,
+                          FakeTensor(pc, torch.float32), ext, raise_on_error=False)
+
+
+def test_contract_argument_errors():
+    a, b, c, d = 0, 1, 2, 3
+    ext = {a: 64, b: 64, c: 64, d: 64}
+    dense3 = [1, 64, 4096]
+    # batch mode (in all three tensors)
+    assert contract_status([a, d, c], dense3, [d, b, c], dense3, [a, b, c], dense3, ext) == fg.FG_ERR_MODES
+    # mode without extent
+    assert contract_status([a, d, 9], dense3, [d, b], [1, 64], [a, b, 9], dense3, ext) == fg.FG_ERR_MODES
+    # repeated mode inside one tensor
+    assert contract_status([a, a, d], dense3, [d, b], [1, 64], [a, b], [1, 64], ext) == fg.FG_ERR_MODES
+    # no unit-stride mode in A
+    assert contract_status([a, d, c], [2, 128, 8192], [d, b], [1, 64], [a, b, c], dense3, ext) == fg.FG_ERR_UNSUPPORTED
+    # merged extent not a multiple of 64
+    ext2 = {a: 64, b: 64, c: 64, d: 32}
+    assert contract_status([a, d, c], [1, 64, 2048], [d, b], [1, 32], [a, b, c], dense3, ext2) == fg.FG_ERR_UNSUPPORTED
+    # misaligned base pointer
+    assert contract_status([a, d, c], dense3, [d, b], [1, 64], [a, b, c], dense3, ext, pa=0x1002) == fg.FG_ERR_ALIGN
+    # an empty mode: nothing to do, OK without a GPU
+    ext3 = {a: 64, b: 0, c: 64, d: 64}
+    assert contract_status([a, d, c], dense3, [d, b], [1, 64], [a, b, c], [1, 64, 0], ext3) == fg.FG_OK
