@@ -8,6 +8,7 @@
 #include <atomic>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 
@@ -57,6 +58,11 @@ const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
 int choose_tile(int64_t M, int64_t N) {
     static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64};
     static const int bn[fg::TILE_COUNT] = {256, 128, 128, 64};
+    // tuning aid: FG_FORCE_TILE=0..3 picks a tile shape if it divides the problem
+    if (const char *f = getenv("FG_FORCE_TILE")) {
+        int t = atoi(f);
+        if (t >= 0 && t < fg::TILE_COUNT && M % bm[t] == 0 && N % bn[t] == 0) return t;
+    }
     int last_fit = -1;
     for (int t = 0; t < fg::TILE_COUNT; ++t) {
         if (M % bm[t] || N % bn[t]) continue;
@@ -197,7 +203,7 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
 struct Contraction {
     int64_t M, N, K;
     const void *A, *B;
-    bool a_kc, b_kc;
+    bool a_kc, b_kc, c_fast;
     fg::ModeGroup a_m, a_k, b_n, b_k, c_m, c_n;
 };
 
@@ -319,6 +325,7 @@ fg_status plan_contraction(int32_t nA, const int32_t *modesA, const int64_t *str
     for (int i = 0; i < tc.n; ++i) if (tc.strides[i] < 0) return fail(FG_ERR_UNSUPPORTED, "negative strides are not supported");
     if (span(ta) * 2 >= (1ll << 31) || span(tb) * 2 >= (1ll << 31)) return fail(FG_ERR_UNSUPPORTED, "A and B must each span less than 2 GiB");
     if (c.M > (1 << 30) || c.N > (1 << 30) || c.K > (1 << 30)) return fail(FG_ERR_UNSUPPORTED, "merged extents above 2^30 are not supported");
+    c.c_fast = nn > 0 && c.c_n.extent[0] % 8 == 0 && span(tc) * 4 < (1ll << 31);
     return FG_OK;
 }
 
@@ -393,6 +400,7 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
     p.C = Cin; p.D = Cout;
     p.has_c = (Cin != nullptr);
     p.alpha = alpha; p.beta = Cin ? beta : 0.f;
+    p.c_fast = c.c_fast ? 1 : 0;
     p.a_m = c.a_m; p.a_k = c.a_k; p.b_n = c.b_n; p.b_k = c.b_k; p.c_m = c.c_m; p.c_n = c.c_n;
     return launch(k, p, (hipStream_t)hip_stream);
 }

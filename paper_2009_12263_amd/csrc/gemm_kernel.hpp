@@ -57,6 +57,7 @@ struct GemmParams {
     float alpha, beta;
     int32_t bias_dim, act, has_c;
     int32_t diag_a;                   // A is diagonal: A points at the diagonal entries
+    int32_t c_fast;                   // contraction: C qualifies for the evenly-spaced column store
     // tensor contraction: mode groups of each tensor
     ModeGroup a_m, a_k, b_n, b_k, c_m, c_n;
 };
@@ -333,8 +334,42 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, floatx16 (&acc)[Cf
                                                       128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, 0);
             }
         }
+    } else if (p.c_fast) {
+        // tensor contraction, common case: the leading column mode of C has an extent that is a
+        // multiple of 8, so the 8 columns 8q .. 8q+7 of an accumulator are evenly spaced, and C
+        // spans less than 2 GiB.  Per-lane part of the offset: the row (one mixed-radix sum per
+        // sub-tile row); the column part is wave-uniform.
+        const int s0 = (int)p.c_n.stride[0];
+        __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(HAS_C ? p.C : p.D), 0, 0x7fffffff, 0x00020000);
+        __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(p.D, 0, 0x7fffffff, 0x00020000);
+        int col4[Cfg::TJ][4];
+#pragma unroll
+        for (int j = 0; j < Cfg::TJ; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) col4[j][q] = (int)group_offset(p.c_n, n_base + 32 * j + 8 * q) * 4;
+#pragma unroll
+        for (int i = 0; i < Cfg::TI; ++i) {
+            const int voff = ((int)group_offset(p.c_m, m_base + 32 * i + lm) + 4 * lh * s0) * 4;
+#pragma unroll
+            for (int j = 0; j < Cfg::TJ; ++j) {
+                float cv[16];
+                if constexpr (HAS_C) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        cv[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, voff, col4[j][r >> 2] + (r & 3) * s0 * 4, 0));
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float y = p.alpha * acc[i][j][r];
+                    if constexpr (HAS_C) y += p.beta * cv[r];
+                    y = y > floor_v ? y : floor_v;
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, voff, col4[j][r >> 2] + (r & 3) * s0 * 4, 0);
+                }
+            }
+        }
     } else {
-        // tensor contraction: element offsets are mixed-radix sums over C's row and column modes
+        // tensor contraction, general case: element offsets are mixed-radix sums over C's row and
+        // column modes
 #pragma unroll
         for (int i = 0; i < Cfg::TI; ++i) {
             const int m = m_base + 32 * i + lm;
