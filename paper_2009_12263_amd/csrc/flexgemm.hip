@@ -73,6 +73,33 @@ int choose_tile(int64_t M, int64_t N) {
 }
 
 
+// Kernel variant for a normalised problem (nullptr: no tile divides it).
+int choose_ctile(int64_t M, int64_t N) {
+    static const int bm[fg::CTILE_COUNT] = {256, 128, 64};
+    static const int bn[fg::CTILE_COUNT] = {128, 128, 64};
+    int last_fit = -1;
+    for (int t = 0; t < fg::CTILE_COUNT; ++t) {
+        if (M % bm[t] || N % bn[t]) continue;
+        last_fit = t;
+        if ((M / bm[t]) * (N / bn[t]) >= kNumCU) return t;
+    }
+    return last_fit;
+}
+
+const fg::KernelEntry *select_kernel(const Problem &q) {
+    if (q.cplx) {
+        const int t = choose_ctile(q.M, q.N);
+        if (t < 0) return nullptr;
+        const int v = (q.a_kc ? 2 : 0) + (q.b_kc ? 0 : 1);     // nn, nt, tn, tt
+        return &fg::kernel_table_cplx()[t * 4 + v];
+    }
+    const int tile = choose_tile(q.M, q.N);
+    if (tile < 0) return nullptr;
+    if (q.a_diag) return &fg::kernel_table_diag()[tile * 4 + (q.b_kc ? 0 : 1)];
+    if (q.b_diag) return &fg::kernel_table_diag()[tile * 4 + (q.a_kc ? 2 : 3)];
+    return &table_for(q.a_kc, q.b_kc)[fg::entry_index(tile, false)];
+}
+
 fg_status launch(const fg::KernelEntry &k, const fg::GemmParams &p, hipStream_t stream) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return fail(FG_ERR_LAUNCH, "no HIP device is current");
@@ -166,6 +193,8 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
         if (ep->bias && !aligned16(ep->bias)) return fail(FG_ERR_ALIGN, "bias must be 16-byte aligned");
     }
     if (cplx && has_ep) return fail(FG_ERR_UNSUPPORTED, "bias and activation are not defined for complex products");
+    if (cplx && (!A->im || !B->im)) return fail(FG_ERR_UNSUPPORTED, "complex products need the imaginary plane of both A and B");
+    if (cplx && (A->layout == FG_DIAG || B->layout == FG_DIAG)) return fail(FG_ERR_UNSUPPORTED, "complex diagonal operands are not supported");
 
     const bool swap = (D->layout == FG_ROW);
     q.cplx = cplx;
@@ -191,6 +220,8 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
         q.B = A->re; q.B_im = A->im; q.ldb = A->ld; q.b_diag = A->layout == FG_DIAG; q.b_kc = (A->layout == FG_ROW);
         q.bias_dim = 1 - q.bias_dim;
     }
+    if (q.a_diag) q.a_kc = true;     // a diagonal operand is synthesised K-contiguous in LDS
+    if (q.b_diag) q.b_kc = true;
     return FG_OK;
 }
 
@@ -342,21 +373,19 @@ fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix 
     Problem q;
     if (fg_status st = normalise(M, N, K, alpha, A, B, beta, C, D, ep, q)) return st;
     if (q.M == 0 || q.N == 0) return FG_OK;
-    if (q.cplx) return fail(FG_ERR_UNSUPPORTED, "complex products are not implemented yet");
-    if (q.a_diag || q.b_diag) return fail(FG_ERR_UNSUPPORTED, "diagonal operands are not implemented yet");
-
-    const int tile = choose_tile(q.M, q.N);
-    if (tile < 0) return fail(FG_ERR_UNSUPPORTED, "no block tile divides M=%lld, N=%lld", (long long)q.M, (long long)q.N);
-    const fg::KernelEntry &k = table_for(q.a_kc, q.b_kc)[fg::entry_index(tile, false)];
+    const fg::KernelEntry *kp = select_kernel(q);
+    if (!kp) return fail(FG_ERR_UNSUPPORTED, "no block tile divides M=%lld, N=%lld", (long long)q.M, (long long)q.N);
+    const fg::KernelEntry &k = *kp;
 
     fg::GemmParams p;
     memset(&p, 0, sizeof p);
     p.M = (int32_t)q.M; p.N = (int32_t)q.N; p.K = (int32_t)q.K;
     p.tiles_m = (int32_t)(q.M / k.bm); p.tiles_n = (int32_t)(q.N / k.bn);
     p.A = (const _Float16 *)q.A; p.B = (const _Float16 *)q.B;
+    p.A_im = (const _Float16 *)q.A_im; p.B_im = (const _Float16 *)q.B_im;
     p.a_rs = q.a_kc ? q.lda : 1; p.a_ks = q.a_kc ? 1 : q.lda;
     p.b_rs = q.b_kc ? q.ldb : 1; p.b_ks = q.b_kc ? 1 : q.ldb;
-    p.C = q.C; p.D = q.D; p.ldc = q.ldc; p.ldd = q.ldd;
+    p.C = q.C; p.D = q.D; p.C_im = q.C_im; p.D_im = q.D_im; p.ldc = q.ldc; p.ldd = q.ldd;
     p.bias = q.bias; p.bias_dim = q.bias_dim; p.act = q.act; p.has_c = q.C != nullptr;
     p.alpha = q.alpha; p.beta = q.beta;
     return launch(k, p, (hipStream_t)hip_stream);
@@ -367,15 +396,26 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
     if (!buf || buf_len <= 0) return fail(FG_ERR_NULL, "buf is NULL or empty");
     buf[0] = 0;
     if (fg_status st = check_sizes(M, N, K)) return st;
-    if ((layoutA != FG_COL && layoutA != FG_ROW) || (layoutB != FG_COL && layoutB != FG_ROW) || (layoutD != FG_COL && layoutD != FG_ROW))
-        return fail(FG_ERR_LAYOUT, "plan query takes FG_COL / FG_ROW layouts");
-    if (is_complex) return fail(FG_ERR_UNSUPPORTED, "complex products are not implemented yet");
-    bool a_kc = layoutA == FG_ROW, b_kc = layoutB == FG_COL;
-    int64_t m = M, n = N;
-    if (layoutD == FG_ROW) { bool t = a_kc; a_kc = b_kc; b_kc = t; m = N; n = M; }
-    const int tile = choose_tile(m, n);
-    if (tile < 0) return fail(FG_ERR_UNSUPPORTED, "no block tile divides the problem");
-    snprintf(buf, (size_t)buf_len, "%s", table_for(a_kc, b_kc)[fg::entry_index(tile, false)].name);
+    auto ok_in = [](int32_t l) { return l == FG_COL || l == FG_ROW || l == FG_DIAG; };
+    if (!ok_in(layoutA) || !ok_in(layoutB) || (layoutD != FG_COL && layoutD != FG_ROW))
+        return fail(FG_ERR_LAYOUT, "plan query: A, B take FG_COL / FG_ROW / FG_DIAG, D takes FG_COL / FG_ROW");
+    if (layoutA == FG_DIAG && layoutB == FG_DIAG) return fail(FG_ERR_UNSUPPORTED, "at most one of A and B may be diagonal");
+    if (is_complex && (layoutA == FG_DIAG || layoutB == FG_DIAG)) return fail(FG_ERR_UNSUPPORTED, "complex diagonal operands are not supported");
+    Problem q;
+    memset(&q, 0, sizeof q);
+    q.cplx = is_complex != 0;
+    if (layoutD == FG_COL) {
+        q.M = M; q.N = N;
+        q.a_diag = layoutA == FG_DIAG; q.b_diag = layoutB == FG_DIAG;
+        q.a_kc = layoutA == FG_ROW || q.a_diag; q.b_kc = layoutB == FG_COL || q.b_diag;
+    } else {
+        q.M = N; q.N = M;
+        q.a_diag = layoutB == FG_DIAG; q.b_diag = layoutA == FG_DIAG;
+        q.a_kc = layoutB == FG_COL || q.a_diag; q.b_kc = layoutA == FG_ROW || q.b_diag;
+    }
+    const fg::KernelEntry *k = select_kernel(q);
+    if (!k) return fail(FG_ERR_UNSUPPORTED, "no block tile divides the problem");
+    snprintf(buf, (size_t)buf_len, "%s", k->name);
     return FG_OK;
 }
 

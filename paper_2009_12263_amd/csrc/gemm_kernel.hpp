@@ -67,7 +67,7 @@ struct GemmParams {
 // 32x32 MFMA accumulators.  A_KC / B_KC: operand is K-contiguous in memory (A row-major,
 // B column-major) rather than M/N-contiguous.  STAGES LDS buffers per operand form a ring over K.
 template <int BM_, int BN_, int BK_, int STAGES_, int WGM_, int WGN_, bool A_KC_, bool B_KC_, bool STRIDED_,
-          bool CPLX_ = false>
+          int DIAG_ = 0, bool CPLX_ = false>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_;
     static constexpr int KSTEPS = BK / 16;                          // MFMA k-slices per tile
@@ -76,13 +76,17 @@ struct TileCfg {
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;
     static constexpr int TI = WTM / 32, TJ = WTN / 32;
     static constexpr bool A_KC = A_KC_, B_KC = B_KC_, STRIDED = STRIDED_, CPLX = CPLX_;
+    static constexpr int DIAG = DIAG_;                              // 0: none, 1: A diagonal, 2: B diagonal
+    static constexpr int PLANES = CPLX ? 2 : 1;                     // real / (real, imaginary)
     static constexpr int A_TILE_BYTES = BM * BK * 2, B_TILE_BYTES = BN * BK * 2;
     static constexpr int A_SLABS = A_TILE_BYTES / 1024 / NWAVES;   // 1 KB direct-to-LDS writes per wave
     static constexpr int B_SLABS = B_TILE_BYTES / 1024 / NWAVES;
-    static constexpr int LOADS_PER_TILE = A_SLABS + B_SLABS;       // per wave and K step
-    // LDS map: [A stage 0 .. A stage S-1 | B stage 0 .. B stage S-1]
-    static constexpr int A_BYTES = A_TILE_BYTES * STAGES;
-    static constexpr int LDS_BYTES = A_BYTES + B_TILE_BYTES * STAGES;
+    // direct loads per wave and K step (a diagonal operand is synthesised, not loaded)
+    static constexpr int LOADS_PER_TILE = ((DIAG == 1 ? 0 : A_SLABS) + (DIAG == 2 ? 0 : B_SLABS)) * PLANES;
+    // LDS map: [A plane 0: stage 0 .. S-1 | A plane 1 ... | B plane 0: stage 0 .. S-1 | B plane 1 ...]
+    static constexpr int A_PLANE_BYTES = A_TILE_BYTES * STAGES, B_PLANE_BYTES = B_TILE_BYTES * STAGES;
+    static constexpr int A_BYTES = A_PLANE_BYTES * PLANES;
+    static constexpr int LDS_BYTES = A_BYTES + B_PLANE_BYTES * PLANES;
     static_assert(BK == 32 || BK == 64, "BK must be 32 or 64");
     static_assert((STAGES & (STAGES - 1)) == 0 && STAGES >= 2, "STAGES must be a power of two");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 accumulators");
@@ -90,6 +94,10 @@ struct TileCfg {
     static_assert(A_TILE_BYTES % (1024 * NWAVES) == 0 && B_TILE_BYTES % (1024 * NWAVES) == 0, "");
     static_assert((STAGES - 1) * LOADS_PER_TILE <= 63, "vmcnt is a 6-bit counter");
     static_assert(LDS_BYTES <= 160 * 1024, "tile ring exceeds the 160 KB LDS of a compute unit");
+    static_assert(DIAG == 0 || !STRIDED, "diagonal operands are a matrix feature");
+    static_assert(DIAG != 1 || A_KC, "a diagonal A is synthesised K-contiguous");
+    static_assert(DIAG != 2 || B_KC, "a diagonal B is synthesised K-contiguous");
+    static_assert(!(CPLX && (DIAG || STRIDED)), "complex products take plain matrices");
 };
 
 // ---- swizzles -------------------------------------------------------------------------------
@@ -202,6 +210,12 @@ struct TileLoader {
         }
     }
 
+    // start at K tile kt0 instead of 0 (plain matrices only)
+    __device__ __forceinline__ void skip(int kt0) {
+        if constexpr (!STRIDED) base += kstep_bytes * kt0;
+        ktile = kt0;
+    }
+
     // issue the loads of the current K step into the LDS tile at `lds_tile`, then advance
     __device__ __forceinline__ void issue(FG_LDS char *lds_tile, int wave) {
         const char *b = base;
@@ -211,6 +225,45 @@ struct TileLoader {
 #pragma unroll
         for (int s = 0; s < SLABS; ++s) load16_to_lds(rsrc, dst + s * 1024u, voff[s]);
         if constexpr (!STRIDED) base += kstep_bytes;
+        ++ktile;
+    }
+};
+
+// ---- diagonal operand (Section 5.2) ---------------------------------------------------------------
+// The operand is a vector d of diagonal entries: element (r, k) is d[r] if r == k and zero
+// otherwise, and zeros are never read from memory.  The tile is synthesised straight into LDS in
+// the K-contiguous swizzled layout, each lane writing the 16-byte chunk a direct load would have
+// written for it.  (The second half of the paper's optimisation, skipping the inner-loop
+// iterations that hold no diagonal entry, is the K range the kernel picks per tile row.)
+template <int R, int BK, int SLABS>
+struct DiagLoader {
+    _Float16 dval[SLABS];    // d[row] of the chunk this lane writes in each slab
+    int pos0[SLABS];         // row - 8*chunk: position of the diagonal inside the chunk when k0 == 0
+    int ktile;
+
+    __device__ __forceinline__ void init(const _Float16 *d, int row0, int ndiag, int wave, int lane) {
+        ktile = 0;
+        constexpr int CPR = BK / 8;
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+            int slab = wave * SLABS + s;
+            int r = slab * (64 / CPR) + lane / CPR;
+            int c = (lane % CPR) ^ kc_swz<BK>(r);
+            dval[s] = (row0 + r < ndiag) ? d[row0 + r] : (_Float16)0.f;
+            pos0[s] = row0 + r - 8 * c;
+        }
+    }
+    __device__ __forceinline__ void skip(int kt0) { ktile = kt0; }
+    __device__ __forceinline__ void issue(FG_LDS char *lds_tile, int wave) {
+        const int k0 = ktile * BK;
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+            const int pos = pos0[s] - k0;          // the chunk holds k0+8c .. k0+8c+7
+            half8 v;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) v[t] = (t == pos) ? dval[s] : (_Float16)0.f;
+            *(FG_LDS half8 *)(lds_tile + (wave * SLABS + s) * 1024 + (threadIdx.x & 63) * 16) = v;
+        }
         ++ktile;
     }
 };
@@ -283,8 +336,8 @@ __device__ __forceinline__ void block_to_tile(int bid, int tiles_m, int tiles_n,
 // column-major D.  The sixteen C values of an accumulator are fetched as one batch of independent
 // loads before any of them is used.
 template <class Cfg, bool HAS_C>
-__device__ __forceinline__ void epilogue(const GemmParams &p, floatx16 (&acc)[Cfg::TI][Cfg::TJ], int m_base, int n_base,
-                                         int lane) {
+__device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, float *Dp, floatx16 (&acc)[Cfg::TI][Cfg::TJ],
+                                         int m_base, int n_base, int lane) {
     const int lm = lane & 31, lh = lane >> 5;
     const bool bias_m_on = p.bias && p.bias_dim == 0, bias_n_on = p.bias && p.bias_dim != 0;
     const float floor_v = p.act == 1 ? 0.f : -__builtin_inff();
@@ -297,8 +350,8 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, floatx16 (&acc)[Cf
         const int voff_d = (lm + 4 * lh * (int)p.ldd) * 4;
         const int ldc4 = (int)p.ldc * 4, ldd4 = (int)p.ldd * 4;
         __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float *>(HAS_C ? p.C + m_base + (int64_t)n_base * p.ldc : p.D), 0, 0x7fffffff, 0x00020000);
-        __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(p.D + m_base + (int64_t)n_base * p.ldd, 0, 0x7fffffff, 0x00020000);
+            const_cast<float *>(HAS_C ? Cp + m_base + (int64_t)n_base * p.ldc : Dp), 0, 0x7fffffff, 0x00020000);
+        __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(Dp + m_base + (int64_t)n_base * p.ldd, 0, 0x7fffffff, 0x00020000);
         constexpr int NB = Cfg::TI * Cfg::TJ;
         float cv[2][16];
         auto load_c = [&](int b, float (&dst)[16]) {
@@ -340,8 +393,8 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, floatx16 (&acc)[Cf
         // spans less than 2 GiB.  Per-lane part of the offset: the row (one mixed-radix sum per
         // sub-tile row); the column part is wave-uniform.
         const int s0 = (int)p.c_n.stride[0];
-        __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(HAS_C ? p.C : p.D), 0, 0x7fffffff, 0x00020000);
-        __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(p.D, 0, 0x7fffffff, 0x00020000);
+        __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(HAS_C ? Cp : Dp), 0, 0x7fffffff, 0x00020000);
+        __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(Dp, 0, 0x7fffffff, 0x00020000);
         int col4[Cfg::TJ][4];
 #pragma unroll
         for (int j = 0; j < Cfg::TJ; ++j)
@@ -384,13 +437,13 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, floatx16 (&acc)[Cf
                     for (int t = 0; t < 4; ++t) off[t] = row_off + group_offset(p.c_n, n_base + 32 * j + 8 * q + 4 * lh + t);
                     if constexpr (HAS_C) {
 #pragma unroll
-                        for (int t = 0; t < 4; ++t) cv[t] = p.C[off[t]];
+                        for (int t = 0; t < 4; ++t) cv[t] = Cp[off[t]];
                     }
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         float y = p.alpha * acc[i][j][4 * q + t];
                         if constexpr (HAS_C) y += p.beta * cv[t];
-                        p.D[off[t]] = y > floor_v ? y : floor_v;
+                        Dp[off[t]] = y > floor_v ? y : floor_v;
                     }
                 }
             }
@@ -412,28 +465,43 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, floatx16 (&acc)[Cf
 //     The barrier that publishes tile kt+1 (and retires tile kt) sits before the LAST slice of
 //     tile kt, whose fragments are already in registers, so the first reads of tile kt+1 are
 //     covered by that slice's MFMAs instead of stalling the matrix unit.
+// Negate eight halves (flip the sign bits): exact.
+__device__ __forceinline__ half8 neg8(half8 v) {
+    u32x4 u = __builtin_bit_cast(u32x4, v);
+    u ^= 0x80008000u;
+    return __builtin_bit_cast(half8, u);
+}
+
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p) {
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     FG_LDS char *smem = (FG_LDS char *)smem_generic;
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, TI = Cfg::TI, TJ = Cfg::TJ;
-    constexpr int S = Cfg::STAGES, KS = Cfg::KSTEPS, L = Cfg::LOADS_PER_TILE;
+    constexpr int S = Cfg::STAGES, KS = Cfg::KSTEPS, L = Cfg::LOADS_PER_TILE, P = Cfg::PLANES;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % Cfg::WGM, wn = wave / Cfg::WGM;
     const int ntiles = p.tiles_m * p.tiles_n;
-    const int nk = p.K / BK;
 
     FG_LDS char *lds_a = smem;
     FG_LDS char *lds_b = smem + Cfg::A_BYTES;
 
-    TileLoader<BM, BK, Cfg::A_KC, Cfg::A_SLABS, Cfg::STRIDED> la;
-    TileLoader<BN, BK, Cfg::B_KC, Cfg::B_SLABS, Cfg::STRIDED> lb;
+    using PlainA = TileLoader<BM, BK, Cfg::A_KC, Cfg::A_SLABS, Cfg::STRIDED>;
+    using PlainB = TileLoader<BN, BK, Cfg::B_KC, Cfg::B_SLABS, Cfg::STRIDED>;
+    using LoaderA = typename std::conditional<Cfg::DIAG == 1, DiagLoader<BM, BK, Cfg::A_SLABS>, PlainA>::type;
+    using LoaderB = typename std::conditional<Cfg::DIAG == 2, DiagLoader<BN, BK, Cfg::B_SLABS>, PlainB>::type;
+    LoaderA la[P];
+    LoaderB lb[P];
     FragReader<BM, BK, Cfg::A_KC, TI> fa;
     FragReader<BN, BK, Cfg::B_KC, TJ> fb;
     fa.init(wm * Cfg::WTM, lane);
     fb.init(wn * Cfg::WTN, lane);
+
+    // K tiles [kt0, kt0 + nkt) of the current output tile.  A diagonal operand has entries only
+    // where its row index equals k, so a tile row m0 needs just the K tiles that meet
+    // [m0, m0 + BM): the "skip iterations off the diagonal" predicate of Section 5.2.
+    int kt0 = 0, nkt = 0;
 
     // start the loads of a tile: point the loaders at its panels and fill the ring
     auto start_tile = [&](int tile_id, int &m0, int &n0) {
@@ -441,13 +509,31 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
         block_to_tile(tile_id, p.tiles_m, p.tiles_n, tm, tn);
         m0 = tm * BM;
         n0 = tn * BN;
-        la.init(p.A, m0, wave, lane, p.a_rs, p.a_ks, p.a_m, p.a_k);
-        lb.init(p.B, n0, wave, lane, p.b_rs, p.b_ks, p.b_n, p.b_k);
+        const int nk = p.K / BK;
+        kt0 = 0;
+        int kt1 = nk;
+        if constexpr (Cfg::DIAG == 1) { kt0 = m0 / BK; kt1 = (m0 + BM) / BK; }
+        if constexpr (Cfg::DIAG == 2) { kt0 = n0 / BK; kt1 = (n0 + BN) / BK; }
+        if (kt1 > nk) kt1 = nk;
+        nkt = kt1 > kt0 ? kt1 - kt0 : 0;
+        const _Float16 *ap[2] = {p.A, p.A_im};
+        const _Float16 *bp[2] = {p.B, p.B_im};
 #pragma unroll
-        for (int s = 0; s < S; ++s)
-            if (s < nk) {
-                la.issue(lds_a + s * Cfg::A_TILE_BYTES, wave);
-                lb.issue(lds_b + s * Cfg::B_TILE_BYTES, wave);
+        for (int q = 0; q < P; ++q) {
+            if constexpr (Cfg::DIAG == 1) la[q].init(ap[q], m0, p.M < p.K ? p.M : p.K, wave, lane);
+            else la[q].init(ap[q], m0, wave, lane, p.a_rs, p.a_ks, p.a_m, p.a_k);
+            if constexpr (Cfg::DIAG == 2) lb[q].init(bp[q], n0, p.N < p.K ? p.N : p.K, wave, lane);
+            else lb[q].init(bp[q], n0, wave, lane, p.b_rs, p.b_ks, p.b_n, p.b_k);
+            if constexpr (Cfg::DIAG != 0) { la[q].skip(kt0); lb[q].skip(kt0); }
+        }
+#pragma unroll
+        for (int st = 0; st < S; ++st)
+            if (st < nkt) {
+#pragma unroll
+                for (int q = 0; q < P; ++q) {
+                    la[q].issue(lds_a + q * Cfg::A_PLANE_BYTES + st * Cfg::A_TILE_BYTES, wave);
+                    lb[q].issue(lds_b + q * Cfg::B_PLANE_BYTES + st * Cfg::B_TILE_BYTES, wave);
+                }
             }
     };
 
@@ -458,26 +544,31 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
 
     while (true) {
         const int m_base = m0 + wm * Cfg::WTM, n_base = n0 + wn * Cfg::WTN;
-        floatx16 acc[TI][TJ];
+        floatx16 acc[P][TI][TJ];
 #pragma unroll
-        for (int i = 0; i < TI; ++i)
+        for (int q = 0; q < P; ++q)
 #pragma unroll
-            for (int j = 0; j < TJ; ++j)
+            for (int i = 0; i < TI; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+                for (int j = 0; j < TJ; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[q][i][j][r] = 0.f;
 
-        if (nk > 0) {
-            if (nk >= S) wait_tile<(S - 1) * L>(); else wait_tile<0>();
+        if (nkt > 0) {
+            if (nkt >= S) wait_tile<(S - 1) * L>(); else wait_tile<0>();
             __builtin_amdgcn_s_barrier();
 
             // A fragments are reloaded in place (the registers of sub-tile i are free once its
             // MFMAs of this slice are issued); B fragments, used by every sub-tile row, are double
-            // buffered.
-            half8 af[TI], bf[2][TJ];
+            // buffered.  Complex operands carry a second set for the imaginary planes.
+            half8 af[P][TI], bf[P][2][TJ];
 #pragma unroll
-            for (int i = 0; i < TI; ++i) af[i] = fa.read(lds_a, i, 0);
+            for (int q = 0; q < P; ++q) {
 #pragma unroll
-            for (int j = 0; j < TJ; ++j) bf[0][j] = fb.read(lds_b, j, 0);
+                for (int i = 0; i < TI; ++i) af[q][i] = fa.read(lds_a + q * Cfg::A_PLANE_BYTES, i, 0);
+#pragma unroll
+                for (int j = 0; j < TJ; ++j) bf[q][0][j] = fb.read(lds_b + q * Cfg::B_PLANE_BYTES, j, 0);
+            }
 
             // one K tile; MORE: another tile follows (publish it, refill the ring, prefetch its
             // first fragments)
@@ -496,30 +587,54 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                     if (last && MORE) {
                         // tile kt+1 has landed (for this wave) and all of this wave's reads of tile
                         // kt have returned; after the barrier both hold for every wave
-                        if (kt + S < nk) wait_tile<(S - 2) * L>(); else wait_tile<0>();
+                        if (kt + S < nkt) wait_tile<(S - 2) * L>(); else wait_tile<0>();
                         __builtin_amdgcn_s_barrier();
-                        if (kt + S < nk) {
-                            la.issue(lds_a + cur * Cfg::A_TILE_BYTES, wave);
-                            lb.issue(lds_b + cur * Cfg::B_TILE_BYTES, wave);
+                        if (kt + S < nkt) {
+#pragma unroll
+                            for (int q = 0; q < P; ++q) {
+                                la[q].issue(lds_a + q * Cfg::A_PLANE_BYTES + cur * Cfg::A_TILE_BYTES, wave);
+                                lb[q].issue(lds_b + q * Cfg::B_PLANE_BYTES + cur * Cfg::B_TILE_BYTES, wave);
+                            }
                         }
                     }
                     if (!last || MORE) {
 #pragma unroll
-                        for (int j = 0; j < TJ; ++j) bf[wb][j] = last ? fb.read(nb, j, 0) : fb.read(tb, j, ks + 1);
+                        for (int q = 0; q < P; ++q)
+#pragma unroll
+                            for (int j = 0; j < TJ; ++j)
+                                bf[q][wb][j] = last ? fb.read(nb + q * Cfg::B_PLANE_BYTES, j, 0)
+                                                    : fb.read(tb + q * Cfg::B_PLANE_BYTES, j, ks + 1);
                     }
 #pragma unroll
                     for (int i = 0; i < TI; ++i) {
+                        // MFMA rows <- our N index, MFMA columns <- our M index: lanes of the
+                        // accumulator then run along M, the contiguous direction of D
+                        if constexpr (!Cfg::CPLX) {
 #pragma unroll
-                        for (int j = 0; j < TJ; ++j)
-                            // MFMA rows <- our N index, MFMA columns <- our M index: lanes of the
-                            // accumulator then run along M, the contiguous direction of D
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[rb][j], af[i], acc[i][j], 0, 0, 0);
-                        if (!last || MORE) af[i] = last ? fa.read(na, i, 0) : fa.read(ta, i, ks + 1);
+                            for (int j = 0; j < TJ; ++j)
+                                acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[0][rb][j], af[0][i], acc[0][i][j], 0, 0, 0);
+                        } else {
+                            // (Ar + i Ai)(Br + i Bi): the four real products of Section 5.4
+                            const half8 nai = neg8(af[1][i]);
+#pragma unroll
+                            for (int j = 0; j < TJ; ++j) {
+                                acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[0][rb][j], af[0][i], acc[0][i][j], 0, 0, 0);
+                                acc[1][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[1][rb][j], af[0][i], acc[1][i][j], 0, 0, 0);
+                                acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[1][rb][j], nai, acc[0][i][j], 0, 0, 0);
+                                acc[1][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[0][rb][j], af[1][i], acc[1][i][j], 0, 0, 0);
+                            }
+                        }
+                        if (!last || MORE) {
+#pragma unroll
+                            for (int q = 0; q < P; ++q)
+                                af[q][i] = last ? fa.read(na + q * Cfg::A_PLANE_BYTES, i, 0)
+                                                : fa.read(ta + q * Cfg::A_PLANE_BYTES, i, ks + 1);
+                        }
                     }
                 }
             };
-            for (int kt = 0; kt + 1 < nk; ++kt) tile_body(kt, std::true_type{});
-            tile_body(nk - 1, std::false_type{});
+            for (int kt = 0; kt + 1 < nkt; ++kt) tile_body(kt, std::true_type{});
+            tile_body(nkt - 1, std::false_type{});
         }
 
         // next tile of this workgroup: once every wave has read its last fragments the LDS ring is
@@ -533,8 +648,12 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
             start_tile(next, m1, n1);
         }
 
-        if (p.has_c) epilogue<Cfg, true>(p, acc, m_base, n_base, lane);
-        else epilogue<Cfg, false>(p, acc, m_base, n_base, lane);
+        if (p.has_c) epilogue<Cfg, true>(p, p.C, p.D, acc[0], m_base, n_base, lane);
+        else epilogue<Cfg, false>(p, p.C, p.D, acc[0], m_base, n_base, lane);
+        if constexpr (Cfg::CPLX) {
+            if (p.has_c) epilogue<Cfg, true>(p, p.C_im, p.D_im, acc[1], m_base, n_base, lane);
+            else epilogue<Cfg, false>(p, p.C_im, p.D_im, acc[1], m_base, n_base, lane);
+        }
 
         if (!more_tiles) break;
         tile = next;

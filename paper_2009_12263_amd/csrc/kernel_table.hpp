@@ -19,6 +19,13 @@ const KernelEntry *kernel_table_nt();   // A M-contiguous, B N-contiguous  (A 'N
 const KernelEntry *kernel_table_tn();   // A K-contiguous, B K-contiguous  (A 'T', B 'N')
 const KernelEntry *kernel_table_tt();   // A K-contiguous, B N-contiguous  (A 'T', B 'T')
 
+// Diagonal operands: index tile * 4 + {0: A diag, B K-contiguous; 1: A diag, B N-contiguous;
+//                                       2: B diag, A K-contiguous; 3: B diag, A M-contiguous}.
+const KernelEntry *kernel_table_diag();
+// Planar complex: index ctile * 4 + {nn, nt, tn, tt}; ctile 0: 256x128, 1: 128x128, 2: 64x64.
+const KernelEntry *kernel_table_cplx();
+enum { CTILE_COUNT = 3 };
+
 // Entry index inside one table: tile * 2 + strided.
 inline int entry_index(int tile, bool strided) { return tile * 2 + (strided ? 1 : 0); }
 
@@ -27,6 +34,11 @@ inline int entry_index(int tile, bool strided) { return tile * 2 + (strided ? 1 
     { gemm_kernel<FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)>, NAME, BM, BN,                  \
       FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)::NTHREADS,                                   \
       FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)::LDS_BYTES }
+
+#define FG_ENTRY_X(BM, BN, BK, ST, WGM, WGN, AKC, BKC, DG, CX, NAME)                                \
+    { gemm_kernel<TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, false, DG, CX>>, NAME, BM, BN,       \
+      TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, false, DG, CX>::NTHREADS,                        \
+      TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, false, DG, CX>::LDS_BYTES }
 
 #define FG_DEFINE_TABLE(FUNC, AKC, BKC, TAG)                                                       \
     const KernelEntry *FUNC() {                                                                    \

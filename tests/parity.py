@@ -156,3 +156,59 @@ def run_contract_case(extents, modesA, modesB, modesC, alpha=1.0, beta=0.0, ints
     r = O.contract(extents, modesA, sA, np16(A), modesB, sB, np16(B), modesC, sC, Cin_host, alpha=alpha, beta=beta, at=at)
     off = (at * np.array(sC, np.int64)[None, :]).sum(axis=1)
     return compare(got_all[off], r["D"], r["G"], K, ints, what)
+
+
+def run_diag_case(M, N, K, side="A", other_layout=fg.FG_COL, ld_layout=fg.FG_COL, alpha=1.0, beta=1.0, with_c=True,
+                  ints=False, config=4, samples: Optional[int] = None, device="cuda", seed=W.DEFAULT_SEED):
+    """D = diag(d) . B + C (side 'A') or A . diag(d) + C (side 'B'); d holds min(rows, cols) entries."""
+    gen = W.small_ints if ints else W.uniform_pm1
+    if side == "A":
+        dvec = gen(min(M, K), W.stream_id(config, "d"), seed=seed, device=device, dtype=torch.float16)
+        X, ldx = make_operand(K, N, other_layout, W.stream_id(config, "B"), device, ints, 0, seed)
+        mA, mB = fg.Matrix(dvec, fg.FG_DIAG, 0), fg.Matrix(X, other_layout, ldx)
+        oA, oB = O.Operand(np16(dvec), O.DIAG, 0), O.Operand(np16(X), other_layout, ldx)
+    else:
+        dvec = gen(min(K, N), W.stream_id(config, "d"), seed=seed, device=device, dtype=torch.float16)
+        X, ldx = make_operand(M, K, other_layout, W.stream_id(config, "A"), device, ints, 0, seed)
+        mA, mB = fg.Matrix(X, other_layout, ldx), fg.Matrix(dvec, fg.FG_DIAG, 0)
+        oA, oB = O.Operand(np16(X), other_layout, ldx), O.Operand(np16(dvec), O.DIAG, 0)
+    lead, other = (M, N) if ld_layout == fg.FG_COL else (N, M)
+    Cbuf = make_f32(lead * other, W.stream_id(config, "C"), device, ints, seed) if with_c else None
+    Dbuf = torch.full((lead * other,), float("nan"), dtype=torch.float32, device=device)
+    fg.fg_gemm(M, N, K, alpha, mA, mB, beta, fg.Matrix(Cbuf, ld_layout, lead) if with_c else None, fg.Matrix(Dbuf, ld_layout, lead))
+    torch.cuda.synchronize()
+    Dm = np16(Dbuf).reshape(other, lead)
+    Dlog = Dm.T if ld_layout == fg.FG_COL else Dm
+    at = sample_positions(M, N, samples, seed=M + N + K) if samples is not None else None
+    r = O.gemm(M, N, K, alpha, oA, oB, beta, np16(Cbuf), None, ld_layout, lead, at=at)
+    got = Dlog if at is None else Dlog[at[0], at[1]]
+    return compare(got, r["D"], r["G"], 1, ints, "diag-%s gemm M=%d N=%d K=%d other=%d D=%d ints=%s" % (side, M, N, K, other_layout, ld_layout, ints))
+
+
+def run_cgemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alpha=1.0, beta=1.0, with_c=True,
+                   ints=False, pad=0, config=4, samples: Optional[int] = None, device="cuda", seed=W.DEFAULT_SEED):
+    """Planar-split complex D = alpha A B + beta C; real and imaginary planes are separate arrays."""
+    Ar, lda = make_operand(M, K, la, W.stream_id(config, "A"), device, ints, pad, seed)
+    Ai, _ = make_operand(M, K, la, W.stream_id(config, "A_im"), device, ints, pad, seed)
+    Br, ldb = make_operand(K, N, lb, W.stream_id(config, "B"), device, ints, pad, seed)
+    Bi, _ = make_operand(K, N, lb, W.stream_id(config, "B_im"), device, ints, pad, seed)
+    lead, other = (M, N) if ld_layout == fg.FG_COL else (N, M)
+    ldc = lead + (4 if pad else 0)
+    Cr = make_f32(ldc * other, W.stream_id(config, "C"), device, ints, seed) if with_c else None
+    Ci = make_f32(ldc * other, W.stream_id(config, "C_im"), device, ints, seed) if with_c else None
+    Dr = torch.full((ldc * other,), float("nan"), dtype=torch.float32, device=device)
+    Di = torch.full((ldc * other,), float("nan"), dtype=torch.float32, device=device)
+    fg.fg_gemm(M, N, K, alpha, fg.Matrix(Ar, la, lda, im=Ai), fg.Matrix(Br, lb, ldb, im=Bi), beta,
+               fg.Matrix(Cr, ld_layout, ldc, im=Ci) if with_c else None, fg.Matrix(Dr, ld_layout, ldc, im=Di))
+    torch.cuda.synchronize()
+    view = lambda t: (np16(t).reshape(other, ldc)[:, :lead].T if ld_layout == fg.FG_COL else np16(t).reshape(other, ldc)[:, :lead])
+    at = sample_positions(M, N, samples, seed=M * 3 + N * 5 + K) if samples is not None else None
+    r = O.gemm(M, N, K, alpha, O.Operand(np16(Ar), la, lda, np16(Ai)), O.Operand(np16(Br), lb, ldb, np16(Bi)), beta,
+               np16(Cr), np16(Ci), ld_layout, ldc, at=at)
+    gr, gi = view(Dr), view(Di)
+    if at is not None:
+        gr, gi = gr[at[0], at[1]], gi[at[0], at[1]]
+    what = "cgemm M=%d N=%d K=%d A=%d B=%d D=%d ints=%s" % (M, N, K, la, lb, ld_layout, ints)
+    w1 = compare(gr, r["D"], r["G"], 2 * K, ints, what + " (real part)")
+    w2 = compare(gi, r["D_im"], r["G_im"], 2 * K, ints, what + " (imaginary part)")
+    return max(w1, w2)
