@@ -27,9 +27,11 @@ if ROOT not in sys.path:
 
 METRIC = "TFLOP/s and % of FP16 MFMA peak, mixed-precision GEMM N=8192 and GETT"
 MFMA_FP16_PEAK_TFLOPS = 2500.0     # MI355X dense FP16 MFMA, published (2.5 PFLOP/s)
-# HBM bytes per launch of the 8192^3 kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (profiles/gemm_nn_8192_pmc.txt); None until that profile has been taken.
-MEASURED_HBM_TRAFFIC_BYTES = None
+# Bytes per launch of the 8192^3 kernel that crossed the L2 <-> memory-side boundary, from two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a
+# plain copy kernel of known size (factors 2.0 and 1.0): profiles/gemm_nn_8192_pmc.md.  Only
+# meaningful for the default workload.
+MEASURED_HBM_TRAFFIC_BYTES = 2.335e9
 
 
 def cpu_baseline(M, N, K, A, lda, B, ldb, C, ldc, budget_s=15.0):
@@ -56,6 +58,77 @@ def cpu_baseline(M, N, K, A, lda, B, ldb, C, ldc, budget_s=15.0):
                       % (count, M * N, M, N, K, K, t)}
 
 
+def extras(fg, W, torch, n, A, B, mC, mD, stream):
+    """Other rows of the hot-path table, outside the timed region: the remaining layout pairs at
+    the same size, the fused-epilogue and layout-adapter configurations and the contractions.
+    Each figure is flops (or algorithmic bytes) over the mean of 10 launches timed with HIP events."""
+    import math
+    res = {}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps=10):
+        for _ in range(3):
+            fn()
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    def guard(name, fn):
+        try:
+            res[name] = fn()
+        except Exception as ex:  # keep the headline line even if an extra cannot run
+            res[name] = "error: %s" % ex
+
+    flops = 2.0 * n ** 3
+    for name, la, lb in (("NT", fg.FG_COL, fg.FG_ROW), ("TN", fg.FG_ROW, fg.FG_COL), ("TT", fg.FG_ROW, fg.FG_ROW)):
+        a2, b2 = fg.Matrix(A, la, n), fg.Matrix(B, lb, n)
+        guard("gemm_%s_%d_TFLOPs" % (name, n), lambda: flops / timed(lambda: fg.fg_gemm(n, n, n, 1.0, a2, b2, 1.0, mC, mD, stream=stream)) * 1e-12)
+
+    m = 4096
+    dev = A.device
+    A4, B4 = A[:m * m], B[:m * m]
+    A4i = W.uniform_pm1(m * m, W.stream_id(4, "A_im"), device=dev)
+    B4i = W.uniform_pm1(m * m, W.stream_id(4, "B_im"), device=dev)
+    C4 = W.uniform_pm1(m * m, W.stream_id(4, "C"), device=dev, dtype=torch.float32)
+    C4i = W.uniform_pm1(m * m, W.stream_id(4, "C_im"), device=dev, dtype=torch.float32)
+    D4, D4i = torch.empty_like(C4), torch.empty_like(C4)
+    bias = W.uniform_pm1(8192, W.stream_id(3, "bias"), device=dev, dtype=torch.float32)
+    dvec = W.uniform_pm1(m, W.stream_id(4, "d"), device=dev)
+    M = fg.Matrix
+    guard("config3_relu_bias_4096_TFLOPs", lambda: 2.0 * m ** 3 / timed(lambda: fg.fg_gemm(
+        m, m, m, 1.0, M(A4, 0, m), M(B4, 0, m), 0.0, None, M(D4, 0, m), bias=bias, bias_dim=0, act=fg.FG_ACT_RELU, stream=stream)) * 1e-12)
+    D3 = torch.empty(8192 * 1024, dtype=torch.float32, device=dev)
+    guard("config3_relu_bias_8192x1024x4096_TFLOPs", lambda: 2.0 * 8192 * 1024 * 4096 / timed(lambda: fg.fg_gemm(
+        8192, 1024, 4096, 1.0, M(A[:8192 * 4096], 0, 8192), M(B[:4096 * 1024], 0, 4096), 0.0, None, M(D3, 0, 8192),
+        bias=bias, bias_dim=0, act=fg.FG_ACT_RELU, stream=stream)) * 1e-12)
+    guard("config4_complex_planar_4096_TFLOPs", lambda: 8.0 * m ** 3 / timed(lambda: fg.fg_gemm(
+        m, m, m, 1.0, M(A4, 0, m, im=A4i), M(B4, 0, m, im=B4i), 1.0, M(C4, 0, m, im=C4i), M(D4, 0, m, im=D4i), stream=stream)) * 1e-12)
+    guard("config4_diagonal_A_4096_GBps", lambda: (m * m * 2 + 2 * m * m * 4 + m * 2) / timed(lambda: fg.fg_gemm(
+        m, m, m, 1.0, M(dvec, fg.FG_DIAG, 0), M(B4, 0, m), 1.0, M(C4, 0, m), M(D4, 0, m), stream=stream)) * 1e-9)
+
+    a, b, c, d, e, f = range(6)
+
+    def contraction(ext, mA, mB, mC):
+        sA = W.col_major_strides(tuple(ext[x] for x in mA))
+        sB = W.col_major_strides(tuple(ext[x] for x in mB))
+        sC = W.col_major_strides(tuple(ext[x] for x in mC))
+        nA, nB, nC = (math.prod(ext[x] for x in ms) for ms in (mA, mB, mC))
+        out = torch.empty(nC, dtype=torch.float32, device=dev)
+        t = timed(lambda: fg.fg_contract(mA, sA, A[:nA], mB, sB, B[:nB], mC, sC, None, out, ext, stream=stream))
+        return 2.0 * math.prod(ext.values()) / t * 1e-12, (nA * 2 + nB * 2 + nC * 4) / t * 1e-9
+
+    def c5a():
+        tf, gb = contraction({a: 256, b: 256, c: 256, d: 256}, [a, d, c], [d, b], [a, b, c])
+        res["config5a_contraction_256_GBps"] = gb
+        return tf
+    guard("config5a_contraction_256_TFLOPs", c5a)
+    guard("config5b_contraction_64_TFLOPs", lambda: contraction({a: 64, b: 64, c: 64, d: 64, e: 64, f: 64}, [a, e, b, f], [d, f, c, e], [a, b, c, d])[0])
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,7 +136,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--size", type=int, default=8192, help="M = N = K of the timed GEMM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--extras", action="store_true", help="also time the other layouts and configs")
+    ap.add_argument("--no-extras", action="store_true", help="skip the untimed-region extras (other layouts and configs)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain elementwise copy kernel (D = -C: 4 M N bytes read, 4 M N written), "
+                         "so a counter profile of this command can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards without any exchange; "
@@ -89,6 +165,8 @@ def main():
     def step():
         fg.fg_gemm(M, N, K, 1.0, mA, mB, 1.0, mC, mD, stream=stream)
 
+    if args.copy_calibration:
+        torch.neg(C, out=D)      # one elementwise kernel: reads 4 M N bytes, writes 4 M N bytes
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -113,23 +191,13 @@ def main():
                                "C,D FP32, uniform[-1,1), alpha=beta=1" % n,
                    "kernel": fg.fg_gemm_plan(M, N, K)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_FP16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_FP16_PEAK_TFLOPS, "traffic": MEASURED_HBM_TRAFFIC_BYTES,
+                     "frac": achieved / MFMA_FP16_PEAK_TFLOPS,
+                     "traffic": MEASURED_HBM_TRAFFIC_BYTES if n == 8192 else None,
                      "kernel_ms": kern_ms},
     }
 
-    if args.extras:
-        extras = {}
-        for name, la, lb in (("NT", fg.FG_COL, fg.FG_ROW), ("TN", fg.FG_ROW, fg.FG_COL), ("TT", fg.FG_ROW, fg.FG_ROW)):
-            a2, b2 = fg.Matrix(A, la, M), fg.Matrix(B, lb, K)
-            for _ in range(3):
-                fg.fg_gemm(M, N, K, 1.0, a2, b2, 1.0, mC, mD, stream=stream)
-            e0.record(stream)
-            for _ in range(10):
-                fg.fg_gemm(M, N, K, 1.0, a2, b2, 1.0, mC, mD, stream=stream)
-            e1.record(stream)
-            torch.cuda.synchronize()
-            extras["gemm_%s_%d_TFLOPs" % (name, n)] = flops / (e0.elapsed_time(e1) / 10 * 1e-3) * 1e-12
-        out["extras"] = extras
+    if not args.no_extras:
+        out["extras"] = extras(fg, W, torch, n, A, B, mC, mD, stream)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(M, N, K, A.cpu().numpy(), M, B.cpu().numpy(), K, C.cpu().numpy(), M)
