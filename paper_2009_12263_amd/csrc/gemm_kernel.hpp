@@ -67,7 +67,7 @@ struct GemmParams {
 // 32x32 MFMA accumulators.  A_KC / B_KC: operand is K-contiguous in memory (A row-major,
 // B column-major) rather than M/N-contiguous.  STAGES LDS buffers per operand form a ring over K.
 template <int BM_, int BN_, int BK_, int STAGES_, int WGM_, int WGN_, bool A_KC_, bool B_KC_, bool STRIDED_,
-          int DIAG_ = 0, bool CPLX_ = false>
+          int DIAG_ = 0, bool CPLX_ = false, bool SPREAD_ = false>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_;
     static constexpr int KSTEPS = BK / 16;                          // MFMA k-slices per tile
@@ -77,6 +77,11 @@ struct TileCfg {
     static constexpr int TI = WTM / 32, TJ = WTN / 32;
     static constexpr bool A_KC = A_KC_, B_KC = B_KC_, STRIDED = STRIDED_, CPLX = CPLX_;
     static constexpr int DIAG = DIAG_;                              // 0: none, 1: A diagonal, 2: B diagonal
+    // SPREAD: the refill loads of a ring buffer are issued one at a time between the MFMAs of two
+    // k-slices (A's part in the slice after the buffer is retired, B's part in the next one)
+    // instead of as one burst: a burst from all waves queues up in the compute unit's single
+    // vector-memory path and holds back the MFMAs behind it in each wave's in-order stream.
+    static constexpr bool SPREAD = SPREAD_;
     static constexpr int PLANES = CPLX ? 2 : 1;                     // real / (real, imaginary)
     static constexpr int A_TILE_BYTES = BM * BK * 2, B_TILE_BYTES = BN * BK * 2;
     static constexpr int A_SLABS = A_TILE_BYTES / 1024 / NWAVES;   // 1 KB direct-to-LDS writes per wave
@@ -98,6 +103,7 @@ struct TileCfg {
     static_assert(DIAG != 1 || A_KC, "a diagonal A is synthesised K-contiguous");
     static_assert(DIAG != 2 || B_KC, "a diagonal B is synthesised K-contiguous");
     static_assert(!(CPLX && (DIAG || STRIDED)), "complex products take plain matrices");
+    static_assert(!SPREAD || STAGES >= 4 || KSTEPS >= 4, "spread refills need slack before the tile is needed");
 };
 
 // ---- swizzles -------------------------------------------------------------------------------
@@ -216,16 +222,27 @@ struct TileLoader {
         ktile = kt0;
     }
 
-    // issue the loads of the current K step into the LDS tile at `lds_tile`, then advance
-    __device__ __forceinline__ void issue(FG_LDS char *lds_tile, int wave) {
+    // The loads of one K step can be issued all at once (issue) or slab by slab between other
+    // instructions (begin, issue_slab x SLABS, advance).
+    u32x4 rsrc_cur;
+    __device__ __forceinline__ void begin() {
         const char *b = base;
         if constexpr (STRIDED) b += group_offset(kg, ktile * BK) * 2;
-        u32x4 rsrc = make_rsrc(b);
-        uint32_t dst = (uint32_t)(uintptr_t)lds_tile + (uint32_t)(wave * SLABS) * 1024u;
-#pragma unroll
-        for (int s = 0; s < SLABS; ++s) load16_to_lds(rsrc, dst + s * 1024u, voff[s]);
+        rsrc_cur = make_rsrc(b);
+    }
+    __device__ __forceinline__ void issue_slab(FG_LDS char *lds_tile, int wave, int s) {
+        uint32_t dst = (uint32_t)(uintptr_t)lds_tile + (uint32_t)(wave * SLABS + s) * 1024u;
+        load16_to_lds(rsrc_cur, dst, voff[s]);
+    }
+    __device__ __forceinline__ void advance() {
         if constexpr (!STRIDED) base += kstep_bytes;
         ++ktile;
+    }
+    __device__ __forceinline__ void issue(FG_LDS char *lds_tile, int wave) {
+        begin();
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) issue_slab(lds_tile, wave, s);
+        advance();
     }
 };
 
@@ -254,17 +271,20 @@ struct DiagLoader {
         }
     }
     __device__ __forceinline__ void skip(int kt0) { ktile = kt0; }
+    __device__ __forceinline__ void begin() {}
+    __device__ __forceinline__ void issue_slab(FG_LDS char *lds_tile, int wave, int s) {
+        const int pos = pos0[s] - ktile * BK;      // the chunk holds k0+8c .. k0+8c+7
+        half8 v;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] = (t == pos) ? dval[s] : (_Float16)0.f;
+        *(FG_LDS half8 *)(lds_tile + (wave * SLABS + s) * 1024 + (threadIdx.x & 63) * 16) = v;
+    }
+    __device__ __forceinline__ void advance() { ++ktile; }
     __device__ __forceinline__ void issue(FG_LDS char *lds_tile, int wave) {
-        const int k0 = ktile * BK;
+        begin();
 #pragma unroll
-        for (int s = 0; s < SLABS; ++s) {
-            const int pos = pos0[s] - k0;          // the chunk holds k0+8c .. k0+8c+7
-            half8 v;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) v[t] = (t == pos) ? dval[s] : (_Float16)0.f;
-            *(FG_LDS half8 *)(lds_tile + (wave * SLABS + s) * 1024 + (threadIdx.x & 63) * 16) = v;
-        }
-        ++ktile;
+        for (int s = 0; s < SLABS; ++s) issue_slab(lds_tile, wave, s);
+        advance();
     }
 };
 
@@ -584,17 +604,34 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                 for (int ks = 0; ks < KS; ++ks) {
                     const int rb = ks & 1, wb = rb ^ 1;     // KS is even: slice 0 always uses buffer 0
                     const bool last = (ks + 1 == KS);
+                    // which refill loads ride along with this slice (SPREAD):
+                    //   last slice (after the barrier): A's part of tile kt+S into the buffer of tile kt
+                    //   slice 0: B's part of tile kt-1+S into the buffer of tile kt-1
+                    bool refill_a = false, refill_b = false;
                     if (last && MORE) {
                         // tile kt+1 has landed (for this wave) and all of this wave's reads of tile
                         // kt have returned; after the barrier both hold for every wave
                         if (kt + S < nkt) wait_tile<(S - 2) * L>(); else wait_tile<0>();
                         __builtin_amdgcn_s_barrier();
                         if (kt + S < nkt) {
+                            if constexpr (Cfg::SPREAD) {
+                                refill_a = true;
 #pragma unroll
-                            for (int q = 0; q < P; ++q) {
-                                la[q].issue(lds_a + q * Cfg::A_PLANE_BYTES + cur * Cfg::A_TILE_BYTES, wave);
-                                lb[q].issue(lds_b + q * Cfg::B_PLANE_BYTES + cur * Cfg::B_TILE_BYTES, wave);
+                                for (int q = 0; q < P; ++q) la[q].begin();
+                            } else {
+#pragma unroll
+                                for (int q = 0; q < P; ++q) {
+                                    la[q].issue(lds_a + q * Cfg::A_PLANE_BYTES + cur * Cfg::A_TILE_BYTES, wave);
+                                    lb[q].issue(lds_b + q * Cfg::B_PLANE_BYTES + cur * Cfg::B_TILE_BYTES, wave);
+                                }
                             }
+                        }
+                    }
+                    if constexpr (Cfg::SPREAD) {
+                        if (ks == 0 && kt >= 1 && kt - 1 + S < nkt) {
+                            refill_b = true;
+#pragma unroll
+                            for (int q = 0; q < P; ++q) lb[q].begin();
                         }
                     }
                     if (!last || MORE) {
@@ -605,6 +642,10 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                                 bf[q][wb][j] = last ? fb.read(nb + q * Cfg::B_PLANE_BYTES, j, 0)
                                                     : fb.read(tb + q * Cfg::B_PLANE_BYTES, j, ks + 1);
                     }
+                    // Scheduling fences keep the order written here: the compiler's scheduler would
+                    // otherwise sink every fragment read down to its first use one slice later and
+                    // expose the LDS latency in front of each MFMA pair.
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int i = 0; i < TI; ++i) {
                         // MFMA rows <- our N index, MFMA columns <- our M index: lanes of the
@@ -629,6 +670,35 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                             for (int q = 0; q < P; ++q)
                                 af[q][i] = last ? fa.read(na + q * Cfg::A_PLANE_BYTES, i, 0)
                                                 : fa.read(ta + q * Cfg::A_PLANE_BYTES, i, ks + 1);
+                        }
+                        if constexpr (Cfg::SPREAD) {
+                            // one refill load after the MFMAs of sub-tile row i, evenly over the slice
+                            const int prev = (kt - 1) & (S - 1);
+#pragma unroll
+                            for (int n = 0; n < Cfg::A_SLABS; ++n)
+                                if (refill_a && i == n * TI / Cfg::A_SLABS) {
+#pragma unroll
+                                    for (int q = 0; q < P; ++q)
+                                        la[q].issue_slab(lds_a + q * Cfg::A_PLANE_BYTES + cur * Cfg::A_TILE_BYTES, wave, n);
+                                }
+#pragma unroll
+                            for (int n = 0; n < Cfg::B_SLABS; ++n)
+                                if (refill_b && i == n * TI / Cfg::B_SLABS) {
+#pragma unroll
+                                    for (int q = 0; q < P; ++q)
+                                        lb[q].issue_slab(lds_b + q * Cfg::B_PLANE_BYTES + prev * Cfg::B_TILE_BYTES, wave, n);
+                                }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if constexpr (Cfg::SPREAD) {
+                        if (refill_a) {
+#pragma unroll
+                            for (int q = 0; q < P; ++q) la[q].advance();
+                        }
+                        if (refill_b) {
+#pragma unroll
+                            for (int q = 0; q < P; ++q) lb[q].advance();
                         }
                     }
                 }

@@ -29,7 +29,8 @@ enum { CTILE_COUNT = 3 };
 // Entry index inside one table: tile * 2 + strided.
 inline int entry_index(int tile, bool strided) { return tile * 2 + (strided ? 1 : 0); }
 
-#define FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR) TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR>
+// real kernels with BK = 64: ring refills are spread between the MFMAs (TileCfg::SPREAD)
+#define FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR) TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR, 0, false, true>
 #define FG_ENTRY(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR, NAME)                                    \
     { gemm_kernel<FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)>, NAME, BM, BN,                  \
       FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)::NTHREADS,                                   \
