@@ -82,6 +82,15 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream):
         except Exception as ex:  # keep the headline line even if an extra cannot run
             res[name] = "error: %s" % ex
 
+    def mfma_ceiling():
+        fl = [0]
+
+        def run():
+            fl[0] = fg.fg_probe_mfma(A, 2000, stream=stream)
+        t = timed(run, reps=5)
+        return fl[0] / t * 1e-12
+    guard("mfma_only_rate_on_this_data_TFLOPs", mfma_ceiling)
+
     flops = 2.0 * n ** 3
     for name, la, lb in (("NT", fg.FG_COL, fg.FG_ROW), ("TN", fg.FG_ROW, fg.FG_COL), ("TT", fg.FG_ROW, fg.FG_ROW)):
         a2, b2 = fg.Matrix(A, la, n), fg.Matrix(B, lb, n)

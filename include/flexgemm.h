@@ -92,8 +92,9 @@ typedef struct {
  *          (beta is then ignored).
  *   D    : FG_F32, FG_COL or FG_ROW; written.
  *   ep   : NULL means no bias and no activation.
- * Complex: if A or B has `im`, the product is complex (a missing `im` is zero), D must have
- * `im`, C (if given) must have `im`, alpha and beta are real, and `ep` must be NULL or empty.
+ * Complex: if A or B has `im`, the product is complex; this version needs `im` on both A and B
+ * (FG_ERR_UNSUPPORTED otherwise), D must have `im`, C (if given) must have `im`, alpha and beta
+ * are real, `ep` must be NULL or empty, and diagonal operands are not combined with complex.
  */
 fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha,
                   const fg_matrix *A, const fg_matrix *B,
@@ -114,7 +115,9 @@ fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha,
  * happens while tiles are loaded and while the result is stored.
  * Requirements of this version (else FG_ERR_UNSUPPORTED): in each of A and B some mode has
  * stride 1 and an extent that is a multiple of 8; the products of the row, column and summed
- * extents are multiples of 64; at most 4 modes per group.
+ * extents are multiples of 64; the summed mode that is walked fastest has an extent that is a
+ * multiple of 64; at most 4 modes per group; A and B each span less than 2 GiB; no negative
+ * strides.
  */
 fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA, const void *A,
                       int32_t nB, const int32_t *modesB, const int64_t *stridesB, const void *B,
@@ -138,6 +141,18 @@ int32_t fg_version(void);
  */
 fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t layoutB,
                        int32_t layoutD, int32_t is_complex, char *buf, int32_t buf_len);
+
+/*
+ * Measurement aid, not part of the method: launches a kernel that only issues
+ * v_mfma_f32_32x32x16_f16 (iters * 32 per wave, 8 waves on each of the 256 compute units) on
+ * operand fragments read from `fp16_operands` (device pointer, 16-byte aligned, at least 48 KiB of
+ * FP16 values, e.g. the A matrix of a workload) and writes the number of floating-point
+ * operations of the launch to *flops_out (host).  Timed by the caller, it gives the MFMA rate the
+ * chip sustains for that operand data: the engine clock is power-managed and dense MFMA power
+ * depends on the operand values.  Returns FG_ERR_NULL / FG_ERR_SHAPE (iters outside 1..2^20) /
+ * FG_ERR_ALIGN / FG_ERR_LAUNCH.
+ */
+fg_status fg_probe_mfma(const void *fp16_operands, int32_t iters, int64_t *flops_out, void *hip_stream);
 
 #ifdef __cplusplus
 }

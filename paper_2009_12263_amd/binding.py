@@ -22,7 +22,7 @@ FG_F16, FG_BF16, FG_F32 = 0, 1, 2
 FG_COL, FG_ROW, FG_DIAG, FG_ZERO = 0, 1, 2, 3
 FG_ACT_NONE, FG_ACT_RELU = 0, 1
 
-EXPORTS = ("fg_gemm", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan")
+EXPORTS = ("fg_gemm", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan", "fg_probe_mfma")
 
 
 class fg_matrix(C.Structure):
@@ -62,6 +62,8 @@ def load_library() -> C.CDLL:
         lib.fg_version.argtypes = []
         lib.fg_gemm_plan.restype = C.c_int
         lib.fg_gemm_plan.argtypes = [i64, i64, i64, i32, i32, i32, i32, C.c_char_p, i32]
+        lib.fg_probe_mfma.restype = C.c_int
+        lib.fg_probe_mfma.argtypes = [vp, i32, C.POINTER(C.c_int64), vp]
         _lib = lib
     return _lib
 
@@ -151,3 +153,12 @@ def fg_contract(modesA: Sequence[int], stridesA: Sequence[int], A: torch.Tensor,
     st = lib.fg_contract(len(mA), mA, sA, ptr(A), len(mB), mB, sB, ptr(B), len(mC), mC, sC, ptr(Cin), ptr(Cout),
                          len(labels), labels, exts, alpha, beta, _stream_handle(stream))
     return _check(st, raise_on_error)
+
+
+def fg_probe_mfma(fp16_operands: torch.Tensor, iters: int, stream=None) -> int:
+    """Launch the MFMA-only measurement kernel on operands from ``fp16_operands``; returns the
+    number of floating-point operations of the launch (see fg_probe_mfma in include/flexgemm.h)."""
+    flops = C.c_int64(0)
+    st = load_library().fg_probe_mfma(fp16_operands.data_ptr(), iters, C.byref(flops), _stream_handle(stream))
+    _check(st, True)
+    return int(flops.value)
