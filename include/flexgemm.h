@@ -116,7 +116,7 @@ fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha,
  * Requirements of this version (else FG_ERR_UNSUPPORTED): in each of A and B some mode has
  * stride 1 and an extent that is a multiple of 8; the products of the row, column and summed
  * extents are multiples of 64; the summed mode that is walked fastest has an extent that is a
- * multiple of 64; at most 4 modes per group; A and B each span less than 2 GiB; no negative
+ * multiple of 64; at most 4 modes per group; A, B and C each span less than 2 GiB; no negative
  * strides.
  */
 fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA, const void *A,

@@ -234,7 +234,7 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
 struct Contraction {
     int64_t M, N, K;
     const void *A, *B;
-    bool a_kc, b_kc, c_fast;
+    bool a_kc, b_kc;
     fg::ModeGroup a_m, a_k, b_n, b_k, c_m, c_n;
 };
 
@@ -322,15 +322,24 @@ fg_status plan_contraction(int32_t nA, const int32_t *modesA, const int64_t *str
         return fail(FG_ERR_UNSUPPORTED, "at most %d modes per merged index", fg::kMaxGroupModes);
     if (nkk == 0) return fail(FG_ERR_UNSUPPORTED, "an outer product (no summed mode) is not supported");
 
+    // Modes of extent 1 carry no index and are dropped.  For the others the kernel divides by the
+    // extent with a multiply-high: with 2^s < e <= 2^(s+1) and magic = floor(2^(32+s)/e) + 1,
+    // floor(idx / e) == (idx * magic) >> (32 + s) for every 0 <= idx < 2^31.
     auto fill = [&](fg::ModeGroup &g, const int32_t *modes, int n, const TensorView &t, int64_t &total) {
-        g.n = n; total = 1;
+        g.n = 0; total = 1;
         for (int i = 0; i < n; ++i) {
             int64_t e; extent_of(modes[i], e);
-            g.extent[i] = (int32_t)e;
-            g.stride[i] = t.strides[find_mode(t, modes[i])];
             total *= e;
+            if (e == 1) continue;
+            int k = g.n++;
+            g.extent[k] = (int32_t)e;
+            g.stride[k] = t.strides[find_mode(t, modes[i])];
+            uint32_t sh = 0;
+            while ((2ull << sh) < (uint64_t)e) ++sh;          // 2^sh < e <= 2^(sh+1)
+            g.shift[k] = sh;
+            g.magic[k] = (uint32_t)(((1ull << (32 + sh)) / (uint64_t)e) + 1);
         }
-        for (int i = n; i < fg::kMaxGroupModes; ++i) { g.extent[i] = 1; g.stride[i] = 0; }
+        for (int i = g.n; i < fg::kMaxGroupModes; ++i) { g.extent[i] = 2; g.stride[i] = 0; g.magic[i] = 0; g.shift[i] = 0; }
     };
     int64_t t1, t2;
     fill(c.a_m, m_modes, nm, ta, c.M); fill(c.c_m, m_modes, nm, tc, t1);
@@ -354,9 +363,9 @@ fg_status plan_contraction(int32_t nA, const int32_t *modesA, const int64_t *str
     for (int i = 0; i < ta.n; ++i) if (ta.strides[i] < 0) return fail(FG_ERR_UNSUPPORTED, "negative strides are not supported");
     for (int i = 0; i < tb.n; ++i) if (tb.strides[i] < 0) return fail(FG_ERR_UNSUPPORTED, "negative strides are not supported");
     for (int i = 0; i < tc.n; ++i) if (tc.strides[i] < 0) return fail(FG_ERR_UNSUPPORTED, "negative strides are not supported");
-    if (span(ta) * 2 >= (1ll << 31) || span(tb) * 2 >= (1ll << 31)) return fail(FG_ERR_UNSUPPORTED, "A and B must each span less than 2 GiB");
+    if (span(ta) * 2 >= (1ll << 31) || span(tb) * 2 >= (1ll << 31) || span(tc) * 4 >= (1ll << 31))
+        return fail(FG_ERR_UNSUPPORTED, "A, B and C must each span less than 2 GiB");
     if (c.M > (1 << 30) || c.N > (1 << 30) || c.K > (1 << 30)) return fail(FG_ERR_UNSUPPORTED, "merged extents above 2^30 are not supported");
-    c.c_fast = nn > 0 && c.c_n.extent[0] % 8 == 0 && span(tc) * 4 < (1ll << 31);
     return FG_OK;
 }
 
@@ -440,7 +449,6 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
     p.C = Cin; p.D = Cout;
     p.has_c = (Cin != nullptr);
     p.alpha = alpha; p.beta = Cin ? beta : 0.f;
-    p.c_fast = c.c_fast ? 1 : 0;
     p.a_m = c.a_m; p.a_k = c.a_k; p.b_n = c.b_n; p.b_k = c.b_k; p.c_m = c.c_m; p.c_n = c.c_n;
     return launch(k, p, (hipStream_t)hip_stream);
 }

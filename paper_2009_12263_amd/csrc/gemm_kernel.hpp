@@ -21,6 +21,7 @@
 // (stride 1) so that 16-byte accesses are possible.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include <type_traits>
@@ -39,7 +40,9 @@ constexpr int kMaxGroupModes = 4;
 // A group of tensor modes merged into one GEMM coordinate (first mode fastest).
 struct ModeGroup {
     int32_t n;
-    int32_t extent[kMaxGroupModes];
+    int32_t extent[kMaxGroupModes];   // every extent is >= 2 (the host drops modes of extent 1)
+    uint32_t magic[kMaxGroupModes];   // division by extent[t]: idx / e == mulhi(idx, magic) >> shift
+    uint32_t shift[kMaxGroupModes];   //   for 0 <= idx < 2^31 (magic = floor(2^(32+shift)/e) + 1, 2^shift < e <= 2^(shift+1))
     int64_t stride[kMaxGroupModes];   // element stride of each mode inside the tensor
 };
 
@@ -57,7 +60,6 @@ struct GemmParams {
     float alpha, beta;
     int32_t bias_dim, act, has_c;
     int32_t diag_a;                   // A is diagonal: A points at the diagonal entries
-    int32_t c_fast;                   // contraction: C qualifies for the evenly-spaced column store
     // tensor contraction: mode groups of each tensor
     ModeGroup a_m, a_k, b_n, b_k, c_m, c_n;
 };
@@ -160,12 +162,32 @@ __device__ __forceinline__ int64_t group_offset(const ModeGroup &g, int idx) {
     for (int t = 0; t < kMaxGroupModes; ++t) {
         if (t < g.n) {
             int e = g.extent[t];
-            int q = idx / e;
+            int q = (int)(__umulhi((uint32_t)idx, g.magic[t]) >> g.shift[t]);
             off += (int64_t)(idx - q * e) * g.stride[t];
             idx = q;
         }
     }
     return off;
+}
+
+// ---- kernel parameters read at the point of use ------------------------------------------------
+// The mode groups of a contraction are needed only when a tile starts and when it is stored.
+// Taken from the by-value kernel argument they would be loaded at kernel entry and stay in scalar
+// registers across the K loop, where the spills cost v_readlane instructions between the MFMAs.
+// Reading them from the kernel-argument segment (explicit arguments start at offset 0 of it)
+// through a pointer the compiler cannot trace keeps the loads where they are written.
+#define FG_CONST __attribute__((address_space(4)))
+template <class T>
+__device__ __forceinline__ T load_param(unsigned offset) {
+    static_assert(sizeof(T) % 4 == 0, "parameters are copied word by word");
+    const FG_CONST char *base = (const FG_CONST char *)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(base));
+    const FG_CONST uint32_t *src = (const FG_CONST uint32_t *)(base + offset);
+    T v;
+    uint32_t *dst = (uint32_t *)&v;
+#pragma unroll
+    for (unsigned w = 0; w < sizeof(T) / 4; ++w) dst[w] = src[w];
+    return v;
 }
 
 // ---- global -> LDS tile loader ----------------------------------------------------------------
@@ -177,7 +199,10 @@ struct TileLoader {
     uint32_t voff[SLABS];    // per-lane byte offset from the moving base (per slab)
     const char *base;        // uniform: start of this block's panel at the current K step
     int64_t kstep_bytes;     // uniform: plain matrices, bytes to advance per K step
-    ModeGroup kg;            // contraction: K mode group (for the per-step offset)
+    int kn, kext[kMaxGroupModes];     // contraction: summed modes (count, extents, element strides)
+    int64_t kstr[kMaxGroupModes];
+    int kdigit[kMaxGroupModes];   // contraction: mixed-radix digits of the current K step's first k
+    int64_t koff;            // contraction: element offset of those digits (kept incrementally)
     int ktile;
 
     __device__ __forceinline__ void init(const _Float16 *ptr, int row0, int wave, int lane,
@@ -188,8 +213,13 @@ struct TileLoader {
             kstep_bytes = BK * ks * 2;
         } else {
             base = (const char *)ptr;
-            kg = kgrp;
+            kn = kgrp.n;
+#pragma unroll
+            for (int t = 0; t < kMaxGroupModes; ++t) { kext[t] = kgrp.extent[t]; kstr[t] = kgrp.stride[t]; }
             kstep_bytes = 0;
+            koff = 0;
+#pragma unroll
+            for (int t = 0; t < kMaxGroupModes; ++t) kdigit[t] = 0;
         }
 #pragma unroll
         for (int s = 0; s < SLABS; ++s) {
@@ -227,7 +257,7 @@ struct TileLoader {
     u32x4 rsrc_cur;
     __device__ __forceinline__ void begin() {
         const char *b = base;
-        if constexpr (STRIDED) b += group_offset(kg, ktile * BK) * 2;
+        if constexpr (STRIDED) b += koff * 2;
         rsrc_cur = make_rsrc(b);
     }
     __device__ __forceinline__ void issue_slab(FG_LDS char *lds_tile, int wave, int s) {
@@ -236,6 +266,21 @@ struct TileLoader {
     }
     __device__ __forceinline__ void advance() {
         if constexpr (!STRIDED) base += kstep_bytes;
+        else {
+            // odometer step of BK along the leading summed mode (its extent is a multiple of BK);
+            // a carry moves one step along the next mode
+            kdigit[0] += BK;
+            koff += (int64_t)BK * kstr[0];
+#pragma unroll
+            for (int t = 0; t + 1 < kMaxGroupModes; ++t) {
+                if (kdigit[t] >= kext[t] && t + 1 < kn) {
+                    kdigit[t] = 0;
+                    koff -= (int64_t)kext[t] * kstr[t];
+                    kdigit[t + 1] += 1;
+                    koff += kstr[t + 1];
+                }
+            }
+        }
         ++ktile;
     }
     __device__ __forceinline__ void issue(FG_LDS char *lds_tile, int wave) {
@@ -407,64 +452,41 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                                                       128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, 0);
             }
         }
-    } else if (p.c_fast) {
-        // tensor contraction, common case: the leading column mode of C has an extent that is a
-        // multiple of 8, so the 8 columns 8q .. 8q+7 of an accumulator are evenly spaced, and C
-        // spans less than 2 GiB.  Per-lane part of the offset: the row (one mixed-radix sum per
-        // sub-tile row); the column part is wave-uniform.
-        const int s0 = (int)p.c_n.stride[0];
+    } else {
+        // tensor contraction: element offsets are mixed-radix sums over C's row and column modes.
+        // Row part: per lane, once per sub-tile row.  Column part: wave-uniform except that the
+        // upper half-wave sits 4 columns further, so each store picks one of two scalar values.
+        // C spans less than 2 GiB (checked by the host), so offsets are 32-bit buffer offsets.
         __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(HAS_C ? Cp : Dp), 0, 0x7fffffff, 0x00020000);
         __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(Dp, 0, 0x7fffffff, 0x00020000);
-        int col4[Cfg::TJ][4];
+        const ModeGroup c_m = load_param<ModeGroup>(offsetof(GemmParams, c_m));
+        const ModeGroup c_n = load_param<ModeGroup>(offsetof(GemmParams, c_n));
+        int row4[Cfg::TI];
 #pragma unroll
-        for (int j = 0; j < Cfg::TJ; ++j)
+        for (int i = 0; i < Cfg::TI; ++i) row4[i] = (int)group_offset(c_m, m_base + 32 * i + lm) * 4;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) col4[j][q] = (int)group_offset(p.c_n, n_base + 32 * j + 8 * q) * 4;
+        for (int j = 0; j < Cfg::TJ; ++j) {
+            int col4[16];
 #pragma unroll
-        for (int i = 0; i < Cfg::TI; ++i) {
-            const int voff = ((int)group_offset(p.c_m, m_base + 32 * i + lm) + 4 * lh * s0) * 4;
+            for (int r = 0; r < 16; ++r) {
+                const int n = n_base + 32 * j + 8 * (r >> 2) + (r & 3);
+                const int lo = (int)group_offset(c_n, n) * 4, hi = (int)group_offset(c_n, n + 4) * 4;
+                col4[r] = lh ? hi : lo;
+            }
 #pragma unroll
-            for (int j = 0; j < Cfg::TJ; ++j) {
+            for (int i = 0; i < Cfg::TI; ++i) {
                 float cv[16];
                 if constexpr (HAS_C) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        cv[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, voff, col4[j][r >> 2] + (r & 3) * s0 * 4, 0));
+                        cv[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, row4[i] + col4[r], 0, 0));
                 }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     float y = p.alpha * acc[i][j][r];
                     if constexpr (HAS_C) y += p.beta * cv[r];
                     y = y > floor_v ? y : floor_v;
-                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, voff, col4[j][r >> 2] + (r & 3) * s0 * 4, 0);
-                }
-            }
-        }
-    } else {
-        // tensor contraction, general case: element offsets are mixed-radix sums over C's row and
-        // column modes
-#pragma unroll
-        for (int i = 0; i < Cfg::TI; ++i) {
-            const int m = m_base + 32 * i + lm;
-            const int64_t row_off = group_offset(p.c_m, m);
-#pragma unroll
-            for (int j = 0; j < Cfg::TJ; ++j) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    int64_t off[4];
-                    float cv[4];
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) off[t] = row_off + group_offset(p.c_n, n_base + 32 * j + 8 * q + 4 * lh + t);
-                    if constexpr (HAS_C) {
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) cv[t] = Cp[off[t]];
-                    }
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        float y = p.alpha * acc[i][j][4 * q + t];
-                        if constexpr (HAS_C) y += p.beta * cv[t];
-                        Dp[off[t]] = y > floor_v ? y : floor_v;
-                    }
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, row4[i] + col4[r], 0, 0);
                 }
             }
         }
@@ -538,12 +560,19 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
         nkt = kt1 > kt0 ? kt1 - kt0 : 0;
         const _Float16 *ap[2] = {p.A, p.A_im};
         const _Float16 *bp[2] = {p.B, p.B_im};
+        ModeGroup g_am = {}, g_ak = {}, g_bn = {}, g_bk = {};
+        if constexpr (Cfg::STRIDED) {
+            g_am = load_param<ModeGroup>(offsetof(GemmParams, a_m));
+            g_ak = load_param<ModeGroup>(offsetof(GemmParams, a_k));
+            g_bn = load_param<ModeGroup>(offsetof(GemmParams, b_n));
+            g_bk = load_param<ModeGroup>(offsetof(GemmParams, b_k));
+        }
 #pragma unroll
         for (int q = 0; q < P; ++q) {
             if constexpr (Cfg::DIAG == 1) la[q].init(ap[q], m0, p.M < p.K ? p.M : p.K, wave, lane);
-            else la[q].init(ap[q], m0, wave, lane, p.a_rs, p.a_ks, p.a_m, p.a_k);
+            else la[q].init(ap[q], m0, wave, lane, p.a_rs, p.a_ks, g_am, g_ak);
             if constexpr (Cfg::DIAG == 2) lb[q].init(bp[q], n0, p.N < p.K ? p.N : p.K, wave, lane);
-            else lb[q].init(bp[q], n0, wave, lane, p.b_rs, p.b_ks, p.b_n, p.b_k);
+            else lb[q].init(bp[q], n0, wave, lane, p.b_rs, p.b_ks, g_bn, g_bk);
             if constexpr (Cfg::DIAG != 0) { la[q].skip(kt0); lb[q].skip(kt0); }
         }
 #pragma unroll
