@@ -26,9 +26,12 @@
  *   - Alignment: element base pointers must be 16-byte aligned; leading dimensions of FP16
  *     operands must be multiples of 8 and of FP32 operands multiples of 4 (Section 4.2.2:
  *     the aligned layouts that permit 128-bit accesses).  Otherwise FG_ERR_ALIGN.
- *   - Sizes: M, N multiples of 64 and K a multiple of 64 (the paper requires inputs padded to
- *     the tile sizes, Section 7).  Otherwise FG_ERR_UNSUPPORTED.  M, N or K equal to zero is
- *     accepted: with M == 0 or N == 0 nothing is done; with K == 0 the product term is zero.
+ *   - Sizes: M and N are arbitrary; tiles that hang over the edge of a matrix are predicated
+ *     (the paper requires inputs padded to the tile sizes and names predication as future work,
+ *     Section 7).  K must be a multiple of 8, otherwise FG_ERR_UNSUPPORTED.  M, N or K equal to
+ *     zero is accepted: with M == 0 or N == 0 nothing is done; with K == 0 the product term is
+ *     zero.  The kernels may read (never write) up to 14 bytes past the last element of A or B
+ *     inside the same 16-byte chunk.
  *   - D may alias C exactly (same pointer, layout and ld: the in-place BLAS form).  A and B
  *     must not overlap D.
  */

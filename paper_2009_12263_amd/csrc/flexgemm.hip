@@ -53,39 +53,38 @@ const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
     return fg::kernel_table_tt();
 }
 
-// The params heuristic: the largest block tile that divides the problem and still gives every
-// compute unit a workgroup; if none fills the GPU, the smallest tile that divides the problem.
-int choose_tile(int64_t M, int64_t N) {
+// The params heuristic (Section 4.2.1 picks the largest tile that fits shared memory; here every
+// tile fits, so the question is how many workgroups a tile shape leaves): the largest block tile
+// that still gives every compute unit a workgroup, else the smallest tile.  Edge tiles are
+// predicated, so a tile need not divide a matrix; the contraction kernels have no edge
+// predication and take only tiles that divide (must_divide; -1 if none does).
+int choose_tile(int64_t M, int64_t N, bool must_divide = false) {
     static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64};
     static const int bn[fg::TILE_COUNT] = {256, 128, 128, 64};
-    // tuning aid: FG_FORCE_TILE=0..3 picks a tile shape if it divides the problem
+    auto fits = [&](int t) { return !must_divide || (M % bm[t] == 0 && N % bn[t] == 0); };
+    // tuning aid: FG_FORCE_TILE=0..3 picks a tile shape
     if (const char *f = getenv("FG_FORCE_TILE")) {
         int t = atoi(f);
-        if (t >= 0 && t < fg::TILE_COUNT && M % bm[t] == 0 && N % bn[t] == 0) return t;
+        if (t >= 0 && t < fg::TILE_COUNT && fits(t)) return t;
     }
-    int last_fit = -1;
+    int last = -1;
     for (int t = 0; t < fg::TILE_COUNT; ++t) {
-        if (M % bm[t] || N % bn[t]) continue;
-        last_fit = t;
-        if ((M / bm[t]) * (N / bn[t]) >= kNumCU) return t;
+        if (!fits(t)) continue;
+        last = t;
+        if (((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]) >= kNumCU) return t;
     }
-    return last_fit;
+    return last;
 }
 
-
-// Kernel variant for a normalised problem (nullptr: no tile divides it).
 int choose_ctile(int64_t M, int64_t N) {
     static const int bm[fg::CTILE_COUNT] = {256, 128, 64};
     static const int bn[fg::CTILE_COUNT] = {128, 128, 64};
-    int last_fit = -1;
-    for (int t = 0; t < fg::CTILE_COUNT; ++t) {
-        if (M % bm[t] || N % bn[t]) continue;
-        last_fit = t;
-        if ((M / bm[t]) * (N / bn[t]) >= kNumCU) return t;
-    }
-    return last_fit;
+    for (int t = 0; t < fg::CTILE_COUNT; ++t)
+        if (((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]) >= kNumCU) return t;
+    return fg::CTILE_COUNT - 1;
 }
 
+// Kernel variant for a normalised problem.
 const fg::KernelEntry *select_kernel(const Problem &q) {
     if (q.cplx) {
         const int t = choose_ctile(q.M, q.N);
@@ -133,8 +132,7 @@ fg_status launch(const fg::KernelEntry &k, const fg::GemmParams &p, hipStream_t 
 
 fg_status check_sizes(int64_t M, int64_t N, int64_t K) {
     if (M < 0 || N < 0 || K < 0) return fail(FG_ERR_SHAPE, "negative size M=%lld N=%lld K=%lld", (long long)M, (long long)N, (long long)K);
-    if (M % 64 || N % 64 || K % 64)
-        return fail(FG_ERR_UNSUPPORTED, "M, N and K must be multiples of 64 (got %lld, %lld, %lld)", (long long)M, (long long)N, (long long)K);
+    if (K % 8) return fail(FG_ERR_UNSUPPORTED, "K must be a multiple of 8 (got %lld)", (long long)K);
     if (M > (1 << 30) || N > (1 << 30) || K > (1 << 30)) return fail(FG_ERR_UNSUPPORTED, "sizes above 2^30 are not supported");
     return FG_OK;
 }
@@ -389,11 +387,16 @@ fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix 
     fg::GemmParams p;
     memset(&p, 0, sizeof p);
     p.M = (int32_t)q.M; p.N = (int32_t)q.N; p.K = (int32_t)q.K;
-    p.tiles_m = (int32_t)(q.M / k.bm); p.tiles_n = (int32_t)(q.N / k.bn);
+    p.tiles_m = (int32_t)((q.M + k.bm - 1) / k.bm); p.tiles_n = (int32_t)((q.N + k.bn - 1) / k.bn);
     p.A = (const _Float16 *)q.A; p.B = (const _Float16 *)q.B;
     p.A_im = (const _Float16 *)q.A_im; p.B_im = (const _Float16 *)q.B_im;
     p.a_rs = q.a_kc ? q.lda : 1; p.a_ks = q.a_kc ? 1 : q.lda;
     p.b_rs = q.b_kc ? q.ldb : 1; p.b_ks = q.b_kc ? 1 : q.ldb;
+    // stored span of each operand, rounded up to whole 16-byte chunks (see TileLoader::begin)
+    auto span8 = [](bool kc, int64_t rows, int64_t k, int64_t ld) { int64_t s = kc ? (rows - 1) * ld + k : (k - 1) * ld + rows; return (s + 7) / 8 * 8; };
+    p.a_span = q.K > 0 ? span8(q.a_kc, q.M, q.K, q.lda) : 0;
+    p.b_span = q.K > 0 ? span8(q.b_kc, q.N, q.K, q.ldb) : 0;
+    if (p.a_span * 2 >= (1ll << 31) || p.b_span * 2 >= (1ll << 31)) return fail(FG_ERR_UNSUPPORTED, "A and B must each span less than 2 GiB");
     p.C = q.C; p.D = q.D; p.C_im = q.C_im; p.D_im = q.D_im; p.ldc = q.ldc; p.ldd = q.ldd;
     p.bias = q.bias; p.bias_dim = q.bias_dim; p.act = q.act; p.has_c = q.C != nullptr;
     p.alpha = q.alpha; p.beta = q.beta;
@@ -438,7 +441,7 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
                                         Cin, Cout, n_modes, mode_labels, mode_extents, c))
         return st;
     if (c.M == 0 || c.N == 0) return FG_OK;
-    const int tile = choose_tile(c.M, c.N);
+    const int tile = choose_tile(c.M, c.N, true);
     if (tile < 0) return fail(FG_ERR_UNSUPPORTED, "no block tile divides the merged extents M=%lld, N=%lld", (long long)c.M, (long long)c.N);
     const fg::KernelEntry &k = table_for(c.a_kc, c.b_kc)[fg::entry_index(tile, true)];
     fg::GemmParams p;

@@ -56,6 +56,7 @@ struct GemmParams {
     const float *bias;
     // plain matrices: offsets of element (row, k) are row*a_rs + k*a_ks (one of them is 1)
     int64_t a_rs, a_ks, b_rs, b_ks;
+    int64_t a_span, b_span;           // plain matrices: elements from the base to one past the last (rounded up to 8)
     int64_t ldc, ldd;                 // column-major C and D: (m, n) at m + n*ld
     float alpha, beta;
     int32_t bias_dim, act, has_c;
@@ -124,17 +125,21 @@ template <int R>
 __device__ __forceinline__ int mc_swz(int krow) { return krow & ((R / 32 - 1) < 3 ? (R / 32 - 1) : 3); }
 
 // ---- buffer resources and direct-to-LDS loads ------------------------------------------------
-// Raw buffer descriptor over a 2 GiB window starting at p (p is workgroup-uniform, so the four
-// words live in scalar registers).
-__device__ __forceinline__ u32x4 make_rsrc(const void *p) {
+// Raw buffer descriptor over `bytes` bytes starting at p (p is workgroup-uniform, so the four
+// words live in scalar registers).  A load whose byte offset reaches past `bytes` returns zeros
+// and touches no memory: that is how tiles that hang over the edge of a matrix are predicated
+// (the paper leaves this to future work, Section 7).
+__device__ __forceinline__ u32x4 make_rsrc(const void *p, uint32_t bytes = 0x7fffffffu) {
     uint64_t a = (uint64_t)p;
     u32x4 r;
     r[0] = (uint32_t)a;
     r[1] = (uint32_t)(a >> 32) & 0xffffu;   // stride 0: offsets are plain byte offsets
-    r[2] = 0x7fffffffu;                     // num_records (bytes)
+    r[2] = bytes;                           // num_records (bytes)
     r[3] = 0x00020000u;                     // 32-bit data format, no swizzle
     return r;
 }
+
+constexpr uint32_t kOutOfRange = 0x80000000u;   // a byte offset no descriptor of ours reaches
 
 // 64 lanes x 16 bytes from global memory straight into LDS: lane l's 16 bytes land at
 // lds_addr + 16*l.  lds_addr is wave-uniform (it goes to M0).  The load is tracked by vmcnt only;
@@ -171,11 +176,12 @@ __device__ __forceinline__ int64_t group_offset(const ModeGroup &g, int idx) {
 }
 
 // ---- kernel parameters read at the point of use ------------------------------------------------
-// The mode groups of a contraction are needed only when a tile starts and when it is stored.
-// Taken from the by-value kernel argument they would be loaded at kernel entry and stay in scalar
+// Almost all parameters are needed only when an output tile starts and when it is stored.  Taken
+// from the by-value kernel argument they would be loaded at kernel entry and stay in scalar
 // registers across the K loop, where the spills cost v_readlane instructions between the MFMAs.
 // Reading them from the kernel-argument segment (explicit arguments start at offset 0 of it)
-// through a pointer the compiler cannot trace keeps the loads where they are written.
+// through a pointer the compiler cannot trace keeps the loads where they are written; words of
+// the copy that are not used are never loaded.
 #define FG_CONST __attribute__((address_space(4)))
 template <class T>
 __device__ __forceinline__ T load_param(unsigned offset) {
@@ -204,13 +210,25 @@ struct TileLoader {
     int kdigit[kMaxGroupModes];   // contraction: mixed-radix digits of the current K step's first k
     int64_t koff;            // contraction: element offset of those digits (kept incrementally)
     int ktile;
+    // plain matrices: one byte past the last stored element, the extent of K, and (K-contiguous
+    // operands) the k offset inside the tile of the chunk this lane fetches in each slab
+    int rem;                 // bytes from `base` to the end of the stored span (may be <= 0)
+    int kstep32;
+    int kdim, klim;          // extent of K; k's left from the current K step on
+    int kchunk[SLABS];
 
     __device__ __forceinline__ void init(const _Float16 *ptr, int row0, int wave, int lane,
-                                         int64_t rs, int64_t ks, const ModeGroup &rg, const ModeGroup &kgrp) {
+                                         int64_t rs, int64_t ks, const ModeGroup &rg, const ModeGroup &kgrp,
+                                         int64_t span = 0, int kdim_ = 0) {
         ktile = 0;
+        klim = BK;
         if constexpr (!STRIDED) {
             base = (const char *)(ptr + (int64_t)row0 * rs);
             kstep_bytes = BK * ks * 2;
+            kstep32 = (int)kstep_bytes;
+            int64_t left = (span - (int64_t)row0 * rs) * 2;          // the host keeps spans below 2 GiB
+            rem = left > 0 ? (int)left : 0;
+            kdim = kdim_;
         } else {
             base = (const char *)ptr;
             kn = kgrp.n;
@@ -231,6 +249,7 @@ struct TileLoader {
                 constexpr int CPR = BK / 8;
                 int r = slab * (64 / CPR) + lane / CPR;
                 int c = (lane % CPR) ^ kc_swz<BK>(r);
+                kchunk[s] = c * 8;
                 if constexpr (!STRIDED) off = (int64_t)r * rs + c * 8;
                 else off = group_offset(rg, row0 + r) + c * 8;     // leading K mode has stride 1
             } else {
@@ -248,25 +267,45 @@ struct TileLoader {
 
     // start at K tile kt0 instead of 0 (plain matrices only)
     __device__ __forceinline__ void skip(int kt0) {
-        if constexpr (!STRIDED) base += kstep_bytes * kt0;
+        if constexpr (!STRIDED) {
+            base += kstep_bytes * kt0;
+            int64_t left = (int64_t)rem - kstep_bytes * kt0;
+            rem = left > 0 ? (int)left : 0;
+        }
         ktile = kt0;
     }
 
     // The loads of one K step can be issued all at once (issue) or slab by slab between other
     // instructions (begin, issue_slab x SLABS, advance).
     u32x4 rsrc_cur;
+    // Edges of a plain matrix: rows past the last one and (M/N-contiguous operands) k past K lie
+    // beyond the stored span, so the descriptor returns zeros for them.  Rows that merely run into
+    // the next column or row of the matrix read finite garbage that only reaches result rows or
+    // columns nobody stores.  A K-contiguous operand's k >= K would read the neighbouring row, so
+    // those chunks are sent out of range explicitly in the last K step.
     __device__ __forceinline__ void begin() {
         const char *b = base;
-        if constexpr (STRIDED) b += koff * 2;
-        rsrc_cur = make_rsrc(b);
+        if constexpr (STRIDED) {
+            b += koff * 2;
+            rsrc_cur = make_rsrc(b);
+        } else {
+            rsrc_cur = make_rsrc(b, (uint32_t)(rem > 0 ? rem : 0));
+            klim = kdim - ktile * BK;
+        }
     }
     __device__ __forceinline__ void issue_slab(FG_LDS char *lds_tile, int wave, int s) {
         uint32_t dst = (uint32_t)(uintptr_t)lds_tile + (uint32_t)(wave * SLABS + s) * 1024u;
-        load16_to_lds(rsrc_cur, dst, voff[s]);
+        uint32_t v = voff[s];
+        if constexpr (KC && !STRIDED) {
+            if (kchunk[s] >= klim) v = kOutOfRange;       // only ever true in the last K step
+        }
+        load16_to_lds(rsrc_cur, dst, v);
     }
     __device__ __forceinline__ void advance() {
-        if constexpr (!STRIDED) base += kstep_bytes;
-        else {
+        if constexpr (!STRIDED) {
+            base += kstep_bytes;
+            rem = rem > kstep32 ? rem - kstep32 : 0;
+        } else {
             // odometer step of BK along the leading summed mode (its extent is a multiple of BK);
             // a carry moves one step along the next mode
             kdigit[0] += BK;
@@ -409,47 +448,77 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
     if constexpr (!Cfg::STRIDED) {
         // (m, n) at m + n*ld.  All accesses are buffer operations on a descriptor whose base is this
         // wave's corner of the tile: the per-lane part of the address is one register for all of
-        // them, the rest is a scalar offset.  The C values of accumulator b+1 are requested before
-        // accumulator b is stored, so a batch of loads never queues behind the previous stores.
+        // them, the rest is a scalar offset.
         const int voff_c = (lm + 4 * lh * (int)p.ldc) * 4;
         const int voff_d = (lm + 4 * lh * (int)p.ldd) * 4;
         const int ldc4 = (int)p.ldc * 4, ldd4 = (int)p.ldd * 4;
         __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<float *>(HAS_C ? Cp + m_base + (int64_t)n_base * p.ldc : Dp), 0, 0x7fffffff, 0x00020000);
         __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(Dp + m_base + (int64_t)n_base * p.ldd, 0, 0x7fffffff, 0x00020000);
-        constexpr int NB = Cfg::TI * Cfg::TJ;
-        float cv[2][16];
-        auto load_c = [&](int b, float (&dst)[16]) {
-            const int i = b / Cfg::TJ, j = b % Cfg::TJ;
+        const bool interior = m_base + Cfg::WTM <= p.M && n_base + Cfg::WTN <= p.N;
+        if (interior) {
+            // The C values of accumulator b+1 are requested before accumulator b is stored, so a
+            // batch of loads never queues behind the previous stores.
+            constexpr int NB = Cfg::TI * Cfg::TJ;
+            float cv[2][16];
+            auto load_c = [&](int b, float (&dst)[16]) {
+                const int i = b / Cfg::TJ, j = b % Cfg::TJ;
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                dst[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                             rc, voff_c, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, 0));
-        };
-        float bias_m[Cfg::TI];
+                for (int r = 0; r < 16; ++r)
+                    dst[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                 rc, voff_c, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, 0));
+            };
+            float bias_m[Cfg::TI];
 #pragma unroll
-        for (int i = 0; i < Cfg::TI; ++i) bias_m[i] = bias_m_on ? p.bias[m_base + 32 * i + lm] : 0.f;
-        if constexpr (HAS_C) load_c(0, cv[0]);
+            for (int i = 0; i < Cfg::TI; ++i) bias_m[i] = bias_m_on ? p.bias[m_base + 32 * i + lm] : 0.f;
+            if constexpr (HAS_C) load_c(0, cv[0]);
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int i = b / Cfg::TJ, j = b % Cfg::TJ;
-            if constexpr (HAS_C) {
-                if (b + 1 < NB) load_c(b + 1, cv[(b + 1) & 1]);
+            for (int b = 0; b < NB; ++b) {
+                const int i = b / Cfg::TJ, j = b % Cfg::TJ;
+                if constexpr (HAS_C) {
+                    if (b + 1 < NB) load_c(b + 1, cv[(b + 1) & 1]);
+                }
+                float bv[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) bv[r] = bias_m[i];
+                if (bias_n_on) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) bv[r] = p.bias[n_base + 32 * j + 8 * (r >> 2) + 4 * lh + (r & 3)];
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float y = p.alpha * acc[i][j][r] + bv[r];
+                    if constexpr (HAS_C) y += p.beta * cv[b & 1][r];
+                    y = y > floor_v ? y : floor_v;
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, voff_d,
+                                                          128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, 0);
+                }
             }
-            float bv[16];
+        } else {
+            // a tile that hangs over the edge of D: rows m >= M are masked per lane (their offset is
+            // sent out of the descriptor's range, which drops the access), columns n >= N per column
 #pragma unroll
-            for (int r = 0; r < 16; ++r) bv[r] = bias_m[i];
-            if (bias_n_on) {
+            for (int i = 0; i < Cfg::TI; ++i) {
+                const int m = m_base + 32 * i + lm;
+                const bool m_ok = m < p.M;
+                const uint32_t vc = m_ok ? (uint32_t)voff_c : kOutOfRange, vd = m_ok ? (uint32_t)voff_d : kOutOfRange;
+                const float bias_mi = (bias_m_on && m_ok) ? p.bias[m] : 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) bv[r] = p.bias[n_base + 32 * j + 8 * (r >> 2) + 4 * lh + (r & 3)];
-            }
+                for (int j = 0; j < Cfg::TJ; ++j) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float y = p.alpha * acc[i][j][r] + bv[r];
-                if constexpr (HAS_C) y += p.beta * cv[b & 1][r];
-                y = y > floor_v ? y : floor_v;
-                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, voff_d,
-                                                      128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, 0);
+                    for (int r = 0; r < 16; ++r) {
+                        const int ncol = n_base + 32 * j + 8 * (r >> 2) + (r & 3);     // + 4 for the upper half-wave
+                        const bool n_ok = ncol + 4 * lh < p.N;
+                        float y = p.alpha * acc[i][j][r] + bias_mi;
+                        if (bias_n_on && n_ok) y += p.bias[ncol + 4 * lh];
+                        if constexpr (HAS_C)
+                            y += p.beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                              rc, n_ok ? vc : kOutOfRange, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, 0));
+                        y = y > floor_v ? y : floor_v;
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, n_ok ? vd : kOutOfRange,
+                                                              128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, 0);
+                    }
+                }
             }
         }
     } else {
@@ -459,8 +528,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
         // C spans less than 2 GiB (checked by the host), so offsets are 32-bit buffer offsets.
         __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(HAS_C ? Cp : Dp), 0, 0x7fffffff, 0x00020000);
         __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(Dp, 0, 0x7fffffff, 0x00020000);
-        const ModeGroup c_m = load_param<ModeGroup>(offsetof(GemmParams, c_m));
-        const ModeGroup c_n = load_param<ModeGroup>(offsetof(GemmParams, c_n));
+        const ModeGroup &c_m = p.c_m, &c_n = p.c_n;
         int row4[Cfg::TI];
 #pragma unroll
         for (int i = 0; i < Cfg::TI; ++i) row4[i] = (int)group_offset(c_m, m_base + 32 * i + lm) * 4;
@@ -547,32 +615,27 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
 
     // start the loads of a tile: point the loaders at its panels and fill the ring
     auto start_tile = [&](int tile_id, int &m0, int &n0) {
+        // parameters are re-read here rather than kept in registers across the K loop
+        const GemmParams tp = load_param<GemmParams>(0);
         int tm, tn;
-        block_to_tile(tile_id, p.tiles_m, p.tiles_n, tm, tn);
+        block_to_tile(tile_id, tp.tiles_m, tp.tiles_n, tm, tn);
         m0 = tm * BM;
         n0 = tn * BN;
-        const int nk = p.K / BK;
+        const int nk = (tp.K + BK - 1) / BK;
         kt0 = 0;
         int kt1 = nk;
         if constexpr (Cfg::DIAG == 1) { kt0 = m0 / BK; kt1 = (m0 + BM) / BK; }
         if constexpr (Cfg::DIAG == 2) { kt0 = n0 / BK; kt1 = (n0 + BN) / BK; }
         if (kt1 > nk) kt1 = nk;
         nkt = kt1 > kt0 ? kt1 - kt0 : 0;
-        const _Float16 *ap[2] = {p.A, p.A_im};
-        const _Float16 *bp[2] = {p.B, p.B_im};
-        ModeGroup g_am = {}, g_ak = {}, g_bn = {}, g_bk = {};
-        if constexpr (Cfg::STRIDED) {
-            g_am = load_param<ModeGroup>(offsetof(GemmParams, a_m));
-            g_ak = load_param<ModeGroup>(offsetof(GemmParams, a_k));
-            g_bn = load_param<ModeGroup>(offsetof(GemmParams, b_n));
-            g_bk = load_param<ModeGroup>(offsetof(GemmParams, b_k));
-        }
+        const _Float16 *ap[2] = {tp.A, tp.A_im};
+        const _Float16 *bp[2] = {tp.B, tp.B_im};
 #pragma unroll
         for (int q = 0; q < P; ++q) {
-            if constexpr (Cfg::DIAG == 1) la[q].init(ap[q], m0, p.M < p.K ? p.M : p.K, wave, lane);
-            else la[q].init(ap[q], m0, wave, lane, p.a_rs, p.a_ks, g_am, g_ak);
-            if constexpr (Cfg::DIAG == 2) lb[q].init(bp[q], n0, p.N < p.K ? p.N : p.K, wave, lane);
-            else lb[q].init(bp[q], n0, wave, lane, p.b_rs, p.b_ks, g_bn, g_bk);
+            if constexpr (Cfg::DIAG == 1) la[q].init(ap[q], m0, tp.M < tp.K ? tp.M : tp.K, wave, lane);
+            else la[q].init(ap[q], m0, wave, lane, tp.a_rs, tp.a_ks, tp.a_m, tp.a_k, tp.a_span, tp.K);
+            if constexpr (Cfg::DIAG == 2) lb[q].init(bp[q], n0, tp.N < tp.K ? tp.N : tp.K, wave, lane);
+            else lb[q].init(bp[q], n0, wave, lane, tp.b_rs, tp.b_ks, tp.b_n, tp.b_k, tp.b_span, tp.K);
             if constexpr (Cfg::DIAG != 0) { la[q].skip(kt0); lb[q].skip(kt0); }
         }
 #pragma unroll
@@ -747,11 +810,14 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
             start_tile(next, m1, n1);
         }
 
-        if (p.has_c) epilogue<Cfg, true>(p, p.C, p.D, acc[0], m_base, n_base, lane);
-        else epilogue<Cfg, false>(p, p.C, p.D, acc[0], m_base, n_base, lane);
-        if constexpr (Cfg::CPLX) {
-            if (p.has_c) epilogue<Cfg, true>(p, p.C_im, p.D_im, acc[1], m_base, n_base, lane);
-            else epilogue<Cfg, false>(p, p.C_im, p.D_im, acc[1], m_base, n_base, lane);
+        {
+            const GemmParams ep = load_param<GemmParams>(0);
+            if (ep.has_c) epilogue<Cfg, true>(ep, ep.C, ep.D, acc[0], m_base, n_base, lane);
+            else epilogue<Cfg, false>(ep, ep.C, ep.D, acc[0], m_base, n_base, lane);
+            if constexpr (Cfg::CPLX) {
+                if (ep.has_c) epilogue<Cfg, true>(ep, ep.C_im, ep.D_im, acc[1], m_base, n_base, lane);
+                else epilogue<Cfg, false>(ep, ep.C_im, ep.D_im, acc[1], m_base, n_base, lane);
+            }
         }
 
         if (!more_tiles) break;

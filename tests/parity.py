@@ -32,7 +32,7 @@ def make_operand(rows: int, cols: int, layout: int, stream: int, device, ints: b
     Returns (device tensor, ld)."""
     lead = rows if layout == fg.FG_COL else cols
     other = cols if layout == fg.FG_COL else rows
-    ld = lead + pad
+    ld = (lead + 7) // 8 * 8 + pad          # leading dimensions of FP16 operands are multiples of 8
     gen = W.small_ints if ints else W.uniform_pm1
     t = gen(ld * other, stream, seed=seed, device=device, dtype=torch.float16)
     return t, ld
@@ -86,7 +86,7 @@ def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alph
     A, lda = make_operand(M, K, la, W.stream_id(config, "A"), device, ints, pad, seed)
     B, ldb = make_operand(K, N, lb, W.stream_id(config, "B"), device, ints, pad, seed)
     lead, other = (M, N) if ld_layout == fg.FG_COL else (N, M)
-    ldc = lead + (4 if pad else 0)
+    ldc = (lead + 3) // 4 * 4 + (4 if pad else 0)   # leading dimensions of FP32 operands are multiples of 4
     Cbuf = make_f32(ldc * other, W.stream_id(config, "C"), device, ints, seed) if with_c else None
     bias = None
     if bias_dim is not None:
@@ -173,14 +173,17 @@ def run_diag_case(M, N, K, side="A", other_layout=fg.FG_COL, ld_layout=fg.FG_COL
         mA, mB = fg.Matrix(X, other_layout, ldx), fg.Matrix(dvec, fg.FG_DIAG, 0)
         oA, oB = O.Operand(np16(X), other_layout, ldx), O.Operand(np16(dvec), O.DIAG, 0)
     lead, other = (M, N) if ld_layout == fg.FG_COL else (N, M)
-    Cbuf = make_f32(lead * other, W.stream_id(config, "C"), device, ints, seed) if with_c else None
-    Dbuf = torch.full((lead * other,), float("nan"), dtype=torch.float32, device=device)
-    fg.fg_gemm(M, N, K, alpha, mA, mB, beta, fg.Matrix(Cbuf, ld_layout, lead) if with_c else None, fg.Matrix(Dbuf, ld_layout, lead))
+    ldc = (lead + 3) // 4 * 4
+    Cbuf = make_f32(ldc * other, W.stream_id(config, "C"), device, ints, seed) if with_c else None
+    Dbuf = torch.full((ldc * other,), float("nan"), dtype=torch.float32, device=device)
+    fg.fg_gemm(M, N, K, alpha, mA, mB, beta, fg.Matrix(Cbuf, ld_layout, ldc) if with_c else None, fg.Matrix(Dbuf, ld_layout, ldc))
     torch.cuda.synchronize()
-    Dm = np16(Dbuf).reshape(other, lead)
+    Dm = np16(Dbuf).reshape(other, ldc)
+    assert ldc == lead or np.isnan(Dm[:, lead:]).all(), "padding of D was written"
+    Dm = Dm[:, :lead]
     Dlog = Dm.T if ld_layout == fg.FG_COL else Dm
     at = sample_positions(M, N, samples, seed=M + N + K) if samples is not None else None
-    r = O.gemm(M, N, K, alpha, oA, oB, beta, np16(Cbuf), None, ld_layout, lead, at=at)
+    r = O.gemm(M, N, K, alpha, oA, oB, beta, np16(Cbuf), None, ld_layout, ldc, at=at)
     got = Dlog if at is None else Dlog[at[0], at[1]]
     return compare(got, r["D"], r["G"], 1, ints, "diag-%s gemm M=%d N=%d K=%d other=%d D=%d ints=%s" % (side, M, N, K, other_layout, ld_layout, ints))
 
@@ -193,7 +196,7 @@ def run_cgemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alp
     Br, ldb = make_operand(K, N, lb, W.stream_id(config, "B"), device, ints, pad, seed)
     Bi, _ = make_operand(K, N, lb, W.stream_id(config, "B_im"), device, ints, pad, seed)
     lead, other = (M, N) if ld_layout == fg.FG_COL else (N, M)
-    ldc = lead + (4 if pad else 0)
+    ldc = (lead + 3) // 4 * 4 + (4 if pad else 0)
     Cr = make_f32(ldc * other, W.stream_id(config, "C"), device, ints, seed) if with_c else None
     Ci = make_f32(ldc * other, W.stream_id(config, "C_im"), device, ints, seed) if with_c else None
     Dr = torch.full((ldc * other,), float("nan"), dtype=torch.float32, device=device)

@@ -47,8 +47,8 @@ def test_gemm_argument_errors():
     assert status(256, 256, 256, 1.0, None, B, 0.0, None, D) == fg.FG_ERR_NULL
     assert status(256, 256, 256, 1.0, A, B, 0.0, None, None) == fg.FG_ERR_NULL
     assert status(-1, 256, 256, 1.0, A, B, 0.0, None, D) == fg.FG_ERR_SHAPE
-    assert status(250, 256, 256, 1.0, A, B, 0.0, None, D) == fg.FG_ERR_UNSUPPORTED
-    assert "multiples of 64" in fg.fg_last_error()
+    assert status(256, 256, 250, 1.0, A, B, 0.0, None, D) == fg.FG_ERR_UNSUPPORTED
+    assert "multiple of 8" in fg.fg_last_error()
     A2, B2, D2 = mats(lda=128)
     assert status(256, 256, 256, 1.0, A2, B2, 0.0, None, D2) == fg.FG_ERR_SHAPE
     A3, B3, D3 = mats(lda=260)
@@ -81,8 +81,11 @@ def test_plan_names_follow_sizes_and_layouts():
     assert fg.fg_gemm_plan(256, 256, 256, fg.FG_COL, fg.FG_ROW) == "gemm_nt_64x64x64"
     # a row-major D is computed as the transposed problem: the operands swap roles
     assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_ROW, fg.FG_ROW, fg.FG_ROW) == "gemm_nn_256x256x64"
+    # sizes need not be multiples of the tile: edge tiles are predicated
+    assert fg.fg_gemm_plan(100, 72, 64) == "gemm_nn_64x64x64"
+    assert fg.fg_gemm_plan(5000, 3000, 1000) == "gemm_nn_256x128x64"
     with pytest.raises(fg.FlexGemmError):
-        fg.fg_gemm_plan(100, 64, 64)
+        fg.fg_gemm_plan(128, 64, 60)
 
 
 def contract_status(mA, sA, mB, sB, mC, sC, ext, pa=0x1000, pb=0x2000, pc=0x3000):

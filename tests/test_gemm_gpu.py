@@ -76,3 +76,22 @@ def test_full_size_4096_ints_sampled():
 def test_config3_relu_bias_shapes():
     say("config 3: 4096^3 relu+bias"); run_gemm_case(4096, 4096, 4096, with_c=False, bias_dim=0, act=fg.FG_ACT_RELU, config=3, samples=4096)
     say("config 3: 8192x1024x4096 relu+bias"); run_gemm_case(8192, 1024, 4096, with_c=False, bias_dim=0, act=fg.FG_ACT_RELU, config=3, samples=4096)
+
+
+@pytest.mark.parametrize("la,lb", list(itertools.product(LAYOUTS, LAYOUTS)))
+@pytest.mark.parametrize("ldl", LAYOUTS)
+def test_arbitrary_sizes_edge_tiles(la, lb, ldl):
+    """M and N need not be multiples of any tile, K only of 8: tiles that hang over the edge are
+    predicated.  Integer inputs make every stored entry bit-exact; the NaN-filled padding of D must
+    stay untouched (checked inside run_gemm_case)."""
+    for (M, N, K) in [(1, 1, 8), (7, 5, 16), (65, 63, 72), (100, 260, 200), (257, 129, 264), (300, 520, 136), (777, 1031, 520)]:
+        say("edge ints M=%d N=%d K=%d la=%d lb=%d D=%d" % (M, N, K, la, lb, ldl))
+        run_gemm_case(M, N, K, la, lb, ldl, ints=True, pad=8, config=2)
+    say("edge floats + bias + relu")
+    run_gemm_case(333, 1111, 248, la, lb, ldl, alpha=0.5, beta=-1.0, bias_dim=0, act=fg.FG_ACT_RELU, pad=8, config=3)
+    run_gemm_case(333, 1111, 248, la, lb, ldl, with_c=False, bias_dim=1, pad=8, config=3)
+
+
+def test_arbitrary_sizes_large():
+    say("5000x3000x1000 ints sampled"); run_gemm_case(5000, 3000, 1000, ints=True, config=2, samples=6000)
+    say("4100x4100x4104 floats sampled"); run_gemm_case(4100, 4100, 4104, fg.FG_ROW, fg.FG_COL, config=2, samples=6000)

@@ -45,3 +45,16 @@ def test_complex_config4_4096():
     """BASELINE config 4: planar complex D = A B + C at 4096^3, sampled."""
     say("cgemm 4096 floats"); run_cgemm_case(4096, 4096, 4096, samples=4096)
     say("cgemm 4096 ints"); run_cgemm_case(4096, 4096, 4096, ints=True, samples=4096)
+
+
+def test_edge_tiles_diagonal_and_complex():
+    """Sizes that are not multiples of any tile (K a multiple of 8) for the layout adapters."""
+    for side in ("A", "B"):
+        for other in LAYOUTS:
+            say("diag %s edge other=%d" % (side, other))
+            run_diag_case(300, 200, 264, side, other, ints=True)
+            run_diag_case(70, 333, 72, side, other, fg.FG_ROW, ints=True)
+    for la, lb in itertools.product(LAYOUTS, LAYOUTS):
+        say("cgemm edge la=%d lb=%d" % (la, lb))
+        run_cgemm_case(100, 75, 40, la, lb, ints=True, pad=8)
+        run_cgemm_case(300, 513, 136, la, lb, ld_layout=fg.FG_ROW, alpha=0.5, beta=1.5)
