@@ -44,7 +44,7 @@ class _GemmProblem(C.Structure):
         ("A_re", C.c_void_p), ("A_im", C.c_void_p), ("layoutA", C.c_int32), ("lda", C.c_int64),
         ("B_re", C.c_void_p), ("B_im", C.c_void_p), ("layoutB", C.c_int32), ("ldb", C.c_int64),
         ("C_re", C.c_void_p), ("C_im", C.c_void_p), ("layoutC", C.c_int32), ("ldc", C.c_int64),
-        ("bias", C.c_void_p), ("bias_dim", C.c_int32), ("act", C.c_int32),
+        ("bias", C.c_void_p), ("bias_dim", C.c_int32), ("act", C.c_int32), ("ab_dtype", C.c_int32),
     ]
 
 
@@ -67,6 +67,8 @@ def lib():
         l = C.CDLL(build())
         l.oracle_half_to_double.restype = C.c_double
         l.oracle_half_to_double.argtypes = [C.c_uint16]
+        l.oracle_bf16_to_double.restype = C.c_double
+        l.oracle_bf16_to_double.argtypes = [C.c_uint16]
         pd = C.c_void_p
         l.oracle_gemm_full.restype = C.c_int
         l.oracle_gemm_full.argtypes = [C.POINTER(_GemmProblem), pd, pd, pd, pd, C.c_int]
@@ -91,19 +93,30 @@ def half_to_double(bits: int) -> float:
     return float(lib().oracle_half_to_double(int(bits) & 0xFFFF))
 
 
+def bf16_to_double(bits: int) -> float:
+    return float(lib().oracle_bf16_to_double(int(bits) & 0xFFFF))
+
+
+F16, BF16 = 0, 1
+
+
 @dataclass
 class Operand:
-    """A stored FP16 operand: ``re`` (and ``im`` for planar complex) are flat or 2-D float16
-    arrays whose memory is read as-is; ``layout`` and ``ld`` say how element (r, c) is found."""
+    """A stored 16-bit operand: ``re`` (and ``im`` for planar complex) are flat or 2-D arrays whose
+    memory is read as-is; ``layout`` and ``ld`` say how element (r, c) is found.  float16 arrays
+    hold binary16 values; uint16 arrays hold the bit patterns of ``dtype`` (F16 or BF16)."""
     re: np.ndarray
     layout: int = COL
     ld: int = 0
     im: Optional[np.ndarray] = None
+    dtype: int = F16
 
 
 def _ptr(a: Optional[np.ndarray], dtype) -> Optional[int]:
     if a is None:
         return None
+    if dtype == np.float16 and a.dtype == np.uint16:
+        dtype = np.uint16                       # raw 16-bit patterns
     if a.dtype != dtype or not a.flags["C_CONTIGUOUS"] and not a.flags["F_CONTIGUOUS"]:
         raise ValueError("oracle buffers must be contiguous %s arrays" % np.dtype(dtype).name)
     return a.ctypes.data
@@ -143,6 +156,9 @@ def _gemm_problem(M, N, K, alpha, A: Operand, B: Operand, beta, Cre, Cim, layout
     if bias is not None:
         _check_span(bias, M if bias_dim == 0 else N, "bias")
     q.bias, q.bias_dim, q.act = _ptr(bias, np.float32), bias_dim, act
+    if A.dtype != B.dtype:
+        raise ValueError("A and B must have the same element type")
+    q.ab_dtype = A.dtype
     return q
 
 

@@ -57,15 +57,36 @@ static double half_bits_to_double(uint16_t h) {
     return sign ? -v : v;
 }
 
-static double g_half_table[65536];
+/* ---- bfloat16 -> double, exact: the upper 16 bits of a binary32 ---------------------------- */
+static double bf16_bits_to_double(uint16_t h) {
+    int sign = (h >> 15) & 1;
+    int expo = (h >> 7) & 0xff;
+    int frac = h & 0x7f;
+    double v;
+    if (expo == 0) {
+        v = ldexp((double)frac, -133);                   /* zero and subnormals: frac * 2^-7 * 2^-126 */
+    } else if (expo == 255) {
+        v = frac ? NAN : INFINITY;
+    } else {
+        v = ldexp((double)(128 + frac), expo - 134);     /* (1 + frac/128) * 2^(expo-127) */
+    }
+    return sign ? -v : v;
+}
+
+/* Decode tables for the two 16-bit input types; index 0: binary16, 1: bfloat16. */
+static double g_half_table[2][65536];
 static pthread_once_t g_half_once = PTHREAD_ONCE_INIT;
 static void build_half_table(void) {
-    for (int i = 0; i < 65536; ++i) g_half_table[i] = half_bits_to_double((uint16_t)i);
+    for (int i = 0; i < 65536; ++i) {
+        g_half_table[0][i] = half_bits_to_double((uint16_t)i);
+        g_half_table[1][i] = bf16_bits_to_double((uint16_t)i);
+    }
 }
-static inline double h2d(uint16_t h) { return g_half_table[h]; }
+static inline double h2d(uint16_t h) { return g_half_table[0][h]; }
 
-/* Exposed so the tests can pin the decoder against numpy's float16. */
+/* Exposed so the tests can pin the decoders against independent conversions. */
 double oracle_half_to_double(uint16_t h) { return half_bits_to_double(h); }
+double oracle_bf16_to_double(uint16_t h) { return bf16_bits_to_double(h); }
 
 /* ---- problem descriptions ------------------------------------------------------- */
 
@@ -84,14 +105,15 @@ typedef struct {
     const float *bias;             /* NULL: none                                 */
     int32_t bias_dim;              /* 0: bias[i] (length M), 1: bias[j] (len N)  */
     int32_t act;
+    int32_t ab_dtype;              /* element type of A and B: 0 binary16, 1 bfloat16 */
 } og_problem;
 
 /* logical element (r, c) of a stored rows x cols operand */
-static inline double operand_at(const uint16_t *p, int32_t layout, int64_t ld, int64_t r, int64_t c) {
-    if (layout == OG_COL) return h2d(p[r + c * ld]);
-    if (layout == OG_ROW) return h2d(p[c + r * ld]);
+static inline double operand_at(const uint16_t *p, int32_t layout, int64_t ld, int64_t r, int64_t c, const double *decode) {
+    if (layout == OG_COL) return decode[p[r + c * ld]];
+    if (layout == OG_ROW) return decode[p[c + r * ld]];
     /* OG_DIAG: p is the vector of diagonal entries, everything else is zero */
-    return (r == c) ? h2d(p[r]) : 0.0;
+    return (r == c) ? decode[p[r]] : 0.0;
 }
 
 static inline double c_at(const float *p, int32_t layout, int64_t ld, int64_t i, int64_t j) {
@@ -102,16 +124,17 @@ static inline double c_at(const float *p, int32_t layout, int64_t ld, int64_t i,
 static void gemm_entry(const og_problem *q, int64_t i, int64_t j,
                        double *d_re, double *d_im, double *g_re, double *g_im) {
     const int is_complex = (q->A_im != NULL) || (q->B_im != NULL);
+    const double *dec = g_half_table[q->ab_dtype ? 1 : 0];
     double s_re = 0.0, s_im = 0.0, m_re = 0.0, m_im = 0.0;
     for (int64_t k = 0; k < q->K; ++k) {
-        double ar = operand_at(q->A_re, q->layoutA, q->lda, i, k);
-        double br = operand_at(q->B_re, q->layoutB, q->ldb, k, j);
+        double ar = operand_at(q->A_re, q->layoutA, q->lda, i, k, dec);
+        double br = operand_at(q->B_re, q->layoutB, q->ldb, k, j, dec);
         if (!is_complex) {
             s_re += ar * br;
             m_re += fabs(ar) * fabs(br);
         } else {
-            double ai = q->A_im ? operand_at(q->A_im, q->layoutA, q->lda, i, k) : 0.0;
-            double bi = q->B_im ? operand_at(q->B_im, q->layoutB, q->ldb, k, j) : 0.0;
+            double ai = q->A_im ? operand_at(q->A_im, q->layoutA, q->lda, i, k, dec) : 0.0;
+            double bi = q->B_im ? operand_at(q->B_im, q->layoutB, q->ldb, k, j, dec) : 0.0;
             /* (ar + i ai)(br + i bi): the four real products of Section 5.4 */
             s_re += ar * br - ai * bi;
             s_im += ar * bi + ai * br;
@@ -147,6 +170,7 @@ static int gemm_problem_ok(const og_problem *q) {
     if (q->C_re && q->layoutC != OG_COL && q->layoutC != OG_ROW) return 0;
     if (q->bias && q->bias_dim != 0 && q->bias_dim != 1) return 0;
     if (q->act != OG_ACT_NONE && q->act != OG_ACT_RELU) return 0;
+    if (q->ab_dtype != 0 && q->ab_dtype != 1) return 0;
     const int is_complex = (q->A_im != NULL) || (q->B_im != NULL);
     if (is_complex && (q->bias || q->act != OG_ACT_NONE)) return 0; /* not defined for complex */
     return 1;

@@ -343,3 +343,31 @@ def test_bad_descriptions_are_rejected():
         O.contract({0: 2, 1: 2}, [0, 1], [1, 2], A, [1], [1], A[:2], [0, 5], [1, 2])  # unknown mode in C
     with pytest.raises(ValueError):
         O.gemm(2, 2, 2, 1.0, Operand(A, COL, 2, A), Operand(A, COL, 2), act=ACT_RELU)  # ReLU of a complex value
+
+
+# ---------------------------------------------------------------- bfloat16 inputs
+def test_bf16_decode_matches_torch_for_every_bit_pattern():
+    import torch
+    bits = torch.arange(65536, dtype=torch.int32).to(torch.int16)
+    want = bits.view(torch.bfloat16).to(torch.float64).numpy()
+    got = np.array([O.bf16_to_double(int(b) & 0xFFFF) for b in bits.tolist()])
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+
+
+def test_bf16_gemm_matches_float64_matmul():
+    import torch
+    M, N, K = 9, 7, 13
+    At = torch.from_numpy(rand_mat(M, K)).to(torch.bfloat16)          # logical M x K
+    Bt = torch.from_numpy(rand_mat(K, N)).to(torch.bfloat16)
+    bits = lambda t: t.contiguous().view(torch.int16).numpy().view(np.uint16).reshape(-1)
+    A = bits(At.t())                                                  # column-major storage, ld = M
+    B = bits(Bt)                                                      # row-major storage, ld = N
+    r = O.gemm(M, N, K, 1.0, Operand(A, COL, M, dtype=O.BF16), Operand(B, ROW, N, dtype=O.BF16))
+    want = At.to(torch.float64).numpy() @ Bt.to(torch.float64).numpy()
+    assert np.allclose(r["D"], want, rtol=0, atol=1e-12)
+    # the same bits read as binary16 give a different (wrong) product: the dtype flag matters
+    r16 = O.gemm(M, N, K, 1.0, Operand(A, COL, M, dtype=O.F16), Operand(B, ROW, N, dtype=O.F16))
+    assert not np.allclose(r16["D"], want, rtol=1e-3, atol=1e-3)
