@@ -44,7 +44,7 @@ class _GemmProblem(C.Structure):
         ("A_re", C.c_void_p), ("A_im", C.c_void_p), ("layoutA", C.c_int32), ("lda", C.c_int64),
         ("B_re", C.c_void_p), ("B_im", C.c_void_p), ("layoutB", C.c_int32), ("ldb", C.c_int64),
         ("C_re", C.c_void_p), ("C_im", C.c_void_p), ("layoutC", C.c_int32), ("ldc", C.c_int64),
-        ("bias", C.c_void_p), ("bias_dim", C.c_int32), ("act", C.c_int32), ("ab_dtype", C.c_int32),
+        ("bias", C.c_void_p), ("bias_dim", C.c_int32), ("act", C.c_int32), ("ab_dtype", C.c_int32), ("dual", C.c_int32),
     ]
 
 
@@ -165,8 +165,8 @@ def _gemm_problem(M, N, K, alpha, A: Operand, B: Operand, beta, Cre, Cim, layout
 def gemm(M: int, N: int, K: int, alpha: float, A: Operand, B: Operand, beta: float = 0.0,
          C_re: Optional[np.ndarray] = None, C_im: Optional[np.ndarray] = None, layoutC: int = COL, ldc: int = 0,
          bias: Optional[np.ndarray] = None, bias_dim: int = 0, act: int = ACT_NONE,
-         at: Optional[Sequence[np.ndarray]] = None, threads: Optional[int] = None):
-    """Evaluate the GEMM definition.
+         at: Optional[Sequence[np.ndarray]] = None, threads: Optional[int] = None, dual: bool = False):
+    """Evaluate the GEMM definition.  ``dual``: the ``im`` planes hold dual parts (eps^2 = 0).
 
     Returns a dict with ``D`` and ``G`` (float64; complex problems also ``D_im`` and ``G_im``).
     Without ``at`` the arrays are (M, N); with ``at=(I, J)`` they are 1-D, one value per listed
@@ -174,6 +174,7 @@ def gemm(M: int, N: int, K: int, alpha: float, A: Operand, B: Operand, beta: flo
     """
     threads = threads or default_threads()
     q = _gemm_problem(M, N, K, alpha, A, B, beta, C_re, C_im, layoutC, ldc, bias, bias_dim, act)
+    q.dual = 1 if dual else 0
     is_complex = A.im is not None or B.im is not None
     if at is None:
         shape, order = (M, N), "F"

@@ -106,6 +106,8 @@ typedef struct {
     int32_t bias_dim;              /* 0: bias[i] (length M), 1: bias[j] (len N)  */
     int32_t act;
     int32_t ab_dtype;              /* element type of A and B: 0 binary16, 1 bfloat16 */
+    int32_t dual;                  /* 1: the second planes are dual parts (eps^2 = 0, Section 5.4)
+                                      instead of imaginary parts (i^2 = -1)        */
 } og_problem;
 
 /* logical element (r, c) of a stored rows x cols operand */
@@ -135,10 +137,16 @@ static void gemm_entry(const og_problem *q, int64_t i, int64_t j,
         } else {
             double ai = q->A_im ? operand_at(q->A_im, q->layoutA, q->lda, i, k, dec) : 0.0;
             double bi = q->B_im ? operand_at(q->B_im, q->layoutB, q->ldb, k, j, dec) : 0.0;
-            /* (ar + i ai)(br + i bi): the four real products of Section 5.4 */
-            s_re += ar * br - ai * bi;
+            if (q->dual) {
+                /* (ar + eps ai)(br + eps bi) with eps^2 = 0: the eps.eps product vanishes */
+                s_re += ar * br;
+                m_re += fabs(ar) * fabs(br);
+            } else {
+                /* (ar + i ai)(br + i bi): the four real products of Section 5.4 */
+                s_re += ar * br - ai * bi;
+                m_re += fabs(ar) * fabs(br) + fabs(ai) * fabs(bi);
+            }
             s_im += ar * bi + ai * br;
-            m_re += fabs(ar) * fabs(br) + fabs(ai) * fabs(bi);
             m_im += fabs(ar) * fabs(bi) + fabs(ai) * fabs(br);
         }
     }

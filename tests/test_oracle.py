@@ -371,3 +371,27 @@ def test_bf16_gemm_matches_float64_matmul():
     # the same bits read as binary16 give a different (wrong) product: the dtype flag matters
     r16 = O.gemm(M, N, K, 1.0, Operand(A, COL, M, dtype=O.F16), Operand(B, ROW, N, dtype=O.F16))
     assert not np.allclose(r16["D"], want, rtol=1e-3, atol=1e-3)
+
+
+# ---------------------------------------------------------------- dual numbers
+def test_dual_product_is_value_and_first_derivative():
+    # A(t) = Ar + t Ad, B(t) = Br + t Bd:  A(t) B(t) = Ar Br + t (Ar Bd + Ad Br) + t^2 Ad Bd.
+    # The dual product keeps the first two coefficients; with integers, the coefficient of t is
+    # (P(1) - P(-1)) / 2 exactly, evaluated here with two ordinary matrix products.
+    M, N, K = 6, 5, 9
+    Ar, Ad = (RNG.integers(-4, 5, size=(M, K)).astype(np.float64) for _ in range(2))
+    Br, Bd = (RNG.integers(-4, 5, size=(K, N)).astype(np.float64) for _ in range(2))
+    Cr, Cd = (RNG.integers(-4, 5, size=(M, N)).astype(np.float32) for _ in range(2))
+    a_re, lda, _ = store(Ar, ROW); a_du, _, _ = store(Ad, ROW)
+    b_re, ldb, _ = store(Br, COL); b_du, _, _ = store(Bd, COL)
+    r = O.gemm(M, N, K, 2.0, Operand(a_re, ROW, lda, a_du), Operand(b_re, COL, ldb, b_du), 3.0,
+               Cr.T.copy().reshape(-1), Cd.T.copy().reshape(-1), COL, M, dual=True)
+    P = lambda t: (Ar + t * Ad) @ (Br + t * Bd)
+    assert np.array_equal(r["D"], 2.0 * (Ar @ Br) + 3.0 * Cr)
+    assert np.array_equal(r["D_im"], 2.0 * (P(1) - P(-1)) / 2 + 3.0 * Cd)
+    # and it differs from the complex product exactly by the eps.eps term
+    c = O.gemm(M, N, K, 2.0, Operand(a_re, ROW, lda, a_du), Operand(b_re, COL, ldb, b_du), 3.0,
+               Cr.T.copy().reshape(-1), Cd.T.copy().reshape(-1), COL, M)
+    assert np.array_equal(r["D"] - c["D"], 2.0 * (Ad @ Bd))
+    assert np.array_equal(r["D_im"], c["D_im"])
+    assert np.array_equal(r["G"], 2.0 * (np.abs(Ar) @ np.abs(Br)) + 3.0 * np.abs(Cr))
