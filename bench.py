@@ -115,6 +115,11 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream):
         bias=bias, bias_dim=0, act=fg.FG_ACT_RELU, stream=stream)) * 1e-12)
     guard("config4_complex_planar_4096_TFLOPs", lambda: 8.0 * m ** 3 / timed(lambda: fg.fg_gemm(
         m, m, m, 1.0, M(A4, 0, m, im=A4i), M(B4, 0, m, im=B4i), 1.0, M(C4, 0, m, im=C4i), M(D4, 0, m, im=D4i), stream=stream)) * 1e-12)
+    guard("dual_planar_4096_TFLOPs", lambda: 6.0 * m ** 3 / timed(lambda: fg.fg_gemm_dual(
+        m, m, m, 1.0, M(A4, 0, m, im=A4i), M(B4, 0, m, im=B4i), 1.0, M(C4, 0, m, im=C4i), M(D4, 0, m, im=D4i), stream=stream)) * 1e-12)
+    Ab, Bb = A.to(torch.bfloat16), B.to(torch.bfloat16)
+    guard("gemm_NN_bf16_%d_TFLOPs" % n, lambda: flops / timed(lambda: fg.fg_gemm(
+        n, n, n, 1.0, M(Ab, 0, n), M(Bb, 0, n), 1.0, mC, mD, stream=stream)) * 1e-12)
     guard("config4_diagonal_A_4096_GBps", lambda: (m * m * 2 + 2 * m * m * 4 + m * 2) / timed(lambda: fg.fg_gemm(
         m, m, m, 1.0, M(dvec, fg.FG_DIAG, 0), M(B4, 0, m), 1.0, M(C4, 0, m), M(D4, 0, m), stream=stream)) * 1e-9)
 
@@ -135,6 +140,8 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream):
         return tf
     guard("config5a_contraction_256_TFLOPs", c5a)
     guard("config5b_contraction_64_TFLOPs", lambda: contraction({a: 64, b: 64, c: 64, d: 64, e: 64, f: 64}, [a, e, b, f], [d, f, c, e], [a, b, c, d])[0])
+    # the contraction the paper measures in Section 5.5: D_abc = A_bda B_dc, (a, b, c, d) = (64, 32, 2048, 2048)
+    guard("paper_contraction_64_32_2048_2048_TFLOPs", lambda: contraction({a: 64, b: 32, c: 2048, d: 2048}, [b, d, a], [d, c], [a, b, c])[0])
     return res
 
 

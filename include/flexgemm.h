@@ -55,7 +55,7 @@ typedef enum {
     FG_ERR_LAUNCH = 7        /* the HIP runtime refused the launch (no device, bad stream)   */
 } fg_status;
 
-typedef enum { FG_F16 = 0, FG_BF16 = 1, FG_F32 = 2 } fg_dtype;   /* A, B: FG_F16.  C, D: FG_F32 */
+typedef enum { FG_F16 = 0, FG_BF16 = 1, FG_F32 = 2 } fg_dtype;   /* A, B: FG_F16 or FG_BF16.  C, D: FG_F32 */
 
 typedef enum {
     FG_COL = 0,   /* column-major ('N'): element (r, c) at r + c*ld                            */
@@ -89,8 +89,11 @@ typedef struct {
  * D = act(alpha * op(A) * op(B) + beta * C + bias)       (Sections 2.2, 4.3.2, 5.1-5.4)
  *
  * op(A) is the logical M x K matrix and op(B) the logical K x N matrix described by A and B;
- * C and D are M x N.  FP16 elements are multiplied exactly and accumulated in FP32.
- *   A, B : FG_F16; layout FG_COL, FG_ROW or FG_DIAG (at most one of A, B diagonal).
+ * C and D are M x N.  16-bit elements are multiplied exactly and accumulated in FP32.
+ *   A, B : both FG_F16 or both FG_BF16 (IEEE binary16 / bfloat16: the matrix unit multiplies
+ *          either kind into FP32, Section 2.2); layout FG_COL, FG_ROW or FG_DIAG (at most one of
+ *          A, B diagonal).  FG_BF16 is accepted for real, non-diagonal operands; otherwise
+ *          FG_ERR_UNSUPPORTED.
  *   C    : FG_F32, FG_COL or FG_ROW with the same layout as D; NULL or FG_ZERO means no C term
  *          (beta is then ignored).
  *   D    : FG_F32, FG_COL or FG_ROW; written.
@@ -104,6 +107,20 @@ fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha,
                   float beta, const fg_matrix *C,
                   const fg_matrix *D, const fg_epilogue *ep,
                   void *hip_stream);
+
+/*
+ * Dual-number product (Section 5.4): every element is x + eps.x' with eps^2 = 0, stored like the
+ * planar complex matrices (value plane at `re`, dual plane at `im`), so
+ *     D.re = alpha * A.re.B.re + beta * C.re
+ *     D.im = alpha * (A.re.B.im + A.im.B.re) + beta * C.im
+ * i.e. a product and its first derivative in one pass (three real products instead of the four
+ * of a complex product).  Arguments, layouts, sizes and errors as for a complex fg_gemm without
+ * epilogue: A, B FG_F16 with both planes, D (and C if given) with both planes, alpha and beta real.
+ */
+fg_status fg_gemm_dual(int64_t M, int64_t N, int64_t K, float alpha,
+                       const fg_matrix *A, const fg_matrix *B,
+                       float beta, const fg_matrix *C,
+                       const fg_matrix *D, void *hip_stream);
 
 /*
  * Cout[modesC] = alpha * sum over contracted modes of A[modesA] * B[modesB] + beta * Cin[modesC]
@@ -140,10 +157,12 @@ int32_t fg_version(void);
  * Name of the kernel variant and block tile that fg_gemm would use for this problem, written as
  * a NUL-terminated string into `buf` (at most `buf_len` bytes).  This is the "params" choice of
  * Section 4.2.1: the largest (nearly) square block tile that divides the problem and fills the
- * GPU.  Returns FG_OK, or the status fg_gemm would return for these sizes and layouts.
+ * GPU.  `variant` (fg_plan_variant) names the operator: real FP16, complex, dual or real BF16.
+ * Returns FG_OK, or the status fg_gemm would return for these sizes and layouts.
  */
+typedef enum { FG_PLAN_REAL = 0, FG_PLAN_COMPLEX = 1, FG_PLAN_DUAL = 2, FG_PLAN_REAL_BF16 = 3 } fg_plan_variant;
 fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t layoutB,
-                       int32_t layoutD, int32_t is_complex, char *buf, int32_t buf_len);
+                       int32_t layoutD, int32_t variant, char *buf, int32_t buf_len);
 
 /*
  * Measurement aid, not part of the method: launches a kernel that only issues

@@ -22,7 +22,8 @@ FG_F16, FG_BF16, FG_F32 = 0, 1, 2
 FG_COL, FG_ROW, FG_DIAG, FG_ZERO = 0, 1, 2, 3
 FG_ACT_NONE, FG_ACT_RELU = 0, 1
 
-EXPORTS = ("fg_gemm", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan", "fg_probe_mfma")
+EXPORTS = ("fg_gemm", "fg_gemm_dual", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan", "fg_probe_mfma")
+FG_PLAN_REAL, FG_PLAN_COMPLEX, FG_PLAN_DUAL, FG_PLAN_REAL_BF16 = 0, 1, 2, 3
 
 
 class fg_matrix(C.Structure):
@@ -54,6 +55,9 @@ def load_library() -> C.CDLL:
         lib.fg_gemm.restype = C.c_int
         lib.fg_gemm.argtypes = [i64, i64, i64, f32, C.POINTER(fg_matrix), C.POINTER(fg_matrix), f32,
                                 C.POINTER(fg_matrix), C.POINTER(fg_matrix), C.POINTER(fg_epilogue), vp]
+        lib.fg_gemm_dual.restype = C.c_int
+        lib.fg_gemm_dual.argtypes = [i64, i64, i64, f32, C.POINTER(fg_matrix), C.POINTER(fg_matrix), f32,
+                                     C.POINTER(fg_matrix), C.POINTER(fg_matrix), vp]
         lib.fg_contract.restype = C.c_int
         lib.fg_contract.argtypes = [i32, vp, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, f32, f32, vp]
         lib.fg_last_error.restype = C.c_char_p
@@ -130,10 +134,23 @@ def fg_gemm(M: int, N: int, K: int, alpha: float, A: Optional[Matrix], B: Option
     return _check(st, raise_on_error)
 
 
+def fg_gemm_dual(M: int, N: int, K: int, alpha: float, A: Optional[Matrix], B: Optional[Matrix], beta: float,
+                 C_: Optional[Matrix], D: Optional[Matrix], stream=None, raise_on_error: bool = True) -> int:
+    """Dual-number product on planar (value, dual part) matrices; see fg_gemm_dual in include/flexgemm.h."""
+    lib = load_library()
+    sa = A._struct() if A is not None else None
+    sb = B._struct() if B is not None else None
+    sc = C_._struct() if C_ is not None else None
+    sd = D._struct() if D is not None else None
+    ref = lambda s: C.byref(s) if s is not None else None
+    st = lib.fg_gemm_dual(M, N, K, alpha, ref(sa), ref(sb), beta, ref(sc), ref(sd), _stream_handle(stream))
+    return _check(st, raise_on_error)
+
+
 def fg_gemm_plan(M: int, N: int, K: int, layoutA: int = FG_COL, layoutB: int = FG_COL, layoutD: int = FG_COL,
-                 is_complex: bool = False) -> str:
+                 variant: int = FG_PLAN_REAL) -> str:
     buf = C.create_string_buffer(128)
-    st = load_library().fg_gemm_plan(M, N, K, layoutA, layoutB, layoutD, int(is_complex), buf, 128)
+    st = load_library().fg_gemm_plan(M, N, K, layoutA, layoutB, layoutD, int(variant), buf, 128)
     _check(st, True)
     return buf.value.decode()
 

@@ -43,7 +43,9 @@ struct Problem {
     const float *bias;
     int bias_dim, act;
     float alpha, beta;
-    bool cplx;
+    bool cplx;               // two planes per operand: complex, or dual when `dual` is set
+    bool dual;
+    bool bf16;               // A and B hold bfloat16
 };
 
 const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
@@ -90,12 +92,17 @@ const fg::KernelEntry *select_kernel(const Problem &q) {
         const int t = choose_ctile(q.M, q.N);
         if (t < 0) return nullptr;
         const int v = (q.a_kc ? 2 : 0) + (q.b_kc ? 0 : 1);     // nn, nt, tn, tt
-        return &fg::kernel_table_cplx()[t * 4 + v];
+        return &(q.dual ? fg::kernel_table_dual() : fg::kernel_table_cplx())[t * 4 + v];
     }
     const int tile = choose_tile(q.M, q.N);
     if (tile < 0) return nullptr;
     if (q.a_diag) return &fg::kernel_table_diag()[tile * 4 + (q.b_kc ? 0 : 1)];
     if (q.b_diag) return &fg::kernel_table_diag()[tile * 4 + (q.a_kc ? 2 : 3)];
+    if (q.bf16) {
+        const fg::KernelEntry *t = !q.a_kc ? (q.b_kc ? fg::kernel_table_nn_bf16() : fg::kernel_table_nt_bf16())
+                                           : (q.b_kc ? fg::kernel_table_tn_bf16() : fg::kernel_table_tt_bf16());
+        return &t[tile];
+    }
     return &table_for(q.a_kc, q.b_kc)[fg::entry_index(tile, false)];
 }
 
@@ -139,7 +146,7 @@ fg_status check_sizes(int64_t M, int64_t N, int64_t K) {
 
 fg_status check_input_matrix(const char *name, const fg_matrix *X, int64_t rows, int64_t cols) {
     if (!X) return fail(FG_ERR_NULL, "%s is NULL", name);
-    if (X->dtype != FG_F16) return fail(X->dtype == FG_BF16 ? FG_ERR_UNSUPPORTED : FG_ERR_LAYOUT, "%s must be FG_F16", name);
+    if (X->dtype != FG_F16 && X->dtype != FG_BF16) return fail(FG_ERR_LAYOUT, "%s must be FG_F16 or FG_BF16", name);
     if (X->layout != FG_COL && X->layout != FG_ROW && X->layout != FG_DIAG) return fail(FG_ERR_LAYOUT, "%s: layout %d is not valid for an input", name, X->layout);
     if (rows > 0 && cols > 0) {
         if (!X->re) return fail(FG_ERR_NULL, "%s->re is NULL", name);
@@ -170,12 +177,17 @@ fg_status check_output_matrix(const char *name, const fg_matrix *X, int64_t rows
 // Validate an fg_gemm call and normalise it so that D is column-major: a row-major D is the
 // column-major D^T = op(B)^T op(A)^T, i.e. the same kernel with the operands exchanged.
 fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
-                    float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, Problem &q) {
+                    float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, bool dual, Problem &q) {
     if (fg_status st = check_sizes(M, N, K)) return st;
     if (fg_status st = check_input_matrix("A", A, M, K)) return st;
     if (fg_status st = check_input_matrix("B", B, K, N)) return st;
     if (!D) return fail(FG_ERR_NULL, "D is NULL");
+    if (A->dtype != B->dtype) return fail(FG_ERR_UNSUPPORTED, "A and B must have the same element type");
+    const bool bf16 = A->dtype == FG_BF16;
     const bool cplx = (A->im != nullptr) || (B->im != nullptr);
+    if (dual && !cplx) return fail(FG_ERR_NULL, "a dual-number product needs the dual planes (im) of A and B");
+    if (bf16 && (cplx || A->layout == FG_DIAG || B->layout == FG_DIAG))
+        return fail(FG_ERR_UNSUPPORTED, "FG_BF16 operands are supported for real, non-diagonal matrices only");
     if (fg_status st = check_output_matrix("D", D, M, N, cplx)) return st;
     const bool has_c = C && C->layout != FG_ZERO && C->re != nullptr;
     if (C && C->layout != FG_ZERO && !C->re && M > 0 && N > 0) return fail(FG_ERR_NULL, "C->re is NULL (pass C == NULL or FG_ZERO for no C term)");
@@ -190,12 +202,14 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
         if (ep->bias && ep->bias_dim != 0 && ep->bias_dim != 1) return fail(FG_ERR_LAYOUT, "bias_dim must be 0 or 1");
         if (ep->bias && !aligned16(ep->bias)) return fail(FG_ERR_ALIGN, "bias must be 16-byte aligned");
     }
-    if (cplx && has_ep) return fail(FG_ERR_UNSUPPORTED, "bias and activation are not defined for complex products");
-    if (cplx && (!A->im || !B->im)) return fail(FG_ERR_UNSUPPORTED, "complex products need the imaginary plane of both A and B");
-    if (cplx && (A->layout == FG_DIAG || B->layout == FG_DIAG)) return fail(FG_ERR_UNSUPPORTED, "complex diagonal operands are not supported");
+    if (cplx && has_ep) return fail(FG_ERR_UNSUPPORTED, "bias and activation are not defined for complex or dual products");
+    if (cplx && (!A->im || !B->im)) return fail(FG_ERR_UNSUPPORTED, "complex and dual products need the second plane of both A and B");
+    if (cplx && (A->layout == FG_DIAG || B->layout == FG_DIAG)) return fail(FG_ERR_UNSUPPORTED, "complex or dual diagonal operands are not supported");
 
     const bool swap = (D->layout == FG_ROW);
     q.cplx = cplx;
+    q.dual = dual;
+    q.bf16 = bf16;
     q.alpha = alpha;
     q.beta = has_c ? beta : 0.f;
     q.C = has_c ? (const float *)C->re : nullptr;
@@ -375,10 +389,10 @@ const char *fg_last_error(void) { return g_err; }
 
 int32_t fg_version(void) { return 100; }   // 0.1.0
 
-fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
-                  float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, void *hip_stream) {
+static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
+                           float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, bool dual, void *hip_stream) {
     Problem q;
-    if (fg_status st = normalise(M, N, K, alpha, A, B, beta, C, D, ep, q)) return st;
+    if (fg_status st = normalise(M, N, K, alpha, A, B, beta, C, D, ep, dual, q)) return st;
     if (q.M == 0 || q.N == 0) return FG_OK;
     const fg::KernelEntry *kp = select_kernel(q);
     if (!kp) return fail(FG_ERR_UNSUPPORTED, "no block tile divides M=%lld, N=%lld", (long long)q.M, (long long)q.N);
@@ -403,8 +417,18 @@ fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix 
     return launch(k, p, (hipStream_t)hip_stream);
 }
 
+fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
+                  float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, void *hip_stream) {
+    return gemm_impl(M, N, K, alpha, A, B, beta, C, D, ep, false, hip_stream);
+}
+
+fg_status fg_gemm_dual(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
+                       float beta, const fg_matrix *C, const fg_matrix *D, void *hip_stream) {
+    return gemm_impl(M, N, K, alpha, A, B, beta, C, D, nullptr, true, hip_stream);
+}
+
 fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t layoutB, int32_t layoutD,
-                       int32_t is_complex, char *buf, int32_t buf_len) {
+                       int32_t variant, char *buf, int32_t buf_len) {
     if (!buf || buf_len <= 0) return fail(FG_ERR_NULL, "buf is NULL or empty");
     buf[0] = 0;
     if (fg_status st = check_sizes(M, N, K)) return st;
@@ -412,10 +436,14 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
     if (!ok_in(layoutA) || !ok_in(layoutB) || (layoutD != FG_COL && layoutD != FG_ROW))
         return fail(FG_ERR_LAYOUT, "plan query: A, B take FG_COL / FG_ROW / FG_DIAG, D takes FG_COL / FG_ROW");
     if (layoutA == FG_DIAG && layoutB == FG_DIAG) return fail(FG_ERR_UNSUPPORTED, "at most one of A and B may be diagonal");
-    if (is_complex && (layoutA == FG_DIAG || layoutB == FG_DIAG)) return fail(FG_ERR_UNSUPPORTED, "complex diagonal operands are not supported");
+    if (variant < FG_PLAN_REAL || variant > FG_PLAN_REAL_BF16) return fail(FG_ERR_LAYOUT, "plan query: unknown variant %d", variant);
+    if (variant != FG_PLAN_REAL && (layoutA == FG_DIAG || layoutB == FG_DIAG))
+        return fail(FG_ERR_UNSUPPORTED, "diagonal operands are supported for real FG_F16 products only");
     Problem q;
     memset(&q, 0, sizeof q);
-    q.cplx = is_complex != 0;
+    q.cplx = variant == FG_PLAN_COMPLEX || variant == FG_PLAN_DUAL;
+    q.dual = variant == FG_PLAN_DUAL;
+    q.bf16 = variant == FG_PLAN_REAL_BF16;
     if (layoutD == FG_COL) {
         q.M = M; q.N = N;
         q.a_diag = layoutA == FG_DIAG; q.b_diag = layoutB == FG_DIAG;

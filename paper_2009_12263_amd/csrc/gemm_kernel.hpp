@@ -70,7 +70,7 @@ struct GemmParams {
 // 32x32 MFMA accumulators.  A_KC / B_KC: operand is K-contiguous in memory (A row-major,
 // B column-major) rather than M/N-contiguous.  STAGES LDS buffers per operand form a ring over K.
 template <int BM_, int BN_, int BK_, int STAGES_, int WGM_, int WGN_, bool A_KC_, bool B_KC_, bool STRIDED_,
-          int DIAG_ = 0, bool CPLX_ = false, bool SPREAD_ = false>
+          int DIAG_ = 0, int CPLX_ = 0, bool SPREAD_ = false, bool BF16_ = false>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_;
     static constexpr int KSTEPS = BK / 16;                          // MFMA k-slices per tile
@@ -78,7 +78,10 @@ struct TileCfg {
     static constexpr int NWAVES = WGM * WGN, NTHREADS = 64 * NWAVES;
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;
     static constexpr int TI = WTM / 32, TJ = WTN / 32;
-    static constexpr bool A_KC = A_KC_, B_KC = B_KC_, STRIDED = STRIDED_, CPLX = CPLX_;
+    static constexpr bool A_KC = A_KC_, B_KC = B_KC_, STRIDED = STRIDED_;
+    // 0: real; 1: complex (i^2 = -1), 2: dual (eps^2 = 0) numbers in planar-split storage
+    static constexpr int CPLX = CPLX_;
+    static constexpr bool BF16 = BF16_;                             // A, B are bfloat16 instead of binary16
     static constexpr int DIAG = DIAG_;                              // 0: none, 1: A diagonal, 2: B diagonal
     // SPREAD: the refill loads of a ring buffer are issued one at a time between the MFMAs of two
     // k-slices (A's part in the slice after the buffer is retired, B's part in the next one)
@@ -582,6 +585,17 @@ __device__ __forceinline__ half8 neg8(half8 v) {
     return __builtin_bit_cast(half8, u);
 }
 
+// One 32x32x16 matrix instruction on 16-bit fragments held as eight raw 16-bit lanes: the same
+// registers are read as binary16 or as bfloat16.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+template <bool BF16>
+__device__ __forceinline__ floatx16 mfma(half8 a, half8 b, floatx16 c) {
+    if constexpr (BF16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p) {
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
@@ -742,19 +756,27 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                     for (int i = 0; i < TI; ++i) {
                         // MFMA rows <- our N index, MFMA columns <- our M index: lanes of the
                         // accumulator then run along M, the contiguous direction of D
-                        if constexpr (!Cfg::CPLX) {
+                        if constexpr (Cfg::CPLX == 0) {
 #pragma unroll
                             for (int j = 0; j < TJ; ++j)
-                                acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[0][rb][j], af[0][i], acc[0][i][j], 0, 0, 0);
-                        } else {
+                                acc[0][i][j] = mfma<Cfg::BF16>(bf[0][rb][j], af[0][i], acc[0][i][j]);
+                        } else if constexpr (Cfg::CPLX == 1) {
                             // (Ar + i Ai)(Br + i Bi): the four real products of Section 5.4
                             const half8 nai = neg8(af[1][i]);
 #pragma unroll
                             for (int j = 0; j < TJ; ++j) {
-                                acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[0][rb][j], af[0][i], acc[0][i][j], 0, 0, 0);
-                                acc[1][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[1][rb][j], af[0][i], acc[1][i][j], 0, 0, 0);
-                                acc[0][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[1][rb][j], nai, acc[0][i][j], 0, 0, 0);
-                                acc[1][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[0][rb][j], af[1][i], acc[1][i][j], 0, 0, 0);
+                                acc[0][i][j] = mfma<Cfg::BF16>(bf[0][rb][j], af[0][i], acc[0][i][j]);
+                                acc[1][i][j] = mfma<Cfg::BF16>(bf[1][rb][j], af[0][i], acc[1][i][j]);
+                                acc[0][i][j] = mfma<Cfg::BF16>(bf[1][rb][j], nai, acc[0][i][j]);
+                                acc[1][i][j] = mfma<Cfg::BF16>(bf[0][rb][j], af[1][i], acc[1][i][j]);
+                            }
+                        } else {
+                            // dual numbers (Ar + eps Ad)(Br + eps Bd), eps^2 = 0: three real products
+#pragma unroll
+                            for (int j = 0; j < TJ; ++j) {
+                                acc[0][i][j] = mfma<Cfg::BF16>(bf[0][rb][j], af[0][i], acc[0][i][j]);
+                                acc[1][i][j] = mfma<Cfg::BF16>(bf[1][rb][j], af[0][i], acc[1][i][j]);
+                                acc[1][i][j] = mfma<Cfg::BF16>(bf[0][rb][j], af[1][i], acc[1][i][j]);
                             }
                         }
                         if (!last || MORE) {

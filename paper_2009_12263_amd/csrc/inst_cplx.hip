@@ -2,10 +2,10 @@
 #include "kernel_table.hpp"
 namespace fg {
 #define FG_CPLX_TILE(BM, BN, WGM, WGN, TAG)                                                        \
-    FG_ENTRY_X(BM, BN, 32, 2, WGM, WGN, false, true, 0, true, "cgemm_nn_" TAG),                    \
-    FG_ENTRY_X(BM, BN, 32, 2, WGM, WGN, false, false, 0, true, "cgemm_nt_" TAG),                   \
-    FG_ENTRY_X(BM, BN, 32, 2, WGM, WGN, true, true, 0, true, "cgemm_tn_" TAG),                     \
-    FG_ENTRY_X(BM, BN, 32, 2, WGM, WGN, true, false, 0, true, "cgemm_tt_" TAG)
+    FG_ENTRY_X(BM, BN, 32, 2, WGM, WGN, false, true, 0, 1, "cgemm_nn_" TAG),                    \
+    FG_ENTRY_X(BM, BN, 32, 2, WGM, WGN, false, false, 0, 1, "cgemm_nt_" TAG),                   \
+    FG_ENTRY_X(BM, BN, 32, 2, WGM, WGN, true, true, 0, 1, "cgemm_tn_" TAG),                     \
+    FG_ENTRY_X(BM, BN, 32, 2, WGM, WGN, true, false, 0, 1, "cgemm_tt_" TAG)
 const KernelEntry *kernel_table_cplx() {
     static const KernelEntry t[CTILE_COUNT * 4] = {
         FG_CPLX_TILE(256, 128, 4, 2, "256x128x32"),

@@ -2,10 +2,10 @@
 #include "kernel_table.hpp"
 namespace fg {
 #define FG_DIAG_TILE(BM, BN, WGM, WGN, TAG)                                                        \
-    FG_ENTRY_X(BM, BN, 64, 2, WGM, WGN, true, true, 1, false, "gemm_diagA_n_" TAG),                \
-    FG_ENTRY_X(BM, BN, 64, 2, WGM, WGN, true, false, 1, false, "gemm_diagA_t_" TAG),               \
-    FG_ENTRY_X(BM, BN, 64, 2, WGM, WGN, true, true, 2, false, "gemm_t_diagB_" TAG),                \
-    FG_ENTRY_X(BM, BN, 64, 2, WGM, WGN, false, true, 2, false, "gemm_n_diagB_" TAG)
+    FG_ENTRY_X(BM, BN, 64, 2, WGM, WGN, true, true, 1, 0, "gemm_diagA_n_" TAG),                \
+    FG_ENTRY_X(BM, BN, 64, 2, WGM, WGN, true, false, 1, 0, "gemm_diagA_t_" TAG),               \
+    FG_ENTRY_X(BM, BN, 64, 2, WGM, WGN, true, true, 2, 0, "gemm_t_diagB_" TAG),                \
+    FG_ENTRY_X(BM, BN, 64, 2, WGM, WGN, false, true, 2, 0, "gemm_n_diagB_" TAG)
 const KernelEntry *kernel_table_diag() {
     static const KernelEntry t[TILE_COUNT * 4] = {
         FG_DIAG_TILE(256, 256, 2, 4, "256x256x64"),

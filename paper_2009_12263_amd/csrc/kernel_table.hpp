@@ -19,22 +19,47 @@ const KernelEntry *kernel_table_nt();   // A M-contiguous, B N-contiguous  (A 'N
 const KernelEntry *kernel_table_tn();   // A K-contiguous, B K-contiguous  (A 'T', B 'N')
 const KernelEntry *kernel_table_tt();   // A K-contiguous, B N-contiguous  (A 'T', B 'T')
 
+// The same four layout pairs with bfloat16 A and B (plain matrices only): index = tile.
+const KernelEntry *kernel_table_nn_bf16();
+const KernelEntry *kernel_table_nt_bf16();
+const KernelEntry *kernel_table_tn_bf16();
+const KernelEntry *kernel_table_tt_bf16();
+
 // Diagonal operands: index tile * 4 + {0: A diag, B K-contiguous; 1: A diag, B N-contiguous;
 //                                       2: B diag, A K-contiguous; 3: B diag, A M-contiguous}.
 const KernelEntry *kernel_table_diag();
 // Planar complex: index ctile * 4 + {nn, nt, tn, tt}; ctile 0: 256x128, 1: 128x128, 2: 64x64.
 const KernelEntry *kernel_table_cplx();
+// Planar dual numbers (eps^2 = 0): same indexing as the complex table.
+const KernelEntry *kernel_table_dual();
 enum { CTILE_COUNT = 3 };
 
 // Entry index inside one table: tile * 2 + strided.
 inline int entry_index(int tile, bool strided) { return tile * 2 + (strided ? 1 : 0); }
 
 // real kernels with BK = 64: ring refills are spread between the MFMAs (TileCfg::SPREAD)
-#define FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR) TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR, 0, false, true>
+#define FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR) TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR, 0, 0, true>
 #define FG_ENTRY(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR, NAME)                                    \
     { gemm_kernel<FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)>, NAME, BM, BN,                  \
       FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)::NTHREADS,                                   \
       FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)::LDS_BYTES }
+
+#define FG_CFG_BF16(BM, BN, BK, ST, WGM, WGN, AKC, BKC) TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, false, 0, 0, true, true>
+#define FG_ENTRY_BF16(BM, BN, BK, ST, WGM, WGN, AKC, BKC, NAME)                                    \
+    { gemm_kernel<FG_CFG_BF16(BM, BN, BK, ST, WGM, WGN, AKC, BKC)>, NAME, BM, BN,                  \
+      FG_CFG_BF16(BM, BN, BK, ST, WGM, WGN, AKC, BKC)::NTHREADS,                                   \
+      FG_CFG_BF16(BM, BN, BK, ST, WGM, WGN, AKC, BKC)::LDS_BYTES }
+
+#define FG_DEFINE_TABLE_BF16(FUNC, AKC, BKC, TAG)                                                  \
+    const KernelEntry *FUNC() {                                                                    \
+        static const KernelEntry t[TILE_COUNT] = {                                                 \
+            FG_ENTRY_BF16(256, 256, 64, 2, 2, 4, AKC, BKC, "gemm_bf16_" TAG "_256x256x64"),        \
+            FG_ENTRY_BF16(256, 128, 64, 2, 4, 2, AKC, BKC, "gemm_bf16_" TAG "_256x128x64"),        \
+            FG_ENTRY_BF16(128, 128, 64, 2, 2, 2, AKC, BKC, "gemm_bf16_" TAG "_128x128x64"),        \
+            FG_ENTRY_BF16(64, 64, 64, 2, 2, 2, AKC, BKC, "gemm_bf16_" TAG "_64x64x64"),            \
+        };                                                                                         \
+        return t;                                                                                  \
+    }
 
 #define FG_ENTRY_X(BM, BN, BK, ST, WGM, WGN, AKC, BKC, DG, CX, NAME)                                \
     { gemm_kernel<TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, false, DG, CX>>, NAME, BM, BN,       \

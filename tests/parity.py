@@ -27,14 +27,15 @@ from paper_2009_12263_amd import workloads as W
 OFFICIAL_RTOL = 2e-3
 
 
-def make_operand(rows: int, cols: int, layout: int, stream: int, device, ints: bool, pad: int = 0, seed=W.DEFAULT_SEED):
-    """A stored rows x cols FP16 operand in FG_COL / FG_ROW layout with ld = extent + pad.
+def make_operand(rows: int, cols: int, layout: int, stream: int, device, ints: bool, pad: int = 0, seed=W.DEFAULT_SEED,
+                 dtype=torch.float16):
+    """A stored rows x cols FP16 (or BF16) operand in FG_COL / FG_ROW layout with ld = extent + pad.
     Returns (device tensor, ld)."""
     lead = rows if layout == fg.FG_COL else cols
     other = cols if layout == fg.FG_COL else rows
     ld = (lead + 7) // 8 * 8 + pad          # leading dimensions of FP16 operands are multiples of 8
     gen = W.small_ints if ints else W.uniform_pm1
-    t = gen(ld * other, stream, seed=seed, device=device, dtype=torch.float16)
+    t = gen(ld * other, stream, seed=seed, device=device, dtype=dtype)
     return t, ld
 
 
@@ -44,7 +45,12 @@ def make_f32(numel: int, stream: int, device, ints: bool, seed=W.DEFAULT_SEED):
 
 
 def np16(t: Optional[torch.Tensor]):
-    return None if t is None else t.detach().cpu().numpy()
+    """Host copy as a numpy array; bfloat16 tensors come back as their uint16 bit patterns."""
+    if t is None:
+        return None
+    if t.dtype == torch.bfloat16:
+        return t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.detach().cpu().numpy()
 
 
 def sample_positions(M: int, N: int, count: int, seed: int, tile: int = 256):
@@ -81,10 +87,12 @@ def compare(got: np.ndarray, ref: np.ndarray, G: np.ndarray, K: int, exact: bool
 
 def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alpha=1.0, beta=1.0, with_c=True,
                   bias_dim=None, act=fg.FG_ACT_NONE, ints=False, pad=0, config=1, samples: Optional[int] = None,
-                  inplace=False, device="cuda", seed=W.DEFAULT_SEED):
+                  inplace=False, device="cuda", seed=W.DEFAULT_SEED, bf16=False):
     """Run fg_gemm on seeded inputs and compare with the oracle.  ``samples`` None: every entry."""
-    A, lda = make_operand(M, K, la, W.stream_id(config, "A"), device, ints, pad, seed)
-    B, ldb = make_operand(K, N, lb, W.stream_id(config, "B"), device, ints, pad, seed)
+    dt = torch.bfloat16 if bf16 else torch.float16
+    odt = O.BF16 if bf16 else O.F16
+    A, lda = make_operand(M, K, la, W.stream_id(config, "A"), device, ints, pad, seed, dt)
+    B, ldb = make_operand(K, N, lb, W.stream_id(config, "B"), device, ints, pad, seed, dt)
     lead, other = (M, N) if ld_layout == fg.FG_COL else (N, M)
     ldc = (lead + 3) // 4 * 4 + (4 if pad else 0)   # leading dimensions of FP32 operands are multiples of 4
     Cbuf = make_f32(ldc * other, W.stream_id(config, "C"), device, ints, seed) if with_c else None
@@ -106,10 +114,10 @@ def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alph
     at = None
     if samples is not None:
         at = sample_positions(M, N, samples, seed=M * 31 + N * 17 + K)
-    r = O.gemm(M, N, K, alpha, O.Operand(np16(A), la, lda), O.Operand(np16(B), lb, ldb), beta,
+    r = O.gemm(M, N, K, alpha, O.Operand(np16(A), la, lda, dtype=odt), O.Operand(np16(B), lb, ldb, dtype=odt), beta,
                C_host, None, ld_layout, ldc, bias=np16(bias), bias_dim=bias_dim or 0, act=act, at=at)
     got = Dlog if at is None else Dlog[at[0], at[1]]
-    what = "gemm M=%d N=%d K=%d A=%d B=%d D=%d alpha=%g beta=%g ints=%s" % (M, N, K, la, lb, ld_layout, alpha, beta, ints)
+    what = ("bf16 " if bf16 else "") + "gemm M=%d N=%d K=%d A=%d B=%d D=%d alpha=%g beta=%g ints=%s" % (M, N, K, la, lb, ld_layout, alpha, beta, ints)
     return compare(got, r["D"], r["G"], K, ints, what)
 
 
@@ -189,8 +197,10 @@ def run_diag_case(M, N, K, side="A", other_layout=fg.FG_COL, ld_layout=fg.FG_COL
 
 
 def run_cgemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alpha=1.0, beta=1.0, with_c=True,
-                   ints=False, pad=0, config=4, samples: Optional[int] = None, device="cuda", seed=W.DEFAULT_SEED):
-    """Planar-split complex D = alpha A B + beta C; real and imaginary planes are separate arrays."""
+                   ints=False, pad=0, config=4, samples: Optional[int] = None, device="cuda", seed=W.DEFAULT_SEED,
+                   dual=False):
+    """Planar-split complex (or, with ``dual``, dual-number) D = alpha A B + beta C; the two planes
+    are separate arrays."""
     Ar, lda = make_operand(M, K, la, W.stream_id(config, "A"), device, ints, pad, seed)
     Ai, _ = make_operand(M, K, la, W.stream_id(config, "A_im"), device, ints, pad, seed)
     Br, ldb = make_operand(K, N, lb, W.stream_id(config, "B"), device, ints, pad, seed)
@@ -201,17 +211,18 @@ def run_cgemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alp
     Ci = make_f32(ldc * other, W.stream_id(config, "C_im"), device, ints, seed) if with_c else None
     Dr = torch.full((ldc * other,), float("nan"), dtype=torch.float32, device=device)
     Di = torch.full((ldc * other,), float("nan"), dtype=torch.float32, device=device)
-    fg.fg_gemm(M, N, K, alpha, fg.Matrix(Ar, la, lda, im=Ai), fg.Matrix(Br, lb, ldb, im=Bi), beta,
-               fg.Matrix(Cr, ld_layout, ldc, im=Ci) if with_c else None, fg.Matrix(Dr, ld_layout, ldc, im=Di))
+    call = fg.fg_gemm_dual if dual else fg.fg_gemm
+    call(M, N, K, alpha, fg.Matrix(Ar, la, lda, im=Ai), fg.Matrix(Br, lb, ldb, im=Bi), beta,
+         fg.Matrix(Cr, ld_layout, ldc, im=Ci) if with_c else None, fg.Matrix(Dr, ld_layout, ldc, im=Di))
     torch.cuda.synchronize()
     view = lambda t: (np16(t).reshape(other, ldc)[:, :lead].T if ld_layout == fg.FG_COL else np16(t).reshape(other, ldc)[:, :lead])
     at = sample_positions(M, N, samples, seed=M * 3 + N * 5 + K) if samples is not None else None
     r = O.gemm(M, N, K, alpha, O.Operand(np16(Ar), la, lda, np16(Ai)), O.Operand(np16(Br), lb, ldb, np16(Bi)), beta,
-               np16(Cr), np16(Ci), ld_layout, ldc, at=at)
+               np16(Cr), np16(Ci), ld_layout, ldc, at=at, dual=dual)
     gr, gi = view(Dr), view(Di)
     if at is not None:
         gr, gi = gr[at[0], at[1]], gi[at[0], at[1]]
-    what = "cgemm M=%d N=%d K=%d A=%d B=%d D=%d ints=%s" % (M, N, K, la, lb, ld_layout, ints)
-    w1 = compare(gr, r["D"], r["G"], 2 * K, ints, what + " (real part)")
-    w2 = compare(gi, r["D_im"], r["G_im"], 2 * K, ints, what + " (imaginary part)")
+    what = ("dual" if dual else "complex") + " gemm M=%d N=%d K=%d A=%d B=%d D=%d ints=%s" % (M, N, K, la, lb, ld_layout, ints)
+    w1 = compare(gr, r["D"], r["G"], K if dual else 2 * K, ints, what + " (first plane)")
+    w2 = compare(gi, r["D_im"], r["G_im"], 2 * K, ints, what + " (second plane)")
     return max(w1, w2)

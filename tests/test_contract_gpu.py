@@ -28,6 +28,14 @@ def test_config5b_64():
     say("5b floats sampled"); run_contract_case(ext, [a, e, b, f], [d, f, c, e], [a, b, c, d], samples=8192)
 
 
+def test_paper_contraction_full_size():
+    """The contraction the paper times in Section 5.5: D_abc = sum_d A_bda B_dc with
+    (a, b, c, d) = (64, 32, 2048, 2048), sampled."""
+    ext = {a: 64, b: 32, c: 2048, d: 2048}
+    say("paper contraction ints sampled"); run_contract_case(ext, [b, d, a], [d, c], [a, b, c], ints=True, samples=8192)
+    say("paper contraction floats sampled"); run_contract_case(ext, [b, d, a], [d, c], [a, b, c], samples=8192)
+
+
 def test_small_contractions_every_entry():
     say("5a-shaped small"); run_contract_case({a: 64, b: 64, c: 3, d: 64}, [a, d, c], [d, b], [a, b, c], ints=True)
     say("5b-shaped small"); run_contract_case({a: 16, b: 4, c: 8, d: 8, e: 64, f: 2}, [a, e, b, f], [d, f, c, e], [a, b, c, d], ints=True)

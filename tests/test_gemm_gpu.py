@@ -95,3 +95,30 @@ def test_arbitrary_sizes_edge_tiles(la, lb, ldl):
 def test_arbitrary_sizes_large():
     say("5000x3000x1000 ints sampled"); run_gemm_case(5000, 3000, 1000, ints=True, config=2, samples=6000)
     say("4100x4100x4104 floats sampled"); run_gemm_case(4100, 4100, 4104, fg.FG_ROW, fg.FG_COL, config=2, samples=6000)
+
+
+@pytest.mark.parametrize("la,lb", list(itertools.product(LAYOUTS, LAYOUTS)))
+def test_bf16_inputs_all_layouts(la, lb):
+    """bfloat16 A and B (Section 2.2: the matrix unit's other 16-bit input type): exact on integers
+    for every tile shape, floats within tolerance, epilogue, edge tiles and a row-major result."""
+    for (M, N, K) in [(64, 64, 64), (128, 192, 256), (768, 1280, 320), (100, 75, 40)]:
+        say("bf16 ints M=%d N=%d K=%d la=%d lb=%d" % (M, N, K, la, lb))
+        run_gemm_case(M, N, K, la, lb, ints=True, pad=8, bf16=True)
+    say("bf16 floats 512"); run_gemm_case(512, 512, 512, la, lb, alpha=0.5, beta=2.0, bf16=True)
+    say("bf16 bias relu row-major D")
+    run_gemm_case(300, 513, 136, la, lb, ld_layout=fg.FG_ROW, bias_dim=1, act=fg.FG_ACT_RELU, bf16=True)
+
+
+def test_bf16_large_sampled():
+    say("bf16 4096 floats"); run_gemm_case(4096, 4096, 4096, samples=4096, bf16=True)
+    say("bf16 8192x1024x4096 ints"); run_gemm_case(8192, 1024, 4096, ints=True, samples=4096, bf16=True)
+
+
+def test_bf16_is_rejected_where_unsupported():
+    A = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
+    H = torch.zeros(64 * 64, dtype=torch.float16, device="cuda")
+    D = torch.zeros(64 * 64, dtype=torch.float32, device="cuda")
+    m = lambda t, **kw: fg.Matrix(t, fg.FG_COL, 64, **kw)
+    assert fg.fg_gemm(64, 64, 64, 1.0, m(A), m(H), 0.0, None, m(D), raise_on_error=False) == fg.FG_ERR_UNSUPPORTED
+    assert fg.fg_gemm(64, 64, 64, 1.0, m(A, im=A), m(A, im=A), 0.0, None, m(D, im=D), raise_on_error=False) == fg.FG_ERR_UNSUPPORTED
+    assert fg.fg_gemm(64, 64, 64, 1.0, fg.Matrix(A, fg.FG_DIAG, 0), m(A), 0.0, None, m(D), raise_on_error=False) == fg.FG_ERR_UNSUPPORTED

@@ -58,3 +58,20 @@ def test_edge_tiles_diagonal_and_complex():
         say("cgemm edge la=%d lb=%d" % (la, lb))
         run_cgemm_case(100, 75, 40, la, lb, ints=True, pad=8)
         run_cgemm_case(300, 513, 136, la, lb, ld_layout=fg.FG_ROW, alpha=0.5, beta=1.5)
+
+
+@pytest.mark.parametrize("la,lb", list(itertools.product(LAYOUTS, LAYOUTS)))
+def test_dual_numbers_all_layouts(la, lb):
+    """Dual-number products (Section 5.4, eps^2 = 0) on the planar layout: exact on integers for
+    every tile shape, floats within tolerance, edge tiles and a row-major result."""
+    for (M, N, K) in [(64, 64, 64), (256, 128, 192), (384, 512, 128), (100, 75, 40)]:
+        say("dual ints M=%d N=%d K=%d la=%d lb=%d" % (M, N, K, la, lb))
+        run_cgemm_case(M, N, K, la, lb, ints=True, pad=8, dual=True)
+    say("dual floats 512"); run_cgemm_case(512, 512, 512, la, lb, alpha=0.5, beta=2.0, dual=True)
+    say("dual row-major D"); run_cgemm_case(300, 513, 136, la, lb, ld_layout=fg.FG_ROW, alpha=0.5, beta=1.5, dual=True)
+    say("dual no C"); run_cgemm_case(256, 384, 128, la, lb, with_c=False, ints=True, dual=True)
+
+
+def test_dual_4096():
+    say("dual 4096 floats"); run_cgemm_case(4096, 4096, 4096, samples=4096, dual=True)
+    say("dual 4096 ints"); run_cgemm_case(4096, 4096, 4096, ints=True, samples=4096, dual=True)
