@@ -45,6 +45,7 @@ class _GemmProblem(C.Structure):
         ("B_re", C.c_void_p), ("B_im", C.c_void_p), ("layoutB", C.c_int32), ("ldb", C.c_int64),
         ("C_re", C.c_void_p), ("C_im", C.c_void_p), ("layoutC", C.c_int32), ("ldc", C.c_int64),
         ("bias", C.c_void_p), ("bias_dim", C.c_int32), ("act", C.c_int32), ("ab_dtype", C.c_int32), ("dual", C.c_int32),
+        ("ab_add", C.c_int32), ("a_add", C.c_double), ("b_add", C.c_double), ("c_act", C.c_int32),
     ]
 
 
@@ -67,6 +68,8 @@ def lib():
         l = C.CDLL(build())
         l.oracle_half_to_double.restype = C.c_double
         l.oracle_half_to_double.argtypes = [C.c_uint16]
+        l.oracle_round_to_half.restype = C.c_double
+        l.oracle_round_to_half.argtypes = [C.c_double]
         l.oracle_bf16_to_double.restype = C.c_double
         l.oracle_bf16_to_double.argtypes = [C.c_uint16]
         pd = C.c_void_p
@@ -95,6 +98,10 @@ def half_to_double(bits: int) -> float:
 
 def bf16_to_double(bits: int) -> float:
     return float(lib().oracle_bf16_to_double(int(bits) & 0xFFFF))
+
+
+def round_to_half(x: float) -> float:
+    return float(lib().oracle_round_to_half(float(x)))
 
 
 F16, BF16 = 0, 1
@@ -165,8 +172,11 @@ def _gemm_problem(M, N, K, alpha, A: Operand, B: Operand, beta, Cre, Cim, layout
 def gemm(M: int, N: int, K: int, alpha: float, A: Operand, B: Operand, beta: float = 0.0,
          C_re: Optional[np.ndarray] = None, C_im: Optional[np.ndarray] = None, layoutC: int = COL, ldc: int = 0,
          bias: Optional[np.ndarray] = None, bias_dim: int = 0, act: int = ACT_NONE,
-         at: Optional[Sequence[np.ndarray]] = None, threads: Optional[int] = None, dual: bool = False):
+         at: Optional[Sequence[np.ndarray]] = None, threads: Optional[int] = None, dual: bool = False,
+         ab_add: Optional[Sequence[float]] = None, c_act: int = ACT_NONE):
     """Evaluate the GEMM definition.  ``dual``: the ``im`` planes hold dual parts (eps^2 = 0).
+    ``ab_add=(a, b)``: every loaded element of A (B) becomes half(element + a) (half(element + b)),
+    a and b binary16 values; ``c_act``: activation applied to C before it is scaled by beta.
 
     Returns a dict with ``D`` and ``G`` (float64; complex problems also ``D_im`` and ``G_im``).
     Without ``at`` the arrays are (M, N); with ``at=(I, J)`` they are 1-D, one value per listed
@@ -175,6 +185,9 @@ def gemm(M: int, N: int, K: int, alpha: float, A: Operand, B: Operand, beta: flo
     threads = threads or default_threads()
     q = _gemm_problem(M, N, K, alpha, A, B, beta, C_re, C_im, layoutC, ldc, bias, bias_dim, act)
     q.dual = 1 if dual else 0
+    if ab_add is not None:
+        q.ab_add, q.a_add, q.b_add = 1, float(ab_add[0]), float(ab_add[1])
+    q.c_act = c_act
     is_complex = A.im is not None or B.im is not None
     if at is None:
         shape, order = (M, N), "F"

@@ -88,6 +88,24 @@ static inline double h2d(uint16_t h) { return g_half_table[0][h]; }
 double oracle_half_to_double(uint16_t h) { return half_bits_to_double(h); }
 double oracle_bf16_to_double(uint16_t h) { return bf16_bits_to_double(h); }
 
+/* Nearest binary16 value (ties to even) of a double, returned as a double.  Used for the
+ * element-wise addition on A and B (Section 4.3 "transforms", Section 5.3 fusion table), which
+ * the method performs in the element type: the exact sum of two binary16 values, which a double
+ * holds exactly, rounded once. */
+static double round_to_half(double x) {
+    if (isnan(x) || isinf(x) || x == 0.0) return x;
+    double ax = fabs(x);
+    int e;
+    (void)frexp(ax, &e);                    /* ax = m * 2^e with m in [0.5, 1): leading bit 2^(e-1) */
+    int lead = e - 1;
+    if (lead < -14) lead = -14;             /* subnormals share the quantum of the lowest binade */
+    double quantum = ldexp(1.0, lead - 10); /* spacing of binary16 values in that binade */
+    double v = nearbyint(ax / quantum) * quantum;   /* round-to-nearest-even is the default mode */
+    if (v > 65504.0) v = INFINITY;
+    return x < 0.0 ? -v : v;
+}
+double oracle_round_to_half(double x) { return round_to_half(x); }
+
 /* ---- problem descriptions ------------------------------------------------------- */
 
 typedef struct {
@@ -108,6 +126,11 @@ typedef struct {
     int32_t ab_dtype;              /* element type of A and B: 0 binary16, 1 bfloat16 */
     int32_t dual;                  /* 1: the second planes are dual parts (eps^2 = 0, Section 5.4)
                                       instead of imaginary parts (i^2 = -1)        */
+    /* transforms applied to loaded elements (Section 4.3 "transforms"; last rows of the fusion
+       table of Section 5.3); real binary16 COL/ROW operands only */
+    int32_t ab_add;                /* 1: A_ik := half(A_ik + a_add), B_kj := half(B_kj + b_add) */
+    double a_add, b_add;           /* must be binary16 values                    */
+    int32_t c_act;                 /* activation applied to C_ij before beta     */
 } og_problem;
 
 /* logical element (r, c) of a stored rows x cols operand */
@@ -131,6 +154,10 @@ static void gemm_entry(const og_problem *q, int64_t i, int64_t j,
     for (int64_t k = 0; k < q->K; ++k) {
         double ar = operand_at(q->A_re, q->layoutA, q->lda, i, k, dec);
         double br = operand_at(q->B_re, q->layoutB, q->ldb, k, j, dec);
+        if (q->ab_add) {
+            ar = round_to_half(ar + q->a_add);
+            br = round_to_half(br + q->b_add);
+        }
         if (!is_complex) {
             s_re += ar * br;
             m_re += fabs(ar) * fabs(br);
@@ -154,6 +181,7 @@ static void gemm_entry(const og_problem *q, int64_t i, int64_t j,
     double t_re = fabs(q->alpha) * m_re, t_im = fabs(q->alpha) * m_im;
     if (q->C_re) {
         double c = c_at(q->C_re, q->layoutC, q->ldc, i, j);
+        if (q->c_act == OG_ACT_RELU) c = (c > 0.0) ? c : 0.0;
         y_re += q->beta * c;
         t_re += fabs(q->beta) * fabs(c);
     }
@@ -179,6 +207,11 @@ static int gemm_problem_ok(const og_problem *q) {
     if (q->bias && q->bias_dim != 0 && q->bias_dim != 1) return 0;
     if (q->act != OG_ACT_NONE && q->act != OG_ACT_RELU) return 0;
     if (q->ab_dtype != 0 && q->ab_dtype != 1) return 0;
+    if (q->c_act != OG_ACT_NONE && q->c_act != OG_ACT_RELU) return 0;
+    if (q->ab_add || q->c_act) {
+        if (q->A_im || q->B_im || q->ab_dtype != 0 || q->layoutA == OG_DIAG || q->layoutB == OG_DIAG) return 0;
+        if (q->ab_add && (round_to_half(q->a_add) != q->a_add || round_to_half(q->b_add) != q->b_add)) return 0;
+    }
     const int is_complex = (q->A_im != NULL) || (q->B_im != NULL);
     if (is_complex && (q->bias || q->act != OG_ACT_NONE)) return 0; /* not defined for complex */
     return 1;

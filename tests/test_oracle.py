@@ -395,3 +395,67 @@ def test_dual_product_is_value_and_first_derivative():
     assert np.array_equal(r["D"] - c["D"], 2.0 * (Ad @ Bd))
     assert np.array_equal(r["D_im"], c["D_im"])
     assert np.array_equal(r["G"], 2.0 * (np.abs(Ar) @ np.abs(Br)) + 3.0 * np.abs(Cr))
+
+
+# ---------------------------------------------------------------- transforms on loaded elements
+def _nearest_half_exact(x):
+    """Round a Fraction to binary16 with ties to even by searching the table of all finite values."""
+    from fractions import Fraction
+    import bisect
+    if not hasattr(_nearest_half_exact, "tab"):
+        bits = np.arange(0, 0x7C00, dtype=np.uint16)                 # non-negative finite values, ascending
+        _nearest_half_exact.tab = [Fraction(float(v)) for v in bits.view(np.float16)]
+    tab = _nearest_half_exact.tab
+    sign, ax = (-1, -x) if x < 0 else (1, x)
+    if ax >= Fraction(65520):
+        return sign * float("inf")
+    hi = bisect.bisect_left(tab, ax)
+    if hi == len(tab):
+        return sign * float(tab[-1])
+    if tab[hi] == ax or hi == 0:
+        return sign * float(tab[hi])
+    lo = hi - 1
+    dl, dh = ax - tab[lo], tab[hi] - ax
+    pick = lo if dl < dh else hi if dh < dl else (lo if lo % 2 == 0 else hi)   # even bit pattern = even mantissa
+    return sign * float(tab[pick])
+
+
+def test_round_to_half_against_exact_rational_rounding():
+    from fractions import Fraction
+    bits = RNG.integers(0, 65536, size=(6000, 2)).astype(np.uint16)
+    vals = bits.view(np.float16).astype(np.float64)
+    ok = np.isfinite(vals).all(axis=1)
+    # add pairs that straddle binades, subnormals and the overflow threshold
+    extra = np.array([[65504.0, 16.0], [65504.0, 15.99], [65504.0, 8.0], [2.0 ** -24, 2.0 ** -24], [2.0 ** -14, -2.0 ** -24],
+                      [1.0, 2.0 ** -11], [1.0, 3 * 2.0 ** -12], [1.0 + 2.0 ** -10, 2.0 ** -11], [-2048.0, -1.0], [0.1, -0.1]])
+    extra = extra.astype(np.float16).astype(np.float64)
+    for a, b in np.concatenate([vals[ok], extra]):
+        want = _nearest_half_exact(Fraction(a) + Fraction(b))
+        got = O.round_to_half(a + b)          # a + b is exact in double
+        assert got == want, (a, b, got, want)
+
+
+def test_ab_add_and_relu_on_c_by_brute_force():
+    M, N, K = 5, 4, 7
+    Am, Bm = rand_mat(M, K), rand_mat(K, N)
+    A, lda, Ah = store(Am, ROW, pad=1); B, ldb, Bh = store(Bm, ROW, pad=2)
+    Cm = rand_mat(M, N).astype(np.float32)
+    bias = rand_mat(1, N).astype(np.float32).reshape(-1)
+    a_add, b_add = float(np.float16(0.3)), float(np.float16(-1.7))
+    r = O.gemm(M, N, K, 1.5, Operand(A, ROW, lda), Operand(B, ROW, ldb), -0.5, Cm.T.copy().reshape(-1), None, COL, M,
+               bias=bias, bias_dim=1, act=ACT_RELU, ab_add=(a_add, b_add), c_act=ACT_RELU)
+    # numpy float16 addition of moderate values rounds once (float32 holds the exact sum)
+    A2 = (Ah.astype(np.float16) + np.float16(a_add)).astype(np.float64)
+    B2 = (Bh.astype(np.float16) + np.float16(b_add)).astype(np.float64)
+    want = np.zeros((M, N))
+    for i in range(M):
+        for j in range(N):
+            acc = sum(A2[i, k] * B2[k, j] for k in range(K))
+            want[i, j] = max(1.5 * acc - 0.5 * max(float(Cm[i, j]), 0.0) + float(bias[j]), 0.0)
+    assert np.allclose(r["D"], want, rtol=0, atol=1e-12)
+    # a zero addend and no activation on C give back the plain product
+    r0 = O.gemm(M, N, K, 1.5, Operand(A, ROW, lda), Operand(B, ROW, ldb), -0.5, Cm.T.copy().reshape(-1), None, COL, M, ab_add=(0.0, 0.0))
+    r1 = O.gemm(M, N, K, 1.5, Operand(A, ROW, lda), Operand(B, ROW, ldb), -0.5, Cm.T.copy().reshape(-1), None, COL, M)
+    assert np.array_equal(r0["D"], r1["D"])
+    with pytest.raises(ValueError):
+        O.gemm(M, N, K, 1.0, Operand(A, ROW, lda), Operand(B, ROW, ldb), ab_add=(0.3, 0.0))     # 0.3 is not a binary16 value
