@@ -113,6 +113,12 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream):
     guard("config3_relu_bias_8192x1024x4096_TFLOPs", lambda: 2.0 * 8192 * 1024 * 4096 / timed(lambda: fg.fg_gemm(
         8192, 1024, 4096, 1.0, M(A[:8192 * 4096], 0, 8192), M(B[:4096 * 1024], 0, 4096), 0.0, None, M(D3, 0, 8192),
         bias=bias, bias_dim=0, act=fg.FG_ACT_RELU, stream=stream)) * 1e-12)
+    # last row of the fusion table (Section 5.3): bias, ReLU on C and D, a constant added to A and B
+    guard("fusion_table_last_row_4096_TFLOPs", lambda: 2.0 * m ** 3 / timed(lambda: fg.fg_gemm(
+        m, m, m, 1.0, M(A4, 0, m), M(B4, 0, m), 1.0, M(C4, 0, m), M(D4, 0, m), bias=bias, bias_dim=0, act=fg.FG_ACT_RELU,
+        a_add=0.5, b_add=-0.25, c_act=fg.FG_ACT_RELU, stream=stream)) * 1e-12)
+    guard("fusion_table_first_row_4096_TFLOPs", lambda: 2.0 * m ** 3 / timed(lambda: fg.fg_gemm(
+        m, m, m, 1.0, M(A4, 0, m), M(B4, 0, m), 1.0, M(C4, 0, m), M(D4, 0, m), stream=stream)) * 1e-12)
     guard("config4_complex_planar_4096_TFLOPs", lambda: 8.0 * m ** 3 / timed(lambda: fg.fg_gemm(
         m, m, m, 1.0, M(A4, 0, m, im=A4i), M(B4, 0, m, im=B4i), 1.0, M(C4, 0, m, im=C4i), M(D4, 0, m, im=D4i), stream=stream)) * 1e-12)
     guard("dual_planar_4096_TFLOPs", lambda: 6.0 * m ** 3 / timed(lambda: fg.fg_gemm_dual(

@@ -108,6 +108,28 @@ fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha,
                   const fg_matrix *D, const fg_epilogue *ep,
                   void *hip_stream);
 
+/* Operations applied to elements right after they are loaded (the "transforms" of Section 4.3;
+ * the last two rows of the fusion table of Section 5.3: ReLU on C, an addition on A and B). */
+typedef struct {
+    float   a_add;   /* every element of A becomes half(A_ik + a_add): a_add is rounded to FP16      */
+    float   b_add;   /* (nearest even) and the sum is formed and rounded once in FP16; likewise B.   */
+                     /* Both 0: A and B are used as stored.                                          */
+    int32_t c_act;   /* fg_act applied to every element of C before it is scaled by beta             */
+} fg_load_transforms;
+
+/*
+ * D = act(alpha * (A + a_add) * (B + b_add) + beta * c_act(C) + bias): fg_gemm with transforms on
+ * the loaded elements.  `lt == NULL` is fg_gemm.  All arguments, requirements and errors as for
+ * fg_gemm; in addition a non-zero a_add or b_add needs real FG_F16 operands in FG_COL or FG_ROW
+ * layout (FG_ERR_UNSUPPORTED for complex, FG_BF16 or diagonal operands), and c_act needs a real
+ * product.  Elements of A and B outside the M x K and K x N matrices stay zero.
+ */
+fg_status fg_gemm_ex(int64_t M, int64_t N, int64_t K, float alpha,
+                     const fg_matrix *A, const fg_matrix *B,
+                     float beta, const fg_matrix *C,
+                     const fg_matrix *D, const fg_epilogue *ep,
+                     const fg_load_transforms *lt, void *hip_stream);
+
 /*
  * Dual-number product (Section 5.4): every element is x + eps.x' with eps^2 = 0, stored like the
  * planar complex matrices (value plane at `re`, dual plane at `im`), so

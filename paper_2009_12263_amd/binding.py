@@ -22,7 +22,7 @@ FG_F16, FG_BF16, FG_F32 = 0, 1, 2
 FG_COL, FG_ROW, FG_DIAG, FG_ZERO = 0, 1, 2, 3
 FG_ACT_NONE, FG_ACT_RELU = 0, 1
 
-EXPORTS = ("fg_gemm", "fg_gemm_dual", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan", "fg_probe_mfma")
+EXPORTS = ("fg_gemm", "fg_gemm_ex", "fg_gemm_dual", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan", "fg_probe_mfma")
 FG_PLAN_REAL, FG_PLAN_COMPLEX, FG_PLAN_DUAL, FG_PLAN_REAL_BF16 = 0, 1, 2, 3
 
 
@@ -32,6 +32,10 @@ class fg_matrix(C.Structure):
 
 class fg_epilogue(C.Structure):
     _fields_ = [("bias", C.c_void_p), ("bias_dim", C.c_int32), ("act", C.c_int32)]
+
+
+class fg_load_transforms(C.Structure):
+    _fields_ = [("a_add", C.c_float), ("b_add", C.c_float), ("c_act", C.c_int32)]
 
 
 class FlexGemmError(RuntimeError):
@@ -55,6 +59,10 @@ def load_library() -> C.CDLL:
         lib.fg_gemm.restype = C.c_int
         lib.fg_gemm.argtypes = [i64, i64, i64, f32, C.POINTER(fg_matrix), C.POINTER(fg_matrix), f32,
                                 C.POINTER(fg_matrix), C.POINTER(fg_matrix), C.POINTER(fg_epilogue), vp]
+        lib.fg_gemm_ex.restype = C.c_int
+        lib.fg_gemm_ex.argtypes = [i64, i64, i64, f32, C.POINTER(fg_matrix), C.POINTER(fg_matrix), f32,
+                                   C.POINTER(fg_matrix), C.POINTER(fg_matrix), C.POINTER(fg_epilogue),
+                                   C.POINTER(fg_load_transforms), vp]
         lib.fg_gemm_dual.restype = C.c_int
         lib.fg_gemm_dual.argtypes = [i64, i64, i64, f32, C.POINTER(fg_matrix), C.POINTER(fg_matrix), f32,
                                      C.POINTER(fg_matrix), C.POINTER(fg_matrix), vp]
@@ -117,8 +125,10 @@ def _check(status: int, raise_on_error: bool) -> int:
 
 def fg_gemm(M: int, N: int, K: int, alpha: float, A: Optional[Matrix], B: Optional[Matrix], beta: float,
             C_: Optional[Matrix], D: Optional[Matrix], bias: Optional[torch.Tensor] = None, bias_dim: int = 0,
-            act: int = FG_ACT_NONE, stream=None, raise_on_error: bool = True) -> int:
-    """D = act(alpha * op(A) * op(B) + beta * C + bias); see fg_gemm in include/flexgemm.h."""
+            act: int = FG_ACT_NONE, stream=None, raise_on_error: bool = True,
+            a_add: float = 0.0, b_add: float = 0.0, c_act: int = FG_ACT_NONE) -> int:
+    """D = act(alpha * op(A) * op(B) + beta * C + bias); see fg_gemm in include/flexgemm.h.
+    With ``a_add``, ``b_add`` or ``c_act`` the call goes to fg_gemm_ex (transforms on loaded elements)."""
     lib = load_library()
     sa = A._struct() if A is not None else None
     sb = B._struct() if B is not None else None
@@ -130,7 +140,11 @@ def fg_gemm(M: int, N: int, K: int, alpha: float, A: Optional[Matrix], B: Option
         ep.bias = bias.data_ptr() if bias is not None else None
         ep.bias_dim, ep.act = bias_dim, act
     ref = lambda s: C.byref(s) if s is not None else None
-    st = lib.fg_gemm(M, N, K, alpha, ref(sa), ref(sb), beta, ref(sc), ref(sd), ref(ep), _stream_handle(stream))
+    if a_add != 0.0 or b_add != 0.0 or c_act != FG_ACT_NONE:
+        lt = fg_load_transforms(a_add, b_add, c_act)
+        st = lib.fg_gemm_ex(M, N, K, alpha, ref(sa), ref(sb), beta, ref(sc), ref(sd), ref(ep), C.byref(lt), _stream_handle(stream))
+    else:
+        st = lib.fg_gemm(M, N, K, alpha, ref(sa), ref(sb), beta, ref(sc), ref(sd), ref(ep), _stream_handle(stream))
     return _check(st, raise_on_error)
 
 

@@ -46,6 +46,9 @@ struct Problem {
     bool cplx;               // two planes per operand: complex, or dual when `dual` is set
     bool dual;
     bool bf16;               // A and B hold bfloat16
+    int c_act;               // activation on loaded C
+    uint16_t a_add, b_add;   // FP16 bit patterns of the addends on loaded A and B; ab_add: in use
+    bool ab_add;
 };
 
 const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
@@ -98,6 +101,11 @@ const fg::KernelEntry *select_kernel(const Problem &q) {
     if (tile < 0) return nullptr;
     if (q.a_diag) return &fg::kernel_table_diag()[tile * 4 + (q.b_kc ? 0 : 1)];
     if (q.b_diag) return &fg::kernel_table_diag()[tile * 4 + (q.a_kc ? 2 : 3)];
+    if (q.ab_add) {
+        const fg::KernelEntry *t = !q.a_kc ? (q.b_kc ? fg::kernel_table_nn_xf() : fg::kernel_table_nt_xf())
+                                           : (q.b_kc ? fg::kernel_table_tn_xf() : fg::kernel_table_tt_xf());
+        return &t[tile];
+    }
     if (q.bf16) {
         const fg::KernelEntry *t = !q.a_kc ? (q.b_kc ? fg::kernel_table_nn_bf16() : fg::kernel_table_nt_bf16())
                                            : (q.b_kc ? fg::kernel_table_tn_bf16() : fg::kernel_table_tt_bf16());
@@ -177,7 +185,8 @@ fg_status check_output_matrix(const char *name, const fg_matrix *X, int64_t rows
 // Validate an fg_gemm call and normalise it so that D is column-major: a row-major D is the
 // column-major D^T = op(B)^T op(A)^T, i.e. the same kernel with the operands exchanged.
 fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
-                    float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, bool dual, Problem &q) {
+                    float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, bool dual,
+                    const fg_load_transforms *lt, Problem &q) {
     if (fg_status st = check_sizes(M, N, K)) return st;
     if (fg_status st = check_input_matrix("A", A, M, K)) return st;
     if (fg_status st = check_input_matrix("B", B, K, N)) return st;
@@ -206,8 +215,29 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
     if (cplx && (!A->im || !B->im)) return fail(FG_ERR_UNSUPPORTED, "complex and dual products need the second plane of both A and B");
     if (cplx && (A->layout == FG_DIAG || B->layout == FG_DIAG)) return fail(FG_ERR_UNSUPPORTED, "complex or dual diagonal operands are not supported");
 
+    // transforms on loaded elements
+    uint16_t a_add = 0, b_add = 0;
+    int c_act = FG_ACT_NONE;
+    if (lt) {
+        if (lt->c_act != FG_ACT_NONE && lt->c_act != FG_ACT_RELU) return fail(FG_ERR_LAYOUT, "unknown activation %d on C", lt->c_act);
+        if (!(lt->a_add == lt->a_add) || !(lt->b_add == lt->b_add)) return fail(FG_ERR_SHAPE, "a_add or b_add is NaN");
+        const _Float16 ha = (_Float16)lt->a_add, hb = (_Float16)lt->b_add;     // round to nearest even
+        memcpy(&a_add, &ha, 2); memcpy(&b_add, &hb, 2);
+        if ((a_add & 0x7fff) == 0) a_add = 0;                                   // -0 adds nothing either
+        if ((b_add & 0x7fff) == 0) b_add = 0;
+        c_act = lt->c_act;
+    }
+    const bool ab_add = a_add != 0 || b_add != 0;
+    if (ab_add && (cplx || bf16 || A->layout == FG_DIAG || B->layout == FG_DIAG))
+        return fail(FG_ERR_UNSUPPORTED, "an addition on A and B needs real FG_F16 operands in FG_COL or FG_ROW layout");
+    if (c_act != FG_ACT_NONE && cplx) return fail(FG_ERR_UNSUPPORTED, "an activation on C is not defined for complex or dual products");
+
     const bool swap = (D->layout == FG_ROW);
     q.cplx = cplx;
+    q.c_act = c_act;
+    q.ab_add = ab_add;
+    q.a_add = swap ? b_add : a_add;
+    q.b_add = swap ? a_add : b_add;
     q.dual = dual;
     q.bf16 = bf16;
     q.alpha = alpha;
@@ -390,9 +420,10 @@ const char *fg_last_error(void) { return g_err; }
 int32_t fg_version(void) { return 100; }   // 0.1.0
 
 static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
-                           float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, bool dual, void *hip_stream) {
+                           float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, bool dual,
+                           const fg_load_transforms *lt, void *hip_stream) {
     Problem q;
-    if (fg_status st = normalise(M, N, K, alpha, A, B, beta, C, D, ep, dual, q)) return st;
+    if (fg_status st = normalise(M, N, K, alpha, A, B, beta, C, D, ep, dual, lt, q)) return st;
     if (q.M == 0 || q.N == 0) return FG_OK;
     const fg::KernelEntry *kp = select_kernel(q);
     if (!kp) return fail(FG_ERR_UNSUPPORTED, "no block tile divides M=%lld, N=%lld", (long long)q.M, (long long)q.N);
@@ -413,18 +444,26 @@ static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const f
     if (p.a_span * 2 >= (1ll << 31) || p.b_span * 2 >= (1ll << 31)) return fail(FG_ERR_UNSUPPORTED, "A and B must each span less than 2 GiB");
     p.C = q.C; p.D = q.D; p.C_im = q.C_im; p.D_im = q.D_im; p.ldc = q.ldc; p.ldd = q.ldd;
     p.bias = q.bias; p.bias_dim = q.bias_dim; p.act = q.act; p.has_c = q.C != nullptr;
+    p.c_act = q.c_act;
+    p.a_add2 = (uint32_t)q.a_add * 0x10001u; p.b_add2 = (uint32_t)q.b_add * 0x10001u;
     p.alpha = q.alpha; p.beta = q.beta;
     return launch(k, p, (hipStream_t)hip_stream);
 }
 
 fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
                   float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, void *hip_stream) {
-    return gemm_impl(M, N, K, alpha, A, B, beta, C, D, ep, false, hip_stream);
+    return gemm_impl(M, N, K, alpha, A, B, beta, C, D, ep, false, nullptr, hip_stream);
+}
+
+fg_status fg_gemm_ex(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
+                     float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep,
+                     const fg_load_transforms *lt, void *hip_stream) {
+    return gemm_impl(M, N, K, alpha, A, B, beta, C, D, ep, false, lt, hip_stream);
 }
 
 fg_status fg_gemm_dual(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
                        float beta, const fg_matrix *C, const fg_matrix *D, void *hip_stream) {
-    return gemm_impl(M, N, K, alpha, A, B, beta, C, D, nullptr, true, hip_stream);
+    return gemm_impl(M, N, K, alpha, A, B, beta, C, D, nullptr, true, nullptr, hip_stream);
 }
 
 fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t layoutB, int32_t layoutD,

@@ -61,6 +61,10 @@ struct GemmParams {
     float alpha, beta;
     int32_t bias_dim, act, has_c;
     int32_t diag_a;                   // A is diagonal: A points at the diagonal entries
+    // transforms on loaded elements (Section 4.3): C_ij := act(C_ij); with TileCfg::XFORM also
+    // A_ik := half(A_ik + a_add), B_kj := half(B_kj + b_add), the addend as two packed halves
+    int32_t c_act;
+    uint32_t a_add2, b_add2;
     // tensor contraction: mode groups of each tensor
     ModeGroup a_m, a_k, b_n, b_k, c_m, c_n;
 };
@@ -70,7 +74,7 @@ struct GemmParams {
 // 32x32 MFMA accumulators.  A_KC / B_KC: operand is K-contiguous in memory (A row-major,
 // B column-major) rather than M/N-contiguous.  STAGES LDS buffers per operand form a ring over K.
 template <int BM_, int BN_, int BK_, int STAGES_, int WGM_, int WGN_, bool A_KC_, bool B_KC_, bool STRIDED_,
-          int DIAG_ = 0, int CPLX_ = 0, bool SPREAD_ = false, bool BF16_ = false>
+          int DIAG_ = 0, int CPLX_ = 0, bool SPREAD_ = false, bool BF16_ = false, bool XFORM_ = false>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_;
     static constexpr int KSTEPS = BK / 16;                          // MFMA k-slices per tile
@@ -82,6 +86,9 @@ struct TileCfg {
     // 0: real; 1: complex (i^2 = -1), 2: dual (eps^2 = 0) numbers in planar-split storage
     static constexpr int CPLX = CPLX_;
     static constexpr bool BF16 = BF16_;                             // A, B are bfloat16 instead of binary16
+    // XFORM: a constant is added to every element of A and of B after it is loaded (the fragment
+    // registers are transformed just before the matrix instructions that consume them)
+    static constexpr bool XFORM = XFORM_;
     static constexpr int DIAG = DIAG_;                              // 0: none, 1: A diagonal, 2: B diagonal
     // SPREAD: the refill loads of a ring buffer are issued one at a time between the MFMAs of two
     // k-slices (A's part in the slice after the buffer is retired, B's part in the next one)
@@ -110,6 +117,7 @@ struct TileCfg {
     static_assert(DIAG != 2 || B_KC, "a diagonal B is synthesised K-contiguous");
     static_assert(!(CPLX && (DIAG || STRIDED)), "complex products take plain matrices");
     static_assert(!SPREAD || STAGES >= 4 || KSTEPS >= 4, "spread refills need slack before the tile is needed");
+    static_assert(!XFORM || (DIAG == 0 && CPLX == 0 && !BF16 && !STRIDED), "element-wise addition on A and B: plain real FP16 matrices");
 };
 
 // ---- swizzles -------------------------------------------------------------------------------
@@ -448,6 +456,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
     const int lm = lane & 31, lh = lane >> 5;
     const bool bias_m_on = p.bias && p.bias_dim == 0, bias_n_on = p.bias && p.bias_dim != 0;
     const float floor_v = p.act == 1 ? 0.f : -__builtin_inff();
+    const float floor_c = p.c_act == 1 ? 0.f : -__builtin_inff();       // activation on loaded C
     if constexpr (!Cfg::STRIDED) {
         // (m, n) at m + n*ld.  All accesses are buffer operations on a descriptor whose base is this
         // wave's corner of the tile: the per-lane part of the address is one register for all of
@@ -491,7 +500,10 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     float y = p.alpha * acc[i][j][r] + bv[r];
-                    if constexpr (HAS_C) y += p.beta * cv[b & 1][r];
+                    if constexpr (HAS_C) {
+                        const float c = cv[b & 1][r];
+                        y += p.beta * (c > floor_c ? c : floor_c);
+                    }
                     y = y > floor_v ? y : floor_v;
                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, voff_d,
                                                           128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, 0);
@@ -514,9 +526,11 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                         const bool n_ok = ncol + 4 * lh < p.N;
                         float y = p.alpha * acc[i][j][r] + bias_mi;
                         if (bias_n_on && n_ok) y += p.bias[ncol + 4 * lh];
-                        if constexpr (HAS_C)
-                            y += p.beta * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                              rc, n_ok ? vc : kOutOfRange, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, 0));
+                        if constexpr (HAS_C) {
+                            const float c = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                rc, n_ok ? vc : kOutOfRange, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, 0));
+                            y += p.beta * (c > floor_c ? c : floor_c);
+                        }
                         y = y > floor_v ? y : floor_v;
                         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, n_ok ? vd : kOutOfRange,
                                                               128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, 0);
@@ -607,6 +621,8 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % Cfg::WGM, wn = wave / Cfg::WGM;
     const int ntiles = p.tiles_m * p.tiles_n;
+    [[maybe_unused]] const uint32_t xf_a = p.a_add2, xf_b = p.b_add2;   // used by TileCfg::XFORM only
+    [[maybe_unused]] const int xf_k = p.K;
 
     FG_LDS char *lds_a = smem;
     FG_LDS char *lds_b = smem + Cfg::A_BYTES;
@@ -752,6 +768,19 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                     // otherwise sink every fragment read down to its first use one slice later and
                     // expose the LDS latency in front of each MFMA pair.
                     __builtin_amdgcn_sched_barrier(0);
+                    // Element-wise addition on the loaded A and B values of this slice.  Positions at
+                    // or beyond K were filled with zeros by the loads and must stay zero, so their
+                    // addend is zero (a lane's eight values share one k chunk, K is a multiple of 8).
+                    half8 add_a, add_b;
+                    if constexpr (Cfg::XFORM) {
+                        const bool in_k = (kt0 + kt) * BK + ks * 16 + 8 * (lane >> 5) < xf_k;
+                        const uint32_t wa = in_k ? xf_a : 0u, wb = in_k ? xf_b : 0u;
+                        add_a = __builtin_bit_cast(half8, u32x4{wa, wa, wa, wa});
+                        add_b = __builtin_bit_cast(half8, u32x4{wb, wb, wb, wb});
+#pragma unroll
+                        for (int j = 0; j < TJ; ++j) bf[0][rb][j] += add_b;
+                        af[0][0] += add_a;
+                    }
 #pragma unroll
                     for (int i = 0; i < TI; ++i) {
                         // MFMA rows <- our N index, MFMA columns <- our M index: lanes of the
@@ -778,6 +807,10 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                                 acc[1][i][j] = mfma<Cfg::BF16>(bf[1][rb][j], af[0][i], acc[1][i][j]);
                                 acc[1][i][j] = mfma<Cfg::BF16>(bf[0][rb][j], af[1][i], acc[1][i][j]);
                             }
+                        }
+                        if constexpr (Cfg::XFORM) {
+                            // the next sub-tile row's values, while this row's instructions run
+                            if (i + 1 < TI) af[0][i + 1] += add_a;
                         }
                         if (!last || MORE) {
 #pragma unroll

@@ -87,7 +87,7 @@ def compare(got: np.ndarray, ref: np.ndarray, G: np.ndarray, K: int, exact: bool
 
 def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alpha=1.0, beta=1.0, with_c=True,
                   bias_dim=None, act=fg.FG_ACT_NONE, ints=False, pad=0, config=1, samples: Optional[int] = None,
-                  inplace=False, device="cuda", seed=W.DEFAULT_SEED, bf16=False):
+                  inplace=False, device="cuda", seed=W.DEFAULT_SEED, bf16=False, ab_add=None, c_act=fg.FG_ACT_NONE):
     """Run fg_gemm on seeded inputs and compare with the oracle.  ``samples`` None: every entry."""
     dt = torch.bfloat16 if bf16 else torch.float16
     odt = O.BF16 if bf16 else O.F16
@@ -103,7 +103,8 @@ def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alph
     C_host = np16(Cbuf).copy() if with_c else None
     fg.fg_gemm(M, N, K, alpha, fg.Matrix(A, la, lda), fg.Matrix(B, lb, ldb), beta,
                fg.Matrix(Cbuf, ld_layout, ldc) if with_c else None, fg.Matrix(Dbuf, ld_layout, ldc),
-               bias=bias, bias_dim=bias_dim or 0, act=act)
+               bias=bias, bias_dim=bias_dim or 0, act=act,
+               a_add=ab_add[0] if ab_add else 0.0, b_add=ab_add[1] if ab_add else 0.0, c_act=c_act)
     torch.cuda.synchronize()
     D_host = np16(Dbuf)
     # padding of D must be untouched
@@ -115,9 +116,10 @@ def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alph
     if samples is not None:
         at = sample_positions(M, N, samples, seed=M * 31 + N * 17 + K)
     r = O.gemm(M, N, K, alpha, O.Operand(np16(A), la, lda, dtype=odt), O.Operand(np16(B), lb, ldb, dtype=odt), beta,
-               C_host, None, ld_layout, ldc, bias=np16(bias), bias_dim=bias_dim or 0, act=act, at=at)
+               C_host, None, ld_layout, ldc, bias=np16(bias), bias_dim=bias_dim or 0, act=act, at=at,
+               ab_add=ab_add, c_act=c_act)
     got = Dlog if at is None else Dlog[at[0], at[1]]
-    what = ("bf16 " if bf16 else "") + "gemm M=%d N=%d K=%d A=%d B=%d D=%d alpha=%g beta=%g ints=%s" % (M, N, K, la, lb, ld_layout, alpha, beta, ints)
+    what = ("bf16 " if bf16 else "") + ("ab_add=%r c_act=%d " % (ab_add, c_act) if (ab_add or c_act) else "") + "gemm M=%d N=%d K=%d A=%d B=%d D=%d alpha=%g beta=%g ints=%s" % (M, N, K, la, lb, ld_layout, alpha, beta, ints)
     return compare(got, r["D"], r["G"], K, ints, what)
 
 

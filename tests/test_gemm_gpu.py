@@ -122,3 +122,41 @@ def test_bf16_is_rejected_where_unsupported():
     assert fg.fg_gemm(64, 64, 64, 1.0, m(A), m(H), 0.0, None, m(D), raise_on_error=False) == fg.FG_ERR_UNSUPPORTED
     assert fg.fg_gemm(64, 64, 64, 1.0, m(A, im=A), m(A, im=A), 0.0, None, m(D, im=D), raise_on_error=False) == fg.FG_ERR_UNSUPPORTED
     assert fg.fg_gemm(64, 64, 64, 1.0, fg.Matrix(A, fg.FG_DIAG, 0), m(A), 0.0, None, m(D), raise_on_error=False) == fg.FG_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("la,lb", list(itertools.product(LAYOUTS, LAYOUTS)))
+def test_transforms_on_loaded_elements_all_layouts(la, lb):
+    """Last rows of the fusion table (Section 5.3): ReLU on the loaded C and a constant added to
+    the loaded A and B values (in FP16), for every tile shape, with edge tiles and a K that is not
+    a multiple of the K tile (the zero fill beyond K must stay zero)."""
+    for (M, N, K) in [(64, 64, 64), (128, 192, 256), (768, 1280, 320), (100, 75, 40), (300, 130, 72)]:
+        say("ab_add ints M=%d N=%d K=%d la=%d lb=%d" % (M, N, K, la, lb))
+        run_gemm_case(M, N, K, la, lb, ints=True, pad=8, ab_add=(2.0, -3.0), c_act=fg.FG_ACT_RELU)
+    say("ab_add floats 512"); run_gemm_case(512, 512, 512, la, lb, alpha=0.5, beta=2.0, ab_add=(0.25, 0.0999755859375))
+    say("ab_add bias relu row-major D")
+    run_gemm_case(300, 513, 136, la, lb, ld_layout=fg.FG_ROW, bias_dim=1, act=fg.FG_ACT_RELU, ab_add=(-0.5, 1.5), c_act=fg.FG_ACT_RELU)
+    say("relu on C only"); run_gemm_case(256, 384, 128, la, lb, c_act=fg.FG_ACT_RELU)
+    say("a_add only"); run_gemm_case(256, 384, 128, la, lb, ints=True, ab_add=(1.0, 0.0))
+
+
+def test_transforms_fusion_table_4096():
+    """The full last row of the fusion table at the paper's size: bias, ReLU on C and D, addition on
+    A and B, N = 4096, sampled."""
+    say("fusion table last row, floats")
+    run_gemm_case(4096, 4096, 4096, bias_dim=0, act=fg.FG_ACT_RELU, ab_add=(0.5, -0.25), c_act=fg.FG_ACT_RELU, samples=4096, config=3)
+    say("fusion table last row, ints")
+    run_gemm_case(4096, 4096, 4096, bias_dim=0, act=fg.FG_ACT_RELU, ab_add=(1.0, -2.0), c_act=fg.FG_ACT_RELU, samples=4096, config=3, ints=True)
+
+
+def test_transforms_are_rejected_where_unsupported():
+    H = torch.zeros(64 * 64, dtype=torch.float16, device="cuda")
+    Bf = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
+    D = torch.zeros(64 * 64, dtype=torch.float32, device="cuda")
+    m = lambda t, **kw: fg.Matrix(t, fg.FG_COL, 64, **kw)
+    kw = dict(raise_on_error=False)
+    assert fg.fg_gemm(64, 64, 64, 1.0, m(Bf), m(Bf), 0.0, None, m(D), a_add=1.0, **kw) == fg.FG_ERR_UNSUPPORTED
+    assert fg.fg_gemm(64, 64, 64, 1.0, m(H, im=H), m(H, im=H), 0.0, None, m(D, im=D), a_add=1.0, **kw) == fg.FG_ERR_UNSUPPORTED
+    assert fg.fg_gemm(64, 64, 64, 1.0, m(H, im=H), m(H, im=H), 0.0, None, m(D, im=D), c_act=fg.FG_ACT_RELU, **kw) == fg.FG_ERR_UNSUPPORTED
+    assert fg.fg_gemm(64, 64, 64, 1.0, fg.Matrix(H, fg.FG_DIAG, 0), m(H), 0.0, None, m(D), b_add=1.0, **kw) == fg.FG_ERR_UNSUPPORTED
+    assert fg.fg_gemm(64, 64, 64, 1.0, m(H), m(H), 0.0, None, m(D), c_act=7, **kw) == fg.FG_ERR_LAYOUT
+    assert fg.fg_gemm(64, 64, 64, 1.0, m(H), m(H), 0.0, None, m(D), a_add=float("nan"), **kw) == fg.FG_ERR_SHAPE
