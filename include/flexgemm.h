@@ -156,10 +156,11 @@ fg_status fg_gemm_dual(int64_t M, int64_t N, int64_t K, float alpha,
  * Cout may equal Cin.  The tensors are never transposed in memory: the mode-to-tile mapping
  * happens while tiles are loaded and while the result is stored.
  * Requirements of this version (else FG_ERR_UNSUPPORTED): in each of A and B some mode has
- * stride 1 and an extent that is a multiple of 8; the products of the row, column and summed
- * extents are multiples of 64; the summed mode that is walked fastest has an extent that is a
- * multiple of 64; at most 4 modes per group; A, B and C each span less than 2 GiB; no negative
- * strides.
+ * stride 1 and an extent that is a multiple of 8; the summed mode that is walked fastest (A's
+ * unit-stride mode if it is summed, else B's, else the first summed mode of A) has an extent that
+ * is a multiple of 64; at most 4 modes of extent above 1 per group; A, B and C each span less than
+ * 2 GiB; no negative strides.  The row and column extents are otherwise arbitrary: tiles that hang
+ * over the merged row or column extent are predicated like the edge tiles of fg_gemm.
  */
 fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA, const void *A,
                       int32_t nB, const int32_t *modesB, const int64_t *stridesB, const void *B,

@@ -61,24 +61,18 @@ const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
 // The params heuristic (Section 4.2.1 picks the largest tile that fits shared memory; here every
 // tile fits, so the question is how many workgroups a tile shape leaves): the largest block tile
 // that still gives every compute unit a workgroup, else the smallest tile.  Edge tiles are
-// predicated, so a tile need not divide a matrix; the contraction kernels have no edge
-// predication and take only tiles that divide (must_divide; -1 if none does).
-int choose_tile(int64_t M, int64_t N, bool must_divide = false) {
+// predicated, so a tile need not divide the problem.
+int choose_tile(int64_t M, int64_t N) {
     static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64};
     static const int bn[fg::TILE_COUNT] = {256, 128, 128, 64};
-    auto fits = [&](int t) { return !must_divide || (M % bm[t] == 0 && N % bn[t] == 0); };
     // tuning aid: FG_FORCE_TILE=0..3 picks a tile shape
     if (const char *f = getenv("FG_FORCE_TILE")) {
         int t = atoi(f);
-        if (t >= 0 && t < fg::TILE_COUNT && fits(t)) return t;
+        if (t >= 0 && t < fg::TILE_COUNT) return t;
     }
-    int last = -1;
-    for (int t = 0; t < fg::TILE_COUNT; ++t) {
-        if (!fits(t)) continue;
-        last = t;
+    for (int t = 0; t < fg::TILE_COUNT; ++t)
         if (((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]) >= kNumCU) return t;
-    }
-    return last;
+    return fg::TILE_COUNT - 1;
 }
 
 int choose_ctile(int64_t M, int64_t N) {
@@ -98,7 +92,6 @@ const fg::KernelEntry *select_kernel(const Problem &q) {
         return &(q.dual ? fg::kernel_table_dual() : fg::kernel_table_cplx())[t * 4 + v];
     }
     const int tile = choose_tile(q.M, q.N);
-    if (tile < 0) return nullptr;
     if (q.a_diag) return &fg::kernel_table_diag()[tile * 4 + (q.b_kc ? 0 : 1)];
     if (q.b_diag) return &fg::kernel_table_diag()[tile * 4 + (q.a_kc ? 2 : 3)];
     if (q.ab_add) {
@@ -390,7 +383,6 @@ fg_status plan_contraction(int32_t nA, const int32_t *modesA, const int64_t *str
     if (nm == 0) c.M = 1;
     if (nn == 0) c.N = 1;
 
-    if (c.M % 64 || c.N % 64 || c.K % 64) return fail(FG_ERR_UNSUPPORTED, "merged extents must be multiples of 64 (rows %lld, columns %lld, summed %lld)", (long long)c.M, (long long)c.N, (long long)c.K);
     if (c.a_k.extent[0] % 64) return fail(FG_ERR_UNSUPPORTED, "the leading summed mode (%d) must have an extent that is a multiple of 64", k_modes[0]);
     if (c.a_kc && c.a_k.stride[0] != 1) return fail(FG_ERR_UNSUPPORTED, "internal: leading summed mode is not contiguous in A");
     if (c.b_kc && c.b_k.stride[0] != 1) return fail(FG_ERR_UNSUPPORTED, "leading summed mode %d is contiguous in A but not in B", k_modes[0]);
@@ -508,13 +500,12 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
                                         Cin, Cout, n_modes, mode_labels, mode_extents, c))
         return st;
     if (c.M == 0 || c.N == 0) return FG_OK;
-    const int tile = choose_tile(c.M, c.N, true);
-    if (tile < 0) return fail(FG_ERR_UNSUPPORTED, "no block tile divides the merged extents M=%lld, N=%lld", (long long)c.M, (long long)c.N);
+    const int tile = choose_tile(c.M, c.N);
     const fg::KernelEntry &k = table_for(c.a_kc, c.b_kc)[fg::entry_index(tile, true)];
     fg::GemmParams p;
     memset(&p, 0, sizeof p);
     p.M = (int32_t)c.M; p.N = (int32_t)c.N; p.K = (int32_t)c.K;
-    p.tiles_m = (int32_t)(c.M / k.bm); p.tiles_n = (int32_t)(c.N / k.bn);
+    p.tiles_m = (int32_t)((c.M + k.bm - 1) / k.bm); p.tiles_n = (int32_t)((c.N + k.bn - 1) / k.bn);
     p.A = (const _Float16 *)c.A; p.B = (const _Float16 *)c.B;
     p.C = Cin; p.D = Cout;
     p.has_c = (Cin != nullptr);

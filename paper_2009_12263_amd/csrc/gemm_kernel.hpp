@@ -230,7 +230,7 @@ struct TileLoader {
 
     __device__ __forceinline__ void init(const _Float16 *ptr, int row0, int wave, int lane,
                                          int64_t rs, int64_t ks, const ModeGroup &rg, const ModeGroup &kgrp,
-                                         int64_t span = 0, int kdim_ = 0) {
+                                         int64_t span = 0, int kdim_ = 0, int rdim = 0) {
         ktile = 0;
         klim = BK;
         if constexpr (!STRIDED) {
@@ -263,6 +263,10 @@ struct TileLoader {
                 kchunk[s] = c * 8;
                 if constexpr (!STRIDED) off = (int64_t)r * rs + c * 8;
                 else off = group_offset(rg, row0 + r) + c * 8;     // leading K mode has stride 1
+                if constexpr (STRIDED) {
+                    // a row past the merged row extent: the load is dropped and LDS gets zeros
+                    if (row0 + r >= rdim) off = kOutOfRange / 2;
+                }
             } else {
                 // slab = (512/R) k-rows x R/8 chunks of 16 bytes
                 constexpr int CH = R / 8;                          // 16-byte chunks per k-row
@@ -271,6 +275,11 @@ struct TileLoader {
                 int c = p ^ (mc_swz<R>(kr) << 2);                   // 64-byte granular XOR
                 if constexpr (!STRIDED) off = (int64_t)kr * ks + c * 8;
                 else off = group_offset(rg, row0 + c * 8) + (int64_t)kr * kgrp.stride[0];
+                if constexpr (STRIDED) {
+                    // chunks of 8 rows never straddle the extent (the leading row mode's extent is
+                    // a multiple of 8)
+                    if (row0 + c * 8 >= rdim) off = kOutOfRange / 2;
+                }
             }
             voff[s] = (uint32_t)(off * 2);
         }
@@ -546,32 +555,44 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
         __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(HAS_C ? Cp : Dp), 0, 0x7fffffff, 0x00020000);
         __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(Dp, 0, 0x7fffffff, 0x00020000);
         const ModeGroup &c_m = p.c_m, &c_n = p.c_n;
-        int row4[Cfg::TI];
+        // rows past the merged row extent and columns past the merged column extent (edge tiles)
+        // are dropped by sending their offset out of the descriptor's range
+        const bool interior = m_base + Cfg::WTM <= p.M && n_base + Cfg::WTN <= p.N;
+        uint32_t row4[Cfg::TI];
 #pragma unroll
-        for (int i = 0; i < Cfg::TI; ++i) row4[i] = (int)group_offset(c_m, m_base + 32 * i + lm) * 4;
+        for (int i = 0; i < Cfg::TI; ++i) {
+            const int m = m_base + 32 * i + lm;
+            row4[i] = (interior || m < p.M) ? (uint32_t)group_offset(c_m, m) * 4u : kOutOfRange;
+        }
 #pragma unroll
         for (int j = 0; j < Cfg::TJ; ++j) {
-            int col4[16];
+            uint32_t col4[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int n = n_base + 32 * j + 8 * (r >> 2) + (r & 3);
-                const int lo = (int)group_offset(c_n, n) * 4, hi = (int)group_offset(c_n, n + 4) * 4;
+                const uint32_t lo = (uint32_t)group_offset(c_n, n) * 4u, hi = (uint32_t)group_offset(c_n, n + 4) * 4u;
                 col4[r] = lh ? hi : lo;
+                if (!interior && n + 4 * lh >= p.N) col4[r] = kOutOfRange;
             }
 #pragma unroll
             for (int i = 0; i < Cfg::TI; ++i) {
+                // both parts are below 2^31 when in range; if either is out of range the sum must not
+                // wrap back into range
+                uint32_t off[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) off[r] = ((row4[i] | col4[r]) & kOutOfRange) ? kOutOfRange : row4[i] + col4[r];
                 float cv[16];
                 if constexpr (HAS_C) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        cv[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, row4[i] + col4[r], 0, 0));
+                        cv[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, off[r], 0, 0));
                 }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     float y = p.alpha * acc[i][j][r];
                     if constexpr (HAS_C) y += p.beta * cv[r];
                     y = y > floor_v ? y : floor_v;
-                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, row4[i] + col4[r], 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, off[r], 0, 0);
                 }
             }
         }
@@ -663,9 +684,9 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
 #pragma unroll
         for (int q = 0; q < P; ++q) {
             if constexpr (Cfg::DIAG == 1) la[q].init(ap[q], m0, tp.M < tp.K ? tp.M : tp.K, wave, lane);
-            else la[q].init(ap[q], m0, wave, lane, tp.a_rs, tp.a_ks, tp.a_m, tp.a_k, tp.a_span, tp.K);
+            else la[q].init(ap[q], m0, wave, lane, tp.a_rs, tp.a_ks, tp.a_m, tp.a_k, tp.a_span, tp.K, tp.M);
             if constexpr (Cfg::DIAG == 2) lb[q].init(bp[q], n0, tp.N < tp.K ? tp.N : tp.K, wave, lane);
-            else lb[q].init(bp[q], n0, wave, lane, tp.b_rs, tp.b_ks, tp.b_n, tp.b_k, tp.b_span, tp.K);
+            else lb[q].init(bp[q], n0, wave, lane, tp.b_rs, tp.b_ks, tp.b_n, tp.b_k, tp.b_span, tp.K, tp.N);
             if constexpr (Cfg::DIAG != 0) { la[q].skip(kt0); lb[q].skip(kt0); }
         }
 #pragma unroll

@@ -36,6 +36,18 @@ def test_paper_contraction_full_size():
     say("paper contraction floats sampled"); run_contract_case(ext, [b, d, a], [d, c], [a, b, c], samples=8192)
 
 
+def test_ragged_extents_every_entry():
+    """Row and column extents that no block tile divides: edge tiles of the strided kernels are
+    predicated in the loads (zeros) and in the stores (dropped)."""
+    say("5a-shaped ragged"); run_contract_case({a: 24, b: 5, c: 7, d: 64}, [a, d, c], [d, b], [a, b, c], ints=True)
+    say("5a-shaped ragged floats beta"); run_contract_case({a: 40, b: 100, c: 9, d: 128}, [a, d, c], [d, b], [a, b, c], alpha=0.5, beta=-2.0)
+    say("5b-shaped ragged"); run_contract_case({a: 16, b: 3, c: 5, d: 8, e: 64, f: 3}, [a, e, b, f], [d, f, c, e], [a, b, c, d], ints=True)
+    say("paper-shaped ragged"); run_contract_case({a: 5, b: 8, c: 33, d: 64}, [b, d, a], [d, c], [a, b, c], ints=True)
+    say("K-contiguous operands, odd rows and columns"); run_contract_case({a: 37, b: 3, c: 51, d: 128}, [d, a, b], [d, c], [a, b, c], ints=True)
+    say("several tiles with a ragged tail"); run_contract_case({a: 72, b: 9, c: 301, d: 64}, [a, d, b], [d, c], [a, b, c], ints=True)
+    say("result's fastest mode in B, ragged"); run_contract_case({a: 56, b: 136, d: 64}, [a, d], [b, d], [b, a], ints=True, beta=1.0)
+
+
 def test_small_contractions_every_entry():
     say("5a-shaped small"); run_contract_case({a: 64, b: 64, c: 3, d: 64}, [a, d, c], [d, b], [a, b, c], ints=True)
     say("5b-shaped small"); run_contract_case({a: 16, b: 4, c: 8, d: 8, e: 64, f: 2}, [a, e, b, f], [d, f, c, e], [a, b, c, d], ints=True)
