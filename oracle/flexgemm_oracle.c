@@ -208,9 +208,12 @@ static int gemm_problem_ok(const og_problem *q) {
     if (q->act != OG_ACT_NONE && q->act != OG_ACT_RELU) return 0;
     if (q->ab_dtype != 0 && q->ab_dtype != 1) return 0;
     if (q->c_act != OG_ACT_NONE && q->c_act != OG_ACT_RELU) return 0;
-    if (q->ab_add || q->c_act) {
+    /* the activation on C touches only C: any real product; the addition on A and B is defined
+       here for stored binary16 matrices only */
+    if (q->c_act && (q->A_im || q->B_im)) return 0;
+    if (q->ab_add) {
         if (q->A_im || q->B_im || q->ab_dtype != 0 || q->layoutA == OG_DIAG || q->layoutB == OG_DIAG) return 0;
-        if (q->ab_add && (round_to_half(q->a_add) != q->a_add || round_to_half(q->b_add) != q->b_add)) return 0;
+        if (round_to_half(q->a_add) != q->a_add || round_to_half(q->b_add) != q->b_add) return 0;
     }
     const int is_complex = (q->A_im != NULL) || (q->B_im != NULL);
     if (is_complex && (q->bias || q->act != OG_ACT_NONE)) return 0; /* not defined for complex */

@@ -160,3 +160,25 @@ def test_transforms_are_rejected_where_unsupported():
     assert fg.fg_gemm(64, 64, 64, 1.0, fg.Matrix(H, fg.FG_DIAG, 0), m(H), 0.0, None, m(D), b_add=1.0, **kw) == fg.FG_ERR_UNSUPPORTED
     assert fg.fg_gemm(64, 64, 64, 1.0, m(H), m(H), 0.0, None, m(D), c_act=7, **kw) == fg.FG_ERR_LAYOUT
     assert fg.fg_gemm(64, 64, 64, 1.0, m(H), m(H), 0.0, None, m(D), a_add=float("nan"), **kw) == fg.FG_ERR_SHAPE
+
+
+def test_seeded_random_shape_sweep():
+    """Forty seeded random problems (sizes up to ~700, K a multiple of 8, every layout triple,
+    random epilogue and transform choices), integer-valued so that every entry must be exact."""
+    import random
+    rng = random.Random(20091226)
+    for case in range(40):
+        M, N = rng.randint(1, 700), rng.randint(1, 700)
+        K = 8 * rng.randint(1, 60)
+        la, lb, ld = rng.choice(LAYOUTS), rng.choice(LAYOUTS), rng.choice(LAYOUTS)
+        with_c = rng.random() < 0.7
+        bias_dim = rng.choice([None, 0, 1])
+        act = rng.choice([fg.FG_ACT_NONE, fg.FG_ACT_RELU])
+        ab_add = rng.choice([None, None, (1.0, -2.0), (0.0, 3.0)])
+        c_act = rng.choice([fg.FG_ACT_NONE, fg.FG_ACT_RELU]) if with_c else fg.FG_ACT_NONE
+        bf16 = ab_add is None and rng.random() < 0.25
+        alpha, beta = rng.choice([(1.0, 1.0), (0.5, 2.0), (-1.0, 0.25), (2.0, -1.0)])
+        say("sweep %d: M=%d N=%d K=%d la=%d lb=%d ld=%d c=%s bias=%s act=%d add=%s c_act=%d bf16=%s" % (
+            case, M, N, K, la, lb, ld, with_c, bias_dim, act, ab_add, c_act, bf16))
+        run_gemm_case(M, N, K, la, lb, ld, alpha=alpha, beta=beta, with_c=with_c, bias_dim=bias_dim, act=act,
+                      ints=True, pad=8 * rng.randint(0, 2), ab_add=ab_add, c_act=c_act, bf16=bf16, seed=1000 + case)
