@@ -459,9 +459,17 @@ __device__ __forceinline__ void block_to_tile(int bid, int tiles_m, int tiles_n,
 // store instruction writes two runs of 32 consecutive m, i.e. two full 128-byte lines of a
 // column-major D.  The sixteen C values of an accumulator are fetched as one batch of independent
 // loads before any of them is used.
+// C is read once and D written once: in the matrix kernels both are marked non-temporal
+// (streaming) so that they do not displace the A and B panels, which other workgroups of the same
+// XCD re-read, from the L2 (measured: 4-5 % of the 8192^3 run time).  Not for a diagonal operand
+// (no panel is re-read, and the hint only takes away what the caches would have kept of C and D)
+// and not for contractions (their stores can be partial lines, which the L2 has to merge).
+template <class Cfg>
+constexpr int stream_policy() { return (Cfg::DIAG == 0 && !Cfg::STRIDED) ? 2 : 0; }   // gfx950 cache policy: bit 1 = nt
 template <class Cfg, bool HAS_C>
 __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, float *Dp, floatx16 (&acc)[Cfg::TI][Cfg::TJ],
                                          int m_base, int n_base, int lane) {
+    constexpr int kStream = stream_policy<Cfg>();
     const int lm = lane & 31, lh = lane >> 5;
     const bool bias_m_on = p.bias && p.bias_dim == 0, bias_n_on = p.bias && p.bias_dim != 0;
     const float floor_v = p.act == 1 ? 0.f : -__builtin_inff();
@@ -481,23 +489,27 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
             // The C values of accumulator b+1 are requested before accumulator b is stored, so a
             // batch of loads never queues behind the previous stores.
             constexpr int NB = Cfg::TI * Cfg::TJ;
-            float cv[2][16];
+            constexpr int AHEAD = 1;                        // batches of C requested ahead of their use
+            float cv[AHEAD + 1][16];
             auto load_c = [&](int b, float (&dst)[16]) {
                 const int i = b / Cfg::TJ, j = b % Cfg::TJ;
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     dst[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                 rc, voff_c, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, 0));
+                                 rc, voff_c, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, kStream));
             };
             float bias_m[Cfg::TI];
 #pragma unroll
             for (int i = 0; i < Cfg::TI; ++i) bias_m[i] = bias_m_on ? p.bias[m_base + 32 * i + lm] : 0.f;
-            if constexpr (HAS_C) load_c(0, cv[0]);
+            if constexpr (HAS_C) {
+#pragma unroll
+                for (int b = 0; b < AHEAD && b < NB; ++b) load_c(b, cv[b % (AHEAD + 1)]);
+            }
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const int i = b / Cfg::TJ, j = b % Cfg::TJ;
                 if constexpr (HAS_C) {
-                    if (b + 1 < NB) load_c(b + 1, cv[(b + 1) & 1]);
+                    if (b + AHEAD < NB) load_c(b + AHEAD, cv[(b + AHEAD) % (AHEAD + 1)]);
                 }
                 float bv[16];
 #pragma unroll
@@ -510,12 +522,12 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                 for (int r = 0; r < 16; ++r) {
                     float y = p.alpha * acc[i][j][r] + bv[r];
                     if constexpr (HAS_C) {
-                        const float c = cv[b & 1][r];
+                        const float c = cv[b % (AHEAD + 1)][r];
                         y += p.beta * (c > floor_c ? c : floor_c);
                     }
                     y = y > floor_v ? y : floor_v;
                     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, voff_d,
-                                                          128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, 0);
+                                                          128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, kStream);
                 }
             }
         } else {
@@ -537,12 +549,12 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                         if (bias_n_on && n_ok) y += p.bias[ncol + 4 * lh];
                         if constexpr (HAS_C) {
                             const float c = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                rc, n_ok ? vc : kOutOfRange, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, 0));
+                                rc, n_ok ? vc : kOutOfRange, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, kStream));
                             y += p.beta * (c > floor_c ? c : floor_c);
                         }
                         y = y > floor_v ? y : floor_v;
                         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, n_ok ? vd : kOutOfRange,
-                                                              128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, 0);
+                                                              128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, kStream);
                     }
                 }
             }
@@ -585,14 +597,14 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                 if constexpr (HAS_C) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        cv[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, off[r], 0, 0));
+                        cv[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, off[r], 0, kStream));
                 }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     float y = p.alpha * acc[i][j][r];
                     if constexpr (HAS_C) y += p.beta * cv[r];
                     y = y > floor_v ? y : floor_v;
-                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, off[r], 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, off[r], 0, kStream);
                 }
             }
         }
