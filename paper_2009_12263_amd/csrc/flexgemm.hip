@@ -59,20 +59,35 @@ const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
 }
 
 // The params heuristic (Section 4.2.1 picks the largest tile that fits shared memory; here every
-// tile fits, so the question is how many workgroups a tile shape leaves): the largest block tile
-// that still gives every compute unit a workgroup, else the smallest tile.  Edge tiles are
-// predicated, so a tile need not divide the problem.
-int choose_tile(int64_t M, int64_t N) {
+// tile fits, so the question is which shape finishes first).  Estimated time of a tile shape =
+// rounds x (tile area) / (rate of one workgroup slot): `rounds` = ceil(tiles / slots) with slots =
+// 256 compute units x workgroups of that shape per unit; the rates are measured fractions of what a
+// compute unit sustains with the 256x256 tile, one set for workgroups that share a unit (more
+// tiles than units) and one for a workgroup that has a unit to itself.  The common factor K is
+// left out.  Edge tiles are predicated, so a tile need not divide the problem.
+int choose_tile(int64_t M, int64_t N, bool allow_smallest = true) {
     static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64};
     static const int bn[fg::TILE_COUNT] = {256, 128, 128, 64};
+    static const int per_cu[fg::TILE_COUNT] = {1, 1, 2, 4};
+    static const double rate_shared[fg::TILE_COUNT] = {1.0, 0.8, 0.73, 0.45};
+    static const double rate_alone[fg::TILE_COUNT] = {1.0, 0.8, 0.43, 0.17};
     // tuning aid: FG_FORCE_TILE=0..3 picks a tile shape
     if (const char *f = getenv("FG_FORCE_TILE")) {
         int t = atoi(f);
         if (t >= 0 && t < fg::TILE_COUNT) return t;
     }
-    for (int t = 0; t < fg::TILE_COUNT; ++t)
-        if (((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]) >= kNumCU) return t;
-    return fg::TILE_COUNT - 1;
+    int best = 0;
+    double best_cost = 0;
+    const int ntypes = allow_smallest ? fg::TILE_COUNT : fg::TILE_COUNT - 1;
+    for (int t = 0; t < ntypes; ++t) {
+        const int64_t tiles = ((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]);
+        const int64_t slots = (int64_t)kNumCU * per_cu[t];
+        const int64_t rounds = (tiles + slots - 1) / slots;
+        const double slot_rate = tiles > kNumCU ? rate_shared[t] / per_cu[t] : rate_alone[t];
+        const double cost = (double)rounds * bm[t] * bn[t] / slot_rate;
+        if (t == 0 || cost < best_cost) { best = t; best_cost = cost; }
+    }
+    return best;
 }
 
 int choose_ctile(int64_t M, int64_t N) {
@@ -500,7 +515,10 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
                                         Cin, Cout, n_modes, mode_labels, mode_extents, c))
         return st;
     if (c.M == 0 || c.N == 0) return FG_OK;
-    const int tile = choose_tile(c.M, c.N);
+    // A result that is not contiguous along the leading row mode is stored in short pieces; the
+    // smallest tile makes them shorter still (measured on the paper's D_abc = A_bda B_dc).
+    const bool rows_contiguous = c.c_m.n == 0 || c.c_m.stride[0] == 1;
+    const int tile = choose_tile(c.M, c.N, rows_contiguous || c.M < 128 || c.N < 128);
     const fg::KernelEntry &k = table_for(c.a_kc, c.b_kc)[fg::entry_index(tile, true)];
     fg::GemmParams p;
     memset(&p, 0, sizeof p);

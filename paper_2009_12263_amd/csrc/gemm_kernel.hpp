@@ -532,32 +532,48 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
             }
         } else {
             // a tile that hangs over the edge of D: rows m >= M are masked per lane (their offset is
-            // sent out of the descriptor's range, which drops the access), columns n >= N per column
+            // sent out of the descriptor's range, which drops the access), columns n >= N per column.
+            // Eight values at a time: their reads of C, then the arithmetic, then their stores.
+            auto run_edge = [&](auto bias_n_tag) {
+                constexpr bool BIAS_N = decltype(bias_n_tag)::value;
 #pragma unroll
-            for (int i = 0; i < Cfg::TI; ++i) {
-                const int m = m_base + 32 * i + lm;
-                const bool m_ok = m < p.M;
-                const uint32_t vc = m_ok ? (uint32_t)voff_c : kOutOfRange, vd = m_ok ? (uint32_t)voff_d : kOutOfRange;
-                const float bias_mi = (bias_m_on && m_ok) ? p.bias[m] : 0.f;
+                for (int i = 0; i < Cfg::TI; ++i) {
+                    const int m = m_base + 32 * i + lm;
+                    const bool m_ok = m < p.M;
+                    const uint32_t vc = m_ok ? (uint32_t)voff_c : kOutOfRange, vd = m_ok ? (uint32_t)voff_d : kOutOfRange;
+                    const float bias_mi = (bias_m_on && m_ok) ? p.bias[m] : 0.f;
 #pragma unroll
-                for (int j = 0; j < Cfg::TJ; ++j) {
+                    for (int j = 0; j < Cfg::TJ; ++j) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int ncol = n_base + 32 * j + 8 * (r >> 2) + (r & 3);     // + 4 for the upper half-wave
-                        const bool n_ok = ncol + 4 * lh < p.N;
-                        float y = p.alpha * acc[i][j][r] + bias_mi;
-                        if (bias_n_on && n_ok) y += p.bias[ncol + 4 * lh];
-                        if constexpr (HAS_C) {
-                            const float c = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                rc, n_ok ? vc : kOutOfRange, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, kStream));
-                            y += p.beta * (c > floor_c ? c : floor_c);
+                        for (int h = 0; h < 2; ++h) {
+                            float cv[8], bv[8];
+#pragma unroll
+                            for (int r8 = 0; r8 < 8; ++r8) {
+                                const int r = 8 * h + r8;
+                                const int ncol = n_base + 32 * j + 8 * (r >> 2) + (r & 3) + 4 * lh;
+                                const bool n_ok = ncol < p.N;
+                                if constexpr (BIAS_N) bv[r8] = p.bias[n_ok ? ncol : p.N - 1];
+                                else bv[r8] = bias_mi;
+                                if constexpr (HAS_C)
+                                    cv[r8] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                        rc, n_ok ? vc : kOutOfRange, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, kStream));
+                            }
+#pragma unroll
+                            for (int r8 = 0; r8 < 8; ++r8) {
+                                const int r = 8 * h + r8;
+                                const bool n_ok = n_base + 32 * j + 8 * (r >> 2) + (r & 3) + 4 * lh < p.N;
+                                float y = p.alpha * acc[i][j][r] + bv[r8];
+                                if constexpr (HAS_C) y += p.beta * (cv[r8] > floor_c ? cv[r8] : floor_c);
+                                y = y > floor_v ? y : floor_v;
+                                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, n_ok ? vd : kOutOfRange,
+                                                                      128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, kStream);
+                            }
                         }
-                        y = y > floor_v ? y : floor_v;
-                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, n_ok ? vd : kOutOfRange,
-                                                              128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, kStream);
                     }
                 }
-            }
+            };
+            if (bias_n_on) run_edge(std::true_type{});
+            else run_edge(std::false_type{});
         }
     } else {
         // tensor contraction: element offsets are mixed-radix sums over C's row and column modes.
@@ -629,6 +645,17 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
 __device__ __forceinline__ half8 neg8(half8 v) {
     u32x4 u = __builtin_bit_cast(u32x4, v);
     u ^= 0x80008000u;
+    return __builtin_bit_cast(half8, u);
+}
+
+// Add the same two packed halves to each of the four register words of a fragment (FP16
+// arithmetic, round to nearest even).
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ half8 add8(half8 v, uint32_t pair) {
+    u32x4 u = __builtin_bit_cast(u32x4, v);
+    const half2v w = __builtin_bit_cast(half2v, pair);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) u[k] = __builtin_bit_cast(uint32_t, (half2v)(__builtin_bit_cast(half2v, (uint32_t)u[k]) + w));
     return __builtin_bit_cast(half8, u);
 }
 
@@ -804,15 +831,14 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                     // Element-wise addition on the loaded A and B values of this slice.  Positions at
                     // or beyond K were filled with zeros by the loads and must stay zero, so their
                     // addend is zero (a lane's eight values share one k chunk, K is a multiple of 8).
-                    half8 add_a, add_b;
+                    uint32_t add_a = 0, add_b = 0;          // two packed halves each
                     if constexpr (Cfg::XFORM) {
                         const bool in_k = (kt0 + kt) * BK + ks * 16 + 8 * (lane >> 5) < xf_k;
-                        const uint32_t wa = in_k ? xf_a : 0u, wb = in_k ? xf_b : 0u;
-                        add_a = __builtin_bit_cast(half8, u32x4{wa, wa, wa, wa});
-                        add_b = __builtin_bit_cast(half8, u32x4{wb, wb, wb, wb});
+                        add_a = in_k ? xf_a : 0u;
+                        add_b = in_k ? xf_b : 0u;
 #pragma unroll
-                        for (int j = 0; j < TJ; ++j) bf[0][rb][j] += add_b;
-                        af[0][0] += add_a;
+                        for (int j = 0; j < TJ; ++j) bf[0][rb][j] = add8(bf[0][rb][j], add_b);
+                        af[0][0] = add8(af[0][0], add_a);
                     }
 #pragma unroll
                     for (int i = 0; i < TI; ++i) {
@@ -843,7 +869,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                         }
                         if constexpr (Cfg::XFORM) {
                             // the next sub-tile row's values, while this row's instructions run
-                            if (i + 1 < TI) af[0][i + 1] += add_a;
+                            if (i + 1 < TI) af[0][i + 1] = add8(af[0][i + 1], add_a);
                         }
                         if (!last || MORE) {
 #pragma unroll

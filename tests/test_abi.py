@@ -77,13 +77,16 @@ def test_empty_problem_is_ok_without_a_gpu():
 def test_plan_names_follow_sizes_and_layouts():
     assert fg.fg_gemm_plan(8192, 8192, 8192) == "gemm_nn_256x256x64"
     assert fg.fg_gemm_plan(8192, 1024, 4096) == "gemm_nn_256x128x64"
-    assert fg.fg_gemm_plan(2048, 2048, 2048, fg.FG_ROW, fg.FG_COL) == "gemm_tn_128x128x64"
+    # 2048^2 outputs: 1024 small tiles (four workgroups per compute unit) beat 256 medium ones
+    assert fg.fg_gemm_plan(2048, 2048, 2048, fg.FG_ROW, fg.FG_COL) == "gemm_tn_64x64x64"
+    # 4100^2: 289 big tiles would need two rounds for 33 leftover tiles; the half-width tile wastes less
+    assert fg.fg_gemm_plan(4100, 4100, 4096) == "gemm_nn_256x128x64"
     assert fg.fg_gemm_plan(256, 256, 256, fg.FG_COL, fg.FG_ROW) == "gemm_nt_64x64x64"
     # a row-major D is computed as the transposed problem: the operands swap roles
     assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_ROW, fg.FG_ROW, fg.FG_ROW) == "gemm_nn_256x256x64"
     # sizes need not be multiples of the tile: edge tiles are predicated
     assert fg.fg_gemm_plan(100, 72, 64) == "gemm_nn_64x64x64"
-    assert fg.fg_gemm_plan(5000, 3000, 1000) == "gemm_nn_256x128x64"
+    assert fg.fg_gemm_plan(5000, 3000, 1000) == "gemm_nn_256x256x64"     # 240 tiles: one round
     with pytest.raises(fg.FlexGemmError):
         fg.fg_gemm_plan(128, 64, 60)
 
