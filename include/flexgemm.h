@@ -177,6 +177,15 @@ const char *fg_last_error(void);
 int32_t fg_version(void);
 
 /*
+ * Optional: prepare every kernel variant on the current device (raise its LDS limit, query its
+ * occupancy).  Without it each variant is prepared by the first call that uses it.  After
+ * fg_init() on a device, fg_gemm / fg_gemm_ex / fg_gemm_dual / fg_contract on that device do
+ * nothing but enqueue one kernel on the given stream, so they may be recorded into a HIP graph
+ * (stream capture) and replayed.  Returns FG_OK or FG_ERR_LAUNCH.
+ */
+fg_status fg_init(void);
+
+/*
  * Name of the kernel variant and block tile that fg_gemm would use for this problem, written as
  * a NUL-terminated string into `buf` (at most `buf_len` bytes).  This is the "params" choice of
  * Section 4.2.1: the largest (nearly) square block tile that divides the problem and fills the

@@ -22,7 +22,7 @@ FG_F16, FG_BF16, FG_F32 = 0, 1, 2
 FG_COL, FG_ROW, FG_DIAG, FG_ZERO = 0, 1, 2, 3
 FG_ACT_NONE, FG_ACT_RELU = 0, 1
 
-EXPORTS = ("fg_gemm", "fg_gemm_ex", "fg_gemm_dual", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan", "fg_probe_mfma")
+EXPORTS = ("fg_init", "fg_gemm", "fg_gemm_ex", "fg_gemm_dual", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan", "fg_probe_mfma")
 FG_PLAN_REAL, FG_PLAN_COMPLEX, FG_PLAN_DUAL, FG_PLAN_REAL_BF16 = 0, 1, 2, 3
 
 
@@ -72,6 +72,8 @@ def load_library() -> C.CDLL:
         lib.fg_last_error.argtypes = []
         lib.fg_version.restype = i32
         lib.fg_version.argtypes = []
+        lib.fg_init.restype = C.c_int
+        lib.fg_init.argtypes = []
         lib.fg_gemm_plan.restype = C.c_int
         lib.fg_gemm_plan.argtypes = [i64, i64, i64, i32, i32, i32, i32, C.c_char_p, i32]
         lib.fg_probe_mfma.restype = C.c_int
@@ -115,6 +117,11 @@ def fg_last_error() -> str:
 
 def fg_version() -> int:
     return int(load_library().fg_version())
+
+
+def fg_init(raise_on_error: bool = True) -> int:
+    """Prepare every kernel variant on the current device; see fg_init in include/flexgemm.h."""
+    return _check(load_library().fg_init(), raise_on_error)
 
 
 def _check(status: int, raise_on_error: bool) -> int:

@@ -122,27 +122,31 @@ const fg::KernelEntry *select_kernel(const Problem &q) {
     return &table_for(q.a_kc, q.b_kc)[fg::entry_index(tile, false)];
 }
 
+// Once per (kernel, device): raise the dynamic LDS limit and ask how many workgroups of this
+// kernel fit on a compute unit.
+fg_status prepare(const fg::KernelEntry &k, int dev, int &per_cu) {
+    static std::mutex m;
+    static struct { const void *fn; int dev; int per_cu; } done[512];
+    static int n_done = 0;
+    std::lock_guard<std::mutex> lock(m);
+    per_cu = 0;
+    for (int i = 0; i < n_done; ++i)
+        if (done[i].fn == (const void *)k.fn && done[i].dev == dev) per_cu = done[i].per_cu;
+    if (per_cu == 0) {
+        hipError_t e = hipFuncSetAttribute((const void *)k.fn, hipFuncAttributeMaxDynamicSharedMemorySize, k.lds_bytes);
+        if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "hipFuncSetAttribute(%s): %s", k.name, hipGetErrorString(e));
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)k.fn, k.threads, (size_t)k.lds_bytes);
+        if (e != hipSuccess || per_cu < 1) return fail(FG_ERR_LAUNCH, "occupancy query for %s failed: %s", k.name, hipGetErrorString(e));
+        if (n_done < 512) { done[n_done].fn = (const void *)k.fn; done[n_done].dev = dev; done[n_done].per_cu = per_cu; ++n_done; }
+    }
+    return FG_OK;
+}
+
 fg_status launch(const fg::KernelEntry &k, const fg::GemmParams &p, hipStream_t stream) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return fail(FG_ERR_LAUNCH, "no HIP device is current");
-    // Once per (kernel, device): raise the dynamic LDS limit and ask how many workgroups of this
-    // kernel fit on a compute unit.
     int per_cu = 0;
-    {
-        static std::mutex m;
-        static struct { const void *fn; int dev; int per_cu; } done[256];
-        static int n_done = 0;
-        std::lock_guard<std::mutex> lock(m);
-        for (int i = 0; i < n_done; ++i)
-            if (done[i].fn == (const void *)k.fn && done[i].dev == dev) per_cu = done[i].per_cu;
-        if (per_cu == 0) {
-            hipError_t e = hipFuncSetAttribute((const void *)k.fn, hipFuncAttributeMaxDynamicSharedMemorySize, k.lds_bytes);
-            if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "hipFuncSetAttribute(%s): %s", k.name, hipGetErrorString(e));
-            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)k.fn, k.threads, (size_t)k.lds_bytes);
-            if (e != hipSuccess || per_cu < 1) return fail(FG_ERR_LAUNCH, "occupancy query for %s failed: %s", k.name, hipGetErrorString(e));
-            if (n_done < 256) { done[n_done].fn = (const void *)k.fn; done[n_done].dev = dev; done[n_done].per_cu = per_cu; ++n_done; }
-        }
-    }
+    if (fg_status st = prepare(k, dev, per_cu)) return st;
     // Persistent workgroups: as many as the GPU holds at once; each walks tiles b, b + grid, ...
     const int ntiles = p.tiles_m * p.tiles_n;
     const int resident = per_cu * kNumCU;
@@ -425,6 +429,27 @@ extern "C" {
 const char *fg_last_error(void) { return g_err; }
 
 int32_t fg_version(void) { return 100; }   // 0.1.0
+
+fg_status fg_init(void) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(FG_ERR_LAUNCH, "no HIP device is current");
+    struct { const fg::KernelEntry *t; int n; } tables[] = {
+        {fg::kernel_table_nn(), fg::TILE_COUNT * 2}, {fg::kernel_table_nt(), fg::TILE_COUNT * 2},
+        {fg::kernel_table_tn(), fg::TILE_COUNT * 2}, {fg::kernel_table_tt(), fg::TILE_COUNT * 2},
+        {fg::kernel_table_nn_bf16(), fg::TILE_COUNT}, {fg::kernel_table_nt_bf16(), fg::TILE_COUNT},
+        {fg::kernel_table_tn_bf16(), fg::TILE_COUNT}, {fg::kernel_table_tt_bf16(), fg::TILE_COUNT},
+        {fg::kernel_table_nn_xf(), fg::TILE_COUNT}, {fg::kernel_table_nt_xf(), fg::TILE_COUNT},
+        {fg::kernel_table_tn_xf(), fg::TILE_COUNT}, {fg::kernel_table_tt_xf(), fg::TILE_COUNT},
+        {fg::kernel_table_diag(), fg::TILE_COUNT * 4},
+        {fg::kernel_table_cplx(), fg::CTILE_COUNT * 4}, {fg::kernel_table_dual(), fg::CTILE_COUNT * 4},
+    };
+    for (auto &tb : tables)
+        for (int i = 0; i < tb.n; ++i) {
+            int per_cu = 0;
+            if (fg_status st = prepare(tb.t[i], dev, per_cu)) return st;
+        }
+    return FG_OK;
+}
 
 static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
                            float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, bool dual,

@@ -182,3 +182,44 @@ def test_seeded_random_shape_sweep():
             case, M, N, K, la, lb, ld, with_c, bias_dim, act, ab_add, c_act, bf16))
         run_gemm_case(M, N, K, la, lb, ld, alpha=alpha, beta=beta, with_c=with_c, bias_dim=bias_dim, act=act,
                       ints=True, pad=8 * rng.randint(0, 2), ab_add=ab_add, c_act=c_act, bf16=bf16, seed=1000 + case)
+
+
+def test_calls_can_be_captured_in_a_hip_graph():
+    """After fg_init() a call only enqueues one kernel on the given stream (no allocation, no
+    synchronisation), so a sequence of calls can be captured into a HIP graph and replayed.  Every
+    replay is checked against the eager result, with eager work and synchronisation between
+    replays."""
+    from paper_2009_12263_amd import workloads as W
+    n = 512
+    dev = "cuda"
+    A = W.uniform_pm1(n * n, 1, device=dev); B = W.uniform_pm1(n * n, 2, device=dev)
+    C = W.uniform_pm1(n * n, 3, device=dev, dtype=torch.float32)
+    bias = W.uniform_pm1(n, 4, device=dev, dtype=torch.float32)
+    D1, D2 = torch.empty_like(C), torch.empty_like(C)
+    m = lambda t, l=fg.FG_COL: fg.Matrix(t, l, n)
+
+    fg.fg_init()
+
+    def chain(out1, out2, stream=None):
+        # out1 = A.B + C;  out2 = relu(0.5 A.B^T + out1 + bias): the second call reads the first's result
+        fg.fg_gemm(n, n, n, 1.0, m(A), m(B), 1.0, m(C), m(out1), stream=stream)
+        fg.fg_gemm(n, n, n, 0.5, m(A), m(B, fg.FG_ROW), 1.0, m(out1), m(out2), bias=bias, bias_dim=0, act=fg.FG_ACT_RELU, stream=stream)
+
+    chain(D1, D2)                                # eager reference
+    torch.cuda.synchronize()
+    want1, want2 = D1.clone(), D2.clone()
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        D1.zero_(); D2.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=s):
+            chain(D1, D2, stream=s)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        D1.fill_(float("nan")); D2.fill_(float("nan"))          # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        say("graph replay %d" % rep)
+        assert torch.equal(D1, want1) and torch.equal(D2, want2), "replay %d differs from the eager result" % rep
