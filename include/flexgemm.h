@@ -16,6 +16,14 @@
  * General conventions
  *   - Every data pointer (matrix/tensor elements, bias) is a DEVICE pointer to memory the
  *     caller owns.  The library never allocates, frees, retains or copies caller memory.
+ *   - The library owns one 64 MiB device workspace per GPU, allocated by fg_init() or by the
+ *     first fg_gemm / fg_gemm_ex call that needs it and kept until the process ends.  It holds the
+ *     partial products of split-K calls (outputs with too few tiles to fill the GPU and a long K
+ *     are computed as partial products over ranges of K plus a reduction pass, the cross-
+ *     workgroup reduction use of the epilogue in Section 4.2.5).  All such calls on one GPU share
+ *     it: calls on one stream are ordered and safe; split-K calls on different streams of one GPU
+ *     must not overlap in time.  The partial products are added in a fixed order, so results do
+ *     not depend on scheduling.
  *   - Every descriptor pointer (fg_matrix, fg_epilogue, mode/extent/stride arrays) is a HOST
  *     pointer, read only during the call.
  *   - Work is enqueued on `hip_stream` (a hipStream_t, NULL = the default stream) and the call
@@ -178,18 +186,19 @@ int32_t fg_version(void);
 
 /*
  * Optional: prepare every kernel variant on the current device (raise its LDS limit, query its
- * occupancy).  Without it each variant is prepared by the first call that uses it.  After
+ * occupancy) and allocate the split-K workspace.  Without it each variant is prepared by the first
+ * call that uses it, and the workspace is allocated by the first call that splits K.  After
  * fg_init() on a device, fg_gemm / fg_gemm_ex / fg_gemm_dual / fg_contract on that device do
- * nothing but enqueue one kernel on the given stream, so they may be recorded into a HIP graph
+ * nothing but enqueue one kernel (two when K is split) on the given stream, so they may be recorded into a HIP graph
  * (stream capture) and replayed.  Returns FG_OK or FG_ERR_LAUNCH.
  */
 fg_status fg_init(void);
 
 /*
  * Name of the kernel variant and block tile that fg_gemm would use for this problem, written as
- * a NUL-terminated string into `buf` (at most `buf_len` bytes).  This is the "params" choice of
- * Section 4.2.1: the largest (nearly) square block tile that divides the problem and fills the
- * GPU.  `variant` (fg_plan_variant) names the operator: real FP16, complex, dual or real BF16.
+ * a NUL-terminated string into `buf` (at most `buf_len` bytes), followed by "+splitk<n>" when K
+ * is split into n ranges.  This is the "params" choice of Section 4.2.1, made here by an estimate
+ * of the run time of every tile shape and split.  `variant` (fg_plan_variant) names the operator: real FP16, complex, dual or real BF16.
  * Returns FG_OK, or the status fg_gemm would return for these sizes and layouts.
  */
 typedef enum { FG_PLAN_REAL = 0, FG_PLAN_COMPLEX = 1, FG_PLAN_DUAL = 2, FG_PLAN_REAL_BF16 = 3 } fg_plan_variant;

@@ -51,6 +51,12 @@ struct Problem {
     bool ab_add;
 };
 
+// What to launch for a normalised problem: block tile, and into how many K ranges the product is
+// split (1: one pass; more: partial products into the workspace, then the reduction pass).
+struct Plan { int tile; int splits; };
+
+constexpr int64_t kWorkspaceBytes = 64ll << 20;    // split-K partial products, per device
+
 const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
     if (!a_kc && b_kc) return fg::kernel_table_nn();
     if (!a_kc && !b_kc) return fg::kernel_table_nt();
@@ -59,33 +65,48 @@ const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
 }
 
 // The params heuristic (Section 4.2.1 picks the largest tile that fits shared memory; here every
-// tile fits, so the question is which shape finishes first).  Estimated time of a tile shape =
-// rounds x (tile area) / (rate of one workgroup slot): `rounds` = ceil(tiles / slots) with slots =
-// 256 compute units x workgroups of that shape per unit; the rates are measured fractions of what a
-// compute unit sustains with the 256x256 tile, one set for workgroups that share a unit (more
-// tiles than units) and one for a workgroup that has a unit to itself.  The common factor K is
-// left out.  Edge tiles are predicated, so a tile need not divide the problem.
-int choose_tile(int64_t M, int64_t N, bool allow_smallest = true) {
+// tile fits, so the question is which shape, and which split of K, finishes first).  Estimated
+// time = rounds x (time of one workgroup on its share of K + a fixed cost per round) + the cost
+// of the reduction pass if K is split.  `rounds` = ceil(workgroups / slots), slots = 256 compute
+// units x workgroups of that shape per unit; a workgroup's rate is a measured fraction of what a
+// compute unit sustains with the 256x256 tile (about 4.7 TFLOP/s), one set for workgroups that
+// share a unit and one for a workgroup that has a unit to itself.  Edge tiles are predicated, so
+// a tile need not divide the problem.  K is split only when the output has too few tiles to fill
+// the GPU and K is long (may_split: plain real products).
+Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_smallest = true) {
     static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64};
     static const int bn[fg::TILE_COUNT] = {256, 128, 128, 64};
     static const int per_cu[fg::TILE_COUNT] = {1, 1, 2, 4};
     static const double rate_shared[fg::TILE_COUNT] = {1.0, 0.8, 0.73, 0.45};
     static const double rate_alone[fg::TILE_COUNT] = {1.0, 0.8, 0.43, 0.17};
-    // tuning aid: FG_FORCE_TILE=0..3 picks a tile shape
-    if (const char *f = getenv("FG_FORCE_TILE")) {
-        int t = atoi(f);
-        if (t >= 0 && t < fg::TILE_COUNT) return t;
-    }
-    int best = 0;
-    double best_cost = 0;
+    static const int split_options[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
+    constexpr double cu_flops = 4.7e12, round_cost = 4e-6, reduce_launch = 6e-6, reduce_bw = 3e12;
+    // tuning aids: FG_FORCE_TILE=0..3 picks a tile shape, FG_FORCE_SPLIT=n a split of K
+    int force_tile = -1, force_split = 0;
+    if (const char *f = getenv("FG_FORCE_TILE")) { int t = atoi(f); if (t >= 0 && t < fg::TILE_COUNT) force_tile = t; }
+    if (const char *f = getenv("FG_FORCE_SPLIT")) force_split = atoi(f);
+    const int64_t nk = (K + 63) / 64;                       // K tiles (every real kernel has BK = 64)
+    const int64_t ldw = (M + 3) / 4 * 4;
+    Plan best{0, 1};
+    double best_cost = -1;
     const int ntypes = allow_smallest ? fg::TILE_COUNT : fg::TILE_COUNT - 1;
     for (int t = 0; t < ntypes; ++t) {
+        if (force_tile >= 0 && t != force_tile) continue;
         const int64_t tiles = ((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]);
         const int64_t slots = (int64_t)kNumCU * per_cu[t];
-        const int64_t rounds = (tiles + slots - 1) / slots;
-        const double slot_rate = tiles > kNumCU ? rate_shared[t] / per_cu[t] : rate_alone[t];
-        const double cost = (double)rounds * bm[t] * bn[t] / slot_rate;
-        if (t == 0 || cost < best_cost) { best = t; best_cost = cost; }
+        auto legal = [&](int S) { return S == 1 || (may_split && S <= nk && (int64_t)S * ldw * N * 4 <= kWorkspaceBytes); };
+        const int forced = (force_split >= 1 && legal(force_split)) ? force_split : (force_split >= 1 ? 1 : 0);
+        for (int S : split_options) {
+            if (forced) { if (S != split_options[0]) break; S = forced; }      // one candidate: the forced split
+            else if (S > 1 && (!legal(S) || nk / S < 4)) break;                   // at least 256 k per share
+            const int64_t wgs = tiles * S;
+            const int64_t rounds = (wgs + slots - 1) / slots;
+            const double rate = wgs > kNumCU ? rate_shared[t] / per_cu[t] : rate_alone[t];
+            const double k_share = (double)((nk + S - 1) / S) * 64;
+            double cost = (double)rounds * (2.0 * bm[t] * bn[t] * k_share / (cu_flops * rate) + round_cost);
+            if (S > 1) cost += reduce_launch + (2.0 * S + 2.0) * (double)M * N * 4 / reduce_bw;
+            if (best_cost < 0 || cost < best_cost) { best = Plan{t, S}; best_cost = cost; }
+        }
     }
     return best;
 }
@@ -99,14 +120,18 @@ int choose_ctile(int64_t M, int64_t N) {
 }
 
 // Kernel variant for a normalised problem.
-const fg::KernelEntry *select_kernel(const Problem &q) {
+const fg::KernelEntry *select_kernel(const Problem &q, int *splits = nullptr) {
+    if (splits) *splits = 1;
     if (q.cplx) {
         const int t = choose_ctile(q.M, q.N);
         if (t < 0) return nullptr;
         const int v = (q.a_kc ? 2 : 0) + (q.b_kc ? 0 : 1);     // nn, nt, tn, tt
         return &(q.dual ? fg::kernel_table_dual() : fg::kernel_table_cplx())[t * 4 + v];
     }
-    const int tile = choose_tile(q.M, q.N);
+    const bool may_split = splits && !q.a_diag && !q.b_diag;
+    const Plan plan = choose_plan(q.M, q.N, q.K, may_split);
+    const int tile = plan.tile;
+    if (splits) *splits = plan.splits;
     if (q.a_diag) return &fg::kernel_table_diag()[tile * 4 + (q.b_kc ? 0 : 1)];
     if (q.b_diag) return &fg::kernel_table_diag()[tile * 4 + (q.a_kc ? 2 : 3)];
     if (q.ab_add) {
@@ -142,13 +167,31 @@ fg_status prepare(const fg::KernelEntry &k, int dev, int &per_cu) {
     return FG_OK;
 }
 
+// Split-K workspace: one allocation of kWorkspaceBytes per device, made by fg_init() or by the
+// first call that splits K, and kept until the process ends.  Every split-K call on a device
+// uses it, so such calls must not overlap in time (calls on one stream never do).
+fg_status workspace(int dev, float **ws) {
+    static std::mutex m;
+    static float *per_dev[64];
+    if (dev < 0 || dev >= 64) return fail(FG_ERR_LAUNCH, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(m);
+    if (!per_dev[dev]) {
+        void *ptr = nullptr;
+        hipError_t e = hipMalloc(&ptr, (size_t)kWorkspaceBytes);
+        if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "hipMalloc of the split-K workspace failed: %s", hipGetErrorString(e));
+        per_dev[dev] = (float *)ptr;
+    }
+    *ws = per_dev[dev];
+    return FG_OK;
+}
+
 fg_status launch(const fg::KernelEntry &k, const fg::GemmParams &p, hipStream_t stream) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return fail(FG_ERR_LAUNCH, "no HIP device is current");
     int per_cu = 0;
     if (fg_status st = prepare(k, dev, per_cu)) return st;
     // Persistent workgroups: as many as the GPU holds at once; each walks tiles b, b + grid, ...
-    const int ntiles = p.tiles_m * p.tiles_n;
+    const int ntiles = p.tiles_m * p.tiles_n * (p.splits > 1 ? p.splits : 1);
     const int resident = per_cu * kNumCU;
     dim3 grid((unsigned)(ntiles < resident ? ntiles : resident)), block((unsigned)k.threads);
     hipLaunchKernelGGL(k.fn, grid, block, (size_t)k.lds_bytes, stream, p);
@@ -448,7 +491,8 @@ fg_status fg_init(void) {
             int per_cu = 0;
             if (fg_status st = prepare(tb.t[i], dev, per_cu)) return st;
         }
-    return FG_OK;
+    float *ws = nullptr;
+    return workspace(dev, &ws);
 }
 
 static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
@@ -457,8 +501,9 @@ static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const f
     Problem q;
     if (fg_status st = normalise(M, N, K, alpha, A, B, beta, C, D, ep, dual, lt, q)) return st;
     if (q.M == 0 || q.N == 0) return FG_OK;
-    const fg::KernelEntry *kp = select_kernel(q);
-    if (!kp) return fail(FG_ERR_UNSUPPORTED, "no block tile divides M=%lld, N=%lld", (long long)q.M, (long long)q.N);
+    int splits = 1;
+    const fg::KernelEntry *kp = select_kernel(q, &splits);
+    if (!kp) return fail(FG_ERR_UNSUPPORTED, "no kernel for M=%lld, N=%lld", (long long)q.M, (long long)q.N);
     const fg::KernelEntry &k = *kp;
 
     fg::GemmParams p;
@@ -479,7 +524,27 @@ static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const f
     p.c_act = q.c_act;
     p.a_add2 = (uint32_t)q.a_add * 0x10001u; p.b_add2 = (uint32_t)q.b_add * 0x10001u;
     p.alpha = q.alpha; p.beta = q.beta;
-    return launch(k, p, (hipStream_t)hip_stream);
+    p.splits = 1;
+    if (splits <= 1) return launch(k, p, (hipStream_t)hip_stream);
+
+    // Split K: `splits` partial products into the workspace, then the reduction pass that also
+    // applies alpha, beta.C, bias and the activations.
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(FG_ERR_LAUNCH, "no HIP device is current");
+    float *ws = nullptr;
+    if (fg_status st = workspace(dev, &ws)) return st;
+    const int64_t ldw = (q.M + 3) / 4 * 4;
+    const int64_t nk = (q.K + 63) / 64;
+    p.splits = splits;
+    p.split_kt = (int32_t)((nk + splits - 1) / splits);
+    p.split_stride = ldw * q.N;
+    p.D = ws; p.ldd = ldw;
+    p.C = nullptr; p.has_c = 0; p.bias = nullptr; p.act = 0; p.c_act = 0; p.alpha = 1.f; p.beta = 0.f;
+    if (fg_status st = launch(k, p, (hipStream_t)hip_stream)) return st;
+    hipError_t e = fg::launch_splitk_reduce(ws, p.split_stride, splits, (int)q.M, (int)q.N, (int)ldw, q.alpha, q.beta, q.C, q.ldc,
+                                            q.D, q.ldd, q.bias, q.bias_dim, q.act, q.c_act, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "launch of the split-K reduction failed: %s", hipGetErrorString(e));
+    return FG_OK;
 }
 
 fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
@@ -524,9 +589,12 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
         q.a_diag = layoutB == FG_DIAG; q.b_diag = layoutA == FG_DIAG;
         q.a_kc = layoutB == FG_COL || q.a_diag; q.b_kc = layoutA == FG_ROW || q.b_diag;
     }
-    const fg::KernelEntry *k = select_kernel(q);
-    if (!k) return fail(FG_ERR_UNSUPPORTED, "no block tile divides the problem");
-    snprintf(buf, (size_t)buf_len, "%s", k->name);
+    q.K = K;
+    int splits = 1;
+    const fg::KernelEntry *k = select_kernel(q, &splits);
+    if (!k) return fail(FG_ERR_UNSUPPORTED, "no kernel for the problem");
+    if (splits > 1) snprintf(buf, (size_t)buf_len, "%s+splitk%d", k->name, splits);
+    else snprintf(buf, (size_t)buf_len, "%s", k->name);
     return FG_OK;
 }
 
@@ -543,7 +611,7 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
     // A result that is not contiguous along the leading row mode is stored in short pieces; the
     // smallest tile makes them shorter still (measured on the paper's D_abc = A_bda B_dc).
     const bool rows_contiguous = c.c_m.n == 0 || c.c_m.stride[0] == 1;
-    const int tile = choose_tile(c.M, c.N, rows_contiguous || c.M < 128 || c.N < 128);
+    const int tile = choose_plan(c.M, c.N, c.K, false, rows_contiguous || c.M < 128 || c.N < 128).tile;
     const fg::KernelEntry &k = table_for(c.a_kc, c.b_kc)[fg::entry_index(tile, true)];
     fg::GemmParams p;
     memset(&p, 0, sizeof p);

@@ -65,6 +65,11 @@ struct GemmParams {
     // A_ik := half(A_ik + a_add), B_kj := half(B_kj + b_add), the addend as two packed halves
     int32_t c_act;
     uint32_t a_add2, b_add2;
+    // split-K (plain real matrices): the launch covers `splits` copies of the tile grid; copy s
+    // sums K tiles [s * split_kt, (s + 1) * split_kt) and writes its raw partial result to
+    // D + s * split_stride (a workspace: alpha = 1, no C, bias or activation in this pass)
+    int32_t splits, split_kt;
+    int64_t split_stride;
     // tensor contraction: mode groups of each tensor
     ModeGroup a_m, a_k, b_n, b_k, c_m, c_n;
 };
@@ -85,6 +90,7 @@ struct TileCfg {
     static constexpr bool A_KC = A_KC_, B_KC = B_KC_, STRIDED = STRIDED_;
     // 0: real; 1: complex (i^2 = -1), 2: dual (eps^2 = 0) numbers in planar-split storage
     static constexpr int CPLX = CPLX_;
+    static constexpr bool SPLITK = !STRIDED_ && DIAG_ == 0 && CPLX_ == 0;   // kernel understands GemmParams::splits
     static constexpr bool BF16 = BF16_;                             // A, B are bfloat16 instead of binary16
     // XFORM: a constant is added to every element of A and of B after it is loaded (the fragment
     // registers are transformed just before the matrix instructions that consume them)
@@ -680,7 +686,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % Cfg::WGM, wn = wave / Cfg::WGM;
-    const int ntiles = p.tiles_m * p.tiles_n;
+    const int ntiles = p.tiles_m * p.tiles_n * (Cfg::SPLITK ? p.splits : 1);
     [[maybe_unused]] const uint32_t xf_a = p.a_add2, xf_b = p.b_add2;   // used by TileCfg::XFORM only
     [[maybe_unused]] const int xf_k = p.K;
 
@@ -704,16 +710,25 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
     int kt0 = 0, nkt = 0;
 
     // start the loads of a tile: point the loaders at its panels and fill the ring
-    auto start_tile = [&](int tile_id, int &m0, int &n0) {
+    auto start_tile = [&](int tile_id, int &m0, int &n0, int &split) {
         // parameters are re-read here rather than kept in registers across the K loop
         const GemmParams tp = load_param<GemmParams>(0);
         int tm, tn;
+        split = 0;
+        if constexpr (Cfg::SPLITK) {
+            const int per_split = tp.tiles_m * tp.tiles_n;
+            split = tile_id / per_split;
+            tile_id -= split * per_split;
+        }
         block_to_tile(tile_id, tp.tiles_m, tp.tiles_n, tm, tn);
         m0 = tm * BM;
         n0 = tn * BN;
         const int nk = (tp.K + BK - 1) / BK;
         kt0 = 0;
         int kt1 = nk;
+        if constexpr (Cfg::SPLITK) {
+            if (tp.splits > 1) { kt0 = split * tp.split_kt; kt1 = kt0 + tp.split_kt; }
+        }
         if constexpr (Cfg::DIAG == 1) { kt0 = m0 / BK; kt1 = (m0 + BM) / BK; }
         if constexpr (Cfg::DIAG == 2) { kt0 = n0 / BK; kt1 = (n0 + BN) / BK; }
         if (kt1 > nk) kt1 = nk;
@@ -726,7 +741,9 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
             else la[q].init(ap[q], m0, wave, lane, tp.a_rs, tp.a_ks, tp.a_m, tp.a_k, tp.a_span, tp.K, tp.M);
             if constexpr (Cfg::DIAG == 2) lb[q].init(bp[q], n0, tp.N < tp.K ? tp.N : tp.K, wave, lane);
             else lb[q].init(bp[q], n0, wave, lane, tp.b_rs, tp.b_ks, tp.b_n, tp.b_k, tp.b_span, tp.K, tp.N);
-            if constexpr (Cfg::DIAG != 0) { la[q].skip(kt0); lb[q].skip(kt0); }
+            if constexpr (Cfg::DIAG != 0 || Cfg::SPLITK) {
+                if (kt0 > 0) { la[q].skip(kt0); lb[q].skip(kt0); }
+            }
         }
 #pragma unroll
         for (int st = 0; st < S; ++st)
@@ -741,8 +758,8 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
 
     int tile = blockIdx.x;
     if (tile >= ntiles) return;
-    int m0, n0;
-    start_tile(tile, m0, n0);
+    int m0, n0, sp0;
+    start_tile(tile, m0, n0, sp0);
 
     while (true) {
         const int m_base = m0 + wm * Cfg::WTM, n_base = n0 + wn * Cfg::WTN;
@@ -917,15 +934,16 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
         // free, so its first loads go out before this tile's results are stored
         const int next = tile + (int)gridDim.x;
         const bool more_tiles = next < ntiles;
-        int m1 = 0, n1 = 0;
+        int m1 = 0, n1 = 0, sp1 = 0;
         if (more_tiles) {
             wait_tile<0>();
             __builtin_amdgcn_s_barrier();
-            start_tile(next, m1, n1);
+            start_tile(next, m1, n1, sp1);
         }
 
         {
-            const GemmParams ep = load_param<GemmParams>(0);
+            GemmParams ep = load_param<GemmParams>(0);
+            if constexpr (Cfg::SPLITK) ep.D += (int64_t)sp0 * ep.split_stride;
             if (ep.has_c) epilogue<Cfg, true>(ep, ep.C, ep.D, acc[0], m_base, n_base, lane);
             else epilogue<Cfg, false>(ep, ep.C, ep.D, acc[0], m_base, n_base, lane);
             if constexpr (Cfg::CPLX) {
@@ -938,6 +956,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
         tile = next;
         m0 = m1;
         n0 = n1;
+        sp0 = sp1;
     }
 }
 

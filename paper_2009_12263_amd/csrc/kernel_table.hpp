@@ -40,6 +40,11 @@ const KernelEntry *kernel_table_cplx();
 const KernelEntry *kernel_table_dual();
 enum { CTILE_COUNT = 3 };
 
+// Second pass of a split-K product (splitk_reduce.hip).
+hipError_t launch_splitk_reduce(const float *W, int64_t stride, int splits, int M, int N, int ldw, float alpha, float beta,
+                                const float *C, int64_t ldc, float *D, int64_t ldd, const float *bias, int bias_dim,
+                                int act, int c_act, hipStream_t stream);
+
 // Entry index inside one table: tile * 2 + strided.
 inline int entry_index(int tile, bool strided) { return tile * 2 + (strided ? 1 : 0); }
 

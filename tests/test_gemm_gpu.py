@@ -223,3 +223,36 @@ def test_calls_can_be_captured_in_a_hip_graph():
         torch.cuda.synchronize()
         say("graph replay %d" % rep)
         assert torch.equal(D1, want1) and torch.equal(D2, want2), "replay %d differs from the eager result" % rep
+
+
+def test_split_k_small_outputs_long_k():
+    """Outputs with too few tiles to fill the GPU and a long K are computed as partial products
+    over K ranges plus a reduction pass (the cross-workgroup reduction use of the epilogue,
+    Section 4.2.5).  Exact on integers; epilogue, transforms, BF16, edge tiles and a row-major
+    result go through the reduction pass."""
+    assert "+splitk" in fg.fg_gemm_plan(512, 512, 8192)
+    assert "+splitk" in fg.fg_gemm_plan(300, 200, 4096)
+    say("split 512x512x8192 ints"); run_gemm_case(512, 512, 8192, ints=True)
+    say("split 512x512x8192 floats"); run_gemm_case(512, 512, 8192, alpha=0.5, beta=2.0)
+    say("split 300x200x4096 ragged, bias, relu, relu on C")
+    run_gemm_case(300, 200, 4096, fg.FG_ROW, fg.FG_COL, ints=True, bias_dim=0, act=fg.FG_ACT_RELU, c_act=fg.FG_ACT_RELU, pad=8)
+    say("split 300x200x4096 row-major D, bias along N")
+    run_gemm_case(300, 200, 4096, fg.FG_COL, fg.FG_ROW, ld_layout=fg.FG_ROW, ints=True, bias_dim=1, alpha=-1.0, beta=0.25)
+    say("split 64x64x32768 no C"); run_gemm_case(64, 64, 32768, with_c=False, ints=True)
+    say("split 1024x1024x8192 floats sampled"); run_gemm_case(1024, 1024, 8192, fg.FG_ROW, fg.FG_ROW, samples=4096)
+    say("split with K tail: 256x128x4104"); run_gemm_case(256, 128, 4104, ints=True)
+    say("split bf16"); run_gemm_case(384, 256, 8192, ints=True, bf16=True)
+    say("split with addition on A and B"); run_gemm_case(384, 256, 8192, ints=True, ab_add=(1.0, -1.0))
+    say("split in place"); run_gemm_case(512, 512, 8192, ints=True, inplace=True)
+
+
+def test_forced_split_counts(monkeypatch):
+    """Every split count the planner can choose, forced on one ragged multi-tile problem, gives the
+    same exact result (FG_FORCE_SPLIT is the library's tuning override)."""
+    for S in (2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64):
+        monkeypatch.setenv("FG_FORCE_SPLIT", str(S))
+        assert ("+splitk%d" % S) in fg.fg_gemm_plan(200, 136, 4160)
+        say("forced split %d" % S); run_gemm_case(200, 136, 4160, ints=True, bias_dim=1, act=fg.FG_ACT_RELU)
+    monkeypatch.setenv("FG_FORCE_SPLIT", "1")
+    assert "+splitk" not in fg.fg_gemm_plan(512, 512, 8192)
+    run_gemm_case(512, 512, 8192, ints=True)
