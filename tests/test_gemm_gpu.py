@@ -256,3 +256,12 @@ def test_forced_split_counts(monkeypatch):
     monkeypatch.setenv("FG_FORCE_SPLIT", "1")
     assert "+splitk" not in fg.fg_gemm_plan(512, 512, 8192)
     run_gemm_case(512, 512, 8192, ints=True)
+
+
+def test_every_entry_of_large_multi_tile_launches():
+    """Every output entry (not a sample) of launches in which each persistent workgroup computes
+    two tiles, with a short K so that the oracle can afford it: a fault that hits a few lanes of a
+    few waves now and then shows up here, while a sample of positions can miss it."""
+    say("8192x4096x64 NN ints, every entry"); run_gemm_case(8192, 4096, 64, ints=True)
+    say("4096x8192x128 TT ints, bias, relu, every entry")
+    run_gemm_case(4096, 8192, 128, fg.FG_ROW, fg.FG_ROW, ints=True, bias_dim=1, act=fg.FG_ACT_RELU)
