@@ -46,6 +46,7 @@ class _GemmProblem(C.Structure):
         ("C_re", C.c_void_p), ("C_im", C.c_void_p), ("layoutC", C.c_int32), ("ldc", C.c_int64),
         ("bias", C.c_void_p), ("bias_dim", C.c_int32), ("act", C.c_int32), ("ab_dtype", C.c_int32), ("dual", C.c_int32),
         ("ab_add", C.c_int32), ("a_add", C.c_double), ("b_add", C.c_double), ("c_act", C.c_int32),
+        ("interleaved_ab", C.c_int32), ("interleaved_c", C.c_int32),
     ]
 
 
@@ -117,6 +118,7 @@ class Operand:
     ld: int = 0
     im: Optional[np.ndarray] = None
     dtype: int = F16
+    interleaved: bool = False   # complex with (real, imaginary) adjacent in ``re``; ``im`` unused, ld in complex elements
 
 
 def _ptr(a: Optional[np.ndarray], dtype) -> Optional[int]:
@@ -134,7 +136,8 @@ def _check_span(a: Optional[np.ndarray], need: int, what: str):
         raise ValueError("%s holds %d elements, the described operand needs %d" % (what, a.size, need))
 
 
-def _gemm_problem(M, N, K, alpha, A: Operand, B: Operand, beta, Cre, Cim, layoutC, ldc, bias, bias_dim, act):
+def _gemm_problem(M, N, K, alpha, A: Operand, B: Operand, beta, Cre, Cim, layoutC, ldc, bias, bias_dim, act,
+                  c_interleaved=False):
     q = _GemmProblem()
     q.M, q.N, q.K, q.alpha, q.beta = M, N, K, float(alpha), float(beta)
 
@@ -147,19 +150,27 @@ def _gemm_problem(M, N, K, alpha, A: Operand, B: Operand, beta, Cre, Cim, layout
             return (rows - 1) * ld + cols
         return min(rows, cols)
 
+    if A.interleaved != B.interleaved:
+        raise ValueError("A and B must both be interleaved or both planar")
     for name, op, rows, cols in (("A", A, M, K), ("B", B, K, N)):
         if op.layout == COL and op.ld < rows or op.layout == ROW and op.ld < cols:
             raise ValueError("leading dimension of %s too small" % name)
-        need = span(op.layout, op.ld, rows, cols)
+        need = span(op.layout, op.ld, rows, cols) * (2 if op.interleaved else 1)
         _check_span(op.re, need, name + ".re")
-        _check_span(op.im, need, name + ".im")
-    q.A_re, q.A_im, q.layoutA, q.lda = _ptr(A.re, np.float16), _ptr(A.im, np.float16), A.layout, A.ld
-    q.B_re, q.B_im, q.layoutB, q.ldb = _ptr(B.re, np.float16), _ptr(B.im, np.float16), B.layout, B.ld
+        if not op.interleaved:
+            _check_span(op.im, need, name + ".im")
+    im_of = lambda op: (_ptr(op.re, np.float16) + 2) if op.interleaved else _ptr(op.im, np.float16)
+    q.A_re, q.A_im, q.layoutA, q.lda = _ptr(A.re, np.float16), im_of(A), A.layout, A.ld
+    q.B_re, q.B_im, q.layoutB, q.ldb = _ptr(B.re, np.float16), im_of(B), B.layout, B.ld
+    q.interleaved_ab = 1 if A.interleaved else 0
     if Cre is not None:
-        need = span(layoutC, ldc, M, N)
+        need = span(layoutC, ldc, M, N) * (2 if c_interleaved else 1)
         _check_span(Cre, need, "C.re")
-        _check_span(Cim, need, "C.im")
+        if not c_interleaved:
+            _check_span(Cim, need, "C.im")
     q.C_re, q.C_im, q.layoutC, q.ldc = _ptr(Cre, np.float32), _ptr(Cim, np.float32), layoutC, ldc
+    if c_interleaved and Cre is not None:
+        q.C_im, q.interleaved_c = _ptr(Cre, np.float32) + 4, 1
     if bias is not None:
         _check_span(bias, M if bias_dim == 0 else N, "bias")
     q.bias, q.bias_dim, q.act = _ptr(bias, np.float32), bias_dim, act
@@ -173,8 +184,10 @@ def gemm(M: int, N: int, K: int, alpha: float, A: Operand, B: Operand, beta: flo
          C_re: Optional[np.ndarray] = None, C_im: Optional[np.ndarray] = None, layoutC: int = COL, ldc: int = 0,
          bias: Optional[np.ndarray] = None, bias_dim: int = 0, act: int = ACT_NONE,
          at: Optional[Sequence[np.ndarray]] = None, threads: Optional[int] = None, dual: bool = False,
-         ab_add: Optional[Sequence[float]] = None, c_act: int = ACT_NONE):
+         ab_add: Optional[Sequence[float]] = None, c_act: int = ACT_NONE, c_interleaved: bool = False):
     """Evaluate the GEMM definition.  ``dual``: the ``im`` planes hold dual parts (eps^2 = 0).
+    Interleaved complex operands: ``Operand(..., interleaved=True)`` for A and B, and
+    ``c_interleaved`` for C (then ``C_re`` is the interleaved array and ``C_im`` is unused).
     ``ab_add=(a, b)``: every loaded element of A (B) becomes half(element + a) (half(element + b)),
     a and b binary16 values; ``c_act``: activation applied to C before it is scaled by beta.
 
@@ -183,12 +196,12 @@ def gemm(M: int, N: int, K: int, alpha: float, A: Operand, B: Operand, beta: flo
     position.
     """
     threads = threads or default_threads()
-    q = _gemm_problem(M, N, K, alpha, A, B, beta, C_re, C_im, layoutC, ldc, bias, bias_dim, act)
+    q = _gemm_problem(M, N, K, alpha, A, B, beta, C_re, C_im, layoutC, ldc, bias, bias_dim, act, c_interleaved)
     q.dual = 1 if dual else 0
     if ab_add is not None:
         q.ab_add, q.a_add, q.b_add = 1, float(ab_add[0]), float(ab_add[1])
     q.c_act = c_act
-    is_complex = A.im is not None or B.im is not None
+    is_complex = A.im is not None or B.im is not None or A.interleaved
     if at is None:
         shape, order = (M, N), "F"
     else:

@@ -131,18 +131,24 @@ typedef struct {
     int32_t ab_add;                /* 1: A_ik := half(A_ik + a_add), B_kj := half(B_kj + b_add) */
     double a_add, b_add;           /* must be binary16 values                    */
     int32_t c_act;                 /* activation applied to C_ij before beta     */
+    /* interleaved complex storage (Section 5.4: the layout of complex matrices in global memory):
+       element e of an operand occupies positions 2e (real part) and 2e + 1 (imaginary part) of one
+       array.  interleaved_ab / interleaved_c = 1: the *_re pointer is that array, the *_im pointer
+       is *_re + 1, and every element index is doubled; leading dimensions count complex elements. */
+    int32_t interleaved_ab, interleaved_c;
 } og_problem;
 
 /* logical element (r, c) of a stored rows x cols operand */
-static inline double operand_at(const uint16_t *p, int32_t layout, int64_t ld, int64_t r, int64_t c, const double *decode) {
-    if (layout == OG_COL) return decode[p[r + c * ld]];
-    if (layout == OG_ROW) return decode[p[c + r * ld]];
+/* `es`: positions per element, 1 (one array per plane) or 2 (interleaved complex) */
+static inline double operand_at(const uint16_t *p, int32_t layout, int64_t ld, int64_t r, int64_t c, const double *decode, int es) {
+    if (layout == OG_COL) return decode[p[es * (r + c * ld)]];
+    if (layout == OG_ROW) return decode[p[es * (c + r * ld)]];
     /* OG_DIAG: p is the vector of diagonal entries, everything else is zero */
-    return (r == c) ? decode[p[r]] : 0.0;
+    return (r == c) ? decode[p[es * r]] : 0.0;
 }
 
-static inline double c_at(const float *p, int32_t layout, int64_t ld, int64_t i, int64_t j) {
-    return (double)((layout == OG_COL) ? p[i + j * ld] : p[j + i * ld]);
+static inline double c_at(const float *p, int32_t layout, int64_t ld, int64_t i, int64_t j, int es) {
+    return (double)((layout == OG_COL) ? p[es * (i + j * ld)] : p[es * (j + i * ld)]);
 }
 
 /* One output entry (i, j): the definition written out. */
@@ -150,10 +156,11 @@ static void gemm_entry(const og_problem *q, int64_t i, int64_t j,
                        double *d_re, double *d_im, double *g_re, double *g_im) {
     const int is_complex = (q->A_im != NULL) || (q->B_im != NULL);
     const double *dec = g_half_table[q->ab_dtype ? 1 : 0];
+    const int es = q->interleaved_ab ? 2 : 1, esc = q->interleaved_c ? 2 : 1;
     double s_re = 0.0, s_im = 0.0, m_re = 0.0, m_im = 0.0;
     for (int64_t k = 0; k < q->K; ++k) {
-        double ar = operand_at(q->A_re, q->layoutA, q->lda, i, k, dec);
-        double br = operand_at(q->B_re, q->layoutB, q->ldb, k, j, dec);
+        double ar = operand_at(q->A_re, q->layoutA, q->lda, i, k, dec, es);
+        double br = operand_at(q->B_re, q->layoutB, q->ldb, k, j, dec, es);
         if (q->ab_add) {
             ar = round_to_half(ar + q->a_add);
             br = round_to_half(br + q->b_add);
@@ -162,8 +169,8 @@ static void gemm_entry(const og_problem *q, int64_t i, int64_t j,
             s_re += ar * br;
             m_re += fabs(ar) * fabs(br);
         } else {
-            double ai = q->A_im ? operand_at(q->A_im, q->layoutA, q->lda, i, k, dec) : 0.0;
-            double bi = q->B_im ? operand_at(q->B_im, q->layoutB, q->ldb, k, j, dec) : 0.0;
+            double ai = q->A_im ? operand_at(q->A_im, q->layoutA, q->lda, i, k, dec, es) : 0.0;
+            double bi = q->B_im ? operand_at(q->B_im, q->layoutB, q->ldb, k, j, dec, es) : 0.0;
             if (q->dual) {
                 /* (ar + eps ai)(br + eps bi) with eps^2 = 0: the eps.eps product vanishes */
                 s_re += ar * br;
@@ -180,13 +187,13 @@ static void gemm_entry(const og_problem *q, int64_t i, int64_t j,
     double y_re = q->alpha * s_re, y_im = q->alpha * s_im;
     double t_re = fabs(q->alpha) * m_re, t_im = fabs(q->alpha) * m_im;
     if (q->C_re) {
-        double c = c_at(q->C_re, q->layoutC, q->ldc, i, j);
+        double c = c_at(q->C_re, q->layoutC, q->ldc, i, j, esc);
         if (q->c_act == OG_ACT_RELU) c = (c > 0.0) ? c : 0.0;
         y_re += q->beta * c;
         t_re += fabs(q->beta) * fabs(c);
     }
     if (is_complex && q->C_im) {
-        double c = c_at(q->C_im, q->layoutC, q->ldc, i, j);
+        double c = c_at(q->C_im, q->layoutC, q->ldc, i, j, esc);
         y_im += q->beta * c;
         t_im += fabs(q->beta) * fabs(c);
     }
@@ -208,6 +215,8 @@ static int gemm_problem_ok(const og_problem *q) {
     if (q->act != OG_ACT_NONE && q->act != OG_ACT_RELU) return 0;
     if (q->ab_dtype != 0 && q->ab_dtype != 1) return 0;
     if (q->c_act != OG_ACT_NONE && q->c_act != OG_ACT_RELU) return 0;
+    if (q->interleaved_ab && (!q->A_im || !q->B_im || q->A_im != q->A_re + 1 || q->B_im != q->B_re + 1)) return 0;
+    if (q->interleaved_c && q->C_re && q->C_im != q->C_re + 1) return 0;
     /* the activation on C touches only C: any real product; the addition on A and B is defined
        here for stored binary16 matrices only */
     if (q->c_act && (q->A_im || q->B_im)) return 0;

@@ -459,3 +459,35 @@ def test_ab_add_and_relu_on_c_by_brute_force():
     assert np.array_equal(r0["D"], r1["D"])
     with pytest.raises(ValueError):
         O.gemm(M, N, K, 1.0, Operand(A, ROW, lda), Operand(B, ROW, ldb), ab_add=(0.3, 0.0))     # 0.3 is not a binary16 value
+
+
+# ---------------------------------------------------------------- interleaved complex storage
+@pytest.mark.parametrize("la,lb,lc", list(itertools.product([COL, ROW], [COL, ROW], [COL, ROW])))
+def test_interleaved_complex_matches_complex128_matmul(la, lb, lc):
+    M, N, K = 7, 5, 9
+
+    def store_c(re, im, layout, pad):
+        buf_r, ld, hr = store(re, layout, pad)
+        buf_i, _, hi = store(im, layout, pad)
+        inter = np.empty(buf_r.size * 2, buf_r.dtype)
+        inter[0::2], inter[1::2] = buf_r, buf_i
+        return inter, ld, hr + 1j * hi
+
+    A, lda, Ac = store_c(rand_mat(M, K), rand_mat(M, K), la, 2)
+    B, ldb, Bc = store_c(rand_mat(K, N), rand_mat(K, N), lb, 1)
+    Cr, Ci = rand_mat(M, N).astype(np.float32), rand_mat(M, N).astype(np.float32)
+    lead = Cr.T if lc == COL else Cr
+    Cint = np.empty(2 * M * N, np.float32)
+    Cint[0::2] = np.ascontiguousarray(Cr.T if lc == COL else Cr).reshape(-1)
+    Cint[1::2] = np.ascontiguousarray(Ci.T if lc == COL else Ci).reshape(-1)
+    ldc = M if lc == COL else N
+    r = O.gemm(M, N, K, 0.5, Operand(A, la, lda, interleaved=True), Operand(B, lb, ldb, interleaved=True), -2.0,
+               Cint, None, lc, ldc, c_interleaved=True)
+    want = 0.5 * (Ac @ Bc) - 2.0 * (Cr.astype(np.float64) + 1j * Ci.astype(np.float64))
+    assert np.allclose(r["D"] + 1j * r["D_im"], want, rtol=0, atol=1e-12)
+    # the same numbers in planar storage give the same result
+    Ar, _, _ = store(Ac.real, la, 2); Ai, _, _ = store(Ac.imag, la, 2)
+    Br, _, _ = store(Bc.real, lb, 1); Bi, _, _ = store(Bc.imag, lb, 1)
+    r2 = O.gemm(M, N, K, 0.5, Operand(Ar, la, lda, Ai), Operand(Br, lb, ldb, Bi), -2.0,
+                np.ascontiguousarray(Cr.T if lc == COL else Cr).reshape(-1), np.ascontiguousarray(Ci.T if lc == COL else Ci).reshape(-1), lc, ldc)
+    assert np.array_equal(r["D"], r2["D"]) and np.array_equal(r["D_im"], r2["D_im"])
