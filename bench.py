@@ -121,6 +121,14 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream):
         m, m, m, 1.0, M(A4, 0, m), M(B4, 0, m), 1.0, M(C4, 0, m), M(D4, 0, m), stream=stream)) * 1e-12)
     guard("config4_complex_planar_4096_TFLOPs", lambda: 8.0 * m ** 3 / timed(lambda: fg.fg_gemm(
         m, m, m, 1.0, M(A4, 0, m, im=A4i), M(B4, 0, m, im=B4i), 1.0, M(C4, 0, m, im=C4i), M(D4, 0, m, im=D4i), stream=stream)) * 1e-12)
+    def cplx_interleaved():
+        weave = lambda x, y: torch.stack((x, y), dim=-1).reshape(-1).contiguous()
+        Aw, Bw, Cw = weave(A4, A4i), weave(B4, B4i), weave(C4, C4i)
+        Dw = torch.empty_like(Cw)
+        il = lambda t, d: M(t, 0, m, dtype=d)
+        return 8.0 * m ** 3 / timed(lambda: fg.fg_gemm(m, m, m, 1.0, il(Aw, fg.FG_CF16), il(Bw, fg.FG_CF16), 1.0,
+                                                        il(Cw, fg.FG_CF32), il(Dw, fg.FG_CF32), stream=stream)) * 1e-12
+    guard("complex_interleaved_4096_TFLOPs", cplx_interleaved)
     guard("dual_planar_4096_TFLOPs", lambda: 6.0 * m ** 3 / timed(lambda: fg.fg_gemm_dual(
         m, m, m, 1.0, M(A4, 0, m, im=A4i), M(B4, 0, m, im=B4i), 1.0, M(C4, 0, m, im=C4i), M(D4, 0, m, im=D4i), stream=stream)) * 1e-12)
     Ab, Bb = A.to(torch.bfloat16), B.to(torch.bfloat16)

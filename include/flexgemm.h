@@ -63,7 +63,12 @@ typedef enum {
     FG_ERR_LAUNCH = 7        /* the HIP runtime refused the launch (no device, bad stream)   */
 } fg_status;
 
-typedef enum { FG_F16 = 0, FG_BF16 = 1, FG_F32 = 2 } fg_dtype;   /* A, B: FG_F16 or FG_BF16.  C, D: FG_F32 */
+typedef enum {
+    FG_F16 = 0, FG_BF16 = 1,   /* A, B: IEEE binary16 / bfloat16                                 */
+    FG_F32 = 2,                /* C, D                                                           */
+    FG_CF16 = 3,               /* A, B: interleaved complex, element = (re, im) as two binary16  */
+    FG_CF32 = 4                /* C, D: interleaved complex, element = (re, im) as two binary32  */
+} fg_dtype;
 
 typedef enum {
     FG_COL = 0,   /* column-major ('N'): element (r, c) at r + c*ld                            */
@@ -75,8 +80,11 @@ typedef enum {
 
 typedef enum { FG_ACT_NONE = 0, FG_ACT_RELU = 1 } fg_act;       /* relu(y) = max(y, 0)         */
 
-/* A matrix operand.  `im == NULL`: real matrix.  `im != NULL`: complex matrix in planar-split
- * storage, real parts at `re` and imaginary parts at `im`, both with the same layout and ld. */
+/* A matrix operand.  `im == NULL`: real matrix, or, with dtype FG_CF16 / FG_CF32, a complex matrix
+ * in interleaved storage (Section 5.4: the real and imaginary part of an element are adjacent;
+ * `re` points at the first real part; ld counts complex elements).  `im != NULL`: complex matrix
+ * in planar-split storage, real parts at `re` and imaginary parts at `im`, both with the same
+ * layout and ld. */
 typedef struct {
     void   *re;
     void   *im;
@@ -109,6 +117,9 @@ typedef struct {
  * Complex: if A or B has `im`, the product is complex; this version needs `im` on both A and B
  * (FG_ERR_UNSUPPORTED otherwise), D must have `im`, C (if given) must have `im`, alpha and beta
  * are real, `ep` must be NULL or empty, and diagonal operands are not combined with complex.
+ * Interleaved complex: A and B FG_CF16, D (and C if given) FG_CF32, all four interleaved (a mix
+ * of planar and interleaved matrices is FG_ERR_UNSUPPORTED); the same rules otherwise.  The parts
+ * are separated while tiles are copied into the LDS (the paper's split shared-memory layout).
  */
 fg_status fg_gemm(int64_t M, int64_t N, int64_t K, float alpha,
                   const fg_matrix *A, const fg_matrix *B,
@@ -198,10 +209,12 @@ fg_status fg_init(void);
  * Name of the kernel variant and block tile that fg_gemm would use for this problem, written as
  * a NUL-terminated string into `buf` (at most `buf_len` bytes), followed by "+splitk<n>" when K
  * is split into n ranges.  This is the "params" choice of Section 4.2.1, made here by an estimate
- * of the run time of every tile shape and split.  `variant` (fg_plan_variant) names the operator: real FP16, complex, dual or real BF16.
+ * of the run time of every tile shape and split.  `variant` (fg_plan_variant) names the operator: real FP16, planar complex, dual, real BF16 or
+ * interleaved complex.
  * Returns FG_OK, or the status fg_gemm would return for these sizes and layouts.
  */
-typedef enum { FG_PLAN_REAL = 0, FG_PLAN_COMPLEX = 1, FG_PLAN_DUAL = 2, FG_PLAN_REAL_BF16 = 3 } fg_plan_variant;
+typedef enum { FG_PLAN_REAL = 0, FG_PLAN_COMPLEX = 1, FG_PLAN_DUAL = 2, FG_PLAN_REAL_BF16 = 3,
+               FG_PLAN_COMPLEX_INTERLEAVED = 4 } fg_plan_variant;
 fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t layoutB,
                        int32_t layoutD, int32_t variant, char *buf, int32_t buf_len);
 

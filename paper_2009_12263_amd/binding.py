@@ -18,12 +18,12 @@ LIB_PATH = os.path.join(_PKG, "libflexgemm.so")
 
 FG_OK = 0
 FG_ERR_NULL, FG_ERR_SHAPE, FG_ERR_LAYOUT, FG_ERR_ALIGN, FG_ERR_UNSUPPORTED, FG_ERR_MODES, FG_ERR_LAUNCH = range(1, 8)
-FG_F16, FG_BF16, FG_F32 = 0, 1, 2
+FG_F16, FG_BF16, FG_F32, FG_CF16, FG_CF32 = 0, 1, 2, 3, 4
 FG_COL, FG_ROW, FG_DIAG, FG_ZERO = 0, 1, 2, 3
 FG_ACT_NONE, FG_ACT_RELU = 0, 1
 
 EXPORTS = ("fg_init", "fg_gemm", "fg_gemm_ex", "fg_gemm_dual", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan", "fg_probe_mfma")
-FG_PLAN_REAL, FG_PLAN_COMPLEX, FG_PLAN_DUAL, FG_PLAN_REAL_BF16 = 0, 1, 2, 3
+FG_PLAN_REAL, FG_PLAN_COMPLEX, FG_PLAN_DUAL, FG_PLAN_REAL_BF16, FG_PLAN_COMPLEX_INTERLEAVED = 0, 1, 2, 3, 4
 
 
 class fg_matrix(C.Structure):
@@ -99,7 +99,8 @@ class Matrix:
             m.dtype = self.dtype
         else:
             t = self.re if self.re is not None else self.im
-            m.dtype = {torch.float16: FG_F16, torch.bfloat16: FG_BF16, torch.float32: FG_F32}.get(
+            m.dtype = {torch.float16: FG_F16, torch.bfloat16: FG_BF16, torch.float32: FG_F32,
+                       torch.complex32: FG_CF16, torch.complex64: FG_CF32}.get(
                 t.dtype if t is not None else torch.float32, -1)
         m.layout, m.ld = self.layout, self.ld
         return m

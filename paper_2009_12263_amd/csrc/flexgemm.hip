@@ -49,6 +49,7 @@ struct Problem {
     int c_act;               // activation on loaded C
     uint16_t a_add, b_add;   // FP16 bit patterns of the addends on loaded A and B; ab_add: in use
     bool ab_add;
+    bool ilv;                // complex matrices in interleaved storage
 };
 
 // What to launch for a normalised problem: block tile, and into how many K ranges the product is
@@ -126,6 +127,7 @@ const fg::KernelEntry *select_kernel(const Problem &q, int *splits = nullptr) {
         const int t = choose_ctile(q.M, q.N);
         if (t < 0) return nullptr;
         const int v = (q.a_kc ? 2 : 0) + (q.b_kc ? 0 : 1);     // nn, nt, tn, tt
+        if (q.ilv) return &fg::kernel_table_cplx_il()[t * 4 + v];
         return &(q.dual ? fg::kernel_table_dual() : fg::kernel_table_cplx())[t * 4 + v];
     }
     const bool may_split = splits && !q.a_diag && !q.b_diag;
@@ -209,7 +211,8 @@ fg_status check_sizes(int64_t M, int64_t N, int64_t K) {
 
 fg_status check_input_matrix(const char *name, const fg_matrix *X, int64_t rows, int64_t cols) {
     if (!X) return fail(FG_ERR_NULL, "%s is NULL", name);
-    if (X->dtype != FG_F16 && X->dtype != FG_BF16) return fail(FG_ERR_LAYOUT, "%s must be FG_F16 or FG_BF16", name);
+    if (X->dtype != FG_F16 && X->dtype != FG_BF16 && X->dtype != FG_CF16) return fail(FG_ERR_LAYOUT, "%s must be FG_F16, FG_BF16 or FG_CF16", name);
+    if (X->dtype == FG_CF16 && (X->im || X->layout == FG_DIAG)) return fail(FG_ERR_LAYOUT, "%s: an interleaved complex matrix has no `im` plane and is not diagonal", name);
     if (X->layout != FG_COL && X->layout != FG_ROW && X->layout != FG_DIAG) return fail(FG_ERR_LAYOUT, "%s: layout %d is not valid for an input", name, X->layout);
     if (rows > 0 && cols > 0) {
         if (!X->re) return fail(FG_ERR_NULL, "%s->re is NULL", name);
@@ -224,7 +227,12 @@ fg_status check_input_matrix(const char *name, const fg_matrix *X, int64_t rows,
 }
 
 fg_status check_output_matrix(const char *name, const fg_matrix *X, int64_t rows, int64_t cols, bool need_im) {
-    if (X->dtype != FG_F32) return fail(FG_ERR_LAYOUT, "%s must be FG_F32", name);
+    if (X->dtype != FG_F32 && X->dtype != FG_CF32) return fail(FG_ERR_LAYOUT, "%s must be FG_F32 or FG_CF32", name);
+    if (X->dtype == FG_CF32) {
+        if (X->im) return fail(FG_ERR_LAYOUT, "%s: an interleaved complex matrix has no `im` plane", name);
+        need_im = false;
+        if (X->ld >= (1ll << 22)) return fail(FG_ERR_UNSUPPORTED, "%s: ld of an interleaved complex matrix must be below 2^22", name);
+    }
     if (X->layout != FG_COL && X->layout != FG_ROW) return fail(FG_ERR_LAYOUT, "%s: layout %d is not valid here", name, X->layout);
     if (rows > 0 && cols > 0) {
         if (!X->re) return fail(FG_ERR_NULL, "%s->re is NULL", name);
@@ -248,7 +256,13 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
     if (!D) return fail(FG_ERR_NULL, "D is NULL");
     if (A->dtype != B->dtype) return fail(FG_ERR_UNSUPPORTED, "A and B must have the same element type");
     const bool bf16 = A->dtype == FG_BF16;
-    const bool cplx = (A->im != nullptr) || (B->im != nullptr);
+    const bool ilv = A->dtype == FG_CF16;
+    if (ilv && (D->dtype != FG_CF32 || (C && C->layout != FG_ZERO && C->re && C->dtype != FG_CF32)))
+        return fail(FG_ERR_UNSUPPORTED, "interleaved complex A and B need interleaved complex (FG_CF32) C and D");
+    if (!ilv && (D->dtype == FG_CF32 || (C && C->dtype == FG_CF32 && C->layout != FG_ZERO && C->re)))
+        return fail(FG_ERR_UNSUPPORTED, "FG_CF32 C and D need FG_CF16 A and B");
+    if (ilv && (dual || lt)) return fail(FG_ERR_UNSUPPORTED, "interleaved complex products take no transforms and are not dual");
+    const bool cplx = ilv || (A->im != nullptr) || (B->im != nullptr);
     if (dual && !cplx) return fail(FG_ERR_NULL, "a dual-number product needs the dual planes (im) of A and B");
     if (bf16 && (cplx || A->layout == FG_DIAG || B->layout == FG_DIAG))
         return fail(FG_ERR_UNSUPPORTED, "FG_BF16 operands are supported for real, non-diagonal matrices only");
@@ -267,7 +281,7 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
         if (ep->bias && !aligned16(ep->bias)) return fail(FG_ERR_ALIGN, "bias must be 16-byte aligned");
     }
     if (cplx && has_ep) return fail(FG_ERR_UNSUPPORTED, "bias and activation are not defined for complex or dual products");
-    if (cplx && (!A->im || !B->im)) return fail(FG_ERR_UNSUPPORTED, "complex and dual products need the second plane of both A and B");
+    if (cplx && !ilv && (!A->im || !B->im)) return fail(FG_ERR_UNSUPPORTED, "complex and dual products need the second plane of both A and B");
     if (cplx && (A->layout == FG_DIAG || B->layout == FG_DIAG)) return fail(FG_ERR_UNSUPPORTED, "complex or dual diagonal operands are not supported");
 
     // transforms on loaded elements
@@ -289,6 +303,7 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
 
     const bool swap = (D->layout == FG_ROW);
     q.cplx = cplx;
+    q.ilv = ilv;
     q.c_act = c_act;
     q.ab_add = ab_add;
     q.a_add = swap ? b_add : a_add;
@@ -485,6 +500,7 @@ fg_status fg_init(void) {
         {fg::kernel_table_tn_xf(), fg::TILE_COUNT}, {fg::kernel_table_tt_xf(), fg::TILE_COUNT},
         {fg::kernel_table_diag(), fg::TILE_COUNT * 4},
         {fg::kernel_table_cplx(), fg::CTILE_COUNT * 4}, {fg::kernel_table_dual(), fg::CTILE_COUNT * 4},
+        {fg::kernel_table_cplx_il(), fg::CTILE_COUNT * 4},
     };
     for (auto &tb : tables)
         for (int i = 0; i < tb.n; ++i) {
@@ -518,7 +534,8 @@ static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const f
     auto span8 = [](bool kc, int64_t rows, int64_t k, int64_t ld) { int64_t s = kc ? (rows - 1) * ld + k : (k - 1) * ld + rows; return (s + 7) / 8 * 8; };
     p.a_span = q.K > 0 ? span8(q.a_kc, q.M, q.K, q.lda) : 0;
     p.b_span = q.K > 0 ? span8(q.b_kc, q.N, q.K, q.ldb) : 0;
-    if (p.a_span * 2 >= (1ll << 31) || p.b_span * 2 >= (1ll << 31)) return fail(FG_ERR_UNSUPPORTED, "A and B must each span less than 2 GiB");
+    const int64_t ab_elem_bytes = q.ilv ? 4 : 2;
+    if (p.a_span * ab_elem_bytes >= (1ll << 31) || p.b_span * ab_elem_bytes >= (1ll << 31)) return fail(FG_ERR_UNSUPPORTED, "A and B must each span less than 2 GiB");
     p.C = q.C; p.D = q.D; p.C_im = q.C_im; p.D_im = q.D_im; p.ldc = q.ldc; p.ldd = q.ldd;
     p.bias = q.bias; p.bias_dim = q.bias_dim; p.act = q.act; p.has_c = q.C != nullptr;
     p.c_act = q.c_act;
@@ -572,12 +589,13 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
     if (!ok_in(layoutA) || !ok_in(layoutB) || (layoutD != FG_COL && layoutD != FG_ROW))
         return fail(FG_ERR_LAYOUT, "plan query: A, B take FG_COL / FG_ROW / FG_DIAG, D takes FG_COL / FG_ROW");
     if (layoutA == FG_DIAG && layoutB == FG_DIAG) return fail(FG_ERR_UNSUPPORTED, "at most one of A and B may be diagonal");
-    if (variant < FG_PLAN_REAL || variant > FG_PLAN_REAL_BF16) return fail(FG_ERR_LAYOUT, "plan query: unknown variant %d", variant);
+    if (variant < FG_PLAN_REAL || variant > FG_PLAN_COMPLEX_INTERLEAVED) return fail(FG_ERR_LAYOUT, "plan query: unknown variant %d", variant);
     if (variant != FG_PLAN_REAL && (layoutA == FG_DIAG || layoutB == FG_DIAG))
         return fail(FG_ERR_UNSUPPORTED, "diagonal operands are supported for real FG_F16 products only");
     Problem q;
     memset(&q, 0, sizeof q);
-    q.cplx = variant == FG_PLAN_COMPLEX || variant == FG_PLAN_DUAL;
+    q.cplx = variant == FG_PLAN_COMPLEX || variant == FG_PLAN_DUAL || variant == FG_PLAN_COMPLEX_INTERLEAVED;
+    q.ilv = variant == FG_PLAN_COMPLEX_INTERLEAVED;
     q.dual = variant == FG_PLAN_DUAL;
     q.bf16 = variant == FG_PLAN_REAL_BF16;
     if (layoutD == FG_COL) {

@@ -79,7 +79,7 @@ struct GemmParams {
 // 32x32 MFMA accumulators.  A_KC / B_KC: operand is K-contiguous in memory (A row-major,
 // B column-major) rather than M/N-contiguous.  STAGES LDS buffers per operand form a ring over K.
 template <int BM_, int BN_, int BK_, int STAGES_, int WGM_, int WGN_, bool A_KC_, bool B_KC_, bool STRIDED_,
-          int DIAG_ = 0, int CPLX_ = 0, bool SPREAD_ = false, bool BF16_ = false, bool XFORM_ = false>
+          int DIAG_ = 0, int CPLX_ = 0, bool SPREAD_ = false, bool BF16_ = false, bool XFORM_ = false, bool ILV_ = false>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_;
     static constexpr int KSTEPS = BK / 16;                          // MFMA k-slices per tile
@@ -95,6 +95,9 @@ struct TileCfg {
     // XFORM: a constant is added to every element of A and of B after it is loaded (the fragment
     // registers are transformed just before the matrix instructions that consume them)
     static constexpr bool XFORM = XFORM_;
+    // ILV: complex operands and results are interleaved in global memory (real and imaginary part
+    // of an element adjacent); LDS and registers keep the planar form
+    static constexpr bool ILV = ILV_;
     static constexpr int DIAG = DIAG_;                              // 0: none, 1: A diagonal, 2: B diagonal
     // SPREAD: the refill loads of a ring buffer are issued one at a time between the MFMAs of two
     // k-slices (A's part in the slice after the buffer is retired, B's part in the next one)
@@ -124,6 +127,7 @@ struct TileCfg {
     static_assert(!(CPLX && (DIAG || STRIDED)), "complex products take plain matrices");
     static_assert(!SPREAD || STAGES >= 4 || KSTEPS >= 4, "spread refills need slack before the tile is needed");
     static_assert(!XFORM || (DIAG == 0 && CPLX == 0 && !BF16 && !STRIDED), "element-wise addition on A and B: plain real FP16 matrices");
+    static_assert(!ILV || (CPLX == 1 && STAGES == 2 && !SPREAD && !STRIDED && DIAG == 0), "interleaved storage: plain complex products");
 };
 
 // ---- swizzles -------------------------------------------------------------------------------
@@ -217,9 +221,15 @@ __device__ __forceinline__ T load_param(unsigned offset) {
 // One operand tile: R rows (M or N index) x BK k.  Each wave issues SLABS direct-to-LDS loads per
 // K step; a load writes 1024 consecutive LDS bytes (lane l writes bytes 16*l .. 16*l+15), so the
 // swizzle is applied by choosing which global chunk each lane fetches.
-template <int R, int BK, bool KC, int SLABS, bool STRIDED>
+// ES = 2: the operand is interleaved complex (two halves per element, Section 5.4's global
+// layout).  Such a tile cannot be copied by direct loads, which cannot separate the parts: it is
+// fetched into registers (fetch), split, and written into the two planes of the planar LDS
+// layout (commit), the conversion the paper places in the global-to-shared copy.
+template <int R, int BK, bool KC, int SLABS, bool STRIDED, int ES = 1>
 struct TileLoader {
+    static_assert(ES == 1 || (ES == 2 && !STRIDED), "interleaved elements: plain matrices only");
     uint32_t voff[SLABS];    // per-lane byte offset from the moving base (per slab)
+    u32x4 stage[ES == 2 ? SLABS : 1][2];   // ES == 2: the 32 fetched bytes of each slab's chunk
     const char *base;        // uniform: start of this block's panel at the current K step
     int64_t kstep_bytes;     // uniform: plain matrices, bytes to advance per K step
     int kn, kext[kMaxGroupModes];     // contraction: summed modes (count, extents, element strides)
@@ -240,10 +250,10 @@ struct TileLoader {
         ktile = 0;
         klim = BK;
         if constexpr (!STRIDED) {
-            base = (const char *)(ptr + (int64_t)row0 * rs);
-            kstep_bytes = BK * ks * 2;
+            base = (const char *)(ptr + (int64_t)row0 * rs * ES);
+            kstep_bytes = BK * ks * 2 * ES;
             kstep32 = (int)kstep_bytes;
-            int64_t left = (span - (int64_t)row0 * rs) * 2;          // the host keeps spans below 2 GiB
+            int64_t left = (span - (int64_t)row0 * rs) * 2 * ES;     // the host keeps spans below 2 GiB
             rem = left > 0 ? (int)left : 0;
             kdim = kdim_;
         } else {
@@ -287,7 +297,7 @@ struct TileLoader {
                     if (row0 + c * 8 >= rdim) off = kOutOfRange / 2;
                 }
             }
-            voff[s] = (uint32_t)(off * 2);
+            voff[s] = (uint32_t)(off * 2 * ES);
         }
     }
 
@@ -353,6 +363,43 @@ struct TileLoader {
 #pragma unroll
         for (int s = 0; s < SLABS; ++s) issue_slab(lds_tile, wave, s);
         advance();
+    }
+
+    // ES == 2: request the current K step's chunks (eight complex values, 32 bytes, per lane and
+    // slab) into registers and move on to the next K step ...
+    __device__ __forceinline__ void fetch() {
+        klim = kdim - ktile * BK;
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, rem > 0 ? rem : 0, 0x00020000);
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+            uint32_t v = voff[s];
+            if constexpr (KC) {
+                if (kchunk[s] >= klim) v = kOutOfRange;
+            }
+            stage[s][0] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, v, 0, 0));
+            stage[s][1] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, v, 16, 0));
+        }
+        advance();
+    }
+    // ... and, once they have arrived, split them into real and imaginary parts and write each
+    // part where a direct load of a planar tile would have put it.
+    __device__ __forceinline__ void commit(FG_LDS char *tile_re, FG_LDS char *tile_im, int wave) {
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+            u32x4 re, im;
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int w = 0; w < 2; ++w) {
+                    // words 2w and 2w+1 of half h hold (re, im) of two consecutive elements
+                    const uint32_t e0 = stage[s][h][2 * w], e1 = stage[s][h][2 * w + 1];
+                    re[2 * h + w] = __builtin_amdgcn_perm(e1, e0, 0x05040100u);
+                    im[2 * h + w] = __builtin_amdgcn_perm(e1, e0, 0x07060302u);
+                }
+            const uint32_t at = (uint32_t)(wave * SLABS + s) * 1024u + (threadIdx.x & 63) * 16u;
+            *(FG_LDS u32x4 *)(tile_re + at) = re;
+            *(FG_LDS u32x4 *)(tile_im + at) = im;
+        }
     }
 };
 
@@ -633,6 +680,56 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
     }
 }
 
+// Interleaved complex C and D (plain complex products): element (m, n) is the pair of floats at
+// 2 (m + n*ld), so a lane reads and writes 8 bytes per element and a half-wave covers 256
+// consecutive bytes.  alpha and beta are real.  Rows and columns past the matrix are masked as in
+// the edge path above; eight elements at a time.
+template <class Cfg, bool HAS_C>
+__device__ __forceinline__ void epilogue_interleaved(const GemmParams &p, floatx16 (&acc_re)[Cfg::TI][Cfg::TJ],
+                                                     floatx16 (&acc_im)[Cfg::TI][Cfg::TJ], int m_base, int n_base, int lane) {
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const int lm = lane & 31, lh = lane >> 5;
+    const int voff_c = (lm + 4 * lh * (int)p.ldc) * 8, voff_d = (lm + 4 * lh * (int)p.ldd) * 8;
+    const int ldc8 = (int)p.ldc * 8, ldd8 = (int)p.ldd * 8;
+    __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(HAS_C ? p.C + 2 * (m_base + (int64_t)n_base * p.ldc) : p.D), 0, 0x7fffffff, 0x00020000);
+    __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(p.D + 2 * (m_base + (int64_t)n_base * p.ldd), 0, 0x7fffffff, 0x00020000);
+#pragma unroll
+    for (int i = 0; i < Cfg::TI; ++i) {
+        const bool m_ok = m_base + 32 * i + lm < p.M;
+        const uint32_t vc = m_ok ? (uint32_t)voff_c : kOutOfRange, vd = m_ok ? (uint32_t)voff_d : kOutOfRange;
+#pragma unroll
+        for (int j = 0; j < Cfg::TJ; ++j) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                u32x2 cv[8];
+                if constexpr (HAS_C) {
+#pragma unroll
+                    for (int r8 = 0; r8 < 8; ++r8) {
+                        const int r = 8 * h + r8;
+                        const bool n_ok = n_base + 32 * j + 8 * (r >> 2) + (r & 3) + 4 * lh < p.N;
+                        cv[r8] = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(
+                            rc, n_ok ? vc : kOutOfRange, 256 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc8, 2));
+                    }
+                }
+#pragma unroll
+                for (int r8 = 0; r8 < 8; ++r8) {
+                    const int r = 8 * h + r8;
+                    const bool n_ok = n_base + 32 * j + 8 * (r >> 2) + (r & 3) + 4 * lh < p.N;
+                    float yr = p.alpha * acc_re[i][j][r], yi = p.alpha * acc_im[i][j][r];
+                    if constexpr (HAS_C) {
+                        yr += p.beta * __builtin_bit_cast(float, (uint32_t)cv[r8][0]);
+                        yi += p.beta * __builtin_bit_cast(float, (uint32_t)cv[r8][1]);
+                    }
+                    u32x2 out = {__builtin_bit_cast(uint32_t, yr), __builtin_bit_cast(uint32_t, yi)};
+                    __builtin_amdgcn_raw_buffer_store_b64(out, rd, n_ok ? vd : kOutOfRange,
+                                                          256 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd8, 2);
+                }
+            }
+        }
+    }
+}
+
 // ---- the kernel -----------------------------------------------------------------------------------
 // Workgroups are persistent: workgroup b computes tiles b, b + gridDim.x, ... so that the first
 // loads of the next tile are in flight while the current tile is stored.
@@ -693,8 +790,9 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
     FG_LDS char *lds_a = smem;
     FG_LDS char *lds_b = smem + Cfg::A_BYTES;
 
-    using PlainA = TileLoader<BM, BK, Cfg::A_KC, Cfg::A_SLABS, Cfg::STRIDED>;
-    using PlainB = TileLoader<BN, BK, Cfg::B_KC, Cfg::B_SLABS, Cfg::STRIDED>;
+    using PlainA = TileLoader<BM, BK, Cfg::A_KC, Cfg::A_SLABS, Cfg::STRIDED, Cfg::ILV ? 2 : 1>;
+    using PlainB = TileLoader<BN, BK, Cfg::B_KC, Cfg::B_SLABS, Cfg::STRIDED, Cfg::ILV ? 2 : 1>;
+    constexpr int NLOADERS = Cfg::ILV ? 1 : P;      // an interleaved operand is one array, not one per plane
     using LoaderA = typename std::conditional<Cfg::DIAG == 1, DiagLoader<BM, BK, Cfg::A_SLABS>, PlainA>::type;
     using LoaderB = typename std::conditional<Cfg::DIAG == 2, DiagLoader<BN, BK, Cfg::B_SLABS>, PlainB>::type;
     LoaderA la[P];
@@ -736,7 +834,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
         const _Float16 *ap[2] = {tp.A, tp.A_im};
         const _Float16 *bp[2] = {tp.B, tp.B_im};
 #pragma unroll
-        for (int q = 0; q < P; ++q) {
+        for (int q = 0; q < NLOADERS; ++q) {
             if constexpr (Cfg::DIAG == 1) la[q].init(ap[q], m0, tp.M < tp.K ? tp.M : tp.K, wave, lane);
             else la[q].init(ap[q], m0, wave, lane, tp.a_rs, tp.a_ks, tp.a_m, tp.a_k, tp.a_span, tp.K, tp.M);
             if constexpr (Cfg::DIAG == 2) lb[q].init(bp[q], n0, tp.N < tp.K ? tp.N : tp.K, wave, lane);
@@ -748,10 +846,17 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
 #pragma unroll
         for (int st = 0; st < S; ++st)
             if (st < nkt) {
+                if constexpr (Cfg::ILV) {
+                    la[0].fetch();
+                    lb[0].fetch();
+                    la[0].commit(lds_a + st * Cfg::A_TILE_BYTES, lds_a + Cfg::A_PLANE_BYTES + st * Cfg::A_TILE_BYTES, wave);
+                    lb[0].commit(lds_b + st * Cfg::B_TILE_BYTES, lds_b + Cfg::B_PLANE_BYTES + st * Cfg::B_TILE_BYTES, wave);
+                } else {
 #pragma unroll
-                for (int q = 0; q < P; ++q) {
-                    la[q].issue(lds_a + q * Cfg::A_PLANE_BYTES + st * Cfg::A_TILE_BYTES, wave);
-                    lb[q].issue(lds_b + q * Cfg::B_PLANE_BYTES + st * Cfg::B_TILE_BYTES, wave);
+                    for (int q = 0; q < P; ++q) {
+                        la[q].issue(lds_a + q * Cfg::A_PLANE_BYTES + st * Cfg::A_TILE_BYTES, wave);
+                        lb[q].issue(lds_b + q * Cfg::B_PLANE_BYTES + st * Cfg::B_TILE_BYTES, wave);
+                    }
                 }
             }
     };
@@ -789,6 +894,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                 for (int j = 0; j < TJ; ++j) bf[q][0][j] = fb.read(lds_b + q * Cfg::B_PLANE_BYTES, j, 0);
             }
 
+            [[maybe_unused]] bool fetched = false;      // ILV: a K step is waiting in registers
             // one K tile; MORE: another tile follows (publish it, refill the ring, prefetch its
             // first fragments)
             auto tile_body = [&](int kt, auto more_tag) {
@@ -808,10 +914,22 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                     //   slice 0: B's part of tile kt-1+S into the buffer of tile kt-1
                     bool refill_a = false, refill_b = false;
                     if (last && MORE) {
+                        if constexpr (Cfg::ILV) {
+                            // the K step fetched into registers one tile ago goes into the buffer
+                            // that tile's barrier retired: it is published by the barrier below
+                            if (fetched) {
+                                la[0].commit(lds_a + nxt * Cfg::A_TILE_BYTES, lds_a + Cfg::A_PLANE_BYTES + nxt * Cfg::A_TILE_BYTES, wave);
+                                lb[0].commit(lds_b + nxt * Cfg::B_TILE_BYTES, lds_b + Cfg::B_PLANE_BYTES + nxt * Cfg::B_TILE_BYTES, wave);
+                            }
+                        }
                         // tile kt+1 has landed (for this wave) and all of this wave's reads of tile
                         // kt have returned; after the barrier both hold for every wave
                         if (kt + S < nkt) wait_tile<(S - 2) * L>(); else wait_tile<0>();
                         __builtin_amdgcn_s_barrier();
+                        if constexpr (Cfg::ILV) {
+                            fetched = kt + S < nkt;
+                            if (fetched) { la[0].fetch(); lb[0].fetch(); }
+                        } else
                         if (kt + S < nkt) {
                             if constexpr (Cfg::SPREAD) {
                                 refill_a = true;
@@ -944,9 +1062,14 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
         {
             GemmParams ep = load_param<GemmParams>(0);
             if constexpr (Cfg::SPLITK) ep.D += (int64_t)sp0 * ep.split_stride;
+            if constexpr (Cfg::ILV) {
+                if (ep.has_c) epilogue_interleaved<Cfg, true>(ep, acc[0], acc[1], m_base, n_base, lane);
+                else epilogue_interleaved<Cfg, false>(ep, acc[0], acc[1], m_base, n_base, lane);
+            } else {
             if (ep.has_c) epilogue<Cfg, true>(ep, ep.C, ep.D, acc[0], m_base, n_base, lane);
             else epilogue<Cfg, false>(ep, ep.C, ep.D, acc[0], m_base, n_base, lane);
-            if constexpr (Cfg::CPLX) {
+            }
+            if constexpr (Cfg::CPLX && !Cfg::ILV) {
                 if (ep.has_c) epilogue<Cfg, true>(ep, ep.C_im, ep.D_im, acc[1], m_base, n_base, lane);
                 else epilogue<Cfg, false>(ep, ep.C_im, ep.D_im, acc[1], m_base, n_base, lane);
             }

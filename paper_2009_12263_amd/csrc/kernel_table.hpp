@@ -36,6 +36,8 @@ const KernelEntry *kernel_table_tt_xf();
 const KernelEntry *kernel_table_diag();
 // Planar complex: index ctile * 4 + {nn, nt, tn, tt}; ctile 0: 256x128, 1: 128x128, 2: 64x64.
 const KernelEntry *kernel_table_cplx();
+// Interleaved complex (real and imaginary part adjacent in A, B, C and D): same indexing.
+const KernelEntry *kernel_table_cplx_il();
 // Planar dual numbers (eps^2 = 0): same indexing as the complex table.
 const KernelEntry *kernel_table_dual();
 enum { CTILE_COUNT = 3 };
@@ -88,6 +90,12 @@ inline int entry_index(int tile, bool strided) { return tile * 2 + (strided ? 1 
         };                                                                                         \
         return t;                                                                                  \
     }
+
+#define FG_CFG_IL(BM, BN, BK, ST, WGM, WGN, AKC, BKC) TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, false, 0, 1, false, false, false, true>
+#define FG_ENTRY_IL(BM, BN, BK, ST, WGM, WGN, AKC, BKC, NAME)                                      \
+    { gemm_kernel<FG_CFG_IL(BM, BN, BK, ST, WGM, WGN, AKC, BKC)>, NAME, BM, BN,                    \
+      FG_CFG_IL(BM, BN, BK, ST, WGM, WGN, AKC, BKC)::NTHREADS,                                     \
+      FG_CFG_IL(BM, BN, BK, ST, WGM, WGN, AKC, BKC)::LDS_BYTES }
 
 #define FG_ENTRY_X(BM, BN, BK, ST, WGM, WGN, AKC, BKC, DG, CX, NAME)                                \
     { gemm_kernel<TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, false, DG, CX>>, NAME, BM, BN,       \

@@ -200,9 +200,10 @@ def run_diag_case(M, N, K, side="A", other_layout=fg.FG_COL, ld_layout=fg.FG_COL
 
 def run_cgemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alpha=1.0, beta=1.0, with_c=True,
                    ints=False, pad=0, config=4, samples: Optional[int] = None, device="cuda", seed=W.DEFAULT_SEED,
-                   dual=False):
+                   dual=False, interleaved=False):
     """Planar-split complex (or, with ``dual``, dual-number) D = alpha A B + beta C; the two planes
-    are separate arrays."""
+    are separate arrays.  ``interleaved``: the same numbers stored with real and imaginary parts
+    adjacent (FG_CF16 inputs, FG_CF32 C and D)."""
     Ar, lda = make_operand(M, K, la, W.stream_id(config, "A"), device, ints, pad, seed)
     Ai, _ = make_operand(M, K, la, W.stream_id(config, "A_im"), device, ints, pad, seed)
     Br, ldb = make_operand(K, N, lb, W.stream_id(config, "B"), device, ints, pad, seed)
@@ -213,9 +214,21 @@ def run_cgemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alp
     Ci = make_f32(ldc * other, W.stream_id(config, "C_im"), device, ints, seed) if with_c else None
     Dr = torch.full((ldc * other,), float("nan"), dtype=torch.float32, device=device)
     Di = torch.full((ldc * other,), float("nan"), dtype=torch.float32, device=device)
-    call = fg.fg_gemm_dual if dual else fg.fg_gemm
-    call(M, N, K, alpha, fg.Matrix(Ar, la, lda, im=Ai), fg.Matrix(Br, lb, ldb, im=Bi), beta,
-         fg.Matrix(Cr, ld_layout, ldc, im=Ci) if with_c else None, fg.Matrix(Dr, ld_layout, ldc, im=Di))
+    if interleaved:
+        weave = lambda x, y: torch.stack((x, y), dim=-1).reshape(-1).contiguous()
+        Aw, Bw = weave(Ar, Ai), weave(Br, Bi)
+        Cw = weave(Cr, Ci) if with_c else None
+        Dw = torch.full((2 * ldc * other,), float("nan"), dtype=torch.float32, device=device)
+        fg.fg_gemm(M, N, K, alpha, fg.Matrix(Aw, la, lda, dtype=fg.FG_CF16), fg.Matrix(Bw, lb, ldb, dtype=fg.FG_CF16), beta,
+                   fg.Matrix(Cw, ld_layout, ldc, dtype=fg.FG_CF32) if with_c else None, fg.Matrix(Dw, ld_layout, ldc, dtype=fg.FG_CF32))
+        torch.cuda.synchronize()
+        Dr, Di = Dw[0::2].contiguous(), Dw[1::2].contiguous()
+        if ldc > lead:
+            assert torch.isnan(Dr.reshape(other, ldc)[:, lead:]).all() and torch.isnan(Di.reshape(other, ldc)[:, lead:]).all(), "padding of D was written"
+    else:
+        call = fg.fg_gemm_dual if dual else fg.fg_gemm
+        call(M, N, K, alpha, fg.Matrix(Ar, la, lda, im=Ai), fg.Matrix(Br, lb, ldb, im=Bi), beta,
+             fg.Matrix(Cr, ld_layout, ldc, im=Ci) if with_c else None, fg.Matrix(Dr, ld_layout, ldc, im=Di))
     torch.cuda.synchronize()
     view = lambda t: (np16(t).reshape(other, ldc)[:, :lead].T if ld_layout == fg.FG_COL else np16(t).reshape(other, ldc)[:, :lead])
     at = sample_positions(M, N, samples, seed=M * 3 + N * 5 + K) if samples is not None else None
@@ -224,7 +237,7 @@ def run_cgemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alp
     gr, gi = view(Dr), view(Di)
     if at is not None:
         gr, gi = gr[at[0], at[1]], gi[at[0], at[1]]
-    what = ("dual" if dual else "complex") + " gemm M=%d N=%d K=%d A=%d B=%d D=%d ints=%s" % (M, N, K, la, lb, ld_layout, ints)
+    what = ("dual" if dual else "interleaved complex" if interleaved else "complex") + " gemm M=%d N=%d K=%d A=%d B=%d D=%d ints=%s" % (M, N, K, la, lb, ld_layout, ints)
     w1 = compare(gr, r["D"], r["G"], K if dual else 2 * K, ints, what + " (first plane)")
     w2 = compare(gi, r["D_im"], r["G_im"], 2 * K, ints, what + " (second plane)")
     return max(w1, w2)

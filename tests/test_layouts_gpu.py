@@ -75,3 +75,35 @@ def test_dual_numbers_all_layouts(la, lb):
 def test_dual_4096():
     say("dual 4096 floats"); run_cgemm_case(4096, 4096, 4096, samples=4096, dual=True)
     say("dual 4096 ints"); run_cgemm_case(4096, 4096, 4096, ints=True, samples=4096, dual=True)
+
+
+@pytest.mark.parametrize("la,lb", list(itertools.product(LAYOUTS, LAYOUTS)))
+def test_interleaved_complex_all_layouts(la, lb):
+    """Complex matrices with real and imaginary parts adjacent in memory (Section 5.4's global
+    layout); the oracle is fed the same numbers in planar form, which its own pins tie to the
+    interleaved form.  Exact on integers for every tile shape, edge tiles, a K tail, no C, and a
+    row-major result."""
+    for (M, N, K) in [(64, 64, 64), (256, 128, 192), (384, 512, 128), (100, 75, 40)]:
+        say("interleaved ints M=%d N=%d K=%d la=%d lb=%d" % (M, N, K, la, lb))
+        run_cgemm_case(M, N, K, la, lb, ints=True, pad=8, interleaved=True)
+    say("interleaved floats 512"); run_cgemm_case(512, 512, 512, la, lb, alpha=0.5, beta=2.0, interleaved=True)
+    say("interleaved row-major D"); run_cgemm_case(300, 513, 136, la, lb, ld_layout=fg.FG_ROW, alpha=0.5, beta=1.5, interleaved=True)
+    say("interleaved no C"); run_cgemm_case(256, 384, 128, la, lb, with_c=False, ints=True, interleaved=True)
+
+
+def test_interleaved_complex_4096():
+    say("interleaved 4096 floats"); run_cgemm_case(4096, 4096, 4096, samples=4096, interleaved=True)
+    say("interleaved 2048x4096x256 ints, every entry"); run_cgemm_case(2048, 4096, 256, ints=True, interleaved=True)
+
+
+def test_interleaved_and_planar_matrices_are_not_mixed():
+    import torch
+    H = torch.zeros(2 * 64 * 64, dtype=torch.float16, device="cuda")
+    F = torch.zeros(2 * 64 * 64, dtype=torch.float32, device="cuda")
+    il = lambda t, d: fg.Matrix(t, fg.FG_COL, 64, dtype=d)
+    kw = dict(raise_on_error=False)
+    assert fg.fg_gemm(64, 64, 64, 1.0, il(H, fg.FG_CF16), il(H, fg.FG_CF16), 0.0, None, fg.Matrix(F, fg.FG_COL, 64, im=F), **kw) == fg.FG_ERR_UNSUPPORTED
+    assert fg.fg_gemm(64, 64, 64, 1.0, il(H, fg.FG_CF16), fg.Matrix(H, fg.FG_COL, 64), 0.0, None, il(F, fg.FG_CF32), **kw) == fg.FG_ERR_UNSUPPORTED
+    assert fg.fg_gemm(64, 64, 64, 1.0, fg.Matrix(H, fg.FG_COL, 64), fg.Matrix(H, fg.FG_COL, 64), 0.0, None, il(F, fg.FG_CF32), **kw) == fg.FG_ERR_UNSUPPORTED
+    assert fg.fg_gemm(64, 64, 64, 1.0, il(H, fg.FG_CF16), il(H, fg.FG_CF16), 0.0, None, il(F, fg.FG_CF32), act=fg.FG_ACT_RELU, **kw) == fg.FG_ERR_UNSUPPORTED
+    assert fg.fg_gemm(64, 64, 64, 1.0, fg.Matrix(H, fg.FG_COL, 64, im=H, dtype=fg.FG_CF16), il(H, fg.FG_CF16), 0.0, None, il(F, fg.FG_CF32), **kw) == fg.FG_ERR_LAYOUT
