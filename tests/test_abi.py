@@ -91,6 +91,25 @@ def test_plan_names_follow_sizes_and_layouts():
         fg.fg_gemm_plan(128, 64, 60)
 
 
+def test_planner_splits_k_only_for_small_outputs_with_long_k(monkeypatch):
+    monkeypatch.delenv("FG_FORCE_SPLIT", raising=False)
+    monkeypatch.delenv("FG_FORCE_TILE", raising=False)
+    for shape in [(8192, 8192, 8192), (4096, 4096, 4096), (2048, 2048, 2048), (1024, 1024, 1024), (65536, 256, 256), (256, 256, 256)]:
+        assert "+splitk" not in fg.fg_gemm_plan(*shape), shape
+    for shape in [(512, 512, 8192), (256, 256, 65536), (64, 64, 32768), (1024, 1024, 8192), (128, 4096, 16384)]:
+        assert "+splitk" in fg.fg_gemm_plan(*shape), shape
+    # every share of K keeps at least four K tiles, and the partial products fit the workspace
+    name = fg.fg_gemm_plan(64, 64, 1024)
+    assert "+splitk" not in name or int(name.split("+splitk")[1]) <= 4
+    assert "+splitk" not in fg.fg_gemm_plan(4096, 4096, 65536)          # output alone fills the GPU
+    # complex, dual and diagonal products are never split
+    assert "+splitk" not in fg.fg_gemm_plan(256, 256, 65536, variant=fg.FG_PLAN_COMPLEX)
+    assert "+splitk" not in fg.fg_gemm_plan(256, 256, 65536, fg.FG_DIAG, fg.FG_COL)
+    assert fg.fg_gemm_plan(4096, 4096, 4096, variant=fg.FG_PLAN_COMPLEX_INTERLEAVED) == "cgemm_il_nn_256x128x32"
+    assert fg.fg_gemm_plan(4096, 4096, 4096, variant=fg.FG_PLAN_DUAL) == "dgemm_nn_256x128x32"
+    assert fg.fg_gemm_plan(8192, 8192, 8192, variant=fg.FG_PLAN_REAL_BF16) == "gemm_bf16_nn_256x256x64"
+
+
 def contract_status(mA, sA, mB, sB, mC, sC, ext, pa=0x1000, pb=0x2000, pc=0x3000):
     import torch
     return fg.fg_contract(mA, sA, FakeTensor(pa, torch.float16), mB, sB, FakeTensor(pb, torch.float16), mC, sC, None,
