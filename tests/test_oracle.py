@@ -256,6 +256,8 @@ CASES = [
     ({0: 2, 1: 3, 2: 2, 3: 3, 4: 4, 5: 2}, [0, 4, 1, 5], [3, 5, 2, 4], [0, 1, 2, 3]),  # two contracted modes
     ({0: 3, 1: 2, 2: 4, 3: 3}, [1, 3, 0], [3, 2], [0, 1, 2]),              # D_abc = A_bda B_dc (Section 5.5)
     ({0: 3, 1: 4}, [0, 1], [1], [0]),                                       # matrix-vector
+    ({0: 3, 1: 2, 2: 4, 3: 3, 4: 2}, [0, 3, 4], [3, 1, 4], [0, 1, 4]),      # batch mode 4: in A, B and C
+    ({0: 3, 1: 2, 3: 3, 4: 2, 5: 3}, [4, 0, 3, 5], [5, 3, 1, 4], [4, 0, 5, 1]),  # two batch modes, interleaved
 ]
 
 
