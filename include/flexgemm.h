@@ -168,17 +168,18 @@ fg_status fg_gemm_dual(int64_t M, int64_t N, int64_t K, float alpha,
  *                                                                     (Sections 4.1 and 5.5)
  * A mode is an integer label; `mode_labels[n_modes]` lists the distinct labels and
  * `mode_extents[n_modes]` their extents.  modesX[nX] / stridesX[nX] give, for tensor X, its
- * modes in storage order and the element stride of each.  Every label must appear in exactly
- * two of {A, B, C}: modes shared by A and C become GEMM rows, modes shared by B and C become
- * GEMM columns, modes shared by A and B are summed over (no batch and no trace modes:
- * FG_ERR_MODES).  A, B are FP16 device tensors, Cin (NULL iff beta term absent) and Cout FP32;
- * Cout may equal Cin.  The tensors are never transposed in memory: the mode-to-tile mapping
- * happens while tiles are loaded and while the result is stored.
- * Requirements of this version (else FG_ERR_UNSUPPORTED): in each of A and B some mode has
- * stride 1 and an extent that is a multiple of 8; the summed mode that is walked fastest (A's
- * unit-stride mode if it is summed, else B's, else the first summed mode of A) has an extent that
- * is a multiple of 64; at most 4 modes of extent above 1 per group; A, B and C each span less than
- * 2 GiB; no negative strides.  The row and column extents are otherwise arbitrary: tiles that hang
+ * modes in storage order and the element stride of each.  Every label that is used must appear
+ * in two or in all three of {A, B, C}: modes shared by A and C become GEMM rows, modes shared by
+ * B and C become GEMM columns, modes shared by A and B are summed over, and modes in all three
+ * are batch modes (an independent contraction per index; FG_ERR_MODES for a mode in one tensor
+ * only or listed twice in a tensor).  A, B are FP16 device tensors, Cin (NULL iff beta term
+ * absent) and Cout FP32; Cout may equal Cin.  The tensors are never transposed in memory: the
+ * mode-to-tile mapping happens while tiles are loaded and while the result is stored.
+ * Requirements of this version (else FG_ERR_UNSUPPORTED): in each of A and B some mode that is
+ * not a batch mode has stride 1 and an extent that is a multiple of 8; the summed mode that is
+ * walked fastest (A's unit-stride mode if it is summed, else B's, else the first summed mode of
+ * A) has an extent that is a multiple of 64; at most 4 modes of extent above 1 per group; A, B
+ * and C each span less than 2 GiB; at most 2^20 batch indices; no negative strides.  The row and column extents are otherwise arbitrary: tiles that hang
  * over the merged row or column extent are predicated like the edge tiles of fg_gemm.
  */
 fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA, const void *A,

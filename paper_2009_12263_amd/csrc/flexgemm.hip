@@ -74,7 +74,7 @@ const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
 // share a unit and one for a workgroup that has a unit to itself.  Edge tiles are predicated, so
 // a tile need not divide the problem.  K is split only when the output has too few tiles to fill
 // the GPU and K is long (may_split: plain real products).
-Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_smallest = true) {
+Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_smallest = true, int64_t batches = 1) {
     static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64};
     static const int bn[fg::TILE_COUNT] = {256, 128, 128, 64};
     static const int per_cu[fg::TILE_COUNT] = {1, 1, 2, 4};
@@ -93,7 +93,7 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_sma
     const int ntypes = allow_smallest ? fg::TILE_COUNT : fg::TILE_COUNT - 1;
     for (int t = 0; t < ntypes; ++t) {
         if (force_tile >= 0 && t != force_tile) continue;
-        const int64_t tiles = ((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]);
+        const int64_t tiles = ((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]) * batches;
         const int64_t slots = (int64_t)kNumCU * per_cu[t];
         auto legal = [&](int S) { return S == 1 || (may_split && S <= nk && (int64_t)S * ldw * N * 4 <= kWorkspaceBytes); };
         const int forced = (force_split >= 1 && legal(force_split)) ? force_split : (force_split >= 1 ? 1 : 0);
@@ -193,7 +193,7 @@ fg_status launch(const fg::KernelEntry &k, const fg::GemmParams &p, hipStream_t 
     int per_cu = 0;
     if (fg_status st = prepare(k, dev, per_cu)) return st;
     // Persistent workgroups: as many as the GPU holds at once; each walks tiles b, b + grid, ...
-    const int ntiles = p.tiles_m * p.tiles_n * (p.splits > 1 ? p.splits : 1);
+    const int ntiles = p.tiles_m * p.tiles_n * (p.splits > 1 ? p.splits : 1) * (p.batches > 1 ? p.batches : 1);
     const int resident = per_cu * kNumCU;
     dim3 grid((unsigned)(ntiles < resident ? ntiles : resident)), block((unsigned)k.threads);
     hipLaunchKernelGGL(k.fn, grid, block, (size_t)k.lds_bytes, stream, p);
@@ -344,7 +344,8 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
 // (the (ba) -> m convention of the paper's layout listing).  No data moves: the kernel computes
 // element offsets from these groups while it loads tiles and stores results.
 struct Contraction {
-    int64_t M, N, K;
+    int64_t M, N, K, batches;
+    fg::ModeGroup a_b, b_b, c_b;
     const void *A, *B;
     bool a_kc, b_kc;
     fg::ModeGroup a_m, a_k, b_n, b_k, c_m, c_n;
@@ -389,48 +390,56 @@ fg_status plan_contraction(int32_t nA, const int32_t *modesA, const int64_t *str
     for (int i = 0; i < n_modes; ++i) {
         int cnt = (find_mode(ta, labels[i]) >= 0) + (find_mode(tb, labels[i]) >= 0) + (find_mode(tc, labels[i]) >= 0);
         if (cnt == 0) continue;
-        if (cnt != 2) return fail(FG_ERR_MODES, "mode %d appears in %d of A, B, C; exactly two are required (no batch or reduction modes)", labels[i], cnt);
+        if (cnt == 1) return fail(FG_ERR_MODES, "mode %d appears in only one of A, B, C (no reduction or broadcast modes)", labels[i]);
         if (extents[i] == 0) any_zero = true;
     }
-    c.M = c.N = 0; c.K = 0;
+    c.M = c.N = 0; c.K = 0; c.batches = 1;
     if (any_zero) return FG_OK;               // an empty tensor: nothing to compute
     if (!A || !B || !Cout) return fail(FG_ERR_NULL, "A, B or Cout is NULL");
     if (!aligned16(A) || !aligned16(B) || !aligned16(Cout) || (Cin && !aligned16(Cin))) return fail(FG_ERR_ALIGN, "tensor base pointers must be 16-byte aligned");
 
     // Lanes of the result run along GEMM rows, so C's unit-stride mode should be a row mode:
-    // exchange the roles of A and B when it belongs to B.
+    // exchange the roles of A and B when it belongs to B only.
     int c_unit = -1;
     for (int i = 0; i < nC; ++i) { int64_t e; extent_of(modesC[i], e); if (stridesC[i] == 1 && e > 1) { c_unit = modesC[i]; break; } }
-    if (c_unit >= 0 && find_mode(tb, c_unit) >= 0) { TensorView t = ta; ta = tb; tb = t; const void *q = A; A = B; B = q; }
+    if (c_unit >= 0 && find_mode(tb, c_unit) >= 0 && find_mode(ta, c_unit) < 0) { TensorView t = ta; ta = tb; tb = t; const void *q = A; A = B; B = q; }
     c.A = A; c.B = B;
+    auto in_a = [&](int32_t l) { return find_mode(ta, l) >= 0; };
+    auto in_b = [&](int32_t l) { return find_mode(tb, l) >= 0; };
+    auto in_c = [&](int32_t l) { return find_mode(tc, l) >= 0; };
+    auto is_row = [&](int32_t l) { return in_a(l) && in_c(l) && !in_b(l); };
+    auto is_col = [&](int32_t l) { return in_b(l) && in_c(l) && !in_a(l); };
+    auto is_sum = [&](int32_t l) { return in_a(l) && in_b(l) && !in_c(l); };
+    auto is_batch = [&](int32_t l) { return in_a(l) && in_b(l) && in_c(l); };
 
     auto unit_mode = [&](const TensorView &t) {
         int best = -1;
         for (int i = 0; i < t.n; ++i) {
             int64_t e; extent_of(t.modes[i], e);
-            if (t.strides[i] == 1 && e % 8 == 0 && e > 0) { best = t.modes[i]; break; }
+            if (t.strides[i] == 1 && e % 8 == 0 && e > 0 && !is_batch(t.modes[i])) { best = t.modes[i]; break; }
         }
         return best;
     };
     const int ua = unit_mode(ta), ub = unit_mode(tb);
-    if (ua < 0 || ub < 0) return fail(FG_ERR_UNSUPPORTED, "A and B each need a mode with stride 1 and an extent that is a multiple of 8");
-    c.a_kc = find_mode(tb, ua) >= 0;          // A's contiguous mode is summed over
-    c.b_kc = find_mode(ta, ub) >= 0;
+    if (ua < 0 || ub < 0) return fail(FG_ERR_UNSUPPORTED, "A and B each need a row, column or summed mode with stride 1 and an extent that is a multiple of 8");
+    c.a_kc = is_sum(ua);                      // A's contiguous mode is summed over
+    c.b_kc = is_sum(ub);
     if (c.a_kc && c.b_kc && ua != ub) return fail(FG_ERR_UNSUPPORTED, "A and B are contiguous along different summed modes (%d and %d)", ua, ub);
 
     // order of the modes inside each merged index
-    int32_t m_modes[16], n_modes_[16], k_modes[16];
-    int nm = 0, nn = 0, nkk = 0;
+    int32_t m_modes[16], n_modes_[16], k_modes[16], b_modes[16];
+    int nm = 0, nn = 0, nkk = 0, nb = 0;
     auto push_unique = [](int32_t *arr, int &n, int32_t label) { for (int i = 0; i < n; ++i) if (arr[i] == label) return; arr[n++] = label; };
     if (!c.a_kc) push_unique(m_modes, nm, ua);
-    else if (c_unit >= 0 && find_mode(ta, c_unit) >= 0) push_unique(m_modes, nm, c_unit);
-    for (int i = 0; i < tc.n; ++i) if (find_mode(ta, tc.modes[i]) >= 0) push_unique(m_modes, nm, tc.modes[i]);
+    else if (c_unit >= 0 && is_row(c_unit)) push_unique(m_modes, nm, c_unit);
+    for (int i = 0; i < tc.n; ++i) if (is_row(tc.modes[i])) push_unique(m_modes, nm, tc.modes[i]);
     if (!c.b_kc) push_unique(n_modes_, nn, ub);
-    for (int i = 0; i < tc.n; ++i) if (find_mode(tb, tc.modes[i]) >= 0) push_unique(n_modes_, nn, tc.modes[i]);
+    for (int i = 0; i < tc.n; ++i) if (is_col(tc.modes[i])) push_unique(n_modes_, nn, tc.modes[i]);
     if (c.a_kc) push_unique(k_modes, nkk, ua);
     else if (c.b_kc) push_unique(k_modes, nkk, ub);
-    for (int i = 0; i < ta.n; ++i) if (find_mode(tb, ta.modes[i]) >= 0) push_unique(k_modes, nkk, ta.modes[i]);
-    if (nm > fg::kMaxGroupModes || nn > fg::kMaxGroupModes || nkk > fg::kMaxGroupModes)
+    for (int i = 0; i < ta.n; ++i) if (is_sum(ta.modes[i])) push_unique(k_modes, nkk, ta.modes[i]);
+    for (int i = 0; i < tc.n; ++i) if (is_batch(tc.modes[i])) push_unique(b_modes, nb, tc.modes[i]);
+    if (nm > fg::kMaxGroupModes || nn > fg::kMaxGroupModes || nkk > fg::kMaxGroupModes || nb > fg::kMaxGroupModes)
         return fail(FG_ERR_UNSUPPORTED, "at most %d modes per merged index", fg::kMaxGroupModes);
     if (nkk == 0) return fail(FG_ERR_UNSUPPORTED, "an outer product (no summed mode) is not supported");
 
@@ -457,6 +466,8 @@ fg_status plan_contraction(int32_t nA, const int32_t *modesA, const int64_t *str
     fill(c.a_m, m_modes, nm, ta, c.M); fill(c.c_m, m_modes, nm, tc, t1);
     fill(c.b_n, n_modes_, nn, tb, c.N); fill(c.c_n, n_modes_, nn, tc, t2);
     fill(c.a_k, k_modes, nkk, ta, c.K); fill(c.b_k, k_modes, nkk, tb, t1);
+    fill(c.a_b, b_modes, nb, ta, c.batches); fill(c.b_b, b_modes, nb, tb, t1); fill(c.c_b, b_modes, nb, tc, t2);
+    if (nb == 0) c.batches = 1;
     if (nm == 0) c.M = 1;
     if (nn == 0) c.N = 1;
 
@@ -476,7 +487,7 @@ fg_status plan_contraction(int32_t nA, const int32_t *modesA, const int64_t *str
     for (int i = 0; i < tc.n; ++i) if (tc.strides[i] < 0) return fail(FG_ERR_UNSUPPORTED, "negative strides are not supported");
     if (span(ta) * 2 >= (1ll << 31) || span(tb) * 2 >= (1ll << 31) || span(tc) * 4 >= (1ll << 31))
         return fail(FG_ERR_UNSUPPORTED, "A, B and C must each span less than 2 GiB");
-    if (c.M > (1 << 30) || c.N > (1 << 30) || c.K > (1 << 30)) return fail(FG_ERR_UNSUPPORTED, "merged extents above 2^30 are not supported");
+    if (c.M > (1 << 30) || c.N > (1 << 30) || c.K > (1 << 30) || c.batches > (1 << 20)) return fail(FG_ERR_UNSUPPORTED, "merged extents above 2^30 (2^20 for batch modes) are not supported");
     return FG_OK;
 }
 
@@ -629,7 +640,7 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
     // A result that is not contiguous along the leading row mode is stored in short pieces; the
     // smallest tile makes them shorter still (measured on the paper's D_abc = A_bda B_dc).
     const bool rows_contiguous = c.c_m.n == 0 || c.c_m.stride[0] == 1;
-    const int tile = choose_plan(c.M, c.N, c.K, false, rows_contiguous || c.M < 128 || c.N < 128).tile;
+    const int tile = choose_plan(c.M, c.N, c.K, false, rows_contiguous || c.M < 128 || c.N < 128, c.batches).tile;
     const fg::KernelEntry &k = table_for(c.a_kc, c.b_kc)[fg::entry_index(tile, true)];
     fg::GemmParams p;
     memset(&p, 0, sizeof p);
@@ -640,6 +651,8 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
     p.has_c = (Cin != nullptr);
     p.alpha = alpha; p.beta = Cin ? beta : 0.f;
     p.a_m = c.a_m; p.a_k = c.a_k; p.b_n = c.b_n; p.b_k = c.b_k; p.c_m = c.c_m; p.c_n = c.c_n;
+    p.a_b = c.a_b; p.b_b = c.b_b; p.c_b = c.c_b; p.batches = (int32_t)c.batches;
+    if ((int64_t)p.tiles_m * p.tiles_n * c.batches >= (1ll << 31)) return fail(FG_ERR_UNSUPPORTED, "too many tiles");
     return launch(k, p, (hipStream_t)hip_stream);
 }
 

@@ -72,6 +72,10 @@ struct GemmParams {
     int64_t split_stride;
     // tensor contraction: mode groups of each tensor
     ModeGroup a_m, a_k, b_n, b_k, c_m, c_n;
+    // batch modes (present in A, B and C): the launch covers `batches` copies of the tile grid,
+    // copy t works on the slices of A, B and C at batch index t
+    ModeGroup a_b, b_b, c_b;
+    int32_t batches;
 };
 
 // ---- tile configuration ---------------------------------------------------------------------
@@ -783,7 +787,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % Cfg::WGM, wn = wave / Cfg::WGM;
-    const int ntiles = p.tiles_m * p.tiles_n * (Cfg::SPLITK ? p.splits : 1);
+    const int ntiles = p.tiles_m * p.tiles_n * (Cfg::SPLITK ? p.splits : 1) * (Cfg::STRIDED ? p.batches : 1);
     [[maybe_unused]] const uint32_t xf_a = p.a_add2, xf_b = p.b_add2;   // used by TileCfg::XFORM only
     [[maybe_unused]] const int xf_k = p.K;
 
@@ -813,7 +817,8 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
         const GemmParams tp = load_param<GemmParams>(0);
         int tm, tn;
         split = 0;
-        if constexpr (Cfg::SPLITK) {
+        if constexpr (Cfg::SPLITK || Cfg::STRIDED) {
+            // which copy of the tile grid: the K range of a split product, or the batch index
             const int per_split = tp.tiles_m * tp.tiles_n;
             split = tile_id / per_split;
             tile_id -= split * per_split;
@@ -833,6 +838,10 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
         nkt = kt1 > kt0 ? kt1 - kt0 : 0;
         const _Float16 *ap[2] = {tp.A, tp.A_im};
         const _Float16 *bp[2] = {tp.B, tp.B_im};
+        if constexpr (Cfg::STRIDED) {
+            ap[0] += group_offset(tp.a_b, split);
+            bp[0] += group_offset(tp.b_b, split);
+        }
 #pragma unroll
         for (int q = 0; q < NLOADERS; ++q) {
             if constexpr (Cfg::DIAG == 1) la[q].init(ap[q], m0, tp.M < tp.K ? tp.M : tp.K, wave, lane);
@@ -1062,6 +1071,11 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
         {
             GemmParams ep = load_param<GemmParams>(0);
             if constexpr (Cfg::SPLITK) ep.D += (int64_t)sp0 * ep.split_stride;
+            if constexpr (Cfg::STRIDED) {
+                const int64_t c_off = group_offset(ep.c_b, sp0);
+                ep.D += c_off;
+                if (ep.has_c) ep.C += c_off;
+            }
             if constexpr (Cfg::ILV) {
                 if (ep.has_c) epilogue_interleaved<Cfg, true>(ep, acc[0], acc[1], m_base, n_base, lane);
                 else epilogue_interleaved<Cfg, false>(ep, acc[0], acc[1], m_base, n_base, lane);

@@ -120,8 +120,8 @@ def test_contract_argument_errors():
     a, b, c, d = 0, 1, 2, 3
     ext = {a: 64, b: 64, c: 64, d: 64}
     dense3 = [1, 64, 4096]
-    # batch mode (in all three tensors)
-    assert contract_status([a, d, c], dense3, [d, b, c], dense3, [a, b, c], dense3, ext) == fg.FG_ERR_MODES
+    # a mode in one tensor only (no reduction or broadcast modes)
+    assert contract_status([a, d, c], dense3, [d, b], [1, 64], [a, b], [1, 64], ext) == fg.FG_ERR_MODES
     # mode without extent
     assert contract_status([a, d, 9], dense3, [d, b], [1, 64], [a, b, 9], dense3, ext) == fg.FG_ERR_MODES
     # repeated mode inside one tensor

@@ -48,6 +48,21 @@ def test_ragged_extents_every_entry():
     say("result's fastest mode in B, ragged"); run_contract_case({a: 56, b: 136, d: 64}, [a, d], [b, d], [b, a], ints=True, beta=1.0)
 
 
+def test_batch_modes():
+    """Modes present in A, B and C: an independent contraction per batch index (one launch)."""
+    g, h = 6, 7
+    say("batched matrix product C[m,n,g] = A[m,k,g] B[k,n,g]")
+    run_contract_case({a: 72, b: 40, d: 64, g: 5}, [a, d, g], [d, b, g], [a, b, g], ints=True)
+    say("batch mode first in B, last in A, middle in C, floats, beta")
+    run_contract_case({a: 64, b: 24, c: 3, d: 128, g: 4}, [a, d, c, g], [d, g, b], [a, g, b, c], alpha=0.5, beta=-1.0)
+    say("two batch modes, two summed modes")
+    run_contract_case({a: 16, b: 8, e: 64, f: 2, g: 3, h: 2}, [a, e, g, f, h], [b, f, h, e, g], [a, b, g, h], ints=True)
+    say("K-contiguous operands with a batch mode")
+    run_contract_case({a: 37, c: 51, d: 128, g: 3}, [d, a, g], [d, c, g], [a, c, g], ints=True)
+    say("64 batches of 256x256x256, sampled")
+    run_contract_case({a: 256, b: 256, d: 256, g: 64}, [a, d, g], [d, b, g], [a, b, g], samples=8192)
+
+
 def test_small_contractions_every_entry():
     say("5a-shaped small"); run_contract_case({a: 64, b: 64, c: 3, d: 64}, [a, d, c], [d, b], [a, b, c], ints=True)
     say("5b-shaped small"); run_contract_case({a: 16, b: 4, c: 8, d: 8, e: 64, f: 2}, [a, e, b, f], [d, f, c, e], [a, b, c, d], ints=True)
