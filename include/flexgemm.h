@@ -18,9 +18,10 @@
  *     caller owns.  The library never allocates, frees, retains or copies caller memory.
  *   - The library owns one 64 MiB device workspace per GPU, allocated by fg_init() or by the
  *     first fg_gemm / fg_gemm_ex call that needs it and kept until the process ends.  It holds the
- *     partial products of split-K calls (outputs with too few tiles to fill the GPU and a long K
- *     are computed as partial products over ranges of K plus a reduction pass, the cross-
- *     workgroup reduction use of the epilogue in Section 4.2.5).  All such calls on one GPU share
+ *     partial products of split-K calls (outputs with too few tiles to fill the GPU and a long K,
+ *     or the leftover tiles of the last, partly filled round of a larger output, are computed as
+ *     partial products over ranges of K plus a reduction pass, the cross-workgroup reduction
+ *     use of the epilogue in Section 4.2.5).  All such calls on one GPU share
  *     it: calls on one stream are ordered and safe; split-K calls on different streams of one GPU
  *     must not overlap in time.  The partial products are added in a fixed order, so results do
  *     not depend on scheduling.
@@ -201,7 +202,7 @@ int32_t fg_version(void);
  * occupancy) and allocate the split-K workspace.  Without it each variant is prepared by the first
  * call that uses it, and the workspace is allocated by the first call that splits K.  After
  * fg_init() on a device, fg_gemm / fg_gemm_ex / fg_gemm_dual / fg_contract on that device do
- * nothing but enqueue one kernel (two when K is split) on the given stream, so they may be recorded into a HIP graph
+ * nothing but enqueue one kernel (two or three when K is split) on the given stream, so they may be recorded into a HIP graph
  * (stream capture) and replayed.  Returns FG_OK or FG_ERR_LAUNCH.
  */
 fg_status fg_init(void);
@@ -209,7 +210,8 @@ fg_status fg_init(void);
 /*
  * Name of the kernel variant and block tile that fg_gemm would use for this problem, written as
  * a NUL-terminated string into `buf` (at most `buf_len` bytes), followed by "+splitk<n>" when K
- * is split into n ranges.  This is the "params" choice of Section 4.2.1, made here by an estimate
+ * is split into n ranges for every tile, or "+tailsplitk<n>" when only the tiles of the last round
+ * are split.  This is the "params" choice of Section 4.2.1, made here by an estimate
  * of the run time of every tile shape and split.  `variant` (fg_plan_variant) names the operator: real FP16, planar complex, dual, real BF16 or
  * interleaved complex.
  * Returns FG_OK, or the status fg_gemm would return for these sizes and layouts.

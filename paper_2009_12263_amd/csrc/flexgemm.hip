@@ -54,7 +54,9 @@ struct Problem {
 
 // What to launch for a normalised problem: block tile, and into how many K ranges the product is
 // split (1: one pass; more: partial products into the workspace, then the reduction pass).
-struct Plan { int tile; int splits; };
+// tail_splits > 1: the tiles that fill whole rounds of the persistent grid are computed in one
+// pass, and only the tiles of the last, partly filled round are split over K.
+struct Plan { int tile; int splits; int tail_splits; };
 
 constexpr int64_t kWorkspaceBytes = 64ll << 20;    // split-K partial products, per device
 
@@ -67,7 +69,7 @@ const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
 
 // The params heuristic (Section 4.2.1 picks the largest tile that fits shared memory; here every
 // tile fits, so the question is which shape, and which split of K, finishes first).  Estimated
-// time = rounds x (time of one workgroup on its share of K + a fixed cost per round) + the cost
+// time = rounds x (time of one workgroup on its share of K + the time of its epilogue) + the cost
 // of the reduction pass if K is split.  `rounds` = ceil(workgroups / slots), slots = 256 compute
 // units x workgroups of that shape per unit; a workgroup's rate is a measured fraction of what a
 // compute unit sustains with the 256x256 tile (about 4.7 TFLOP/s), one set for workgroups that
@@ -81,32 +83,59 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_sma
     static const double rate_shared[fg::TILE_COUNT] = {1.0, 0.8, 0.73, 0.45};
     static const double rate_alone[fg::TILE_COUNT] = {1.0, 0.8, 0.43, 0.17};
     static const int split_options[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
-    constexpr double cu_flops = 4.7e12, round_cost = 4e-6, reduce_launch = 6e-6, reduce_bw = 3e12;
-    // tuning aids: FG_FORCE_TILE=0..3 picks a tile shape, FG_FORCE_SPLIT=n a split of K
-    int force_tile = -1, force_split = 0;
+    constexpr double cu_flops = 4.7e12, round_fixed = 2e-6, cu_cd_bw = 25e9, reduce_launch = 6e-6, reduce_bw = 3e12;
+    // tuning aids: FG_FORCE_TILE=0..3 picks a tile shape, FG_FORCE_SPLIT=n a split of K for every
+    // tile, FG_FORCE_TAIL=n a split of K for the tiles of the last round (1: never)
+    int force_tile = -1, force_split = 0, force_tail = 0;
     if (const char *f = getenv("FG_FORCE_TILE")) { int t = atoi(f); if (t >= 0 && t < fg::TILE_COUNT) force_tile = t; }
     if (const char *f = getenv("FG_FORCE_SPLIT")) force_split = atoi(f);
+    if (const char *f = getenv("FG_FORCE_TAIL")) force_tail = atoi(f);
     const int64_t nk = (K + 63) / 64;                       // K tiles (every real kernel has BK = 64)
-    const int64_t ldw = (M + 3) / 4 * 4;
-    Plan best{0, 1};
+    Plan best{0, 1, 1};
     double best_cost = -1;
     const int ntypes = allow_smallest ? fg::TILE_COUNT : fg::TILE_COUNT - 1;
     for (int t = 0; t < ntypes; ++t) {
         if (force_tile >= 0 && t != force_tile) continue;
         const int64_t tiles = ((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]) * batches;
         const int64_t slots = (int64_t)kNumCU * per_cu[t];
-        auto legal = [&](int S) { return S == 1 || (may_split && S <= nk && (int64_t)S * ldw * N * 4 <= kWorkspaceBytes); };
+        const int64_t slot_bytes = (int64_t)bm[t] * bn[t] * 4;
+        auto share_time = [&](int64_t wgs, int S) {     // one workgroup on 1/S of K, plus its epilogue
+            const bool shared = wgs > kNumCU;
+            const double rate = shared ? rate_shared[t] / per_cu[t] : rate_alone[t];
+            // the C read and D write of a tile stream at what one compute unit gets of the memory
+            // bandwidth, divided among the workgroups that share the unit
+            const double epilogue = round_fixed + (shared ? per_cu[t] : 1) * 8.0 * bm[t] * bn[t] / cu_cd_bw;
+            return 2.0 * bm[t] * bn[t] * (double)((nk + S - 1) / S) * 64 / (cu_flops * rate) + epilogue;
+        };
+        auto reduce_time = [&](int64_t ntile, int S) { return reduce_launch + (2.0 * S + 2.0) * (double)ntile * slot_bytes / reduce_bw; };
+        auto consider = [&](int S, int tail, double cost) {
+            if (best_cost < 0 || cost < best_cost) { best = Plan{t, S, tail}; best_cost = cost; }
+        };
+        // (a) every tile split S ways (S = 1: the plain launch)
+        auto legal = [&](int S) { return S == 1 || (may_split && S <= nk && tiles * S * slot_bytes <= kWorkspaceBytes); };
         const int forced = (force_split >= 1 && legal(force_split)) ? force_split : (force_split >= 1 ? 1 : 0);
         for (int S : split_options) {
             if (forced) { if (S != split_options[0]) break; S = forced; }      // one candidate: the forced split
             else if (S > 1 && (!legal(S) || nk / S < 4)) break;                   // at least 256 k per share
             const int64_t wgs = tiles * S;
             const int64_t rounds = (wgs + slots - 1) / slots;
-            const double rate = wgs > kNumCU ? rate_shared[t] / per_cu[t] : rate_alone[t];
-            const double k_share = (double)((nk + S - 1) / S) * 64;
-            double cost = (double)rounds * (2.0 * bm[t] * bn[t] * k_share / (cu_flops * rate) + round_cost);
-            if (S > 1) cost += reduce_launch + (2.0 * S + 2.0) * (double)M * N * 4 / reduce_bw;
-            if (best_cost < 0 || cost < best_cost) { best = Plan{t, S}; best_cost = cost; }
+            double cost = (double)rounds * share_time(wgs, S);
+            if (S > 1) cost += reduce_time(tiles, S);
+            consider(S, 1, cost);
+        }
+        // (b) whole rounds in one pass, the tiles of the last, partly filled round split over K
+        const int64_t full = tiles / slots * slots, rest = tiles - full;
+        if (may_split && full > 0 && rest > 0 && force_split < 1 && force_tail != 1) {
+            for (int S : split_options) {
+                if (S == 1) continue;
+                if (force_tail > 1) { if (S != split_options[1]) break; S = force_tail; }
+                const bool fits = S <= nk && rest * S * slot_bytes <= kWorkspaceBytes;
+                if (force_tail > 1) { if (!fits) break; }
+                else if (!fits || nk / S < 4 || rest * S > slots) break;
+                const double cost = (double)(full / slots) * share_time(full, 1) + 2e-6 +
+                                    (double)((rest * S + slots - 1) / slots) * share_time(rest * S, S) + reduce_time(rest, S);
+                consider(1, S, force_tail > 1 ? 0.0 : cost);
+            }
         }
     }
     return best;
@@ -121,8 +150,8 @@ int choose_ctile(int64_t M, int64_t N) {
 }
 
 // Kernel variant for a normalised problem.
-const fg::KernelEntry *select_kernel(const Problem &q, int *splits = nullptr) {
-    if (splits) *splits = 1;
+const fg::KernelEntry *select_kernel(const Problem &q, Plan *plan_out = nullptr) {
+    if (plan_out) *plan_out = Plan{0, 1, 1};
     if (q.cplx) {
         const int t = choose_ctile(q.M, q.N);
         if (t < 0) return nullptr;
@@ -130,10 +159,10 @@ const fg::KernelEntry *select_kernel(const Problem &q, int *splits = nullptr) {
         if (q.ilv) return &fg::kernel_table_cplx_il()[t * 4 + v];
         return &(q.dual ? fg::kernel_table_dual() : fg::kernel_table_cplx())[t * 4 + v];
     }
-    const bool may_split = splits && !q.a_diag && !q.b_diag;
+    const bool may_split = plan_out && !q.a_diag && !q.b_diag;
     const Plan plan = choose_plan(q.M, q.N, q.K, may_split);
     const int tile = plan.tile;
-    if (splits) *splits = plan.splits;
+    if (plan_out) *plan_out = plan;
     if (q.a_diag) return &fg::kernel_table_diag()[tile * 4 + (q.b_kc ? 0 : 1)];
     if (q.b_diag) return &fg::kernel_table_diag()[tile * 4 + (q.a_kc ? 2 : 3)];
     if (q.ab_add) {
@@ -193,7 +222,8 @@ fg_status launch(const fg::KernelEntry &k, const fg::GemmParams &p, hipStream_t 
     int per_cu = 0;
     if (fg_status st = prepare(k, dev, per_cu)) return st;
     // Persistent workgroups: as many as the GPU holds at once; each walks tiles b, b + grid, ...
-    const int ntiles = p.tiles_m * p.tiles_n * (p.splits > 1 ? p.splits : 1) * (p.batches > 1 ? p.batches : 1);
+    const int ntiles = p.tile_count > 0 ? p.tile_count * (p.splits > 1 ? p.splits : 1)
+                                        : p.tiles_m * p.tiles_n * (p.batches > 1 ? p.batches : 1);
     const int resident = per_cu * kNumCU;
     dim3 grid((unsigned)(ntiles < resident ? ntiles : resident)), block((unsigned)k.threads);
     hipLaunchKernelGGL(k.fn, grid, block, (size_t)k.lds_bytes, stream, p);
@@ -528,8 +558,8 @@ static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const f
     Problem q;
     if (fg_status st = normalise(M, N, K, alpha, A, B, beta, C, D, ep, dual, lt, q)) return st;
     if (q.M == 0 || q.N == 0) return FG_OK;
-    int splits = 1;
-    const fg::KernelEntry *kp = select_kernel(q, &splits);
+    Plan plan{0, 1, 1};
+    const fg::KernelEntry *kp = select_kernel(q, &plan);
     if (!kp) return fail(FG_ERR_UNSUPPORTED, "no kernel for M=%lld, N=%lld", (long long)q.M, (long long)q.N);
     const fg::KernelEntry &k = *kp;
 
@@ -552,25 +582,43 @@ static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const f
     p.c_act = q.c_act;
     p.a_add2 = (uint32_t)q.a_add * 0x10001u; p.b_add2 = (uint32_t)q.b_add * 0x10001u;
     p.alpha = q.alpha; p.beta = q.beta;
-    p.splits = 1;
-    if (splits <= 1) return launch(k, p, (hipStream_t)hip_stream);
+    const int64_t tiles64 = (int64_t)p.tiles_m * p.tiles_n;
+    if (tiles64 >= (1ll << 31) / 64) return fail(FG_ERR_UNSUPPORTED, "too many tiles");
+    const int tiles = (int)tiles64;
+    p.tile_begin = 0; p.tile_count = tiles; p.splits = 1;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (plan.splits <= 1 && plan.tail_splits <= 1) return launch(k, p, stream);
 
-    // Split K: `splits` partial products into the workspace, then the reduction pass that also
-    // applies alpha, beta.C, bias and the activations.
+    // Split K for all tiles, or for the tiles of the last round only: partial products into the
+    // workspace, then the reduction pass that also applies alpha, beta.C, bias and the activations.
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return fail(FG_ERR_LAUNCH, "no HIP device is current");
     float *ws = nullptr;
     if (fg_status st = workspace(dev, &ws)) return st;
-    const int64_t ldw = (q.M + 3) / 4 * 4;
+    int S = plan.splits, first = 0, count = tiles;
+    if (plan.tail_splits > 1) {
+        int per_cu = 0;
+        if (fg_status st = prepare(k, dev, per_cu)) return st;
+        const int slots = per_cu * kNumCU;
+        first = tiles / slots * slots; count = tiles - first; S = plan.tail_splits;
+        if (first == 0 || count == 0 || (int64_t)count * S * k.bm * k.bn * 4 > kWorkspaceBytes) { S = 1; }
+        else {
+            fg::GemmParams head = p;
+            head.tile_count = first;
+            if (fg_status st = launch(k, head, stream)) return st;
+        }
+        if (S == 1) return launch(k, p, stream);
+    }
     const int64_t nk = (q.K + 63) / 64;
-    p.splits = splits;
-    p.split_kt = (int32_t)((nk + splits - 1) / splits);
-    p.split_stride = ldw * q.N;
-    p.D = ws; p.ldd = ldw;
-    p.C = nullptr; p.has_c = 0; p.bias = nullptr; p.act = 0; p.c_act = 0; p.alpha = 1.f; p.beta = 0.f;
-    if (fg_status st = launch(k, p, (hipStream_t)hip_stream)) return st;
-    hipError_t e = fg::launch_splitk_reduce(ws, p.split_stride, splits, (int)q.M, (int)q.N, (int)ldw, q.alpha, q.beta, q.C, q.ldc,
-                                            q.D, q.ldd, q.bias, q.bias_dim, q.act, q.c_act, (hipStream_t)hip_stream);
+    fg::GemmParams part = p;
+    part.tile_begin = first; part.tile_count = count;
+    part.splits = S;
+    part.split_kt = (int32_t)((nk + S - 1) / S);
+    part.D = ws;
+    part.C = nullptr; part.has_c = 0; part.bias = nullptr; part.act = 0; part.c_act = 0; part.alpha = 1.f; part.beta = 0.f;
+    if (fg_status st = launch(k, part, stream)) return st;
+    hipError_t e = fg::launch_splitk_reduce(ws, S, first, count, k.bm, k.bn, p.tiles_m, p.tiles_n, (int)q.M, (int)q.N, q.alpha, q.beta,
+                                            q.C, q.ldc, q.D, q.ldd, q.bias, q.bias_dim, q.act, q.c_act, stream);
     if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "launch of the split-K reduction failed: %s", hipGetErrorString(e));
     return FG_OK;
 }
@@ -619,10 +667,11 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
         q.a_kc = layoutB == FG_COL || q.a_diag; q.b_kc = layoutA == FG_ROW || q.b_diag;
     }
     q.K = K;
-    int splits = 1;
-    const fg::KernelEntry *k = select_kernel(q, &splits);
+    Plan plan{0, 1, 1};
+    const fg::KernelEntry *k = select_kernel(q, &plan);
     if (!k) return fail(FG_ERR_UNSUPPORTED, "no kernel for the problem");
-    if (splits > 1) snprintf(buf, (size_t)buf_len, "%s+splitk%d", k->name, splits);
+    if (plan.splits > 1) snprintf(buf, (size_t)buf_len, "%s+splitk%d", k->name, plan.splits);
+    else if (plan.tail_splits > 1) snprintf(buf, (size_t)buf_len, "%s+tailsplitk%d", k->name, plan.tail_splits);
     else snprintf(buf, (size_t)buf_len, "%s", k->name);
     return FG_OK;
 }

@@ -65,11 +65,12 @@ struct GemmParams {
     // A_ik := half(A_ik + a_add), B_kj := half(B_kj + b_add), the addend as two packed halves
     int32_t c_act;
     uint32_t a_add2, b_add2;
-    // split-K (plain real matrices): the launch covers `splits` copies of the tile grid; copy s
-    // sums K tiles [s * split_kt, (s + 1) * split_kt) and writes its raw partial result to
-    // D + s * split_stride (a workspace: alpha = 1, no C, bias or activation in this pass)
+    // Plain real matrices: the launch covers the tile ids [tile_begin, tile_begin + tile_count).
+    // splits > 1 (split-K): it covers `splits` copies of that range; work item w = s * tile_count
+    // + t sums K tiles [s * split_kt, (s + 1) * split_kt) of tile tile_begin + t and writes the raw
+    // BM x BN partial result (alpha = 1, no C, bias or activation) to slot w of the workspace D.
+    int32_t tile_begin, tile_count;
     int32_t splits, split_kt;
-    int64_t split_stride;
     // tensor contraction: mode groups of each tensor
     ModeGroup a_m, a_k, b_n, b_k, c_m, c_n;
     // batch modes (present in A, B and C): the launch covers `batches` copies of the tile grid,
@@ -787,7 +788,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave % Cfg::WGM, wn = wave / Cfg::WGM;
-    const int ntiles = p.tiles_m * p.tiles_n * (Cfg::SPLITK ? p.splits : 1) * (Cfg::STRIDED ? p.batches : 1);
+    const int ntiles = Cfg::SPLITK ? p.tile_count * p.splits : p.tiles_m * p.tiles_n * (Cfg::STRIDED ? p.batches : 1);
     [[maybe_unused]] const uint32_t xf_a = p.a_add2, xf_b = p.b_add2;   // used by TileCfg::XFORM only
     [[maybe_unused]] const int xf_k = p.K;
 
@@ -817,11 +818,16 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
         const GemmParams tp = load_param<GemmParams>(0);
         int tm, tn;
         split = 0;
-        if constexpr (Cfg::SPLITK || Cfg::STRIDED) {
-            // which copy of the tile grid: the K range of a split product, or the batch index
-            const int per_split = tp.tiles_m * tp.tiles_n;
-            split = tile_id / per_split;
-            tile_id -= split * per_split;
+        if constexpr (Cfg::SPLITK) {
+            // which K range of a split product, and which tile of this launch's range
+            split = tile_id / tp.tile_count;
+            tile_id = tp.tile_begin + (tile_id - split * tp.tile_count);
+        }
+        if constexpr (Cfg::STRIDED) {
+            // which batch index
+            const int per_batch = tp.tiles_m * tp.tiles_n;
+            split = tile_id / per_batch;
+            tile_id -= split * per_batch;
         }
         block_to_tile(tile_id, tp.tiles_m, tp.tiles_n, tm, tn);
         m0 = tm * BM;
@@ -1070,7 +1076,15 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
 
         {
             GemmParams ep = load_param<GemmParams>(0);
-            if constexpr (Cfg::SPLITK) ep.D += (int64_t)sp0 * ep.split_stride;
+            [[maybe_unused]] int mb = m_base, nb = n_base;
+            if constexpr (Cfg::SPLITK) {
+                if (ep.splits > 1) {
+                    // a whole BM x BN partial tile into workspace slot `tile`, tile-local coordinates
+                    ep.D += (int64_t)tile * (BM * BN);
+                    ep.ldd = BM; ep.M = BM; ep.N = BN;
+                    mb = wm * Cfg::WTM; nb = wn * Cfg::WTN;
+                }
+            }
             if constexpr (Cfg::STRIDED) {
                 const int64_t c_off = group_offset(ep.c_b, sp0);
                 ep.D += c_off;
@@ -1080,8 +1094,8 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                 if (ep.has_c) epilogue_interleaved<Cfg, true>(ep, acc[0], acc[1], m_base, n_base, lane);
                 else epilogue_interleaved<Cfg, false>(ep, acc[0], acc[1], m_base, n_base, lane);
             } else {
-            if (ep.has_c) epilogue<Cfg, true>(ep, ep.C, ep.D, acc[0], m_base, n_base, lane);
-            else epilogue<Cfg, false>(ep, ep.C, ep.D, acc[0], m_base, n_base, lane);
+            if (ep.has_c) epilogue<Cfg, true>(ep, ep.C, ep.D, acc[0], mb, nb, lane);
+            else epilogue<Cfg, false>(ep, ep.C, ep.D, acc[0], mb, nb, lane);
             }
             if constexpr (Cfg::CPLX && !Cfg::ILV) {
                 if (ep.has_c) epilogue<Cfg, true>(ep, ep.C_im, ep.D_im, acc[1], m_base, n_base, lane);

@@ -43,9 +43,9 @@ const KernelEntry *kernel_table_dual();
 enum { CTILE_COUNT = 3 };
 
 // Second pass of a split-K product (splitk_reduce.hip).
-hipError_t launch_splitk_reduce(const float *W, int64_t stride, int splits, int M, int N, int ldw, float alpha, float beta,
-                                const float *C, int64_t ldc, float *D, int64_t ldd, const float *bias, int bias_dim,
-                                int act, int c_act, hipStream_t stream);
+hipError_t launch_splitk_reduce(const float *W, int splits, int tile_begin, int tile_count, int bm, int bn, int tiles_m,
+                                int tiles_n, int M, int N, float alpha, float beta, const float *C, int64_t ldc, float *D,
+                                int64_t ldd, const float *bias, int bias_dim, int act, int c_act, hipStream_t stream);
 
 // Entry index inside one table: tile * 2 + strided.
 inline int entry_index(int tile, bool strided) { return tile * 2 + (strided ? 1 : 0); }

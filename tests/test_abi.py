@@ -79,8 +79,8 @@ def test_plan_names_follow_sizes_and_layouts():
     assert fg.fg_gemm_plan(8192, 1024, 4096) == "gemm_nn_256x128x64"
     # 2048^2 outputs: 1024 small tiles (four workgroups per compute unit) beat 256 medium ones
     assert fg.fg_gemm_plan(2048, 2048, 2048, fg.FG_ROW, fg.FG_COL) == "gemm_tn_64x64x64"
-    # 4100^2: 289 big tiles would need two rounds for 33 leftover tiles; the half-width tile wastes less
-    assert fg.fg_gemm_plan(4100, 4100, 4096) == "gemm_nn_256x128x64"
+    # 4100^2: 289 big tiles are one full round of 256 plus 33 leftover tiles, which are split over K
+    assert fg.fg_gemm_plan(4100, 4100, 4096) == "gemm_nn_256x256x64+tailsplitk4"
     assert fg.fg_gemm_plan(256, 256, 256, fg.FG_COL, fg.FG_ROW) == "gemm_nt_64x64x64"
     # a row-major D is computed as the transposed problem: the operands swap roles
     assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_ROW, fg.FG_ROW, fg.FG_ROW) == "gemm_nn_256x256x64"
@@ -94,6 +94,7 @@ def test_plan_names_follow_sizes_and_layouts():
 def test_planner_splits_k_only_for_small_outputs_with_long_k(monkeypatch):
     monkeypatch.delenv("FG_FORCE_SPLIT", raising=False)
     monkeypatch.delenv("FG_FORCE_TILE", raising=False)
+    monkeypatch.delenv("FG_FORCE_TAIL", raising=False)
     for shape in [(8192, 8192, 8192), (4096, 4096, 4096), (2048, 2048, 2048), (1024, 1024, 1024), (65536, 256, 256), (256, 256, 256)]:
         assert "+splitk" not in fg.fg_gemm_plan(*shape), shape
     for shape in [(512, 512, 8192), (256, 256, 65536), (64, 64, 32768), (1024, 1024, 8192), (128, 4096, 16384)]:

@@ -265,3 +265,22 @@ def test_every_entry_of_large_multi_tile_launches():
     say("8192x4096x64 NN ints, every entry"); run_gemm_case(8192, 4096, 64, ints=True)
     say("4096x8192x128 TT ints, bias, relu, every entry")
     run_gemm_case(4096, 8192, 128, fg.FG_ROW, fg.FG_ROW, ints=True, bias_dim=1, act=fg.FG_ACT_RELU)
+
+
+def test_tail_round_split(monkeypatch):
+    """More tiles than the persistent grid holds at once, with a small remainder: the full rounds
+    run as one pass and only the leftover tiles are split over K (plus the reduction pass).  Forced
+    on small tiles so that the oracle can check every entry, then the planner's own choice."""
+    monkeypatch.setenv("FG_FORCE_TILE", "3")                      # 64x64 tiles: 1024 workgroups resident
+    for S in (2, 3, 7):
+        monkeypatch.setenv("FG_FORCE_TAIL", str(S))
+        assert ("+tailsplitk%d" % S) in fg.fg_gemm_plan(2100, 2112, 512)
+        say("tail split %d on 33x33 tiles of 64x64, ragged edge" % S)
+        run_gemm_case(2100, 2112, 512, ints=True, bias_dim=0, act=fg.FG_ACT_RELU)
+    say("tail split, row-major operands and result, C with ReLU on C")
+    run_gemm_case(2112, 2100, 456, fg.FG_ROW, fg.FG_ROW, ld_layout=fg.FG_ROW, ints=True, c_act=fg.FG_ACT_RELU, alpha=2.0, beta=-1.0)
+    monkeypatch.delenv("FG_FORCE_TILE")
+    monkeypatch.delenv("FG_FORCE_TAIL")
+    assert "+tailsplitk" in fg.fg_gemm_plan(4100, 4100, 4096)
+    say("planner's choice: 4100x4100x4096 floats sampled"); run_gemm_case(4100, 4100, 4096, samples=6000)
+    say("planner's choice: 4100x4100x4096 ints sampled"); run_gemm_case(4100, 4100, 4096, ints=True, samples=6000, bias_dim=1)
