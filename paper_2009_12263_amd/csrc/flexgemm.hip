@@ -501,7 +501,16 @@ fg_status plan_contraction(int32_t nA, const int32_t *modesA, const int64_t *str
     if (nm == 0) c.M = 1;
     if (nn == 0) c.N = 1;
 
-    if (c.a_k.extent[0] % 64) return fail(FG_ERR_UNSUPPORTED, "the leading summed mode (%d) must have an extent that is a multiple of 64", k_modes[0]);
+    // K steps of 64 walk the leading summed mode; when its extent is not a multiple of 64 the
+    // last step of each pass is zero-filled, so the kernel sees that extent rounded up
+    if ((c.a_kc || c.b_kc) && c.a_k.extent[0] % 8) return fail(FG_ERR_UNSUPPORTED, "the leading summed mode (%d) is contiguous in A or B and must have an extent that is a multiple of 8", k_modes[0]);
+    if (c.a_k.n == 0) {
+        // every summed mode has extent 1: one K step whose k = 0 alone is loaded
+        c.a_k.n = c.b_k.n = 1;
+        c.a_k.extent[0] = c.b_k.extent[0] = 1;
+        c.a_k.stride[0] = c.b_k.stride[0] = 0;
+    }
+    c.K = c.K / c.a_k.extent[0] * ((c.a_k.extent[0] + 63) / 64 * 64);
     if (c.a_kc && c.a_k.stride[0] != 1) return fail(FG_ERR_UNSUPPORTED, "internal: leading summed mode is not contiguous in A");
     if (c.b_kc && c.b_k.stride[0] != 1) return fail(FG_ERR_UNSUPPORTED, "leading summed mode %d is contiguous in A but not in B", k_modes[0]);
     if (!c.a_kc && (c.a_m.stride[0] != 1 || c.a_m.extent[0] % 8)) return fail(FG_ERR_UNSUPPORTED, "A's contiguous row mode must have an extent that is a multiple of 8");

@@ -292,6 +292,7 @@ struct TileLoader {
                 // slab = (512/R) k-rows x R/8 chunks of 16 bytes
                 constexpr int CH = R / 8;                          // 16-byte chunks per k-row
                 int kr = slab * (64 / CH) + lane / CH;
+                if constexpr (STRIDED) kchunk[s] = kr;             // k offset of this lane's k-row inside the tile
                 int p = lane % CH;                                  // physical chunk
                 int c = p ^ (mc_swz<R>(kr) << 2);                   // 64-byte granular XOR
                 if constexpr (!STRIDED) off = (int64_t)kr * ks + c * 8;
@@ -340,6 +341,11 @@ struct TileLoader {
         if constexpr (KC && !STRIDED) {
             if (kchunk[s] >= klim) v = kOutOfRange;       // only ever true in the last K step
         }
+        if constexpr (STRIDED) {
+            // K steps walk the leading summed mode in strides of BK; when its extent is not a
+            // multiple of BK the last step of each pass hangs over it: those k are zero-filled
+            if (kdigit[0] + kchunk[s] >= kext[0]) v = kOutOfRange;
+        }
         load16_to_lds(rsrc_cur, dst, v);
     }
     __device__ __forceinline__ void advance() {
@@ -347,15 +353,15 @@ struct TileLoader {
             base += kstep_bytes;
             rem = rem > kstep32 ? rem - kstep32 : 0;
         } else {
-            // odometer step of BK along the leading summed mode (its extent is a multiple of BK);
-            // a carry moves one step along the next mode
+            // odometer step of BK along the leading summed mode (the steps of one pass cover its
+            // extent rounded up to a multiple of BK); a carry moves one step along the next mode
             kdigit[0] += BK;
             koff += (int64_t)BK * kstr[0];
 #pragma unroll
             for (int t = 0; t + 1 < kMaxGroupModes; ++t) {
                 if (kdigit[t] >= kext[t] && t + 1 < kn) {
+                    koff -= (int64_t)kdigit[t] * kstr[t];
                     kdigit[t] = 0;
-                    koff -= (int64_t)kext[t] * kstr[t];
                     kdigit[t + 1] += 1;
                     koff += kstr[t + 1];
                 }

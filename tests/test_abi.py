@@ -129,9 +129,9 @@ def test_contract_argument_errors():
     assert contract_status([a, a, d], dense3, [d, b], [1, 64], [a, b], [1, 64], ext) == fg.FG_ERR_MODES
     # no unit-stride mode in A
     assert contract_status([a, d, c], [2, 128, 8192], [d, b], [1, 64], [a, b, c], dense3, ext) == fg.FG_ERR_UNSUPPORTED
-    # merged extent not a multiple of 64
-    ext2 = {a: 64, b: 64, c: 64, d: 32}
-    assert contract_status([a, d, c], [1, 64, 2048], [d, b], [1, 32], [a, b, c], dense3, ext2) == fg.FG_ERR_UNSUPPORTED
+    # B is contiguous along the summed mode, whose extent is not a multiple of 8
+    ext2 = {a: 64, b: 64, c: 64, d: 36}
+    assert contract_status([a, d, c], [1, 64, 2304], [d, b], [1, 36], [a, b, c], dense3, ext2) == fg.FG_ERR_UNSUPPORTED
     # misaligned base pointer
     assert contract_status([a, d, c], dense3, [d, b], [1, 64], [a, b, c], dense3, ext, pa=0x1002) == fg.FG_ERR_ALIGN
     # an empty mode: nothing to do, OK without a GPU

@@ -48,6 +48,25 @@ def test_ragged_extents_every_entry():
     say("result's fastest mode in B, ragged"); run_contract_case({a: 56, b: 136, d: 64}, [a, d], [b, d], [b, a], ints=True, beta=1.0)
 
 
+def test_summed_extents_that_are_not_multiples_of_64():
+    """The leading summed mode is walked in steps of 64; other extents leave a zero-filled
+    remainder in the last step of each pass."""
+    say("K-contiguous A and B, leading summed extent 40, second summed mode")
+    run_contract_case({a: 37, c: 51, d: 40, e: 3}, [d, a, e], [d, e, c], [a, c], ints=True)
+    say("M-contiguous A (5a-shaped), summed extent 104")
+    run_contract_case({a: 72, b: 40, c: 3, d: 104}, [a, d, c], [d, b], [a, b, c], ints=True)
+    say("summed extent 8")
+    run_contract_case({a: 64, b: 64, d: 8}, [a, d], [d, b], [a, b], ints=True)
+    say("5b-shaped with extents 72 and 5, floats")
+    run_contract_case({a: 16, b: 4, c: 8, d: 8, e: 72, f: 5}, [a, e, b, f], [d, f, c, e], [a, b, c, d], alpha=0.5, beta=-2.0)
+    say("both operands M/N-contiguous, odd summed extent 13")
+    run_contract_case({a: 64, b: 72, d: 13, e: 3}, [a, d, e], [b, e, d], [a, b], ints=True)
+    say("every summed mode has extent 1")
+    run_contract_case({a: 64, b: 72, d: 1}, [a, d], [b, d], [a, b], ints=True)
+    say("summed extent 200 with a batch mode, sampled floats")
+    run_contract_case({a: 256, b: 200, d: 200, f: 6}, [a, d, f], [d, b, f], [a, b, f], samples=4000)
+
+
 def test_batch_modes():
     """Modes present in A, B and C: an independent contraction per batch index (one launch)."""
     g, h = 6, 7
