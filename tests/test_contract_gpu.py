@@ -104,3 +104,42 @@ def test_delta_gives_mode_permutation():
     delta = torch.eye(n, dtype=torch.float16).reshape(-1)
     # C[a,b,c] = sum_d A[a,d,c] delta[d,b] = A[a,b,c]: checked against the oracle, which was pinned to this identity
     run_contract_case(ext, [a, d, c], [d, b], [a, b, c], ints=True, B_override=delta)
+
+
+def test_seeded_random_contraction_sweep():
+    """Thirty seeded random contractions: one or two row, column and summed modes, sometimes a
+    batch mode, random order of the modes inside each tensor, random extents; the first mode of A
+    and of B is given an extent that is a multiple of 8 (the library's requirement for the
+    contiguous mode).  Integer-valued, every entry compared."""
+    import random
+    rng = random.Random(5)
+    for case in range(30):
+        labels = iter(range(100))
+        rows = [next(labels) for _ in range(rng.randint(1, 2))]
+        cols = [next(labels) for _ in range(rng.randint(1, 2))]
+        sums = [next(labels) for _ in range(rng.randint(1, 2))]
+        batch = [next(labels)] if rng.random() < 0.3 else []
+        ext = {}
+        for m in rows + cols:
+            ext[m] = rng.choice([1, 2, 3, 5, 8, 12, 24, 40])
+        for m in sums:
+            ext[m] = rng.choice([1, 2, 3, 8, 16, 40, 72])
+        for m in batch:
+            ext[m] = rng.choice([2, 3])
+        mA = rows + sums + batch
+        mB = cols + sums + batch
+        mC = rows + cols + batch
+        rng.shuffle(mA); rng.shuffle(mB); rng.shuffle(mC)
+        # the contiguous (first) mode of A and B must not be a batch mode and needs an extent % 8 == 0
+        for modes in (mA, mB):
+            free = [m for m in modes if m not in batch]
+            first = rng.choice(free)
+            modes.remove(first); modes.insert(0, first)
+        for first in (mA[0], mB[0]):
+            if ext[first] % 8:
+                ext[first] = rng.choice([8, 16, 24, 40])
+        if mA[0] in sums and mB[0] in sums and mA[0] != mB[0]:
+            mB.remove(mA[0]); mB.insert(0, mA[0])          # contiguous along different summed modes is unsupported
+        beta = rng.choice([0.0, 1.0, -0.5])
+        say("sweep %d: A%s B%s C%s ext=%s beta=%g" % (case, mA, mB, mC, ext, beta))
+        run_contract_case(ext, mA, mB, mC, alpha=rng.choice([1.0, 2.0, -1.0]), beta=beta, ints=True, seed=2000 + case)
