@@ -32,15 +32,19 @@
  *   - Errors are reported by the return value only; nothing is launched when a call fails, and
  *     nothing is thrown or aborted across this boundary.  fg_last_error() gives a message.
  *   - Leading dimensions and strides are in ELEMENTS.
- *   - Alignment: element base pointers must be 16-byte aligned; leading dimensions of FP16
- *     operands must be multiples of 8 and of FP32 operands multiples of 4 (Section 4.2.2:
- *     the aligned layouts that permit 128-bit accesses).  Otherwise FG_ERR_ALIGN.
+ *   - Alignment: the tiled kernels need element base pointers that are 16-byte aligned, leading
+ *     dimensions of 16-bit operands that are multiples of 8 and of FP32 operands multiples of 4
+ *     (Section 4.2.2: the aligned layouts that permit 128-bit accesses), and a K that is a
+ *     multiple of 8.  A real, non-diagonal product that misses any of these (any leading
+ *     dimension, pointers aligned to an element only, any K) is computed by a general kernel:
+ *     same operation and options, much slower.  Complex, dual and diagonal products have no
+ *     general kernel: FG_ERR_ALIGN (FG_ERR_UNSUPPORTED for K).  Pointers that are not aligned to
+ *     an element are always FG_ERR_ALIGN.
  *   - Sizes: M and N are arbitrary; tiles that hang over the edge of a matrix are predicated
  *     (the paper requires inputs padded to the tile sizes and names predication as future work,
- *     Section 7).  K must be a multiple of 8, otherwise FG_ERR_UNSUPPORTED.  M, N or K equal to
- *     zero is accepted: with M == 0 or N == 0 nothing is done; with K == 0 the product term is
- *     zero.  The kernels may read (never write) up to 14 bytes past the last element of A or B
- *     inside the same 16-byte chunk.
+ *     Section 7).  M, N or K equal to zero is accepted: with M == 0 or N == 0 nothing is done;
+ *     with K == 0 the product term is zero.  The tiled kernels may read (never write) up to 14
+ *     bytes past the last element of A or B inside the same 16-byte chunk.
  *   - D may alias C exactly (same pointer, layout and ld: the in-place BLAS form).  A and B
  *     must not overlap D.
  */

@@ -27,6 +27,23 @@ fg_status fail(fg_status st, const char *fmt, ...) {
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool aligned_to(const void *p, unsigned bytes) { return (reinterpret_cast<uintptr_t>(p) & (bytes - 1)) == 0; }
+
+// Requirements of the tiled kernels that the general kernel does not have (16-byte aligned bases,
+// leading dimensions in whole 16-byte chunks, K a multiple of 8).  A call that misses one of them
+// is noted here while it is validated; plain real products then run on the general kernel, every
+// other kind of product fails with the noted status and message.
+struct Relaxed { fg_status status; char msg[256]; };
+thread_local Relaxed g_relaxed = {FG_OK, ""};
+
+void note_relaxed(fg_status st, const char *fmt, ...) {
+    if (g_relaxed.status != FG_OK) return;          // keep the first
+    g_relaxed.status = st;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_relaxed.msg, sizeof g_relaxed.msg, fmt, ap);
+    va_end(ap);
+}
 
 constexpr int kNumCU = 256;   // MI355X: 8 XCDs x 32 compute units
 
@@ -50,6 +67,7 @@ struct Problem {
     uint16_t a_add, b_add;   // FP16 bit patterns of the addends on loaded A and B; ab_add: in use
     bool ab_add;
     bool ilv;                // complex matrices in interleaved storage
+    bool general;            // operands miss a requirement of the tiled kernels: use the general kernel
 };
 
 // What to launch for a normalised problem: block tile, and into how many K ranges the product is
@@ -234,7 +252,7 @@ fg_status launch(const fg::KernelEntry &k, const fg::GemmParams &p, hipStream_t 
 
 fg_status check_sizes(int64_t M, int64_t N, int64_t K) {
     if (M < 0 || N < 0 || K < 0) return fail(FG_ERR_SHAPE, "negative size M=%lld N=%lld K=%lld", (long long)M, (long long)N, (long long)K);
-    if (K % 8) return fail(FG_ERR_UNSUPPORTED, "K must be a multiple of 8 (got %lld)", (long long)K);
+    if (K % 8) note_relaxed(FG_ERR_UNSUPPORTED, "K must be a multiple of 8 (got %lld)", (long long)K);
     if (M > (1 << 30) || N > (1 << 30) || K > (1 << 30)) return fail(FG_ERR_UNSUPPORTED, "sizes above 2^30 are not supported");
     return FG_OK;
 }
@@ -246,11 +264,12 @@ fg_status check_input_matrix(const char *name, const fg_matrix *X, int64_t rows,
     if (X->layout != FG_COL && X->layout != FG_ROW && X->layout != FG_DIAG) return fail(FG_ERR_LAYOUT, "%s: layout %d is not valid for an input", name, X->layout);
     if (rows > 0 && cols > 0) {
         if (!X->re) return fail(FG_ERR_NULL, "%s->re is NULL", name);
-        if (!aligned16(X->re) || (X->im && !aligned16(X->im))) return fail(FG_ERR_ALIGN, "%s: element pointers must be 16-byte aligned", name);
+        if (!aligned_to(X->re, 2) || (X->im && !aligned_to(X->im, 2))) return fail(FG_ERR_ALIGN, "%s: element pointers must be aligned to an element", name);
+        if (!aligned16(X->re) || (X->im && !aligned16(X->im))) note_relaxed(FG_ERR_ALIGN, "%s: element pointers must be 16-byte aligned", name);
         if (X->layout != FG_DIAG) {
             int64_t need = X->layout == FG_COL ? rows : cols;
             if (X->ld < need) return fail(FG_ERR_SHAPE, "%s: ld=%lld is smaller than %lld", name, (long long)X->ld, (long long)need);
-            if (X->ld % 8) return fail(FG_ERR_ALIGN, "%s: ld=%lld must be a multiple of 8", name, (long long)X->ld);
+            if (X->ld % 8) note_relaxed(FG_ERR_ALIGN, "%s: ld=%lld must be a multiple of 8", name, (long long)X->ld);
         }
     }
     return FG_OK;
@@ -267,10 +286,11 @@ fg_status check_output_matrix(const char *name, const fg_matrix *X, int64_t rows
     if (rows > 0 && cols > 0) {
         if (!X->re) return fail(FG_ERR_NULL, "%s->re is NULL", name);
         if (need_im && !X->im) return fail(FG_ERR_NULL, "%s->im is NULL but the product is complex", name);
-        if (!aligned16(X->re) || (X->im && !aligned16(X->im))) return fail(FG_ERR_ALIGN, "%s: element pointers must be 16-byte aligned", name);
+        if (!aligned_to(X->re, 4) || (X->im && !aligned_to(X->im, 4))) return fail(FG_ERR_ALIGN, "%s: element pointers must be aligned to an element", name);
+        if (!aligned16(X->re) || (X->im && !aligned16(X->im))) note_relaxed(FG_ERR_ALIGN, "%s: element pointers must be 16-byte aligned", name);
         int64_t need = X->layout == FG_COL ? rows : cols;
         if (X->ld < need) return fail(FG_ERR_SHAPE, "%s: ld=%lld is smaller than %lld", name, (long long)X->ld, (long long)need);
-        if (X->ld % 4) return fail(FG_ERR_ALIGN, "%s: ld=%lld must be a multiple of 4", name, (long long)X->ld);
+        if (X->ld % 4) note_relaxed(FG_ERR_ALIGN, "%s: ld=%lld must be a multiple of 4", name, (long long)X->ld);
     }
     return FG_OK;
 }
@@ -280,6 +300,7 @@ fg_status check_output_matrix(const char *name, const fg_matrix *X, int64_t rows
 fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
                     float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, bool dual,
                     const fg_load_transforms *lt, Problem &q) {
+    g_relaxed.status = FG_OK;
     if (fg_status st = check_sizes(M, N, K)) return st;
     if (fg_status st = check_input_matrix("A", A, M, K)) return st;
     if (fg_status st = check_input_matrix("B", B, K, N)) return st;
@@ -308,7 +329,7 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
     if (ep) {
         if (ep->act != FG_ACT_NONE && ep->act != FG_ACT_RELU) return fail(FG_ERR_LAYOUT, "unknown activation %d", ep->act);
         if (ep->bias && ep->bias_dim != 0 && ep->bias_dim != 1) return fail(FG_ERR_LAYOUT, "bias_dim must be 0 or 1");
-        if (ep->bias && !aligned16(ep->bias)) return fail(FG_ERR_ALIGN, "bias must be 16-byte aligned");
+        if (ep->bias && !aligned_to(ep->bias, 4)) return fail(FG_ERR_ALIGN, "bias must be aligned to an element");
     }
     if (cplx && has_ep) return fail(FG_ERR_UNSUPPORTED, "bias and activation are not defined for complex or dual products");
     if (cplx && !ilv && (!A->im || !B->im)) return fail(FG_ERR_UNSUPPORTED, "complex and dual products need the second plane of both A and B");
@@ -364,6 +385,11 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
     }
     if (q.a_diag) q.a_kc = true;     // a diagonal operand is synthesised K-contiguous in LDS
     if (q.b_diag) q.b_kc = true;
+    q.general = false;
+    if (g_relaxed.status != FG_OK) {
+        if (cplx || q.a_diag || q.b_diag) return fail(g_relaxed.status, "%s (complex, dual and diagonal products have no general kernel)", g_relaxed.msg);
+        q.general = true;
+    }
     return FG_OK;
 }
 
@@ -567,6 +593,22 @@ static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const f
     Problem q;
     if (fg_status st = normalise(M, N, K, alpha, A, B, beta, C, D, ep, dual, lt, q)) return st;
     if (q.M == 0 || q.N == 0) return FG_OK;
+    if (q.general) {
+        fg::FallbackParams f;
+        memset(&f, 0, sizeof f);
+        f.M = (int32_t)q.M; f.N = (int32_t)q.N; f.K = (int32_t)q.K;
+        f.A = (const uint16_t *)q.A; f.B = (const uint16_t *)q.B;
+        f.a_rs = q.a_kc ? q.lda : 1; f.a_ks = q.a_kc ? 1 : q.lda;
+        f.b_rs = q.b_kc ? q.ldb : 1; f.b_ks = q.b_kc ? 1 : q.ldb;
+        f.C = q.C; f.D = q.D; f.ldc = q.ldc; f.ldd = q.ldd;
+        f.bias = q.bias; f.bias_dim = q.bias_dim; f.act = q.act; f.c_act = q.c_act;
+        f.alpha = q.alpha; f.beta = q.beta;
+        f.a_add = q.a_add; f.b_add = q.b_add; f.ab_add = q.ab_add; f.bf16 = q.bf16;
+        if ((int64_t)((q.M + 63) / 64) * ((q.N + 63) / 64) >= (1ll << 31)) return fail(FG_ERR_UNSUPPORTED, "too many tiles");
+        hipError_t e = fg::launch_gemm_fallback(f, (hipStream_t)hip_stream);
+        if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "launch of the general kernel failed: %s", hipGetErrorString(e));
+        return FG_OK;
+    }
     Plan plan{0, 1, 1};
     const fg::KernelEntry *kp = select_kernel(q, &plan);
     if (!kp) return fail(FG_ERR_UNSUPPORTED, "no kernel for M=%lld, N=%lld", (long long)q.M, (long long)q.N);
@@ -652,6 +694,7 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
                        int32_t variant, char *buf, int32_t buf_len) {
     if (!buf || buf_len <= 0) return fail(FG_ERR_NULL, "buf is NULL or empty");
     buf[0] = 0;
+    g_relaxed.status = FG_OK;
     if (fg_status st = check_sizes(M, N, K)) return st;
     auto ok_in = [](int32_t l) { return l == FG_COL || l == FG_ROW || l == FG_DIAG; };
     if (!ok_in(layoutA) || !ok_in(layoutB) || (layoutD != FG_COL && layoutD != FG_ROW))
@@ -676,6 +719,12 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
         q.a_kc = layoutB == FG_COL || q.a_diag; q.b_kc = layoutA == FG_ROW || q.b_diag;
     }
     q.K = K;
+    if (g_relaxed.status != FG_OK) {
+        // K is not a multiple of 8 (alignment is not known to this query)
+        if (q.cplx || q.a_diag || q.b_diag) return fail(g_relaxed.status, "%s (complex, dual and diagonal products have no general kernel)", g_relaxed.msg);
+        snprintf(buf, (size_t)buf_len, "gemm_general_64x64x32");
+        return FG_OK;
+    }
     Plan plan{0, 1, 1};
     const fg::KernelEntry *k = select_kernel(q, &plan);
     if (!k) return fail(FG_ERR_UNSUPPORTED, "no kernel for the problem");

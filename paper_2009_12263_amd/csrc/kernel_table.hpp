@@ -47,6 +47,24 @@ hipError_t launch_splitk_reduce(const float *W, int splits, int tile_begin, int 
                                 int tiles_n, int M, int N, float alpha, float beta, const float *C, int64_t ldc, float *D,
                                 int64_t ldd, const float *bias, int bias_dim, int act, int c_act, hipStream_t stream);
 
+// General kernel for real products with unaligned operands or a K that is not a multiple of 8
+// (gemm_fallback.hip).  D is column-major; A is addressed as A[m * a_rs + k * a_ks], B as
+// B[n * b_rs + k * b_ks] (element strides).
+struct FallbackParams {
+    int32_t M, N, K;
+    const uint16_t *A, *B;
+    int64_t a_rs, a_ks, b_rs, b_ks;
+    const float *C;
+    float *D;
+    int64_t ldc, ldd;
+    const float *bias;
+    int32_t bias_dim, act, c_act;
+    float alpha, beta;
+    uint16_t a_add, b_add;       // FP16 bit patterns added to loaded A and B elements when ab_add
+    bool ab_add, bf16;
+};
+hipError_t launch_gemm_fallback(const FallbackParams &p, hipStream_t stream);
+
 // Entry index inside one table: tile * 2 + strided.
 inline int entry_index(int tile, bool strided) { return tile * 2 + (strided ? 1 : 0); }
 

@@ -123,6 +123,44 @@ def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alph
     return compare(got, r["D"], r["G"], K, ints, what)
 
 
+def run_unaligned_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alpha=1.0, beta=1.0, with_c=True,
+                            bias_dim=None, act=fg.FG_ACT_NONE, ints=True, pads=(1, 3, 1), offsets=(1, 3, 1), config=2,
+                            device="cuda", seed=W.DEFAULT_SEED, bf16=False, ab_add=None, c_act=fg.FG_ACT_NONE):
+    """fg_gemm on operands that miss the alignment of the tiled kernels: leading dimensions
+    extent + pads[i] (any value), base pointers `offsets[i]` elements into their allocations
+    (A, B, C/D), any K.  Every entry is compared with the oracle."""
+    dt = torch.bfloat16 if bf16 else torch.float16
+    odt = O.BF16 if bf16 else O.F16
+    gen = W.small_ints if ints else W.uniform_pm1
+    lda = (M if la == fg.FG_COL else K) + pads[0]
+    ldb = (K if lb == fg.FG_COL else N) + pads[1]
+    lead, other = (M, N) if ld_layout == fg.FG_COL else (N, M)
+    ldc = lead + pads[2]
+    A = gen(lda * (K if la == fg.FG_COL else M) + offsets[0], W.stream_id(config, "A"), seed=seed, device=device, dtype=dt)[offsets[0]:]
+    B = gen(ldb * (N if lb == fg.FG_COL else K) + offsets[1], W.stream_id(config, "B"), seed=seed, device=device, dtype=dt)[offsets[1]:]
+    Cbuf = gen(ldc * other + offsets[2], W.stream_id(config, "C"), seed=seed, device=device, dtype=torch.float32)[offsets[2]:] if with_c else None
+    bias = None
+    if bias_dim is not None:
+        bias = gen((M if bias_dim == 0 else N) + 1, W.stream_id(config, "bias"), seed=seed, device=device, dtype=torch.float32)[1:]
+    Dbuf = torch.full((ldc * other + offsets[2],), float("nan"), dtype=torch.float32, device=device)[offsets[2]:]
+    fg.fg_gemm(M, N, K, alpha, fg.Matrix(A, la, lda), fg.Matrix(B, lb, ldb), beta,
+               fg.Matrix(Cbuf, ld_layout, ldc) if with_c else None, fg.Matrix(Dbuf, ld_layout, ldc),
+               bias=bias, bias_dim=bias_dim or 0, act=act,
+               a_add=ab_add[0] if ab_add else 0.0, b_add=ab_add[1] if ab_add else 0.0, c_act=c_act)
+    torch.cuda.synchronize()
+    Dm = np16(Dbuf).reshape(other, ldc)
+    if ldc > lead:
+        assert np.isnan(Dm[:, lead:]).all(), "padding of D was written"
+    Dlog = Dm[:, :lead].T if ld_layout == fg.FG_COL else Dm[:, :lead]
+    r = O.gemm(M, N, K, alpha, O.Operand(np.ascontiguousarray(np16(A)), la, lda, dtype=odt),
+               O.Operand(np.ascontiguousarray(np16(B)), lb, ldb, dtype=odt), beta,
+               np.ascontiguousarray(np16(Cbuf)) if with_c else None, None, ld_layout, ldc,
+               bias=np.ascontiguousarray(np16(bias)) if bias is not None else None, bias_dim=bias_dim or 0, act=act,
+               ab_add=ab_add, c_act=c_act)
+    what = "unaligned gemm M=%d N=%d K=%d A=%d B=%d D=%d pads=%s offsets=%s" % (M, N, K, la, lb, ld_layout, pads, offsets)
+    return compare(Dlog, r["D"], r["G"], K, ints, what)
+
+
 def run_contract_case(extents, modesA, modesB, modesC, alpha=1.0, beta=0.0, ints=False, samples: Optional[int] = None,
                       stridesA=None, stridesB=None, stridesC=None, inplace=False, config=5, device="cuda",
                       seed=W.DEFAULT_SEED, B_override=None):

@@ -47,14 +47,22 @@ def test_gemm_argument_errors():
     assert status(256, 256, 256, 1.0, None, B, 0.0, None, D) == fg.FG_ERR_NULL
     assert status(256, 256, 256, 1.0, A, B, 0.0, None, None) == fg.FG_ERR_NULL
     assert status(-1, 256, 256, 1.0, A, B, 0.0, None, D) == fg.FG_ERR_SHAPE
-    assert status(256, 256, 250, 1.0, A, B, 0.0, None, D) == fg.FG_ERR_UNSUPPORTED
-    assert "multiple of 8" in fg.fg_last_error()
     A2, B2, D2 = mats(lda=128)
     assert status(256, 256, 256, 1.0, A2, B2, 0.0, None, D2) == fg.FG_ERR_SHAPE
-    A3, B3, D3 = mats(lda=260)
-    assert status(256, 256, 256, 1.0, A3, B3, 0.0, None, D3) == fg.FG_ERR_ALIGN
-    A4, B4, D4 = mats(pa=0x1008)
+    # a pointer that is not aligned to an element is rejected for every kind of product
+    A4, B4, D4 = mats(pa=0x1001)
     assert status(256, 256, 256, 1.0, A4, B4, 0.0, None, D4) == fg.FG_ERR_ALIGN
+    # what the general kernel absorbs for real products (K % 8, ld % 8, 16-byte alignment) stays an
+    # error for complex ones, which have no general kernel
+    import torch
+    im = lambda m: fg.Matrix(m.re, m.layout, m.ld, im=m.re)
+    Ac, Bc, Dc = mats()
+    assert status(256, 256, 250, 1.0, im(Ac), im(Bc), 0.0, None, im(Dc)) == fg.FG_ERR_UNSUPPORTED
+    assert "multiple of 8" in fg.fg_last_error()
+    A3, B3, D3 = mats(lda=260)
+    assert status(256, 256, 256, 1.0, im(A3), im(B3), 0.0, None, im(D3)) == fg.FG_ERR_ALIGN
+    A8, B8, D8 = mats(pa=0x1008)
+    assert status(256, 256, 256, 1.0, im(A8), im(B8), 0.0, None, im(D8)) == fg.FG_ERR_ALIGN
     A5, B5, D5 = mats()
     A5.layout = 7
     assert status(256, 256, 256, 1.0, A5, B5, 0.0, None, D5) == fg.FG_ERR_LAYOUT
@@ -87,8 +95,9 @@ def test_plan_names_follow_sizes_and_layouts():
     # sizes need not be multiples of the tile: edge tiles are predicated
     assert fg.fg_gemm_plan(100, 72, 64) == "gemm_nn_64x64x64"
     assert fg.fg_gemm_plan(5000, 3000, 1000) == "gemm_nn_256x256x64"     # 240 tiles: one round
+    assert fg.fg_gemm_plan(128, 64, 60) == "gemm_general_64x64x32"       # K % 8 != 0: the general kernel
     with pytest.raises(fg.FlexGemmError):
-        fg.fg_gemm_plan(128, 64, 60)
+        fg.fg_gemm_plan(128, 64, 60, variant=fg.FG_PLAN_COMPLEX)
 
 
 def test_planner_splits_k_only_for_small_outputs_with_long_k(monkeypatch):

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 from paper_2009_12263_amd import binding as fg
-from tests.parity import run_gemm_case
+from tests.parity import run_gemm_case, run_unaligned_gemm_case
 
 pytestmark = pytest.mark.gpu
 
@@ -284,3 +284,28 @@ def test_tail_round_split(monkeypatch):
     assert "+tailsplitk" in fg.fg_gemm_plan(4100, 4100, 4096)
     say("planner's choice: 4100x4100x4096 floats sampled"); run_gemm_case(4100, 4100, 4096, samples=6000)
     say("planner's choice: 4100x4100x4096 ints sampled"); run_gemm_case(4100, 4100, 4096, ints=True, samples=6000, bias_dim=1)
+
+
+@pytest.mark.parametrize("la,lb,ld", list(itertools.product(LAYOUTS, LAYOUTS, LAYOUTS)))
+def test_unaligned_operands_use_the_general_kernel(la, lb, ld):
+    """Odd leading dimensions, base pointers aligned to an element only and a K that is not a
+    multiple of 8: real products fall back to the general kernel with the same semantics."""
+    say("odd everything 70x45x13"); run_unaligned_gemm_case(70, 45, 13, la, lb, ld)
+    say("several tiles, bias, relu, relu on C"); run_unaligned_gemm_case(150, 131, 77, la, lb, ld, bias_dim=0, act=fg.FG_ACT_RELU, c_act=fg.FG_ACT_RELU, alpha=2.0, beta=-1.0)
+    say("floats"); run_unaligned_gemm_case(129, 65, 100, la, lb, ld, ints=False, alpha=0.5, beta=1.5, bias_dim=1)
+    say("only K is odd (aligned operands)"); run_unaligned_gemm_case(128, 64, 60, la, lb, ld, pads=(0, 0, 0), offsets=(0, 0, 0))
+    say("only a pointer is unaligned"); run_unaligned_gemm_case(128, 64, 64, la, lb, ld, pads=(0, 0, 0), offsets=(4, 0, 0))
+    say("bf16"); run_unaligned_gemm_case(70, 45, 21, la, lb, ld, bf16=True)
+    say("addition on A and B"); run_unaligned_gemm_case(70, 45, 21, la, lb, ld, ab_add=(1.0, -2.0), with_c=False)
+
+
+def test_general_kernel_is_only_for_plain_real_products():
+    H = torch.zeros(64 * 72 + 8, dtype=torch.float16, device="cuda")
+    F = torch.zeros(64 * 72 + 8, dtype=torch.float32, device="cuda")
+    kw = dict(raise_on_error=False)
+    m = lambda t, **k: fg.Matrix(t, fg.FG_COL, 66, **k)          # ld = 66: not a multiple of 8
+    assert fg.fg_gemm(64, 64, 64, 1.0, m(H), m(H), 0.0, None, m(F), **kw) == fg.FG_OK
+    assert fg.fg_gemm(64, 64, 64, 1.0, m(H, im=H), m(H, im=H), 0.0, None, fg.Matrix(F, fg.FG_COL, 64, im=F), **kw) == fg.FG_ERR_ALIGN
+    assert fg.fg_gemm(64, 64, 64, 1.0, fg.Matrix(H, fg.FG_DIAG, 0), m(H), 0.0, None, m(F), **kw) == fg.FG_ERR_ALIGN
+    assert fg.fg_gemm(64, 64, 60, 1.0, fg.Matrix(H, fg.FG_DIAG, 0), fg.Matrix(H, fg.FG_COL, 64), 0.0, None, fg.Matrix(F, fg.FG_COL, 64), **kw) == fg.FG_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
