@@ -61,7 +61,10 @@ def cpu_baseline(M, N, K, A, lda, B, ldb, C, ldc, budget_s=15.0):
 def extras(fg, W, torch, n, A, B, mC, mD, stream):
     """Other rows of the hot-path table, outside the timed region: the remaining layout pairs at
     the same size, the fused-epilogue and layout-adapter configurations and the contractions.
-    Each figure is flops (or algorithmic bytes) over the mean of 10 launches timed with HIP events."""
+    Each figure is flops (or algorithmic bytes) over the mean of 10 launches timed with HIP events;
+    the "_cold" ones rotate over independent operand sets so that nothing is served from a cache
+    filled by the previous launch (working sets below 512 MB otherwise stay in the 256 MB
+    memory-side cache between launches)."""
     import math
     res = {}
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -75,6 +78,22 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream):
         e1.record(stream)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps * 1e-3
+
+    def timed_cold(make, set_bytes, reps=3):
+        """Mean launch time when no operand is left in a cache by the previous launch: `make()`
+        builds one independent set of operands and returns the call on it; the launches rotate
+        over enough sets that a set is touched again only after more than 768 MB of other sets
+        (the memory-side cache holds 256 MB, the L2s 32 MB)."""
+        calls = [make() for _ in range(max(2, -(-768_000_000 // int(set_bytes)) + 1))]
+        for fn in calls:
+            fn()
+        e0.record(stream)
+        for _ in range(reps):
+            for fn in calls:
+                fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (reps * len(calls)) * 1e-3
 
     def guard(name, fn):
         try:
@@ -134,23 +153,43 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream):
     Ab, Bb = A.to(torch.bfloat16), B.to(torch.bfloat16)
     guard("gemm_NN_bf16_%d_TFLOPs" % n, lambda: flops / timed(lambda: fg.fg_gemm(
         n, n, n, 1.0, M(Ab, 0, n), M(Bb, 0, n), 1.0, mC, mD, stream=stream)) * 1e-12)
-    guard("config4_diagonal_A_4096_GBps", lambda: (m * m * 2 + 2 * m * m * 4 + m * 2) / timed(lambda: fg.fg_gemm(
+    diag_bytes = m * m * 2 + 2 * m * m * 4 + m * 2
+    guard("config4_diagonal_A_4096_GBps", lambda: diag_bytes / timed(lambda: fg.fg_gemm(
         m, m, m, 1.0, M(dvec, fg.FG_DIAG, 0), M(B4, 0, m), 1.0, M(C4, 0, m), M(D4, 0, m), stream=stream)) * 1e-9)
+
+    def diag_set():
+        b, c, d = B4.clone(), C4.clone(), torch.empty_like(D4)
+        return lambda: fg.fg_gemm(m, m, m, 1.0, M(dvec, fg.FG_DIAG, 0), M(b, 0, m), 1.0, M(c, 0, m), M(d, 0, m), stream=stream)
+    guard("config4_diagonal_A_4096_cold_GBps", lambda: diag_bytes / timed_cold(diag_set, diag_bytes) * 1e-9)
+
+    def square_set():
+        a_, b, c, d = A4.clone(), B4.clone(), C4.clone(), torch.empty_like(D4)
+        return lambda: fg.fg_gemm(m, m, m, 1.0, M(a_, 0, m), M(b, 0, m), 1.0, M(c, 0, m), M(d, 0, m), stream=stream)
+    guard("gemm_NN_4096_cold_TFLOPs", lambda: 2.0 * m ** 3 / timed_cold(square_set, 12 * m * m) * 1e-12)
 
     a, b, c, d, e, f = range(6)
 
-    def contraction(ext, mA, mB, mC):
+    def contraction(ext, mA, mB, mC, cold=False):
         sA = W.col_major_strides(tuple(ext[x] for x in mA))
         sB = W.col_major_strides(tuple(ext[x] for x in mB))
         sC = W.col_major_strides(tuple(ext[x] for x in mC))
         nA, nB, nC = (math.prod(ext[x] for x in ms) for ms in (mA, mB, mC))
-        out = torch.empty(nC, dtype=torch.float32, device=dev)
-        t = timed(lambda: fg.fg_contract(mA, sA, A[:nA], mB, sB, B[:nB], mC, sC, None, out, ext, stream=stream))
-        return 2.0 * math.prod(ext.values()) / t * 1e-12, (nA * 2 + nB * 2 + nC * 4) / t * 1e-9
+        nbytes = nA * 2 + nB * 2 + nC * 4
+
+        def one_set(copy=True):
+            ta, tb = (A[:nA].clone(), B[:nB].clone()) if copy else (A[:nA], B[:nB])
+            out = torch.empty(nC, dtype=torch.float32, device=dev)
+            return lambda: fg.fg_contract(mA, sA, ta, mB, sB, tb, mC, sC, None, out, ext, stream=stream)
+        t = timed_cold(one_set, nbytes) if cold else timed(one_set(copy=False))
+        return 2.0 * math.prod(ext.values()) / t * 1e-12, nbytes / t * 1e-9
 
     def c5a():
-        tf, gb = contraction({a: 256, b: 256, c: 256, d: 256}, [a, d, c], [d, b], [a, b, c])
+        ext = {a: 256, b: 256, c: 256, d: 256}
+        tf, gb = contraction(ext, [a, d, c], [d, b], [a, b, c])
         res["config5a_contraction_256_GBps"] = gb
+        tfc, gbc = contraction(ext, [a, d, c], [d, b], [a, b, c], cold=True)
+        res["config5a_contraction_256_cold_TFLOPs"] = tfc
+        res["config5a_contraction_256_cold_GBps"] = gbc
         return tf
     guard("config5a_contraction_256_TFLOPs", c5a)
     guard("config5b_contraction_64_TFLOPs", lambda: contraction({a: 64, b: 64, c: 64, d: 64, e: 64, f: 64}, [a, e, b, f], [d, f, c, e], [a, b, c, d])[0])
@@ -213,6 +252,15 @@ def main():
     value = flops / (wall_ms * 1e-3) * 1e-12
     achieved = flops / (kern_ms * 1e-3) * 1e-12
 
+    # spread of single launches (outside the timed region): each launch between its own two events
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+    for b, e in evs:
+        b.record(stream)
+        step()
+        e.record(stream)
+    torch.cuda.synchronize()
+    per_launch = sorted(b.elapsed_time(e) for b, e in evs)
+
     out = {
         "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak",
@@ -223,11 +271,16 @@ def main():
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_FP16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_FP16_PEAK_TFLOPS,
                      "traffic": MEASURED_HBM_TRAFFIC_BYTES if n == 8192 else None,
-                     "kernel_ms": kern_ms},
+                     "kernel_ms": kern_ms,
+                     "per_launch_ms_min": per_launch[0], "per_launch_ms_median": per_launch[len(per_launch) // 2],
+                     "frac_of_mfma_only_rate_on_this_data": None},
     }
 
     if not args.no_extras:
         out["extras"] = extras(fg, W, torch, n, A, B, mC, mD, stream)
+        sustained = out["extras"].get("mfma_only_rate_on_this_data_TFLOPs")
+        if isinstance(sustained, float) and sustained > 0:
+            out["roofline"]["frac_of_mfma_only_rate_on_this_data"] = achieved / sustained
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(M, N, K, A.cpu().numpy(), M, B.cpu().numpy(), K, C.cpu().numpy(), M)

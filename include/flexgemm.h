@@ -185,8 +185,9 @@ fg_status fg_gemm_dual(int64_t M, int64_t N, int64_t K, float alpha,
  * above 1 per group; A, B and C each span less than 2 GiB; at most 2^20 batch indices; no
  * negative strides.  (The summed mode that is walked fastest -- A's unit-stride mode if it is
  * summed, else B's, else the first summed mode of A -- is covered in steps of 64; an extent that
- * is not a multiple of 64 costs the zero-filled remainder of the last step.)  The row and column extents are otherwise arbitrary: tiles that hang
- * over the merged row or column extent are predicated like the edge tiles of fg_gemm.
+ * is not a multiple of 64 costs the zero-filled remainder of the last step.)  The row and
+ * column extents are otherwise arbitrary: tiles that hang over the merged row or column extent
+ * are predicated like the edge tiles of fg_gemm.
  */
 fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA, const void *A,
                       int32_t nB, const int32_t *modesB, const int64_t *stridesB, const void *B,

@@ -187,16 +187,16 @@ __device__ __forceinline__ void wait_tile() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NEWER) : "memory");
 }
 
+// Element offset of merged index idx.  Branch-free: the host pads the unused modes of a group
+// with magic 0 and stride 0, for which the quotient is 0 and the term vanishes.
 __device__ __forceinline__ int64_t group_offset(const ModeGroup &g, int idx) {
     int64_t off = 0;
 #pragma unroll
     for (int t = 0; t < kMaxGroupModes; ++t) {
-        if (t < g.n) {
-            int e = g.extent[t];
-            int q = (int)(__umulhi((uint32_t)idx, g.magic[t]) >> g.shift[t]);
-            off += (int64_t)(idx - q * e) * g.stride[t];
-            idx = q;
-        }
+        const int e = g.extent[t];
+        const int q = (int)(__umulhi((uint32_t)idx, g.magic[t]) >> g.shift[t]);
+        off += (int64_t)(idx - q * e) * g.stride[t];
+        idx = q;
     }
     return off;
 }
@@ -641,8 +641,10 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
         }
     } else {
         // tensor contraction: element offsets are mixed-radix sums over C's row and column modes.
-        // Row part: per lane, once per sub-tile row.  Column part: wave-uniform except that the
-        // upper half-wave sits 4 columns further, so each store picks one of two scalar values.
+        // Row part: per lane, once per sub-tile row.  Column part: the 32 columns of a sub-tile are
+        // decomposed in parallel, lane l taking column l % 32, and each register's column (the
+        // upper half-wave sits 4 columns further) is then fetched from the lane that holds it;
+        // decomposing them one after the other on the scalar unit cost several microseconds per tile.
         // C spans less than 2 GiB (checked by the host), so offsets are 32-bit buffer offsets.
         __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(HAS_C ? Cp : Dp), 0, 0x7fffffff, 0x00020000);
         __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(Dp, 0, 0x7fffffff, 0x00020000);
@@ -658,14 +660,12 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
         }
 #pragma unroll
         for (int j = 0; j < Cfg::TJ; ++j) {
+            const int ncol = n_base + 32 * j + lm;
+            const uint32_t col_of_lane = (interior || ncol < p.N) ? (uint32_t)group_offset(c_n, ncol) * 4u : kOutOfRange;
             uint32_t col4[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int n = n_base + 32 * j + 8 * (r >> 2) + (r & 3);
-                const uint32_t lo = (uint32_t)group_offset(c_n, n) * 4u, hi = (uint32_t)group_offset(c_n, n + 4) * 4u;
-                col4[r] = lh ? hi : lo;
-                if (!interior && n + 4 * lh >= p.N) col4[r] = kOutOfRange;
-            }
+            for (int r = 0; r < 16; ++r)
+                col4[r] = (uint32_t)__builtin_amdgcn_ds_bpermute((8 * (r >> 2) + (r & 3) + 4 * lh) * 4, (int)col_of_lane);
 #pragma unroll
             for (int i = 0; i < Cfg::TI; ++i) {
                 // both parts are below 2^31 when in range; if either is out of range the sum must not
