@@ -193,7 +193,7 @@ const fg::KernelEntry *select_kernel(const Problem &q, Plan *plan_out = nullptr)
                                            : (q.b_kc ? fg::kernel_table_tn_bf16() : fg::kernel_table_tt_bf16());
         return &t[tile];
     }
-    return &table_for(q.a_kc, q.b_kc)[fg::entry_index(tile, false)];
+    return &table_for(q.a_kc, q.b_kc)[fg::entry_index(tile, fg::VARIANT_MATRIX)];
 }
 
 // Once per (kernel, device): raise the dynamic LDS limit and ask how many workgroups of this
@@ -568,8 +568,8 @@ fg_status fg_init(void) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return fail(FG_ERR_LAUNCH, "no HIP device is current");
     struct { const fg::KernelEntry *t; int n; } tables[] = {
-        {fg::kernel_table_nn(), fg::TILE_COUNT * 2}, {fg::kernel_table_nt(), fg::TILE_COUNT * 2},
-        {fg::kernel_table_tn(), fg::TILE_COUNT * 2}, {fg::kernel_table_tt(), fg::TILE_COUNT * 2},
+        {fg::kernel_table_nn(), fg::TILE_COUNT * fg::VARIANT_COUNT}, {fg::kernel_table_nt(), fg::TILE_COUNT * fg::VARIANT_COUNT},
+        {fg::kernel_table_tn(), fg::TILE_COUNT * fg::VARIANT_COUNT}, {fg::kernel_table_tt(), fg::TILE_COUNT * fg::VARIANT_COUNT},
         {fg::kernel_table_nn_bf16(), fg::TILE_COUNT}, {fg::kernel_table_nt_bf16(), fg::TILE_COUNT},
         {fg::kernel_table_tn_bf16(), fg::TILE_COUNT}, {fg::kernel_table_tt_bf16(), fg::TILE_COUNT},
         {fg::kernel_table_nn_xf(), fg::TILE_COUNT}, {fg::kernel_table_nt_xf(), fg::TILE_COUNT},
@@ -748,7 +748,17 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
     // smallest tile makes them shorter still (measured on the paper's D_abc = A_bda B_dc).
     const bool rows_contiguous = c.c_m.n == 0 || c.c_m.stride[0] == 1;
     const int tile = choose_plan(c.M, c.N, c.K, false, rows_contiguous || c.M < 128 || c.N < 128, c.batches).tile;
-    const fg::KernelEntry &k = table_for(c.a_kc, c.b_kc)[fg::entry_index(tile, true)];
+    // The result streams past the L2 only if every store of 32 consecutive rows is one whole,
+    // aligned 128-byte line: leading row mode contiguous with an extent that is a multiple of 32,
+    // every other stride of C and its base a multiple of 32 elements.
+    auto whole_lines = [](const fg::ModeGroup &g, int first) {
+        for (int t = first; t < g.n; ++t) if (g.stride[t] % 32) return false;
+        return true;
+    };
+    const bool c_stream = c.c_m.n > 0 && c.c_m.stride[0] == 1 && c.c_m.extent[0] % 32 == 0 && whole_lines(c.c_m, 1) &&
+                          whole_lines(c.c_n, 0) && whole_lines(c.c_b, 0) && (uintptr_t)Cout % 128 == 0 &&
+                          (!Cin || (uintptr_t)Cin % 128 == 0);
+    const fg::KernelEntry &k = table_for(c.a_kc, c.b_kc)[fg::entry_index(tile, c_stream ? fg::VARIANT_CONTRACT_STREAM : fg::VARIANT_CONTRACT)];
     fg::GemmParams p;
     memset(&p, 0, sizeof p);
     p.M = (int32_t)c.M; p.N = (int32_t)c.N; p.K = (int32_t)c.K;

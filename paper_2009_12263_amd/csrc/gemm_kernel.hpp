@@ -84,7 +84,8 @@ struct GemmParams {
 // 32x32 MFMA accumulators.  A_KC / B_KC: operand is K-contiguous in memory (A row-major,
 // B column-major) rather than M/N-contiguous.  STAGES LDS buffers per operand form a ring over K.
 template <int BM_, int BN_, int BK_, int STAGES_, int WGM_, int WGN_, bool A_KC_, bool B_KC_, bool STRIDED_,
-          int DIAG_ = 0, int CPLX_ = 0, bool SPREAD_ = false, bool BF16_ = false, bool XFORM_ = false, bool ILV_ = false>
+          int DIAG_ = 0, int CPLX_ = 0, bool SPREAD_ = false, bool BF16_ = false, bool XFORM_ = false, bool ILV_ = false,
+          bool CSTREAM_ = false>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_;
     static constexpr int KSTEPS = BK / 16;                          // MFMA k-slices per tile
@@ -104,6 +105,9 @@ struct TileCfg {
     // of an element adjacent); LDS and registers keep the planar form
     static constexpr bool ILV = ILV_;
     static constexpr int DIAG = DIAG_;                              // 0: none, 1: A diagonal, 2: B diagonal
+    // CSTREAM (contractions): every run of 32 rows of the result is one whole, aligned 128-byte
+    // line of C, so C and D stream past the L2 like a matrix's (see stream_policy)
+    static constexpr bool CSTREAM = CSTREAM_;
     // SPREAD: the refill loads of a ring buffer are issued one at a time between the MFMAs of two
     // k-slices (A's part in the slice after the buffer is retired, B's part in the next one)
     // instead of as one burst: a burst from all waves queues up in the compute unit's single
@@ -132,6 +136,7 @@ struct TileCfg {
     static_assert(!(CPLX && (DIAG || STRIDED)), "complex products take plain matrices");
     static_assert(!SPREAD || STAGES >= 4 || KSTEPS >= 4, "spread refills need slack before the tile is needed");
     static_assert(!XFORM || (DIAG == 0 && CPLX == 0 && !BF16 && !STRIDED), "element-wise addition on A and B: plain real FP16 matrices");
+    static_assert(!CSTREAM || STRIDED, "the streaming variant is a contraction kernel");
     static_assert(!ILV || (CPLX == 1 && STAGES == 2 && !SPREAD && !STRIDED && DIAG == 0), "interleaved storage: plain complex products");
 };
 
@@ -526,10 +531,12 @@ __device__ __forceinline__ void block_to_tile(int bid, int tiles_m, int tiles_n,
 // C is read once and D written once: in the matrix kernels both are marked non-temporal
 // (streaming) so that they do not displace the A and B panels, which other workgroups of the same
 // XCD re-read, from the L2 (measured: 4-5 % of the 8192^3 run time).  Not for a diagonal operand
-// (no panel is re-read, and the hint only takes away what the caches would have kept of C and D)
-// and not for contractions (their stores can be partial lines, which the L2 has to merge).
+// (no panel is re-read, and the hint only takes away what the caches would have kept of C and D);
+// for contractions only in the variants the host picks when the stores are whole lines
+// (TileCfg::CSTREAM): partial lines are merged by the L2, and streaming them past it measured
+// three times slower.
 template <class Cfg>
-constexpr int stream_policy() { return (Cfg::DIAG == 0 && !Cfg::STRIDED) ? 2 : 0; }   // gfx950 cache policy: bit 1 = nt
+constexpr int stream_policy() { return (Cfg::DIAG == 0 && (!Cfg::STRIDED || Cfg::CSTREAM)) ? 2 : 0; }   // gfx950 cache policy: bit 1 = nt
 template <class Cfg, bool HAS_C>
 __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, float *Dp, floatx16 (&acc)[Cfg::TI][Cfg::TJ],
                                          int m_base, int n_base, int lane) {

@@ -65,8 +65,9 @@ struct FallbackParams {
 };
 hipError_t launch_gemm_fallback(const FallbackParams &p, hipStream_t stream);
 
-// Entry index inside one table: tile * 2 + strided.
-inline int entry_index(int tile, bool strided) { return tile * 2 + (strided ? 1 : 0); }
+// Entry index inside one table of real kernels: three variants per tile.
+enum Variant { VARIANT_MATRIX = 0, VARIANT_CONTRACT = 1, VARIANT_CONTRACT_STREAM = 2, VARIANT_COUNT = 3 };
+inline int entry_index(int tile, int variant) { return tile * VARIANT_COUNT + variant; }
 
 // real kernels with BK = 64: ring refills are spread between the MFMAs (TileCfg::SPREAD)
 #define FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR) TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR, 0, 0, true>
@@ -74,6 +75,13 @@ inline int entry_index(int tile, bool strided) { return tile * 2 + (strided ? 1 
     { gemm_kernel<FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)>, NAME, BM, BN,                  \
       FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)::NTHREADS,                                   \
       FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)::LDS_BYTES }
+
+// contraction kernels whose result streams past the L2 (TileCfg::CSTREAM)
+#define FG_CFG_GS(BM, BN, BK, ST, WGM, WGN, AKC, BKC) TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, true, 0, 0, true, false, false, false, true>
+#define FG_ENTRY_GS(BM, BN, BK, ST, WGM, WGN, AKC, BKC, NAME)                                      \
+    { gemm_kernel<FG_CFG_GS(BM, BN, BK, ST, WGM, WGN, AKC, BKC)>, NAME, BM, BN,                    \
+      FG_CFG_GS(BM, BN, BK, ST, WGM, WGN, AKC, BKC)::NTHREADS,                                     \
+      FG_CFG_GS(BM, BN, BK, ST, WGM, WGN, AKC, BKC)::LDS_BYTES }
 
 #define FG_CFG_BF16(BM, BN, BK, ST, WGM, WGN, AKC, BKC) TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, false, 0, 0, true, true>
 #define FG_ENTRY_BF16(BM, BN, BK, ST, WGM, WGN, AKC, BKC, NAME)                                    \
@@ -122,15 +130,19 @@ inline int entry_index(int tile, bool strided) { return tile * 2 + (strided ? 1 
 
 #define FG_DEFINE_TABLE(FUNC, AKC, BKC, TAG)                                                       \
     const KernelEntry *FUNC() {                                                                    \
-        static const KernelEntry t[TILE_COUNT * 2] = {                                             \
-            FG_ENTRY(256, 256, 64, 2, 2, 4, AKC, BKC, false, "gemm_" TAG "_256x256x64"),                  \
-            FG_ENTRY(256, 256, 64, 2, 2, 4, AKC, BKC, true, "gett_" TAG "_256x256x64"),                   \
-            FG_ENTRY(256, 128, 64, 2, 4, 2, AKC, BKC, false, "gemm_" TAG "_256x128x64"),                  \
-            FG_ENTRY(256, 128, 64, 2, 4, 2, AKC, BKC, true, "gett_" TAG "_256x128x64"),                   \
-            FG_ENTRY(128, 128, 64, 2, 2, 2, AKC, BKC, false, "gemm_" TAG "_128x128x64"),                  \
-            FG_ENTRY(128, 128, 64, 2, 2, 2, AKC, BKC, true, "gett_" TAG "_128x128x64"),                   \
-            FG_ENTRY(64, 64, 64, 2, 2, 2, AKC, BKC, false, "gemm_" TAG "_64x64x64"),                      \
-            FG_ENTRY(64, 64, 64, 2, 2, 2, AKC, BKC, true, "gett_" TAG "_64x64x64"),                       \
+        static const KernelEntry t[TILE_COUNT * VARIANT_COUNT] = {                                 \
+            FG_ENTRY(256, 256, 64, 2, 2, 4, AKC, BKC, false, "gemm_" TAG "_256x256x64"),           \
+            FG_ENTRY(256, 256, 64, 2, 2, 4, AKC, BKC, true, "gett_" TAG "_256x256x64"),            \
+            FG_ENTRY_GS(256, 256, 64, 2, 2, 4, AKC, BKC, "gett_stream_" TAG "_256x256x64"),        \
+            FG_ENTRY(256, 128, 64, 2, 4, 2, AKC, BKC, false, "gemm_" TAG "_256x128x64"),           \
+            FG_ENTRY(256, 128, 64, 2, 4, 2, AKC, BKC, true, "gett_" TAG "_256x128x64"),            \
+            FG_ENTRY_GS(256, 128, 64, 2, 4, 2, AKC, BKC, "gett_stream_" TAG "_256x128x64"),        \
+            FG_ENTRY(128, 128, 64, 2, 2, 2, AKC, BKC, false, "gemm_" TAG "_128x128x64"),           \
+            FG_ENTRY(128, 128, 64, 2, 2, 2, AKC, BKC, true, "gett_" TAG "_128x128x64"),            \
+            FG_ENTRY_GS(128, 128, 64, 2, 2, 2, AKC, BKC, "gett_stream_" TAG "_128x128x64"),        \
+            FG_ENTRY(64, 64, 64, 2, 2, 2, AKC, BKC, false, "gemm_" TAG "_64x64x64"),               \
+            FG_ENTRY(64, 64, 64, 2, 2, 2, AKC, BKC, true, "gett_" TAG "_64x64x64"),                \
+            FG_ENTRY_GS(64, 64, 64, 2, 2, 2, AKC, BKC, "gett_stream_" TAG "_64x64x64"),            \
         };                                                                                         \
         return t;                                                                                  \
     }
