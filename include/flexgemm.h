@@ -44,7 +44,11 @@
  *     (the paper requires inputs padded to the tile sizes and names predication as future work,
  *     Section 7).  M, N or K equal to zero is accepted: with M == 0 or N == 0 nothing is done;
  *     with K == 0 the product term is zero.  The tiled kernels may read (never write) up to 14
- *     bytes past the last element of A or B inside the same 16-byte chunk.
+ *     bytes past the last element of A or B inside the same 16-byte chunk.  A matrix may be of
+ *     any size in bytes (also above 2 GiB); what is bounded is the leading dimension
+ *     (FG_ERR_UNSUPPORTED beyond): below 2^22 elements for an operand stored with K contiguous
+ *     (A row-major, B column-major), below 2^24 for the other layouts of A and B, below 2^21
+ *     for C and D; half of each for interleaved complex matrices.  M, N and K are at most 2^30.
  *   - D may alias C exactly (same pointer, layout and ld: the in-place BLAS form).  A and B
  *     must not overlap D.
  */

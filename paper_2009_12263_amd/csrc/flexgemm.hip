@@ -626,8 +626,14 @@ static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const f
     auto span8 = [](bool kc, int64_t rows, int64_t k, int64_t ld) { int64_t s = kc ? (rows - 1) * ld + k : (k - 1) * ld + rows; return (s + 7) / 8 * 8; };
     p.a_span = q.K > 0 ? span8(q.a_kc, q.M, q.K, q.lda) : 0;
     p.b_span = q.K > 0 ? span8(q.b_kc, q.N, q.K, q.ldb) : 0;
+    // A and B may be of any size; what must fit 32 bits is the byte offset a lane forms inside one
+    // block panel at one K step (up to 256 rows by 64 k) and the advance from one K step to the next.
     const int64_t ab_elem_bytes = q.ilv ? 4 : 2;
-    if (p.a_span * ab_elem_bytes >= (1ll << 31) || p.b_span * ab_elem_bytes >= (1ll << 31)) return fail(FG_ERR_UNSUPPORTED, "A and B must each span less than 2 GiB");
+    auto reach = [&](bool kc, int64_t ld) { return (kc ? 255 * ld + 64 : 64 * ld + 256) * ab_elem_bytes; };
+    if ((!q.a_diag && reach(q.a_kc, q.lda) >= (1ll << 31)) || (!q.b_diag && reach(q.b_kc, q.ldb) >= (1ll << 31)))
+        return fail(FG_ERR_UNSUPPORTED, "leading dimension of A or B too large (row-of-K operands: below 2^22 elements, others below 2^24)");
+    const int64_t cd_limit = q.ilv ? (1ll << 20) : (1ll << 21);
+    if (q.ldc >= cd_limit || q.ldd >= cd_limit) return fail(FG_ERR_UNSUPPORTED, "leading dimension of C or D must be below 2^21 elements (2^20 interleaved)");
     p.C = q.C; p.D = q.D; p.C_im = q.C_im; p.D_im = q.D_im; p.ldc = q.ldc; p.ldd = q.ldd;
     p.bias = q.bias; p.bias_dim = q.bias_dim; p.act = q.act; p.has_c = q.C != nullptr;
     p.c_act = q.c_act;

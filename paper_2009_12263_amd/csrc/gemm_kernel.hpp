@@ -249,8 +249,7 @@ struct TileLoader {
     int ktile;
     // plain matrices: one byte past the last stored element, the extent of K, and (K-contiguous
     // operands) the k offset inside the tile of the chunk this lane fetches in each slab
-    int rem;                 // bytes from `base` to the end of the stored span (may be <= 0)
-    int kstep32;
+    int64_t rem;             // bytes from `base` to the end of the stored span (0 once past it)
     int kdim, klim;          // extent of K; k's left from the current K step on
     int kchunk[SLABS];
 
@@ -262,9 +261,8 @@ struct TileLoader {
         if constexpr (!STRIDED) {
             base = (const char *)(ptr + (int64_t)row0 * rs * ES);
             kstep_bytes = BK * ks * 2 * ES;
-            kstep32 = (int)kstep_bytes;
-            int64_t left = (span - (int64_t)row0 * rs) * 2 * ES;     // the host keeps spans below 2 GiB
-            rem = left > 0 ? (int)left : 0;
+            const int64_t left = (span - (int64_t)row0 * rs) * 2 * ES;
+            rem = left > 0 ? left : 0;
             kdim = kdim_;
         } else {
             base = (const char *)ptr;
@@ -316,8 +314,8 @@ struct TileLoader {
     __device__ __forceinline__ void skip(int kt0) {
         if constexpr (!STRIDED) {
             base += kstep_bytes * kt0;
-            int64_t left = (int64_t)rem - kstep_bytes * kt0;
-            rem = left > 0 ? (int)left : 0;
+            const int64_t left = rem - kstep_bytes * kt0;
+            rem = left > 0 ? left : 0;
         }
         ktile = kt0;
     }
@@ -330,13 +328,16 @@ struct TileLoader {
     // the next column or row of the matrix read finite garbage that only reaches result rows or
     // columns nobody stores.  A K-contiguous operand's k >= K would read the neighbouring row, so
     // those chunks are sent out of range explicitly in the last K step.
+    // Size of the descriptor window at `base`: what is left of the stored span, at most 2 GiB - 1
+    // (the host keeps every offset a lane can form below that, so a longer rest is never needed).
+    __device__ __forceinline__ uint32_t window() const { return (uint32_t)(rem < 0x7fffffffll ? rem : 0x7fffffffll); }
     __device__ __forceinline__ void begin() {
         const char *b = base;
         if constexpr (STRIDED) {
             b += koff * 2;
             rsrc_cur = make_rsrc(b);
         } else {
-            rsrc_cur = make_rsrc(b, (uint32_t)(rem > 0 ? rem : 0));
+            rsrc_cur = make_rsrc(b, window());
             klim = kdim - ktile * BK;
         }
     }
@@ -356,7 +357,7 @@ struct TileLoader {
     __device__ __forceinline__ void advance() {
         if constexpr (!STRIDED) {
             base += kstep_bytes;
-            rem = rem > kstep32 ? rem - kstep32 : 0;
+            rem = rem > kstep_bytes ? rem - kstep_bytes : 0;
         } else {
             // odometer step of BK along the leading summed mode (the steps of one pass cover its
             // extent rounded up to a multiple of BK); a carry moves one step along the next mode
@@ -385,7 +386,7 @@ struct TileLoader {
     // slab) into registers and move on to the next K step ...
     __device__ __forceinline__ void fetch() {
         klim = kdim - ktile * BK;
-        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, rem > 0 ? rem : 0, 0x00020000);
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, (int)window(), 0x00020000);
 #pragma unroll
         for (int s = 0; s < SLABS; ++s) {
             uint32_t v = voff[s];

@@ -267,6 +267,22 @@ def test_every_entry_of_large_multi_tile_launches():
     run_gemm_case(4096, 8192, 128, fg.FG_ROW, fg.FG_ROW, ints=True, bias_dim=1, act=fg.FG_ACT_RELU)
 
 
+def test_operands_larger_than_2_gib():
+    """A (then B) alone spans more than 2 GiB, once with K along columns and once along rows:
+    the panels of the later tiles and the later K steps start beyond the reach of a 32-bit byte
+    offset from the matrix base.  Integer data: every sampled entry must be exact."""
+    say("A column-major 40000x32768 (2.4 GiB), ragged M"); run_gemm_case(40000, 192, 32768, ints=True, samples=1500)
+    torch.cuda.empty_cache()
+    say("A row-major 40000x32768"); run_gemm_case(40000, 192, 32768, la=fg.FG_ROW, ints=True, samples=1500, alpha=-1.0, beta=2.0)
+    torch.cuda.empty_cache()
+    say("B row-major 32768x40000"); run_gemm_case(192, 40000, 32768, lb=fg.FG_ROW, ints=True, samples=1500, with_c=False)
+    torch.cuda.empty_cache()
+    K = 4194240         # B is stored with K contiguous: its leading dimension must stay below 2^22
+    assert "+splitk" in fg.fg_gemm_plan(320, 320, K)
+    say("split K, A and B 2.5 GiB each: 320x320x%d" % K); run_gemm_case(320, 320, K, samples=300)
+    torch.cuda.empty_cache()
+
+
 def test_tail_round_split(monkeypatch):
     """More tiles than the persistent grid holds at once, with a small remainder: the full rounds
     run as one pass and only the leftover tiles are split over K (plus the reduction pass).  Forced
