@@ -249,7 +249,7 @@ struct TileLoader {
     int ktile;
     // plain matrices: one byte past the last stored element, the extent of K, and (K-contiguous
     // operands) the k offset inside the tile of the chunk this lane fetches in each slab
-    int64_t rem;             // bytes from `base` to the end of the stored span (0 once past it)
+    int64_t rem;             // bytes from `base` to the end of the stored span (negative once past it)
     int kdim, klim;          // extent of K; k's left from the current K step on
     int kchunk[SLABS];
 
@@ -261,8 +261,7 @@ struct TileLoader {
         if constexpr (!STRIDED) {
             base = (const char *)(ptr + (int64_t)row0 * rs * ES);
             kstep_bytes = BK * ks * 2 * ES;
-            const int64_t left = (span - (int64_t)row0 * rs) * 2 * ES;
-            rem = left > 0 ? left : 0;
+            rem = (span - (int64_t)row0 * rs) * 2 * ES;
             kdim = kdim_;
         } else {
             base = (const char *)ptr;
@@ -314,8 +313,7 @@ struct TileLoader {
     __device__ __forceinline__ void skip(int kt0) {
         if constexpr (!STRIDED) {
             base += kstep_bytes * kt0;
-            const int64_t left = rem - kstep_bytes * kt0;
-            rem = left > 0 ? left : 0;
+            rem -= kstep_bytes * kt0;
         }
         ktile = kt0;
     }
@@ -330,7 +328,15 @@ struct TileLoader {
     // those chunks are sent out of range explicitly in the last K step.
     // Size of the descriptor window at `base`: what is left of the stored span, at most 2 GiB - 1
     // (the host keeps every offset a lane can form below that, so a longer rest is never needed).
-    __device__ __forceinline__ uint32_t window() const { return (uint32_t)(rem < 0x7fffffffll ? rem : 0x7fffffffll); }
+    // Written on the two 32-bit halves: the scalar unit has no 64-bit ordered compare, and the
+    // vector compares the compiler would use instead sit between the MFMAs of the K loop.
+    __device__ __forceinline__ uint32_t window() const {
+        int32_t hi = (int32_t)(rem >> 32);
+        uint32_t lo = (uint32_t)rem;
+        asm volatile("" : "+s"(hi), "+s"(lo));      // keeps the compiler from fusing the halves again
+        const uint32_t w = (hi != 0 || lo > 0x7fffffffu) ? 0x7fffffffu : lo;
+        return hi < 0 ? 0u : w;
+    }
     __device__ __forceinline__ void begin() {
         const char *b = base;
         if constexpr (STRIDED) {
@@ -357,7 +363,7 @@ struct TileLoader {
     __device__ __forceinline__ void advance() {
         if constexpr (!STRIDED) {
             base += kstep_bytes;
-            rem = rem > kstep_bytes ? rem - kstep_bytes : 0;
+            rem -= kstep_bytes;
         } else {
             // odometer step of BK along the leading summed mode (the steps of one pass cover its
             // extent rounded up to a multiple of BK); a carry moves one step along the next mode
