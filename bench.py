@@ -31,7 +31,7 @@ MFMA_FP16_PEAK_TFLOPS = 2500.0     # MI355X dense FP16 MFMA, published (2.5 PFLO
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a
 # plain copy kernel of known size (factors 2.0 and 1.0): profiles/gemm_nn_8192_pmc.md.  Only
 # meaningful for the default workload.
-MEASURED_HBM_TRAFFIC_BYTES = 2.197e9
+MEASURED_HBM_TRAFFIC_BYTES = 2.273e9
 
 
 def cpu_baseline(M, N, K, A, lda, B, ldb, C, ldc, budget_s=15.0):
@@ -58,7 +58,7 @@ def cpu_baseline(M, N, K, A, lda, B, ldb, C, ldc, budget_s=15.0):
                       % (count, M * N, M, N, K, K, t)}
 
 
-def extras(fg, W, torch, n, A, B, mC, mD, stream):
+def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True):
     """Other rows of the hot-path table, outside the timed region: the remaining layout pairs at
     the same size, the fused-epilogue and layout-adapter configurations and the contractions.
     Each figure is flops (or algorithmic bytes) over the mean of 10 launches timed with HIP events;
@@ -96,6 +96,8 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream):
         return e0.elapsed_time(e1) / (reps * len(calls)) * 1e-3
 
     def guard(name, fn):
+        if name.endswith(("_cold_GBps", "_cold_TFLOPs")) and not cold:
+            return
         try:
             res[name] = fn()
         except Exception as ex:  # keep the headline line even if an extra cannot run
@@ -187,9 +189,10 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream):
         ext = {a: 256, b: 256, c: 256, d: 256}
         tf, gb = contraction(ext, [a, d, c], [d, b], [a, b, c])
         res["config5a_contraction_256_GBps"] = gb
-        tfc, gbc = contraction(ext, [a, d, c], [d, b], [a, b, c], cold=True)
-        res["config5a_contraction_256_cold_TFLOPs"] = tfc
-        res["config5a_contraction_256_cold_GBps"] = gbc
+        if cold:
+            tfc, gbc = contraction(ext, [a, d, c], [d, b], [a, b, c], cold=True)
+            res["config5a_contraction_256_cold_TFLOPs"] = tfc
+            res["config5a_contraction_256_cold_GBps"] = gbc
         return tf
     guard("config5a_contraction_256_TFLOPs", c5a)
     guard("config5b_contraction_64_TFLOPs", lambda: contraction({a: 64, b: 64, c: 64, d: 64, e: 64, f: 64}, [a, e, b, f], [d, f, c, e], [a, b, c, d])[0])
@@ -206,6 +209,8 @@ def main():
     ap.add_argument("--size", type=int, default=8192, help="M = N = K of the timed GEMM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed-region extras (other layouts and configs)")
+    ap.add_argument("--no-cold", action="store_true",
+                    help="skip the cache-cold extras (keeps one group of launches per workload in a profile)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain elementwise copy kernel (D = -C: 4 M N bytes read, 4 M N written), "
                          "so a counter profile of this command can be scaled")
@@ -277,7 +282,7 @@ def main():
     }
 
     if not args.no_extras:
-        out["extras"] = extras(fg, W, torch, n, A, B, mC, mD, stream)
+        out["extras"] = extras(fg, W, torch, n, A, B, mC, mD, stream, cold=not args.no_cold)
         sustained = out["extras"].get("mfma_only_rate_on_this_data_TFLOPs")
         if isinstance(sustained, float) and sustained > 0:
             out["roofline"]["frac_of_mfma_only_rate_on_this_data"] = achieved / sustained
