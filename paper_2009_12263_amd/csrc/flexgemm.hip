@@ -776,6 +776,14 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
     p.a_m = c.a_m; p.a_k = c.a_k; p.b_n = c.b_n; p.b_k = c.b_k; p.c_m = c.c_m; p.c_n = c.c_n;
     p.a_b = c.a_b; p.b_b = c.b_b; p.c_b = c.c_b; p.batches = (int32_t)c.batches;
     if ((int64_t)p.tiles_m * p.tiles_n * c.batches >= (1ll << 31)) return fail(FG_ERR_UNSUPPORTED, "too many tiles");
+    // Row order inside a tile (tile_row in the kernel): when A is contiguous along its leading row
+    // mode but C along the next one, and the leading mode is short enough that a tile spans at
+    // least four values of the next, let every accumulator hold 8 x 4 of (leading, next).
+    p.perm_z = 1;
+    if (!c.a_kc && c.c_m.n >= 2 && c.c_m.stride[1] == 1) {
+        const int e0 = c.a_m.extent[0];
+        if (e0 % 8 == 0 && k.bm % e0 == 0 && k.bm / e0 >= 4) p.perm_z = k.bm / e0;
+    }
     return launch(k, p, (hipStream_t)hip_stream);
 }
 

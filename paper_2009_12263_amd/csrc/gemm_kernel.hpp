@@ -77,7 +77,25 @@ struct GemmParams {
     // copy t works on the slices of A, B and C at batch index t
     ModeGroup a_b, b_b, c_b;
     int32_t batches;
+    // Contractions with an M-contiguous A: order in which the matrix unit sees the rows of a block
+    // tile (tile_row below).  1: the order in which they are loaded.
+    int32_t perm_z;
 };
+
+// Row permutation inside a block tile of a contraction (A contiguous along its leading row mode).
+// A's tiles are loaded in A's own order: with a leading row mode of extent 8 Y the tile holds, for
+// each of Z = BM / (8 Y) values of the next row modes, Y chunks of 8 consecutive rows.  When the
+// result is contiguous along the *second* row mode, lanes that hold 32 consecutive rows of that
+// order store 32 values that are far apart in C.  The matrix unit is therefore fed the rows in
+// the order (8 rows, Z, Y): position x + 8 (z + Z y) takes tile row x + 8 (y + Y z), so that the
+// 32 rows of an accumulator are 8 rows x 4 consecutive values of the second mode and a store
+// touches a quarter of the lines.  Only fragment reads and the epilogue know of it: both address
+// rows per lane, so the permutation is free.  z_count = 1 is the identity.
+__device__ __forceinline__ int tile_row(int pos, int rows, int z_count) {
+    const int x = pos & 7, q = pos >> 3;
+    const int z = q % z_count, y = q / z_count;
+    return x + 8 * (y + (rows / 8 / z_count) * z);
+}
 
 // ---- tile configuration ---------------------------------------------------------------------
 // BM x BN x BK block tile, WGM x WGN waves, each wave owns a (32*TI) x (32*TJ) sub-tile made of
@@ -479,7 +497,7 @@ struct FragReader {
     static constexpr int KSTEPS = BK / 16;
     uint32_t addr[KC ? KSTEPS : NT];
 
-    __device__ __forceinline__ void init(int row_base, int lane) {
+    __device__ __forceinline__ void init(int row_base, int lane, int perm_z = 1) {
         if constexpr (KC) {
             int r = row_base + (lane & 31);
 #pragma unroll
@@ -492,7 +510,7 @@ struct FragReader {
             int kr = 8 * (g >> 1) + (i16 >> 2);                    // + 16*ks + 4*t
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                int m = row_base + 32 * t + 16 * (g & 1) + 4 * (i16 & 3);
+                int m = tile_row(row_base + 32 * t + 16 * (g & 1) + 4 * (i16 & 3), R, perm_z);   // 4 rows per address
                 int c64 = (m >> 5) ^ mc_swz<R>(kr);
                 addr[t] = kr * (R * 2) + c64 * 64 + (m & 31) * 2;
             }
@@ -665,11 +683,15 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
         const ModeGroup &c_m = p.c_m, &c_n = p.c_n;
         // rows past the merged row extent and columns past the merged column extent (edge tiles)
         // are dropped by sending their offset out of the descriptor's range
-        const bool interior = m_base + Cfg::WTM <= p.M && n_base + Cfg::WTN <= p.N;
+        // (a wave's rows can lie anywhere in the block tile when its rows are permuted, hence the
+        // whole tile's row range)
+        const int tile_m0 = m_base & ~(Cfg::BM - 1);
+        const bool interior = tile_m0 + Cfg::BM <= p.M && n_base + Cfg::WTN <= p.N;
         uint32_t row4[Cfg::TI];
 #pragma unroll
         for (int i = 0; i < Cfg::TI; ++i) {
-            const int m = m_base + 32 * i + lm;
+            int m = m_base + 32 * i + lm;
+            if constexpr (!Cfg::A_KC) m = tile_m0 + tile_row(m - tile_m0, Cfg::BM, p.perm_z);
             row4[i] = (interior || m < p.M) ? (uint32_t)group_offset(c_m, m) * 4u : kOutOfRange;
         }
 #pragma unroll
@@ -824,7 +846,8 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
     LoaderB lb[P];
     FragReader<BM, BK, Cfg::A_KC, TI> fa;
     FragReader<BN, BK, Cfg::B_KC, TJ> fb;
-    fa.init(wm * Cfg::WTM, lane);
+    if constexpr (Cfg::STRIDED && !Cfg::A_KC) fa.init(wm * Cfg::WTM, lane, p.perm_z);
+    else fa.init(wm * Cfg::WTM, lane);
     fb.init(wn * Cfg::WTN, lane);
 
     // K tiles [kt0, kt0 + nkt) of the current output tile.  A diagonal operand has entries only

@@ -36,6 +36,21 @@ def test_paper_contraction_full_size():
     say("paper contraction floats sampled"); run_contract_case(ext, [b, d, a], [d, c], [a, b, c], samples=8192)
 
 
+def test_result_contiguous_along_the_second_row_mode():
+    """A is contiguous along one row mode and the result along another (the shape of the paper's
+    own example): the rows of a block tile are then fed to the matrix unit in a permuted order so
+    that a store covers consecutive elements of the result.  Every entry, integer data (exact):
+    leading extents 8, 16, 32 and 64 (the last too long for the permutation), row extents that
+    no tile divides, three row modes, alpha/beta with the result updated in place."""
+    say("leading 16, 6 of the next"); run_contract_case({a: 6, b: 16, c: 40, d: 64}, [b, d, a], [d, c], [a, b, c], ints=True)
+    say("leading 8, 20 of the next"); run_contract_case({a: 20, b: 8, c: 72, d: 128}, [b, d, a], [d, c], [a, b, c], ints=True, beta=1.0)
+    say("leading 32, 5 of the next, in place"); run_contract_case({a: 5, b: 32, c: 136, d: 64}, [b, d, a], [d, c], [a, b, c], ints=True, alpha=2.0, beta=-1.0, inplace=True)
+    say("leading 32, 40 of the next, many tiles"); run_contract_case({a: 40, b: 32, c: 264, d: 192}, [b, d, a], [d, c], [a, b, c], ints=True)
+    say("leading 64"); run_contract_case({a: 12, b: 64, c: 48, d: 64}, [b, d, a], [d, c], [a, b, c], ints=True)
+    say("three row modes, result order a, e, b"); run_contract_case({a: 12, b: 16, c: 40, d: 64, e: 3}, [b, d, e, a], [d, c], [a, e, b, c], ints=True)
+    say("B also a tensor, floats"); run_contract_case({a: 24, b: 16, c: 8, d: 64, e: 5, f: 2}, [b, d, a, f], [d, f, c, e], [a, b, c, e], alpha=0.5, beta=-2.0)
+
+
 def test_ragged_extents_every_entry():
     """Row and column extents that no block tile divides: edge tiles of the strided kernels are
     predicated in the loads (zeros) and in the stores (dropped)."""
