@@ -156,6 +156,10 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True):
     guard("gemm_NN_bf16_%d_TFLOPs" % n, lambda: flops / timed(lambda: fg.fg_gemm(
         n, n, n, 1.0, M(Ab, 0, n), M(Bb, 0, n), 1.0, mC, mD, stream=stream)) * 1e-12)
     diag_bytes = m * m * 2 + 2 * m * m * 4 + m * 2
+    # C and D stored as binary16 (the type-conversion transform of Section 4.2.3): same flops, half the C and D bytes
+    Ch, Dh = mC.re.to(torch.float16), torch.empty(n * n, dtype=torch.float16, device=dev)
+    guard("gemm_NN_%d_binary16_C_D_TFLOPs" % n, lambda: flops / timed(lambda: fg.fg_gemm(
+        n, n, n, 1.0, M(A, 0, n), M(B, 0, n), 1.0, M(Ch, 0, n), M(Dh, 0, n), stream=stream)) * 1e-12)
     guard("config4_diagonal_A_4096_GBps", lambda: diag_bytes / timed(lambda: fg.fg_gemm(
         m, m, m, 1.0, M(dvec, fg.FG_DIAG, 0), M(B4, 0, m), 1.0, M(C4, 0, m), M(D4, 0, m), stream=stream)) * 1e-9)
 

@@ -73,7 +73,7 @@ typedef enum {
 } fg_status;
 
 typedef enum {
-    FG_F16 = 0, FG_BF16 = 1,   /* A, B: IEEE binary16 / bfloat16                                 */
+    FG_F16 = 0, FG_BF16 = 1,   /* A, B: IEEE binary16 / bfloat16 (FG_F16 also for C, D: see fg_gemm) */
     FG_F32 = 2,                /* C, D                                                           */
     FG_CF16 = 3,               /* A, B: interleaved complex, element = (re, im) as two binary16  */
     FG_CF32 = 4                /* C, D: interleaved complex, element = (re, im) as two binary32  */
@@ -122,6 +122,13 @@ typedef struct {
  *   C    : FG_F32, FG_COL or FG_ROW with the same layout as D; NULL or FG_ZERO means no C term
  *          (beta is then ignored).
  *   D    : FG_F32, FG_COL or FG_ROW; written.
+ *   C, D stored in lower precision (the type-conversion use of transforms, Section 4.2.3): D, and
+ *          C if given, may both be FG_F16.  C is widened exactly when it is loaded, everything
+ *          is computed in FP32 as above, and the result is rounded to nearest even when it is
+ *          stored.  Any leading dimension and element-aligned pointers are accepted for them.
+ *          For real FG_F16 A and B in FG_COL / FG_ROW layout without an addition on A and B, and
+ *          with A, B, K meeting the alignment of the tiled kernels (FG_ERR_UNSUPPORTED or
+ *          FG_ERR_ALIGN otherwise).
  *   ep   : NULL means no bias and no activation.
  * Complex: if A or B has `im`, the product is complex; this version needs `im` on both A and B
  * (FG_ERR_UNSUPPORTED otherwise), D must have `im`, C (if given) must have `im`, alpha and beta
@@ -222,12 +229,12 @@ fg_status fg_init(void);
  * a NUL-terminated string into `buf` (at most `buf_len` bytes), followed by "+splitk<n>" when K
  * is split into n ranges for every tile, or "+tailsplitk<n>" when only the tiles of the last round
  * are split.  This is the "params" choice of Section 4.2.1, made here by an estimate
- * of the run time of every tile shape and split.  `variant` (fg_plan_variant) names the operator: real FP16, planar complex, dual, real BF16 or
- * interleaved complex.
+ * of the run time of every tile shape and split.  `variant` (fg_plan_variant) names the operator: real FP16, planar complex, dual, real BF16,
+ * interleaved complex, or real FP16 with C and D stored as binary16.
  * Returns FG_OK, or the status fg_gemm would return for these sizes and layouts.
  */
 typedef enum { FG_PLAN_REAL = 0, FG_PLAN_COMPLEX = 1, FG_PLAN_DUAL = 2, FG_PLAN_REAL_BF16 = 3,
-               FG_PLAN_COMPLEX_INTERLEAVED = 4 } fg_plan_variant;
+               FG_PLAN_COMPLEX_INTERLEAVED = 4, FG_PLAN_REAL_F16_CD = 5 } fg_plan_variant;
 fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t layoutB,
                        int32_t layoutD, int32_t variant, char *buf, int32_t buf_len);
 

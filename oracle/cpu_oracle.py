@@ -105,6 +105,15 @@ def round_to_half(x: float) -> float:
     return float(lib().oracle_round_to_half(float(x)))
 
 
+def round_array_to_half(x: np.ndarray) -> np.ndarray:
+    """Every element rounded to the nearest binary16 value (ties to even), as float64: what a
+    result stored in binary16 holds when the value before the store is ``x`` (the type
+    conversion before a store, Section 4.2.3).  Element by element through round_to_half."""
+    f = lib().oracle_round_to_half
+    flat = np.asarray(x, np.float64).reshape(-1)
+    return np.array([f(float(v)) for v in flat], np.float64).reshape(np.shape(x))
+
+
 F16, BF16 = 0, 1
 
 
@@ -196,6 +205,10 @@ def gemm(M: int, N: int, K: int, alpha: float, A: Operand, B: Operand, beta: flo
     position.
     """
     threads = threads or default_threads()
+    if C_re is not None and C_re.dtype == np.float16:
+        # C stored as binary16: every element is widened exactly when it is loaded (the type
+        # conversion after a load, Section 4.2.3)
+        C_re = C_re.astype(np.float32)
     q = _gemm_problem(M, N, K, alpha, A, B, beta, C_re, C_im, layoutC, ldc, bias, bias_dim, act, c_interleaved)
     q.dual = 1 if dual else 0
     if ab_add is not None:

@@ -23,7 +23,7 @@ FG_COL, FG_ROW, FG_DIAG, FG_ZERO = 0, 1, 2, 3
 FG_ACT_NONE, FG_ACT_RELU = 0, 1
 
 EXPORTS = ("fg_init", "fg_gemm", "fg_gemm_ex", "fg_gemm_dual", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan", "fg_probe_mfma")
-FG_PLAN_REAL, FG_PLAN_COMPLEX, FG_PLAN_DUAL, FG_PLAN_REAL_BF16, FG_PLAN_COMPLEX_INTERLEAVED = 0, 1, 2, 3, 4
+FG_PLAN_REAL, FG_PLAN_COMPLEX, FG_PLAN_DUAL, FG_PLAN_REAL_BF16, FG_PLAN_COMPLEX_INTERLEAVED, FG_PLAN_REAL_F16_CD = 0, 1, 2, 3, 4, 5
 
 
 class fg_matrix(C.Structure):

@@ -68,6 +68,7 @@ struct Problem {
     bool ab_add;
     bool ilv;                // complex matrices in interleaved storage
     bool general;            // operands miss a requirement of the tiled kernels: use the general kernel
+    bool cd16;               // C and D hold binary16 (converted when loaded / stored)
 };
 
 // What to launch for a normalised problem: block tile, and into how many K ranges the product is
@@ -77,6 +78,13 @@ struct Problem {
 struct Plan { int tile; int splits; int tail_splits; };
 
 constexpr int64_t kWorkspaceBytes = 64ll << 20;    // split-K partial products, per device
+
+const fg::KernelEntry *table_h16_for(bool a_kc, bool b_kc) {
+    if (!a_kc && b_kc) return fg::kernel_table_nn_h16();
+    if (!a_kc && !b_kc) return fg::kernel_table_nt_h16();
+    if (a_kc && b_kc) return fg::kernel_table_tn_h16();
+    return fg::kernel_table_tt_h16();
+}
 
 const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
     if (!a_kc && b_kc) return fg::kernel_table_nn();
@@ -177,7 +185,7 @@ const fg::KernelEntry *select_kernel(const Problem &q, Plan *plan_out = nullptr)
         if (q.ilv) return &fg::kernel_table_cplx_il()[t * 4 + v];
         return &(q.dual ? fg::kernel_table_dual() : fg::kernel_table_cplx())[t * 4 + v];
     }
-    const bool may_split = plan_out && !q.a_diag && !q.b_diag;
+    const bool may_split = plan_out && !q.a_diag && !q.b_diag && !q.cd16;   // the reduction pass writes FP32
     const Plan plan = choose_plan(q.M, q.N, q.K, may_split);
     const int tile = plan.tile;
     if (plan_out) *plan_out = plan;
@@ -188,6 +196,7 @@ const fg::KernelEntry *select_kernel(const Problem &q, Plan *plan_out = nullptr)
                                            : (q.b_kc ? fg::kernel_table_tn_xf() : fg::kernel_table_tt_xf());
         return &t[tile];
     }
+    if (q.cd16) return &table_h16_for(q.a_kc, q.b_kc)[tile];
     if (q.bf16) {
         const fg::KernelEntry *t = !q.a_kc ? (q.b_kc ? fg::kernel_table_nn_bf16() : fg::kernel_table_nt_bf16())
                                            : (q.b_kc ? fg::kernel_table_tn_bf16() : fg::kernel_table_tt_bf16());
@@ -276,7 +285,20 @@ fg_status check_input_matrix(const char *name, const fg_matrix *X, int64_t rows,
 }
 
 fg_status check_output_matrix(const char *name, const fg_matrix *X, int64_t rows, int64_t cols, bool need_im) {
-    if (X->dtype != FG_F32 && X->dtype != FG_CF32) return fail(FG_ERR_LAYOUT, "%s must be FG_F32 or FG_CF32", name);
+    if (X->dtype != FG_F32 && X->dtype != FG_CF32 && X->dtype != FG_F16) return fail(FG_ERR_LAYOUT, "%s must be FG_F32, FG_F16 or FG_CF32", name);
+    if (X->dtype == FG_F16) {
+        // stored as binary16: the kernels access it element by element, so any ld and any
+        // element-aligned pointer will do
+        if (X->im) return fail(FG_ERR_UNSUPPORTED, "%s: binary16 storage is for real matrices", name);
+        if (X->layout != FG_COL && X->layout != FG_ROW) return fail(FG_ERR_LAYOUT, "%s: layout %d is not valid here", name, X->layout);
+        if (rows > 0 && cols > 0) {
+            if (!X->re) return fail(FG_ERR_NULL, "%s->re is NULL", name);
+            if (!aligned_to(X->re, 2)) return fail(FG_ERR_ALIGN, "%s: element pointers must be aligned to an element", name);
+            const int64_t need = X->layout == FG_COL ? rows : cols;
+            if (X->ld < need) return fail(FG_ERR_SHAPE, "%s: ld=%lld is smaller than %lld", name, (long long)X->ld, (long long)need);
+        }
+        return FG_OK;
+    }
     if (X->dtype == FG_CF32) {
         if (X->im) return fail(FG_ERR_LAYOUT, "%s: an interleaved complex matrix has no `im` plane", name);
         need_im = false;
@@ -318,11 +340,15 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
     if (bf16 && (cplx || A->layout == FG_DIAG || B->layout == FG_DIAG))
         return fail(FG_ERR_UNSUPPORTED, "FG_BF16 operands are supported for real, non-diagonal matrices only");
     if (fg_status st = check_output_matrix("D", D, M, N, cplx)) return st;
+    const bool cd16 = D->dtype == FG_F16;
+    if (cd16 && (cplx || bf16 || A->layout == FG_DIAG || B->layout == FG_DIAG))
+        return fail(FG_ERR_UNSUPPORTED, "FG_F16 C and D are supported for real FG_F16 products in FG_COL or FG_ROW layout");
     const bool has_c = C && C->layout != FG_ZERO && C->re != nullptr;
     if (C && C->layout != FG_ZERO && !C->re && M > 0 && N > 0) return fail(FG_ERR_NULL, "C->re is NULL (pass C == NULL or FG_ZERO for no C term)");
     if (has_c) {
         if (fg_status st = check_output_matrix("C", C, M, N, cplx)) return st;
         if (C->layout != D->layout) return fail(FG_ERR_LAYOUT, "C and D must have the same layout");
+        if ((C->dtype == FG_F16) != cd16) return fail(FG_ERR_UNSUPPORTED, "C and D must have the same element type");
     }
     if (A->layout == FG_DIAG && B->layout == FG_DIAG) return fail(FG_ERR_UNSUPPORTED, "at most one of A and B may be diagonal");
     const bool has_ep = ep && (ep->bias || ep->act != FG_ACT_NONE);
@@ -348,12 +374,13 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
         c_act = lt->c_act;
     }
     const bool ab_add = a_add != 0 || b_add != 0;
-    if (ab_add && (cplx || bf16 || A->layout == FG_DIAG || B->layout == FG_DIAG))
-        return fail(FG_ERR_UNSUPPORTED, "an addition on A and B needs real FG_F16 operands in FG_COL or FG_ROW layout");
+    if (ab_add && (cplx || bf16 || cd16 || A->layout == FG_DIAG || B->layout == FG_DIAG))
+        return fail(FG_ERR_UNSUPPORTED, "an addition on A and B needs real FG_F16 operands in FG_COL or FG_ROW layout and FP32 C and D");
     if (c_act != FG_ACT_NONE && cplx) return fail(FG_ERR_UNSUPPORTED, "an activation on C is not defined for complex or dual products");
 
     const bool swap = (D->layout == FG_ROW);
     q.cplx = cplx;
+    q.cd16 = cd16;
     q.ilv = ilv;
     q.c_act = c_act;
     q.ab_add = ab_add;
@@ -388,6 +415,7 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
     q.general = false;
     if (g_relaxed.status != FG_OK) {
         if (cplx || q.a_diag || q.b_diag) return fail(g_relaxed.status, "%s (complex, dual and diagonal products have no general kernel)", g_relaxed.msg);
+        if (cd16) return fail(g_relaxed.status, "%s (products with FG_F16 C and D have no general kernel)", g_relaxed.msg);
         q.general = true;
     }
     return FG_OK;
@@ -574,6 +602,8 @@ fg_status fg_init(void) {
         {fg::kernel_table_tn_bf16(), fg::TILE_COUNT}, {fg::kernel_table_tt_bf16(), fg::TILE_COUNT},
         {fg::kernel_table_nn_xf(), fg::TILE_COUNT}, {fg::kernel_table_nt_xf(), fg::TILE_COUNT},
         {fg::kernel_table_tn_xf(), fg::TILE_COUNT}, {fg::kernel_table_tt_xf(), fg::TILE_COUNT},
+        {fg::kernel_table_nn_h16(), fg::TILE_COUNT}, {fg::kernel_table_nt_h16(), fg::TILE_COUNT},
+        {fg::kernel_table_tn_h16(), fg::TILE_COUNT}, {fg::kernel_table_tt_h16(), fg::TILE_COUNT},
         {fg::kernel_table_diag(), fg::TILE_COUNT * 4},
         {fg::kernel_table_cplx(), fg::CTILE_COUNT * 4}, {fg::kernel_table_dual(), fg::CTILE_COUNT * 4},
         {fg::kernel_table_cplx_il(), fg::CTILE_COUNT * 4},
@@ -706,7 +736,7 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
     if (!ok_in(layoutA) || !ok_in(layoutB) || (layoutD != FG_COL && layoutD != FG_ROW))
         return fail(FG_ERR_LAYOUT, "plan query: A, B take FG_COL / FG_ROW / FG_DIAG, D takes FG_COL / FG_ROW");
     if (layoutA == FG_DIAG && layoutB == FG_DIAG) return fail(FG_ERR_UNSUPPORTED, "at most one of A and B may be diagonal");
-    if (variant < FG_PLAN_REAL || variant > FG_PLAN_COMPLEX_INTERLEAVED) return fail(FG_ERR_LAYOUT, "plan query: unknown variant %d", variant);
+    if (variant < FG_PLAN_REAL || variant > FG_PLAN_REAL_F16_CD) return fail(FG_ERR_LAYOUT, "plan query: unknown variant %d", variant);
     if (variant != FG_PLAN_REAL && (layoutA == FG_DIAG || layoutB == FG_DIAG))
         return fail(FG_ERR_UNSUPPORTED, "diagonal operands are supported for real FG_F16 products only");
     Problem q;
@@ -715,6 +745,7 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
     q.ilv = variant == FG_PLAN_COMPLEX_INTERLEAVED;
     q.dual = variant == FG_PLAN_DUAL;
     q.bf16 = variant == FG_PLAN_REAL_BF16;
+    q.cd16 = variant == FG_PLAN_REAL_F16_CD;
     if (layoutD == FG_COL) {
         q.M = M; q.N = N;
         q.a_diag = layoutA == FG_DIAG; q.b_diag = layoutB == FG_DIAG;
@@ -727,7 +758,7 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
     q.K = K;
     if (g_relaxed.status != FG_OK) {
         // K is not a multiple of 8 (alignment is not known to this query)
-        if (q.cplx || q.a_diag || q.b_diag) return fail(g_relaxed.status, "%s (complex, dual and diagonal products have no general kernel)", g_relaxed.msg);
+        if (q.cplx || q.a_diag || q.b_diag || q.cd16) return fail(g_relaxed.status, "%s (complex, dual, diagonal and FG_F16-result products have no general kernel)", g_relaxed.msg);
         snprintf(buf, (size_t)buf_len, "gemm_general_64x64x32");
         return FG_OK;
     }

@@ -103,7 +103,7 @@ __device__ __forceinline__ int tile_row(int pos, int rows, int z_count) {
 // B column-major) rather than M/N-contiguous.  STAGES LDS buffers per operand form a ring over K.
 template <int BM_, int BN_, int BK_, int STAGES_, int WGM_, int WGN_, bool A_KC_, bool B_KC_, bool STRIDED_,
           int DIAG_ = 0, int CPLX_ = 0, bool SPREAD_ = false, bool BF16_ = false, bool XFORM_ = false, bool ILV_ = false,
-          bool CSTREAM_ = false>
+          bool CSTREAM_ = false, bool CD16_ = false>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_;
     static constexpr int KSTEPS = BK / 16;                          // MFMA k-slices per tile
@@ -114,7 +114,7 @@ struct TileCfg {
     static constexpr bool A_KC = A_KC_, B_KC = B_KC_, STRIDED = STRIDED_;
     // 0: real; 1: complex (i^2 = -1), 2: dual (eps^2 = 0) numbers in planar-split storage
     static constexpr int CPLX = CPLX_;
-    static constexpr bool SPLITK = !STRIDED_ && DIAG_ == 0 && CPLX_ == 0;   // kernel understands GemmParams::splits
+    static constexpr bool SPLITK = !STRIDED_ && DIAG_ == 0 && CPLX_ == 0 && !CD16_;   // kernel understands GemmParams::splits
     static constexpr bool BF16 = BF16_;                             // A, B are bfloat16 instead of binary16
     // XFORM: a constant is added to every element of A and of B after it is loaded (the fragment
     // registers are transformed just before the matrix instructions that consume them)
@@ -126,6 +126,10 @@ struct TileCfg {
     // CSTREAM (contractions): every run of 32 rows of the result is one whole, aligned 128-byte
     // line of C, so C and D stream past the L2 like a matrix's (see stream_policy)
     static constexpr bool CSTREAM = CSTREAM_;
+    // CD16: C and D are stored as IEEE binary16 and converted on the way (the type-conversion use
+    // of transforms, Section 4.2.3: lower precision in memory, FP32 in the computation): C is
+    // widened exactly when loaded, the FP32 result is rounded to nearest even when stored
+    static constexpr bool CD16 = CD16_;
     // SPREAD: the refill loads of a ring buffer are issued one at a time between the MFMAs of two
     // k-slices (A's part in the slice after the buffer is retired, B's part in the next one)
     // instead of as one burst: a burst from all waves queues up in the compute unit's single
@@ -155,6 +159,7 @@ struct TileCfg {
     static_assert(!SPREAD || STAGES >= 4 || KSTEPS >= 4, "spread refills need slack before the tile is needed");
     static_assert(!XFORM || (DIAG == 0 && CPLX == 0 && !BF16 && !STRIDED), "element-wise addition on A and B: plain real FP16 matrices");
     static_assert(!CSTREAM || STRIDED, "the streaming variant is a contraction kernel");
+    static_assert(!CD16 || (CPLX == 0 && DIAG == 0 && !STRIDED && !ILV), "binary16 C and D: plain real matrix kernels");
     static_assert(!ILV || (CPLX == 1 && STAGES == 2 && !SPREAD && !STRIDED && DIAG == 0), "interleaved storage: plain complex products");
 };
 
@@ -560,6 +565,26 @@ __device__ __forceinline__ void block_to_tile(int bid, int tiles_m, int tiles_n,
 // for contractions only in the variants the host picks when the stores are whole lines
 // (TileCfg::CSTREAM): partial lines are merged by the L2, and streaming them past it measured
 // three times slower.
+// One element of C or D through a buffer descriptor: FP32, or binary16 widened / rounded (CD16).
+template <bool HALF, int POLICY>
+__device__ __forceinline__ float load_cd(__amdgpu_buffer_rsrc_t r, uint32_t voff, int soff) {
+    if constexpr (HALF) {
+        const unsigned short bits = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, POLICY);
+        return (float)__builtin_bit_cast(_Float16, bits);
+    } else {
+        return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, POLICY));
+    }
+}
+template <bool HALF, int POLICY>
+__device__ __forceinline__ void store_cd(float y, __amdgpu_buffer_rsrc_t r, uint32_t voff, int soff) {
+    if constexpr (HALF) {
+        const _Float16 h = (_Float16)y;                                  // round to nearest even
+        __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, h), r, voff, soff, POLICY);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), r, voff, soff, POLICY);
+    }
+}
+
 template <class Cfg>
 constexpr int stream_policy() { return (Cfg::DIAG == 0 && (!Cfg::STRIDED || Cfg::CSTREAM)) ? 2 : 0; }   // gfx950 cache policy: bit 1 = nt
 template <class Cfg, bool HAS_C>
@@ -574,12 +599,15 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
         // (m, n) at m + n*ld.  All accesses are buffer operations on a descriptor whose base is this
         // wave's corner of the tile: the per-lane part of the address is one register for all of
         // them, the rest is a scalar offset.
-        const int voff_c = (lm + 4 * lh * (int)p.ldc) * 4;
-        const int voff_d = (lm + 4 * lh * (int)p.ldd) * 4;
-        const int ldc4 = (int)p.ldc * 4, ldd4 = (int)p.ldd * 4;
+        constexpr bool H = Cfg::CD16;
+        constexpr int ES = H ? 2 : 4;                                    // bytes per element of C and D
+        const int voff_c = (lm + 4 * lh * (int)p.ldc) * ES;
+        const int voff_d = (lm + 4 * lh * (int)p.ldd) * ES;
+        const int ldc4 = (int)p.ldc * ES, ldd4 = (int)p.ldd * ES;
+        const char *Cb = (const char *)Cp, *Db = (const char *)Dp;
         __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float *>(HAS_C ? Cp + m_base + (int64_t)n_base * p.ldc : Dp), 0, 0x7fffffff, 0x00020000);
-        __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(Dp + m_base + (int64_t)n_base * p.ldd, 0, 0x7fffffff, 0x00020000);
+            const_cast<char *>(HAS_C ? Cb + (m_base + (int64_t)n_base * p.ldc) * ES : Db), 0, 0x7fffffff, 0x00020000);
+        __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(Db + (m_base + (int64_t)n_base * p.ldd) * ES), 0, 0x7fffffff, 0x00020000);
         const bool interior = m_base + Cfg::WTM <= p.M && n_base + Cfg::WTN <= p.N;
         if (interior) {
             // The C values of accumulator b+1 are requested before accumulator b is stored, so a
@@ -591,8 +619,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                 const int i = b / Cfg::TJ, j = b % Cfg::TJ;
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    dst[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                 rc, voff_c, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, kStream));
+                    dst[r] = load_cd<H, kStream>(rc, voff_c, 32 * ES * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4);
             };
             float bias_m[Cfg::TI];
 #pragma unroll
@@ -622,8 +649,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                         y += p.beta * (c > floor_c ? c : floor_c);
                     }
                     y = y > floor_v ? y : floor_v;
-                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, voff_d,
-                                                          128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, kStream);
+                    store_cd<H, kStream>(y, rd, voff_d, 32 * ES * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4);
                 }
             }
         } else {
@@ -651,8 +677,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                                 if constexpr (BIAS_N) bv[r8] = p.bias[n_ok ? ncol : p.N - 1];
                                 else bv[r8] = bias_mi;
                                 if constexpr (HAS_C)
-                                    cv[r8] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                        rc, n_ok ? vc : kOutOfRange, 128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4, kStream));
+                                    cv[r8] = load_cd<H, kStream>(rc, n_ok ? vc : kOutOfRange, 32 * ES * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4);
                             }
 #pragma unroll
                             for (int r8 = 0; r8 < 8; ++r8) {
@@ -661,8 +686,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                                 float y = p.alpha * acc[i][j][r] + bv[r8];
                                 if constexpr (HAS_C) y += p.beta * (cv[r8] > floor_c ? cv[r8] : floor_c);
                                 y = y > floor_v ? y : floor_v;
-                                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, n_ok ? vd : kOutOfRange,
-                                                                      128 * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4, kStream);
+                                store_cd<H, kStream>(y, rd, n_ok ? vd : kOutOfRange, 32 * ES * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4);
                             }
                         }
                     }

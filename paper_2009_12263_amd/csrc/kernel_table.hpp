@@ -31,6 +31,12 @@ const KernelEntry *kernel_table_nt_xf();
 const KernelEntry *kernel_table_tn_xf();
 const KernelEntry *kernel_table_tt_xf();
 
+// The four layout pairs with C and D stored as binary16 (TileCfg::CD16): index = tile.
+const KernelEntry *kernel_table_nn_h16();
+const KernelEntry *kernel_table_nt_h16();
+const KernelEntry *kernel_table_tn_h16();
+const KernelEntry *kernel_table_tt_h16();
+
 // Diagonal operands: index tile * 4 + {0: A diag, B K-contiguous; 1: A diag, B N-contiguous;
 //                                       2: B diag, A K-contiguous; 3: B diag, A M-contiguous}.
 const KernelEntry *kernel_table_diag();
@@ -96,6 +102,23 @@ inline int entry_index(int tile, int variant) { return tile * VARIANT_COUNT + va
             FG_ENTRY_BF16(256, 128, 64, 2, 4, 2, AKC, BKC, "gemm_bf16_" TAG "_256x128x64"),        \
             FG_ENTRY_BF16(128, 128, 64, 2, 2, 2, AKC, BKC, "gemm_bf16_" TAG "_128x128x64"),        \
             FG_ENTRY_BF16(64, 64, 64, 2, 2, 2, AKC, BKC, "gemm_bf16_" TAG "_64x64x64"),            \
+        };                                                                                         \
+        return t;                                                                                  \
+    }
+
+#define FG_CFG_H16(BM, BN, BK, ST, WGM, WGN, AKC, BKC) TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, false, 0, 0, true, false, false, false, false, true>
+#define FG_ENTRY_H16(BM, BN, BK, ST, WGM, WGN, AKC, BKC, NAME)                                     \
+    { gemm_kernel<FG_CFG_H16(BM, BN, BK, ST, WGM, WGN, AKC, BKC)>, NAME, BM, BN,                   \
+      FG_CFG_H16(BM, BN, BK, ST, WGM, WGN, AKC, BKC)::NTHREADS,                                    \
+      FG_CFG_H16(BM, BN, BK, ST, WGM, WGN, AKC, BKC)::LDS_BYTES }
+
+#define FG_DEFINE_TABLE_H16(FUNC, AKC, BKC, TAG)                                                   \
+    const KernelEntry *FUNC() {                                                                    \
+        static const KernelEntry t[TILE_COUNT] = {                                                 \
+            FG_ENTRY_H16(256, 256, 64, 2, 2, 4, AKC, BKC, "gemm_h16_" TAG "_256x256x64"),          \
+            FG_ENTRY_H16(256, 128, 64, 2, 4, 2, AKC, BKC, "gemm_h16_" TAG "_256x128x64"),          \
+            FG_ENTRY_H16(128, 128, 64, 2, 2, 2, AKC, BKC, "gemm_h16_" TAG "_128x128x64"),          \
+            FG_ENTRY_H16(64, 64, 64, 2, 2, 2, AKC, BKC, "gemm_h16_" TAG "_64x64x64"),              \
         };                                                                                         \
         return t;                                                                                  \
     }

@@ -67,39 +67,54 @@ def sample_positions(M: int, N: int, count: int, seed: int, tile: int = 256):
     return np.array(I, np.int64), np.array(J, np.int64)
 
 
-def compare(got: np.ndarray, ref: np.ndarray, G: np.ndarray, K: int, exact: bool, what: str):
+def compare(got: np.ndarray, ref: np.ndarray, G: np.ndarray, K: int, exact: bool, what: str, half_out: bool = False):
+    """half_out: the result is stored as binary16.  Exact cases: it must equal the exact result
+    rounded once to binary16.  Otherwise both bars grow by one binary16 rounding of the result,
+    2^-11 |D_ref|, doubled for the few cases in which rounding the FP32 value instead of the
+    exact one lands on the other neighbour."""
     got = got.astype(np.float64)
     assert np.isfinite(got).all(), what + ": non-finite output"
+    if half_out:
+        assert np.abs(ref).max(initial=0.0) < 65504.0, what + ": the test's results do not fit binary16"
+        if exact:
+            ref = O.round_array_to_half(ref)
     err = np.abs(got - ref)
     if exact:
         bad = np.flatnonzero(err.reshape(-1) != 0)
         assert bad.size == 0, "%s: %d entries differ from the exact result (first at flat index %d: got %r want %r)" % (
             what, bad.size, bad[0], got.reshape(-1)[bad[0]], ref.reshape(-1)[bad[0]])
         return 0.0
-    official = OFFICIAL_RTOL * G
+    official = OFFICIAL_RTOL * G + (2.0 ** -10 * np.abs(ref) if half_out else 0.0)
     tiny = np.finfo(np.float32).tiny
     worst = float(np.max(err / np.maximum(G, tiny))) if err.size else 0.0
     assert (err <= official + tiny).all(), "%s: official tolerance exceeded, max err/G = %g" % (what, worst)
-    tight = 4.0 * math.sqrt(max(K, 1)) * 2.0 ** -24 * G + 2.0 ** -22 * np.abs(ref) + tiny
+    tight = 4.0 * math.sqrt(max(K, 1)) * 2.0 ** -24 * G + 2.0 ** -22 * np.abs(ref) + tiny + (2.0 ** -10 * np.abs(ref) if half_out else 0.0)
     assert (err <= tight).all(), "%s: tight tolerance exceeded, max err/G = %g" % (what, worst)
     return worst
 
 
 def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alpha=1.0, beta=1.0, with_c=True,
                   bias_dim=None, act=fg.FG_ACT_NONE, ints=False, pad=0, config=1, samples: Optional[int] = None,
-                  inplace=False, device="cuda", seed=W.DEFAULT_SEED, bf16=False, ab_add=None, c_act=fg.FG_ACT_NONE):
-    """Run fg_gemm on seeded inputs and compare with the oracle.  ``samples`` None: every entry."""
+                  inplace=False, device="cuda", seed=W.DEFAULT_SEED, bf16=False, ab_add=None, c_act=fg.FG_ACT_NONE,
+                  cd16=False):
+    """Run fg_gemm on seeded inputs and compare with the oracle.  ``samples`` None: every entry.
+    ``cd16``: C and D are stored as binary16 (any leading dimension)."""
     dt = torch.bfloat16 if bf16 else torch.float16
     odt = O.BF16 if bf16 else O.F16
     A, lda = make_operand(M, K, la, W.stream_id(config, "A"), device, ints, pad, seed, dt)
     B, ldb = make_operand(K, N, lb, W.stream_id(config, "B"), device, ints, pad, seed, dt)
     lead, other = (M, N) if ld_layout == fg.FG_COL else (N, M)
     ldc = (lead + 3) // 4 * 4 + (4 if pad else 0)   # leading dimensions of FP32 operands are multiples of 4
-    Cbuf = make_f32(ldc * other, W.stream_id(config, "C"), device, ints, seed) if with_c else None
+    cd_dtype = torch.float32
+    if cd16:
+        ldc = lead + (3 if pad else 0)
+        cd_dtype = torch.float16
+    gen_cd = W.small_ints if ints else W.uniform_pm1
+    Cbuf = gen_cd(ldc * other, W.stream_id(config, "C"), seed=seed, device=device, dtype=cd_dtype) if with_c else None
     bias = None
     if bias_dim is not None:
         bias = make_f32(M if bias_dim == 0 else N, W.stream_id(config, "bias"), device, ints, seed)
-    Dbuf = Cbuf if (inplace and with_c) else torch.full((ldc * other,), float("nan"), dtype=torch.float32, device=device)
+    Dbuf = Cbuf if (inplace and with_c) else torch.full((ldc * other,), float("nan"), dtype=cd_dtype, device=device)
     C_host = np16(Cbuf).copy() if with_c else None
     fg.fg_gemm(M, N, K, alpha, fg.Matrix(A, la, lda), fg.Matrix(B, lb, ldb), beta,
                fg.Matrix(Cbuf, ld_layout, ldc) if with_c else None, fg.Matrix(Dbuf, ld_layout, ldc),
@@ -120,7 +135,7 @@ def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alph
                ab_add=ab_add, c_act=c_act)
     got = Dlog if at is None else Dlog[at[0], at[1]]
     what = ("bf16 " if bf16 else "") + ("ab_add=%r c_act=%d " % (ab_add, c_act) if (ab_add or c_act) else "") + "gemm M=%d N=%d K=%d A=%d B=%d D=%d alpha=%g beta=%g ints=%s" % (M, N, K, la, lb, ld_layout, alpha, beta, ints)
-    return compare(got, r["D"], r["G"], K, ints, what)
+    return compare(got, r["D"], r["G"], K, ints, ("f16 C,D " if cd16 else "") + what, half_out=cd16)
 
 
 def run_unaligned_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alpha=1.0, beta=1.0, with_c=True,

@@ -77,6 +77,34 @@ def test_gemm_argument_errors():
     assert status(256, 256, 256, 1.0, A, B, 0.0, None, D, act=9) == fg.FG_ERR_LAYOUT
 
 
+def test_binary16_c_and_d_rules():
+    """C and D stored as binary16: accepted for real FG_F16 products with any leading dimension of
+    C and D; C and D must agree in type; no K split (the reduction pass writes FP32), no general
+    kernel, no BF16 inputs, no planar complex."""
+    import torch
+    A, B, D = mats()
+    Dh = fg.Matrix(FakeTensor(0x3002, torch.float16), fg.FG_COL, 259)      # odd ld, 2-byte aligned pointer
+    Ch = fg.Matrix(FakeTensor(0x7002, torch.float16), fg.FG_COL, 301)
+    assert status(256, 256, 256, 1.0, A, B, 1.0, fg.Matrix(D.re, fg.FG_COL, 256), Dh) == fg.FG_ERR_UNSUPPORTED   # FP32 C, binary16 D
+    assert "same element type" in fg.fg_last_error()
+    assert status(256, 256, 256, 1.0, A, B, 1.0, Ch, D) == fg.FG_ERR_UNSUPPORTED
+    assert status(256, 256, 250, 1.0, A, B, 1.0, Ch, Dh) == fg.FG_ERR_UNSUPPORTED          # K % 8: no general kernel
+    assert "general kernel" in fg.fg_last_error()
+    assert status(256, 256, 256, 1.0, A, B, 1.0, Ch, fg.Matrix(FakeTensor(0x3001, torch.float16), fg.FG_COL, 256)) == fg.FG_ERR_ALIGN
+    Ab, Bb, _ = mats()
+    Ab.dtype = Bb.dtype = fg.FG_BF16
+    assert status(256, 256, 256, 1.0, Ab, Bb, 0.0, None, Dh) == fg.FG_ERR_UNSUPPORTED
+    im = lambda m: fg.Matrix(m.re, m.layout, m.ld, im=m.re)
+    assert status(256, 256, 256, 1.0, im(A), im(B), 0.0, None, im(Dh)) == fg.FG_ERR_UNSUPPORTED
+    assert status(256, 256, 256, 1.0, A, B, 0.0, None, Dh, a_add=0.5) == fg.FG_ERR_UNSUPPORTED
+    assert fg.fg_gemm_plan(8192, 8192, 8192, variant=fg.FG_PLAN_REAL_F16_CD) == "gemm_h16_nn_256x256x64"
+    assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_ROW, fg.FG_ROW, fg.FG_ROW, variant=fg.FG_PLAN_REAL_F16_CD) == "gemm_h16_nn_256x256x64"
+    assert "+" not in fg.fg_gemm_plan(512, 512, 8192, variant=fg.FG_PLAN_REAL_F16_CD)
+    assert "+" not in fg.fg_gemm_plan(4100, 4100, 4096, variant=fg.FG_PLAN_REAL_F16_CD)
+    with pytest.raises(fg.FlexGemmError):
+        fg.fg_gemm_plan(128, 64, 60, variant=fg.FG_PLAN_REAL_F16_CD)
+
+
 def test_empty_problem_is_ok_without_a_gpu():
     A, B, D = mats(M=0)
     assert status(0, 256, 256, 1.0, A, B, 0.0, None, D) == fg.FG_OK

@@ -267,6 +267,22 @@ def test_every_entry_of_large_multi_tile_launches():
     run_gemm_case(4096, 8192, 128, fg.FG_ROW, fg.FG_ROW, ints=True, bias_dim=1, act=fg.FG_ACT_RELU)
 
 
+def test_c_and_d_stored_as_binary16():
+    """The type-conversion transform (Section 4.2.3): C and D live in memory as binary16, are
+    widened when loaded and rounded to nearest even when stored, the arithmetic stays FP32.
+    Integer data: every entry must equal the exact result rounded once to binary16."""
+    for la, lb in itertools.product((fg.FG_COL, fg.FG_ROW), repeat=2):
+        say("f16 C,D ints, layouts A=%d B=%d, ragged 300x200x256" % (la, lb))
+        run_gemm_case(300, 200, 256, la, lb, ints=True, cd16=True)
+    say("row-major C and D, odd leading dimension, bias along N, ReLU"); run_gemm_case(260, 190, 128, fg.FG_ROW, fg.FG_COL, ld_layout=fg.FG_ROW, ints=True, cd16=True, pad=8, bias_dim=1, act=fg.FG_ACT_RELU)
+    say("no C, bias along M"); run_gemm_case(512, 256, 512, ints=True, cd16=True, with_c=False, bias_dim=0)
+    say("in place, ReLU on C, beta = -3"); run_gemm_case(256, 384, 192, ints=True, cd16=True, inplace=True, c_act=fg.FG_ACT_RELU, beta=-3.0)
+    say("every entry of a launch with two tiles per workgroup"); run_gemm_case(4096, 8192, 64, ints=True, cd16=True, samples=200000)
+    say("floats, 1024x768x2048"); run_gemm_case(1024, 768, 2048, cd16=True, alpha=0.5, beta=-2.0)
+    say("floats, 4096^3 sampled (the 256x256 tile)"); run_gemm_case(4096, 4096, 4096, fg.FG_COL, fg.FG_ROW, cd16=True, samples=4000)
+    say("small tiles"); run_gemm_case(64, 72, 64, ints=True, cd16=True)
+
+
 def test_operands_larger_than_2_gib():
     """A (then B) alone spans more than 2 GiB, once with K along columns and once along rows:
     the panels of the later tiles and the later K steps start beyond the reach of a 32-bit byte

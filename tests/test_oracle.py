@@ -493,3 +493,40 @@ def test_interleaved_complex_matches_complex128_matmul(la, lb, lc):
     r2 = O.gemm(M, N, K, 0.5, Operand(Ar, la, lda, Ai), Operand(Br, lb, ldb, Bi), -2.0,
                 np.ascontiguousarray(Cr.T if lc == COL else Cr).reshape(-1), np.ascontiguousarray(Ci.T if lc == COL else Ci).reshape(-1), lc, ldc)
     assert np.array_equal(r["D"], r2["D"]) and np.array_equal(r["D_im"], r2["D_im"])
+
+
+def test_round_array_to_half_matches_an_independent_conversion():
+    """The rounding applied to results stored as binary16, against numpy's own double -> half
+    conversion (an independent implementation of round-to-nearest-even): random values over the
+    whole exponent range, exact ties at every scale, the subnormal range, and values at and
+    beyond the largest finite binary16 number."""
+    rng = np.random.default_rng(7)
+    x = np.concatenate([
+        rng.standard_normal(4000) * 10.0 ** rng.integers(-9, 5, 4000),
+        (np.arange(1, 4097) + 0.5) * 2.0 ** -3,                     # ties between neighbours, ulp 2^-3 .. 2^-1
+        (2048 + np.arange(0, 600)) * 1.0 + 0.0,                      # integers above 2048: every other one is a tie
+        np.arange(-40, 40) * 2.0 ** -25,                             # around the smallest subnormal 2^-24
+        np.array([65504.0, 65519.99, 65520.0, 65535.0, 1e6, -65520.0, 0.0, -0.0]),
+    ])
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).astype(np.float64)
+    got = O.round_array_to_half(x)
+    assert np.array_equal(got, want)
+    assert np.array_equal(np.signbit(got), np.signbit(want))
+
+
+def test_gemm_with_binary16_c_uses_the_stored_values():
+    """C stored as binary16 is widened exactly: with A = I the result is alpha B + beta C on the
+    binary16 values of C, and the same problem with C widened by hand gives the same numbers."""
+    n = 24
+    rng = np.random.default_rng(3)
+    A = np.eye(n, dtype=np.float16)
+    B = rng.uniform(-1, 1, (n, n)).astype(np.float16)
+    Ch = rng.uniform(-4, 4, n * n).astype(np.float16)
+    r = O.gemm(n, n, n, 2.0, O.Operand(A.T.copy().reshape(-1), O.COL, n), O.Operand(B.T.copy().reshape(-1), O.COL, n),
+               -0.5, Ch, None, O.COL, n)
+    want = 2.0 * B.astype(np.float64) - 0.5 * Ch.astype(np.float64).reshape(n, n).T
+    assert np.array_equal(r["D"], want)
+    r32 = O.gemm(n, n, n, 2.0, O.Operand(A.T.copy().reshape(-1), O.COL, n), O.Operand(B.T.copy().reshape(-1), O.COL, n),
+                 -0.5, Ch.astype(np.float32), None, O.COL, n)
+    assert np.array_equal(r["D"], r32["D"]) and np.array_equal(r["G"], r32["G"])
