@@ -610,10 +610,15 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
         __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(Db + (m_base + (int64_t)n_base * p.ldd) * ES), 0, 0x7fffffff, 0x00020000);
         const bool interior = m_base + Cfg::WTM <= p.M && n_base + Cfg::WTN <= p.N;
         if (interior) {
-            // The C values of accumulator b+1 are requested before accumulator b is stored, so a
-            // batch of loads never queues behind the previous stores.
+            // Per accumulator (a batch of 16 values): the C values of the batch after next are
+            // requested, the 16 results of this batch are computed, then their 16 stores go out
+            // together.  Measured on 8192^3 against computing and storing value by value with one
+            // batch of C requested ahead: +3 % (two batches ahead: +0.6 % of that).  Loads and
+            // stores complete in issue order as far as the wave's counter can tell, so a batch of C
+            // only counts as arrived once every store issued before its request is acknowledged;
+            // two batches ahead, that is the stores of three batches ago.
             constexpr int NB = Cfg::TI * Cfg::TJ;
-            constexpr int AHEAD = 1;                        // batches of C requested ahead of their use
+            constexpr int AHEAD = 2;                        // batches of C requested ahead of their use
             float cv[AHEAD + 1][16];
             auto load_c = [&](int b, float (&dst)[16]) {
                 const int i = b / Cfg::TJ, j = b % Cfg::TJ;
@@ -641,16 +646,19 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
 #pragma unroll
                     for (int r = 0; r < 16; ++r) bv[r] = p.bias[n_base + 32 * j + 8 * (r >> 2) + 4 * lh + (r & 3)];
                 }
+                float y[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    float y = p.alpha * acc[i][j][r] + bv[r];
+                    float v = p.alpha * acc[i][j][r] + bv[r];
                     if constexpr (HAS_C) {
                         const float c = cv[b % (AHEAD + 1)][r];
-                        y += p.beta * (c > floor_c ? c : floor_c);
+                        v += p.beta * (c > floor_c ? c : floor_c);
                     }
-                    y = y > floor_v ? y : floor_v;
-                    store_cd<H, kStream>(y, rd, voff_d, 32 * ES * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4);
+                    y[r] = v > floor_v ? v : floor_v;
                 }
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    store_cd<H, kStream>(y[r], rd, voff_d, 32 * ES * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4);
             }
         } else {
             // a tile that hangs over the edge of D: rows m >= M are masked per lane (their offset is
