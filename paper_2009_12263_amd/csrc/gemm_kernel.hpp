@@ -734,26 +734,39 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 col4[r] = (uint32_t)__builtin_amdgcn_ds_bpermute((8 * (r >> 2) + (r & 3) + 4 * lh) * 4, (int)col_of_lane);
-#pragma unroll
-            for (int i = 0; i < Cfg::TI; ++i) {
-                // both parts are below 2^31 when in range; if either is out of range the sum must not
-                // wrap back into range
-                uint32_t off[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) off[r] = ((row4[i] | col4[r]) & kOutOfRange) ? kOutOfRange : row4[i] + col4[r];
-                float cv[16];
+            // both parts are below 2^31 when in range; if either is out of range the sum must not
+            // wrap back into range (formed again for the store rather than kept: registers are short here)
+            auto offset = [&](int i, int r) { return ((row4[i] | col4[r]) & kOutOfRange) ? kOutOfRange : row4[i] + col4[r]; };
+            // As in the matrix epilogue: the 16 stores of an accumulator go out together, and, where
+            // registers allow (the smaller tiles), the C values of the next accumulator of this
+            // column block are requested before this one's results are computed.
+            constexpr int AHEAD = (Cfg::TI * Cfg::TJ <= 4) ? 1 : 0;
+            float cv[AHEAD + 1][16];
+            auto load_c = [&](int i) {
                 if constexpr (HAS_C) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        cv[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, off[r], 0, kStream));
+                        cv[i % (AHEAD + 1)][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, offset(i, r), 0, kStream));
                 }
+            };
+            if constexpr (AHEAD == 1) load_c(0);
+#pragma unroll
+            for (int i = 0; i < Cfg::TI; ++i) {
+                if constexpr (AHEAD == 1) {
+                    if (i + 1 < Cfg::TI) load_c(i + 1);
+                } else {
+                    load_c(i);
+                }
+                float y[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    float y = p.alpha * acc[i][j][r];
-                    if constexpr (HAS_C) y += p.beta * cv[r];
-                    y = y > floor_v ? y : floor_v;
-                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y), rd, off[r], 0, kStream);
+                    float v = p.alpha * acc[i][j][r];
+                    if constexpr (HAS_C) v += p.beta * cv[i % (AHEAD + 1)][r];
+                    y[r] = v > floor_v ? v : floor_v;
                 }
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, y[r]), rd, offset(i, r), 0, kStream);
             }
         }
     }
