@@ -31,7 +31,7 @@ MFMA_FP16_PEAK_TFLOPS = 2500.0     # MI355X dense FP16 MFMA, published (2.5 PFLO
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a
 # plain copy kernel of known size (factors 2.0 and 1.0): profiles/gemm_nn_8192_pmc.md.  Only
 # meaningful for the default workload.
-MEASURED_HBM_TRAFFIC_BYTES = 2.273e9
+MEASURED_HBM_TRAFFIC_BYTES = 2.681e9
 
 
 def cpu_baseline(M, N, K, A, lda, B, ldb, C, ldc, budget_s=15.0):
