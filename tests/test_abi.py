@@ -21,6 +21,37 @@ def test_library_exports_every_declared_symbol():
     assert fg.fg_version() >= 100
 
 
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 (and as C++), and a C program that only
+    includes it links against the shared library and can make the calls that need no GPU."""
+    import shutil
+    import subprocess
+    if not shutil.which("gcc"):
+        pytest.skip("no host C compiler")
+    src = tmp_path / "use.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "flexgemm.h"\n'
+        "int main(void) {\n"
+        "    char name[64];\n"
+        "    fg_matrix m; m.re = 0; m.im = 0; m.dtype = FG_F16; m.layout = FG_COL; m.ld = 8;\n"
+        "    if (fg_version() < 100) return 1;\n"
+        "    if (fg_gemm_plan(8192, 8192, 8192, FG_COL, FG_COL, FG_COL, FG_PLAN_REAL, name, (int32_t)sizeof name) != FG_OK) return 2;\n"
+        "    if (fg_gemm(8, 8, 8, 1.0f, 0, &m, 0.0f, 0, &m, 0, 0) != FG_ERR_NULL) return 3;\n"
+        '    printf("%s|%s\\n", name, fg_last_error());\n'
+        "    return 0;\n}\n")
+    inc = os.path.join(ROOT, "include")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-fsyntax-only", str(src)])
+    if shutil.which("g++"):
+        subprocess.check_call(["g++", "-std=c++11", "-Wall", "-I", inc, "-fsyntax-only", "-x", "c++", str(src)])
+    exe = tmp_path / "use"
+    libdir = os.path.dirname(fg.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-l:libflexgemm.so", "-Wl,-rpath," + libdir])
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, out
+    plan, err = out.stdout.strip().split("|")
+    assert plan == "gemm_nn_256x256x64" and "A is NULL" in err
+
+
 class FakeTensor:
     """Stands in for a device tensor: the library only looks at the pointer value before launch."""
     def __init__(self, ptr, dtype):
