@@ -102,15 +102,16 @@ const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
 // share a unit and one for a workgroup that has a unit to itself.  Edge tiles are predicated, so
 // a tile need not divide the problem.  K is split only when the output has too few tiles to fill
 // the GPU and K is long (may_split: plain real products).
-Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_smallest = true, int64_t batches = 1) {
-    static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64};
-    static const int bn[fg::TILE_COUNT] = {256, 128, 128, 64};
-    static const int per_cu[fg::TILE_COUNT] = {1, 1, 2, 4};
-    static const double rate_shared[fg::TILE_COUNT] = {1.0, 0.8, 0.73, 0.45};
-    static const double rate_alone[fg::TILE_COUNT] = {1.0, 0.8, 0.43, 0.17};
+Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_smallest = true, int64_t batches = 1,
+                 bool allow_deep = true) {
+    static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64, 128};
+    static const int bn[fg::TILE_COUNT] = {256, 128, 128, 64, 128};
+    static const int per_cu[fg::TILE_COUNT] = {1, 1, 2, 4, 1};
+    static const double rate_shared[fg::TILE_COUNT] = {1.0, 0.8, 0.73, 0.45, 0.51};
+    static const double rate_alone[fg::TILE_COUNT] = {1.0, 0.8, 0.43, 0.17, 0.51};
     static const int split_options[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
     constexpr double cu_flops = 4.7e12, round_fixed = 2e-6, cu_cd_bw = 25e9, reduce_launch = 6e-6, reduce_bw = 3e12;
-    // tuning aids: FG_FORCE_TILE=0..3 picks a tile shape, FG_FORCE_SPLIT=n a split of K for every
+    // tuning aids: FG_FORCE_TILE=0..4 picks a tile shape, FG_FORCE_SPLIT=n a split of K for every
     // tile, FG_FORCE_TAIL=n a split of K for the tiles of the last round (1: never)
     int force_tile = -1, force_split = 0, force_tail = 0;
     if (const char *f = getenv("FG_FORCE_TILE")) { int t = atoi(f); if (t >= 0 && t < fg::TILE_COUNT) force_tile = t; }
@@ -119,18 +120,24 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_sma
     const int64_t nk = (K + 63) / 64;                       // K tiles (every real kernel has BK = 64)
     Plan best{0, 1, 1};
     double best_cost = -1;
-    const int ntypes = allow_smallest ? fg::TILE_COUNT : fg::TILE_COUNT - 1;
-    for (int t = 0; t < ntypes; ++t) {
+    for (int t = 0; t < fg::TILE_COUNT; ++t) {
         if (force_tile >= 0 && t != force_tile) continue;
+        if (t == fg::TILE_64x64 && !allow_smallest) continue;
+        if (t == fg::TILE_128x128_DEEP && !allow_deep) continue;
         const int64_t tiles = ((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]) * batches;
         const int64_t slots = (int64_t)kNumCU * per_cu[t];
         const int64_t slot_bytes = (int64_t)bm[t] * bn[t] * 4;
         auto share_time = [&](int64_t wgs, int S) {     // one workgroup on 1/S of K, plus its epilogue
-            const bool shared = wgs > kNumCU;
-            const double rate = shared ? rate_shared[t] / per_cu[t] : rate_alone[t];
+            // workgroups that share a compute unit at a time: a unit's rate grows linearly from the
+            // lone-workgroup rate to the rate with every slot taken, and is divided among them
+            int64_t n = (wgs + kNumCU - 1) / kNumCU;
+            if (n > per_cu[t]) n = per_cu[t];
+            const double unit_rate = per_cu[t] == 1 ? rate_alone[t]
+                                   : rate_alone[t] + (rate_shared[t] - rate_alone[t]) * (double)(n - 1) / (per_cu[t] - 1);
+            const double rate = unit_rate / (double)n;
             // the C read and D write of a tile stream at what one compute unit gets of the memory
             // bandwidth, divided among the workgroups that share the unit
-            const double epilogue = round_fixed + (shared ? per_cu[t] : 1) * 8.0 * bm[t] * bn[t] / cu_cd_bw;
+            const double epilogue = round_fixed + (double)n * 8.0 * bm[t] * bn[t] / cu_cd_bw;
             return 2.0 * bm[t] * bn[t] * (double)((nk + S - 1) / S) * 64 / (cu_flops * rate) + epilogue;
         };
         auto reduce_time = [&](int64_t ntile, int S) { return reduce_launch + (2.0 * S + 2.0) * (double)ntile * slot_bytes / reduce_bw; };
@@ -186,7 +193,7 @@ const fg::KernelEntry *select_kernel(const Problem &q, Plan *plan_out = nullptr)
         return &(q.dual ? fg::kernel_table_dual() : fg::kernel_table_cplx())[t * 4 + v];
     }
     const bool may_split = plan_out && !q.a_diag && !q.b_diag && !q.cd16;   // the reduction pass writes FP32
-    const Plan plan = choose_plan(q.M, q.N, q.K, may_split);
+    const Plan plan = choose_plan(q.M, q.N, q.K, may_split, true, 1, !q.a_diag && !q.b_diag);
     const int tile = plan.tile;
     if (plan_out) *plan_out = plan;
     if (q.a_diag) return &fg::kernel_table_diag()[tile * 4 + (q.b_kc ? 0 : 1)];
@@ -604,13 +611,14 @@ fg_status fg_init(void) {
         {fg::kernel_table_tn_xf(), fg::TILE_COUNT}, {fg::kernel_table_tt_xf(), fg::TILE_COUNT},
         {fg::kernel_table_nn_h16(), fg::TILE_COUNT}, {fg::kernel_table_nt_h16(), fg::TILE_COUNT},
         {fg::kernel_table_tn_h16(), fg::TILE_COUNT}, {fg::kernel_table_tt_h16(), fg::TILE_COUNT},
-        {fg::kernel_table_diag(), fg::TILE_COUNT * 4},
+        {fg::kernel_table_diag(), fg::DIAG_TILE_COUNT * 4},
         {fg::kernel_table_cplx(), fg::CTILE_COUNT * 4}, {fg::kernel_table_dual(), fg::CTILE_COUNT * 4},
         {fg::kernel_table_cplx_il(), fg::CTILE_COUNT * 4},
     };
     for (auto &tb : tables)
         for (int i = 0; i < tb.n; ++i) {
             int per_cu = 0;
+            if (!tb.t[i].fn) continue;          // a variant that is not built for this tile
             if (fg_status st = prepare(tb.t[i], dev, per_cu)) return st;
         }
     float *ws = nullptr;
@@ -784,7 +792,7 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
     // A result that is not contiguous along the leading row mode is stored in short pieces; the
     // smallest tile makes them shorter still (measured on the paper's D_abc = A_bda B_dc).
     const bool rows_contiguous = c.c_m.n == 0 || c.c_m.stride[0] == 1;
-    const int tile = choose_plan(c.M, c.N, c.K, false, rows_contiguous || c.M < 128 || c.N < 128, c.batches).tile;
+    const int tile = choose_plan(c.M, c.N, c.K, false, rows_contiguous || c.M < 128 || c.N < 128, c.batches, false).tile;
     // The result streams past the L2 only if every store of 32 consecutive rows is one whole,
     // aligned 128-byte line: leading row mode contiguous with an extent that is a multiple of 32,
     // every other stride of C and its base a multiple of 32 elements.
@@ -796,6 +804,7 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
                           whole_lines(c.c_n, 0) && whole_lines(c.c_b, 0) && (uintptr_t)Cout % 128 == 0 &&
                           (!Cin || (uintptr_t)Cin % 128 == 0);
     const fg::KernelEntry &k = table_for(c.a_kc, c.b_kc)[fg::entry_index(tile, c_stream ? fg::VARIANT_CONTRACT_STREAM : fg::VARIANT_CONTRACT)];
+    if (!k.fn) return fail(FG_ERR_UNSUPPORTED, "internal: no contraction kernel for tile %d", tile);
     fg::GemmParams p;
     memset(&p, 0, sizeof p);
     p.M = (int32_t)c.M; p.N = (int32_t)c.N; p.K = (int32_t)c.K;

@@ -7,7 +7,7 @@ namespace fg {
     FG_ENTRY_X(BM, BN, 64, 2, WGM, WGN, true, true, 2, 0, "gemm_t_diagB_" TAG),                \
     FG_ENTRY_X(BM, BN, 64, 2, WGM, WGN, false, true, 2, 0, "gemm_n_diagB_" TAG)
 const KernelEntry *kernel_table_diag() {
-    static const KernelEntry t[TILE_COUNT * 4] = {
+    static const KernelEntry t[DIAG_TILE_COUNT * 4] = {
         FG_DIAG_TILE(256, 256, 2, 4, "256x256x64"),
         FG_DIAG_TILE(256, 128, 4, 2, "256x128x64"),
         FG_DIAG_TILE(128, 128, 2, 2, "128x128x64"),

@@ -5,7 +5,11 @@
 
 namespace fg {
 
-enum TileId { TILE_256x256 = 0, TILE_256x128 = 1, TILE_128x128 = 2, TILE_64x64 = 3, TILE_COUNT = 4 };
+// TILE_128x128_DEEP: the 128x128 tile with a ring of four buffers (128 KB of LDS, one workgroup per
+// compute unit), for outputs of at most one such tile per unit: a lone 4-wave workgroup turns a K
+// tile over in 512 cycles, too fast for a two-buffer ring to cover the memory latency.
+enum TileId { TILE_256x256 = 0, TILE_256x128 = 1, TILE_128x128 = 2, TILE_64x64 = 3, TILE_128x128_DEEP = 4, TILE_COUNT = 5,
+              DIAG_TILE_COUNT = 4 };
 
 struct KernelEntry {
     void (*fn)(const GemmParams);
@@ -102,6 +106,7 @@ inline int entry_index(int tile, int variant) { return tile * VARIANT_COUNT + va
             FG_ENTRY_BF16(256, 128, 64, 2, 4, 2, AKC, BKC, "gemm_bf16_" TAG "_256x128x64"),        \
             FG_ENTRY_BF16(128, 128, 64, 2, 2, 2, AKC, BKC, "gemm_bf16_" TAG "_128x128x64"),        \
             FG_ENTRY_BF16(64, 64, 64, 2, 2, 2, AKC, BKC, "gemm_bf16_" TAG "_64x64x64"),            \
+            FG_ENTRY_BF16(128, 128, 64, 4, 2, 2, AKC, BKC, "gemm_bf16_" TAG "_128x128x64_deep"),   \
         };                                                                                         \
         return t;                                                                                  \
     }
@@ -119,6 +124,7 @@ inline int entry_index(int tile, int variant) { return tile * VARIANT_COUNT + va
             FG_ENTRY_H16(256, 128, 64, 2, 4, 2, AKC, BKC, "gemm_h16_" TAG "_256x128x64"),          \
             FG_ENTRY_H16(128, 128, 64, 2, 2, 2, AKC, BKC, "gemm_h16_" TAG "_128x128x64"),          \
             FG_ENTRY_H16(64, 64, 64, 2, 2, 2, AKC, BKC, "gemm_h16_" TAG "_64x64x64"),              \
+            FG_ENTRY_H16(128, 128, 64, 4, 2, 2, AKC, BKC, "gemm_h16_" TAG "_128x128x64_deep"),     \
         };                                                                                         \
         return t;                                                                                  \
     }
@@ -136,6 +142,7 @@ inline int entry_index(int tile, int variant) { return tile * VARIANT_COUNT + va
             FG_ENTRY_XF(256, 128, 64, 2, 4, 2, AKC, BKC, "gemm_abadd_" TAG "_256x128x64"),         \
             FG_ENTRY_XF(128, 128, 64, 2, 2, 2, AKC, BKC, "gemm_abadd_" TAG "_128x128x64"),         \
             FG_ENTRY_XF(64, 64, 64, 2, 2, 2, AKC, BKC, "gemm_abadd_" TAG "_64x64x64"),             \
+            FG_ENTRY_XF(128, 128, 64, 4, 2, 2, AKC, BKC, "gemm_abadd_" TAG "_128x128x64_deep"),    \
         };                                                                                         \
         return t;                                                                                  \
     }
@@ -166,6 +173,8 @@ inline int entry_index(int tile, int variant) { return tile * VARIANT_COUNT + va
             FG_ENTRY(64, 64, 64, 2, 2, 2, AKC, BKC, false, "gemm_" TAG "_64x64x64"),               \
             FG_ENTRY(64, 64, 64, 2, 2, 2, AKC, BKC, true, "gett_" TAG "_64x64x64"),                \
             FG_ENTRY_GS(64, 64, 64, 2, 2, 2, AKC, BKC, "gett_stream_" TAG "_64x64x64"),            \
+            FG_ENTRY(128, 128, 64, 4, 2, 2, AKC, BKC, false, "gemm_" TAG "_128x128x64_deep"),      \
+            /* no contraction variants of the deep tile (measured: no faster there): entries stay empty */ \
         };                                                                                         \
         return t;                                                                                  \
     }

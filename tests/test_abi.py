@@ -144,8 +144,11 @@ def test_empty_problem_is_ok_without_a_gpu():
 def test_plan_names_follow_sizes_and_layouts():
     assert fg.fg_gemm_plan(8192, 8192, 8192) == "gemm_nn_256x256x64"
     assert fg.fg_gemm_plan(8192, 1024, 4096) == "gemm_nn_256x128x64"
-    # 2048^2 outputs: 1024 small tiles (four workgroups per compute unit) beat 256 medium ones
-    assert fg.fg_gemm_plan(2048, 2048, 2048, fg.FG_ROW, fg.FG_COL) == "gemm_tn_64x64x64"
+    # 2048^2 outputs: 256 medium tiles, one per compute unit, with the ring of four buffers that a
+    # workgroup alone on its unit needs to cover the memory latency
+    assert fg.fg_gemm_plan(2048, 2048, 2048, fg.FG_ROW, fg.FG_COL) == "gemm_tn_128x128x64_deep"
+    assert fg.fg_gemm_plan(1024, 1024, 1024) == "gemm_nn_64x64x64"
+    assert fg.fg_gemm_plan(4096, 2048, 2048) == "gemm_nn_256x128x64"        # 512 medium tiles would share units: two buffers
     # 4100^2: 289 big tiles are one full round of 256 plus 33 leftover tiles, which are split over K
     assert fg.fg_gemm_plan(4100, 4100, 4096) == "gemm_nn_256x256x64+tailsplitk4"
     assert fg.fg_gemm_plan(256, 256, 256, fg.FG_COL, fg.FG_ROW) == "gemm_nt_64x64x64"

@@ -51,6 +51,19 @@ def test_result_contiguous_along_the_second_row_mode():
     say("B also a tensor, floats"); run_contract_case({a: 24, b: 16, c: 8, d: 64, e: 5, f: 2}, [b, d, a, f], [d, f, c, e], [a, b, c, e], alpha=0.5, beta=-2.0)
 
 
+def test_every_tile_shape_in_the_contraction_kernels(monkeypatch):
+    """The four block tiles of the contraction kernels forced in turn on contractions with a
+    contiguous result (streaming stores), a permuted one, batch modes and a C operand: integer
+    data, every entry exact."""
+    for tile in range(4):
+        monkeypatch.setenv("FG_FORCE_TILE", str(tile))
+        say("tile %d" % tile)
+        run_contract_case({a: 64, b: 72, c: 5, d: 192}, [a, d, c], [d, b], [a, b, c], ints=True)
+        run_contract_case({a: 12, b: 16, c: 40, d: 320}, [b, d, a], [d, c], [a, b, c], ints=True, beta=1.0)
+        run_contract_case({a: 40, b: 24, c: 3, d: 128, e: 2}, [a, d, c, e], [d, e, b], [a, e, b, c], ints=True, alpha=2.0, beta=-1.0)
+    monkeypatch.delenv("FG_FORCE_TILE")
+
+
 def test_ragged_extents_every_entry():
     """Row and column extents that no block tile divides: edge tiles of the strided kernels are
     predicated in the loads (zeros) and in the stores (dropped)."""

@@ -283,6 +283,30 @@ def test_c_and_d_stored_as_binary16():
     say("small tiles"); run_gemm_case(64, 72, 64, ints=True, cd16=True)
 
 
+def test_every_tile_shape_in_every_kernel_family(monkeypatch):
+    """Each of the five block tiles (256x256, 256x128, 128x128, 64x64 and the 128x128 tile with a
+    ring of four buffers) forced in turn on one ragged problem, for the plain, BF16, A/B-addition
+    and binary16-result kernels and all four layout pairs: integer data, every entry exact.  The
+    deep-ring tile is also run over a K that is shorter than its ring and with K split."""
+    for tile in range(5):
+        monkeypatch.setenv("FG_FORCE_TILE", str(tile))
+        for la, lb in itertools.product((fg.FG_COL, fg.FG_ROW), repeat=2):
+            say("tile %d layouts A=%d B=%d: plain, bf16, ab_add, f16 C,D" % (tile, la, lb))
+            run_gemm_case(300, 264, 448, la, lb, ints=True, bias_dim=0)
+            run_gemm_case(300, 264, 448, la, lb, ints=True, bf16=True)
+            run_gemm_case(300, 264, 192, la, lb, ints=True, ab_add=(1.0, -2.0), c_act=fg.FG_ACT_RELU)
+            run_gemm_case(300, 264, 448, la, lb, ints=True, cd16=True, act=fg.FG_ACT_RELU)
+    monkeypatch.setenv("FG_FORCE_TILE", "4")
+    for K in (64, 128, 192, 256, 320):
+        say("deep ring, K = %d" % K); run_gemm_case(256, 384, K, ints=True)
+    monkeypatch.setenv("FG_FORCE_SPLIT", "3")
+    say("deep ring, K split in 3"); run_gemm_case(384, 256, 1536, fg.FG_ROW, fg.FG_COL, ints=True, bias_dim=1, act=fg.FG_ACT_RELU)
+    monkeypatch.delenv("FG_FORCE_SPLIT")
+    monkeypatch.delenv("FG_FORCE_TILE")
+    say("planner's own choice of the deep ring, floats"); assert "deep" in fg.fg_gemm_plan(2048, 2048, 2048)
+    run_gemm_case(2048, 2048, 2048, samples=4000)
+
+
 def test_operands_larger_than_2_gib():
     """A (then B) alone spans more than 2 GiB, once with K along columns and once along rows:
     the panels of the later tiles and the later K steps start beyond the reach of a 32-bit byte
