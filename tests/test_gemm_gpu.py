@@ -323,6 +323,27 @@ def test_operands_larger_than_2_gib():
     torch.cuda.empty_cache()
 
 
+def test_split_k_results_do_not_depend_on_arrival_order(monkeypatch):
+    """The K ranges of a tile are computed by workgroups on different XCDs and added up from the
+    workspace.  Many launches in a row on fresh data (a stale read would return a previous
+    launch's partial products), more work items than resident workgroups, many K ranges per tile
+    and ranges that are empty: integer data, every entry exact, every time."""
+    cases = [(512, 512, 4096, 3, 8), (640, 1152, 2048, 3, 5), (1100, 900, 1536, 3, 7), (256, 384, 8192, 2, 16),
+             (384, 256, 4096, 4, 6), (2100, 2112, 640, 3, 3), (128, 128, 576, 3, 4)]
+    for rep in range(4):
+        for (m, n, k, tile, S) in cases:
+            monkeypatch.setenv("FG_FORCE_TILE", str(tile))
+            monkeypatch.setenv("FG_FORCE_SPLIT", str(S))
+            assert ("+splitk%d" % S) in fg.fg_gemm_plan(m, n, k)
+            say("launch %d: %dx%dx%d tile %d split %d" % (rep, m, n, k, tile, S))
+            run_gemm_case(m, n, k, fg.FG_COL if rep % 2 else fg.FG_ROW, fg.FG_COL, ints=True, seed=1000 + 17 * rep + S,
+                          bias_dim=rep % 2, act=fg.FG_ACT_RELU if rep & 2 else fg.FG_ACT_NONE, beta=1.0 if rep % 3 else -2.0)
+    monkeypatch.delenv("FG_FORCE_TILE")
+    monkeypatch.delenv("FG_FORCE_SPLIT")
+    for rep in range(6):
+        say("planner's split, launch %d" % rep); run_gemm_case(512, 512, 8192, ints=True, seed=50 + rep)
+
+
 def test_tail_round_split(monkeypatch):
     """More tiles than the persistent grid holds at once, with a small remainder: the full rounds
     run as one pass and only the leftover tiles are split over K (plus the reduction pass).  Forced
