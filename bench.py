@@ -220,8 +220,8 @@ def main():
                          "so a counter profile of this command can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (the path shards without any exchange; "
-                 "see DESIGN.md); run with --gpus 1")
+        sys.exit("bench.py: this build runs on one GPU only (D's tiles are independent, so the path would shard "
+                 "over GPUs without any exchange, but that is not built); run with --gpus 1")
 
     import torch
     from paper_2009_12263_amd import binding as fg
