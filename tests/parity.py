@@ -2,7 +2,7 @@
 C ABI binding, evaluate the oracle (all entries, or a sample) and compare.
 
 Tolerances (written here once, used by every test):
-  * official bar (the benchmark spec of this build):
+  * official bar (the tolerance stated for this implementation):
         |D - D_ref| <= 2e-3 * (|alpha| (|A||B|)_ij + |beta| |C_ij|)            elementwise;
   * tight bar, derived from the arithmetic: FP16 x FP16 products are exact in FP32, so the only
     error is FP32 accumulation, at worst K * 2^-24 * G and in practice ~sqrt(K) * 2^-24 * G;
