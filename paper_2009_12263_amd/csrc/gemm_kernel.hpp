@@ -1000,8 +1000,16 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
             [[maybe_unused]] bool fetched = false;      // ILV: a K step is waiting in registers
             // one K tile; MORE: another tile follows (publish it, refill the ring, prefetch its
             // first fragments)
-            auto tile_body = [&](int kt, auto more_tag) {
+            // RA: the ring buffer this tile retires is refilled (tile kt+S exists); RB (spread
+            // refills): B's part of the previous tile's refill is still to be issued (tile kt-1+S
+            // exists and kt >= 1).  Passed as compile-time constants by the peeled loop below, so
+            // that the steady-state body is straight-line code (8192^3: +5 % over testing them per
+            // tile, whose booleans lived in vector registers between the MFMAs); the interleaved
+            // complex kernels, short of registers, test RA per tile as before.
+            auto tile_body = [&](int kt, auto more_tag, auto ra_tag, auto rb_tag) {
                 constexpr bool MORE = decltype(more_tag)::value;
+                const bool RA = Cfg::ILV ? (kt + S < nkt) : decltype(ra_tag)::value;
+                [[maybe_unused]] constexpr bool RB = decltype(rb_tag)::value;
                 const int cur = kt & (S - 1);
                 const int nxt = (kt + 1) & (S - 1);
                 FG_LDS const char *ta = lds_a + cur * Cfg::A_TILE_BYTES;
@@ -1027,13 +1035,13 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                         }
                         // tile kt+1 has landed (for this wave) and all of this wave's reads of tile
                         // kt have returned; after the barrier both hold for every wave
-                        if (kt + S < nkt) wait_tile<(S - 2) * L>(); else wait_tile<0>();
+                        if (RA) wait_tile<(S - 2) * L>(); else wait_tile<0>();
                         __builtin_amdgcn_s_barrier();
                         if constexpr (Cfg::ILV) {
-                            fetched = kt + S < nkt;
+                            fetched = RA;
                             if (fetched) { la[0].fetch(); lb[0].fetch(); }
                         } else
-                        if (kt + S < nkt) {
+                        if (RA) {
                             if constexpr (Cfg::SPREAD) {
                                 refill_a = true;
 #pragma unroll
@@ -1048,7 +1056,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                         }
                     }
                     if constexpr (Cfg::SPREAD) {
-                        if (ks == 0 && kt >= 1 && kt - 1 + S < nkt) {
+                        if (ks == 0 && RB) {
                             refill_b = true;
 #pragma unroll
                             for (int q = 0; q < P; ++q) lb[q].begin();
@@ -1147,8 +1155,20 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                     }
                 }
             };
-            for (int kt = 0; kt + 1 < nkt; ++kt) tile_body(kt, std::true_type{});
-            tile_body(nkt - 1, std::false_type{});
+            constexpr std::true_type T{};
+            constexpr std::false_type F{};
+            if constexpr (Cfg::ILV) {
+                for (int kt = 0; kt + 1 < nkt; ++kt) tile_body(kt, T, F, F);     // (RA is evaluated in the body)
+            } else
+            if (nkt > 1) {
+                if (S < nkt) tile_body(0, T, T, F); else tile_body(0, T, F, F);
+                int kt = 1;
+                for (; kt + S < nkt; ++kt) tile_body(kt, T, T, T);
+                for (; kt + 1 < nkt; ++kt) {            // at most S - 1 tiles: nothing left to refill with
+                    if (kt - 1 + S < nkt) tile_body(kt, T, F, T); else tile_body(kt, T, F, F);
+                }
+            }
+            tile_body(nkt - 1, F, F, F);
         }
 
         // next tile of this workgroup: once every wave has read its last fragments the LDS ring is
