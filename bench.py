@@ -31,7 +31,7 @@ MFMA_FP16_PEAK_TFLOPS = 2500.0     # MI355X dense FP16 MFMA, published (2.5 PFLO
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a
 # plain copy kernel of known size (factors 2.0 and 1.0): profiles/gemm_nn_8192_pmc.md.  Only
 # meaningful for the default workload.
-MEASURED_HBM_TRAFFIC_BYTES = 2.681e9
+MEASURED_HBM_TRAFFIC_BYTES = 2.175e9
 
 
 def cpu_baseline(M, N, K, A, lda, B, ldb, C, ldc, budget_s=15.0):
@@ -208,8 +208,11 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    # Defaults: the engine clock dips after the first few launches of a fresh process and takes about
+    # a hundred launches (0.1 s) to settle, so the default warm-up covers that and the timed region
+    # measures the steady state (see profiles/gemm_nn_8192_kernel_trace.md for the series).
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--size", type=int, default=8192, help="M = N = K of the timed GEMM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed-region extras (other layouts and configs)")
