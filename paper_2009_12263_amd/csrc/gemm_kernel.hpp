@@ -609,6 +609,88 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
             const_cast<char *>(HAS_C ? Cb + (m_base + (int64_t)n_base * p.ldc) * ES : Db), 0, 0x7fffffff, 0x00020000);
         __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(Db + (m_base + (int64_t)n_base * p.ldd) * ES), 0, 0x7fffffff, 0x00020000);
         const bool interior = m_base + Cfg::WTM <= p.M && n_base + Cfg::WTN <= p.N;
+        constexpr bool PAIR = H && Cfg::TI % 2 == 0;
+        if constexpr (PAIR) if (interior) {
+            // Accumulators i and i+1 of a column block taken together.  In the accumulator layout a
+            // store instruction covers 32 rows of column n (lower half-wave) and 32 rows of column
+            // n + 4 (upper half-wave): for binary16 that is two half lines.  Exchanging the upper
+            // half of accumulator i's register with the lower half of accumulator i+1's gives one
+            // register with 64 consecutive rows of column n and one with those of column n + 4, so
+            // that every instruction moves whole 128-byte lines; C arrives in that layout and the
+            // same exchange brings it back to the accumulators'.  Batches of 16 values (8 registers
+            // of each of the two accumulators), requested two batches ahead as below.
+            constexpr int NB = Cfg::TI * Cfg::TJ;
+            constexpr int AHEAD = 2;
+            const int voff_p = lane * ES;
+            float cv[AHEAD + 1][16];
+            auto load_c = [&](int b, float (&dst)[16]) {
+                const int ip = b / (2 * Cfg::TJ), j = (b >> 1) % Cfg::TJ, h = b & 1;
+#pragma unroll
+                for (int r8 = 0; r8 < 8; ++r8) {
+                    const int r = 8 * h + r8, col = 32 * j + 8 * (r >> 2) + (r & 3);
+                    dst[2 * r8] = load_cd<H, kStream>(rc, voff_p, 64 * ES * ip + col * ldc4);
+                    dst[2 * r8 + 1] = load_cd<H, kStream>(rc, voff_p, 64 * ES * ip + (col + 4) * ldc4);
+                }
+            };
+            auto exchange = [](float &x, float &y) {
+                // upper half of x <-> lower half of y.  The two words are copied out of the result
+                // before their bits are reinterpreted: a bit cast applied to an element of the
+                // vector itself compiled to a read of element 0 both times.
+                const auto s = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
+                const unsigned s0 = s[0], s1 = s[1];
+                x = __builtin_bit_cast(float, s0);
+                y = __builtin_bit_cast(float, s1);
+            };
+            float bias_m[Cfg::TI];
+#pragma unroll
+            for (int i = 0; i < Cfg::TI; ++i) bias_m[i] = bias_m_on ? p.bias[m_base + 32 * i + lm] : 0.f;
+            if constexpr (HAS_C) {
+#pragma unroll
+                for (int b = 0; b < AHEAD && b < NB; ++b) load_c(b, cv[b % (AHEAD + 1)]);
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int ip = b / (2 * Cfg::TJ), j = (b >> 1) % Cfg::TJ, h = b & 1;
+                if constexpr (HAS_C) {
+                    if (b + AHEAD < NB) load_c(b + AHEAD, cv[(b + AHEAD) % (AHEAD + 1)]);
+                }
+                float b0[8], b1[8];
+#pragma unroll
+                for (int r8 = 0; r8 < 8; ++r8) { b0[r8] = bias_m[2 * ip]; b1[r8] = bias_m[2 * ip + 1]; }
+                if (bias_n_on) {
+#pragma unroll
+                    for (int r8 = 0; r8 < 8; ++r8) {
+                        const int r = 8 * h + r8;
+                        b0[r8] = b1[r8] = p.bias[n_base + 32 * j + 8 * (r >> 2) + 4 * lh + (r & 3)];
+                    }
+                }
+                float y[16];
+#pragma unroll
+                for (int r8 = 0; r8 < 8; ++r8) {
+                    const int r = 8 * h + r8;
+                    float v0 = p.alpha * acc[2 * ip][j][r] + b0[r8];
+                    float v1 = p.alpha * acc[2 * ip + 1][j][r] + b1[r8];
+                    if constexpr (HAS_C) {
+                        float c0 = cv[b % (AHEAD + 1)][2 * r8], c1 = cv[b % (AHEAD + 1)][2 * r8 + 1];
+                        exchange(c0, c1);
+                        v0 += p.beta * (c0 > floor_c ? c0 : floor_c);
+                        v1 += p.beta * (c1 > floor_c ? c1 : floor_c);
+                    }
+                    v0 = v0 > floor_v ? v0 : floor_v;
+                    v1 = v1 > floor_v ? v1 : floor_v;
+                    exchange(v0, v1);
+                    y[2 * r8] = v0;
+                    y[2 * r8 + 1] = v1;
+                }
+#pragma unroll
+                for (int r8 = 0; r8 < 8; ++r8) {
+                    const int r = 8 * h + r8, col = 32 * j + 8 * (r >> 2) + (r & 3);
+                    store_cd<H, kStream>(y[2 * r8], rd, voff_p, 64 * ES * ip + col * ldd4);
+                    store_cd<H, kStream>(y[2 * r8 + 1], rd, voff_p, 64 * ES * ip + (col + 4) * ldd4);
+                }
+            }
+            return;
+        }
         if (interior) {
             // Per accumulator (a batch of 16 values): the C values of the batch after next are
             // requested, the 16 results of this batch are computed, then their 16 stores go out

@@ -283,6 +283,22 @@ def test_c_and_d_stored_as_binary16():
     say("small tiles"); run_gemm_case(64, 72, 64, ints=True, cd16=True)
 
 
+def test_binary16_c_and_d_whole_line_stores(monkeypatch):
+    """With binary16 C and D the tiles whose waves hold at least two 32-row accumulators exchange
+    half-registers between them so that loads and stores cover whole lines: every epilogue option
+    on that path, on each such tile, with interior and edge waves in one launch.  Integer data:
+    every entry must equal the exact result rounded once."""
+    for tile in (0, 1, 2, 4):
+        monkeypatch.setenv("FG_FORCE_TILE", str(tile))
+        say("tile %d: bias along N, ReLU, ReLU on C, beta = -3, in place" % tile)
+        run_gemm_case(600, 520, 128, ints=True, cd16=True, bias_dim=1, act=fg.FG_ACT_RELU, c_act=fg.FG_ACT_RELU, beta=-3.0, inplace=True)
+        say("tile %d: bias along M, no C, row-major D" % tile)
+        run_gemm_case(520, 600, 192, fg.FG_ROW, fg.FG_ROW, ld_layout=fg.FG_ROW, ints=True, cd16=True, bias_dim=0, with_c=False, pad=8)
+        say("tile %d: alpha = -2, beta = 1, separate C" % tile)
+        run_gemm_case(512, 512, 64, fg.FG_COL, fg.FG_ROW, ints=True, cd16=True, alpha=-2.0)
+    monkeypatch.delenv("FG_FORCE_TILE")
+
+
 def test_every_tile_shape_in_every_kernel_family(monkeypatch):
     """Each of the five block tiles (256x256, 256x128, 128x128, 64x64 and the 128x128 tile with a
     ring of four buffers) forced in turn on one ragged problem, for the plain, BF16, A/B-addition
