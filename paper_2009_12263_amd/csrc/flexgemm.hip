@@ -102,19 +102,29 @@ const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
 // share a unit and one for a workgroup that has a unit to itself.  Edge tiles are predicated, so
 // a tile need not divide the problem.  K is split only when the output has too few tiles to fill
 // the GPU and K is long (may_split: plain real products).
+// allow_k32: the kernel family has the 256x256 tile with 16x16x32 matrix instructions
+// (TILE_256x256_K32).  It is not a candidate of its own: it replaces the 256x256 tile when that
+// one is chosen and the output has at least one such tile per compute unit (measured 0 to +5 %
+// there, K from 1024 to 8192; -3 to -8 % when fewer units are busy).
 Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_smallest = true, int64_t batches = 1,
-                 bool allow_deep = true) {
-    static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64, 128};
-    static const int bn[fg::TILE_COUNT] = {256, 128, 128, 64, 128};
-    static const int per_cu[fg::TILE_COUNT] = {1, 1, 2, 4, 1};
-    static const double rate_shared[fg::TILE_COUNT] = {1.0, 0.8, 0.73, 0.45, 0.51};
-    static const double rate_alone[fg::TILE_COUNT] = {1.0, 0.8, 0.43, 0.17, 0.51};
+                 bool allow_deep = true, bool allow_k32 = false) {
+    static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64, 128, 256};
+    static const int bn[fg::TILE_COUNT] = {256, 128, 128, 64, 128, 256};
+    static const int per_cu[fg::TILE_COUNT] = {1, 1, 2, 4, 1, 1};
+    static const double rate_shared[fg::TILE_COUNT] = {1.0, 0.8, 0.73, 0.45, 0.51, 1.0};
+    static const double rate_alone[fg::TILE_COUNT] = {1.0, 0.8, 0.43, 0.17, 0.51, 1.0};
     static const int split_options[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
     constexpr double cu_flops = 4.7e12, round_fixed = 2e-6, cu_cd_bw = 25e9, reduce_launch = 6e-6, reduce_bw = 3e12;
-    // tuning aids: FG_FORCE_TILE=0..4 picks a tile shape, FG_FORCE_SPLIT=n a split of K for every
+    // tuning aids: FG_FORCE_TILE=0..5 picks a tile shape (5: the 256x256 tile, k32 kernel where there is one), FG_FORCE_SPLIT=n a split of K for every
     // tile, FG_FORCE_TAIL=n a split of K for the tiles of the last round (1: never)
     int force_tile = -1, force_split = 0, force_tail = 0;
-    if (const char *f = getenv("FG_FORCE_TILE")) { int t = atoi(f); if (t >= 0 && t < fg::TILE_COUNT) force_tile = t; }
+    bool force_k32 = false, forced_plain = false;
+    if (const char *f = getenv("FG_FORCE_TILE")) {
+        int t = atoi(f);
+        if (t == fg::TILE_256x256_K32) { t = fg::TILE_256x256; force_k32 = true; }
+        else forced_plain = (t == fg::TILE_256x256);
+        if (t >= 0 && t < fg::TILE_COUNT) force_tile = t;
+    }
     if (const char *f = getenv("FG_FORCE_SPLIT")) force_split = atoi(f);
     if (const char *f = getenv("FG_FORCE_TAIL")) force_tail = atoi(f);
     const int64_t nk = (K + 63) / 64;                       // K tiles (every real kernel has BK = 64)
@@ -124,6 +134,7 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_sma
         if (force_tile >= 0 && t != force_tile) continue;
         if (t == fg::TILE_64x64 && !allow_smallest) continue;
         if (t == fg::TILE_128x128_DEEP && !allow_deep) continue;
+        if (t == fg::TILE_256x256_K32) continue;
         const int64_t tiles = ((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]) * batches;
         const int64_t slots = (int64_t)kNumCU * per_cu[t];
         const int64_t slot_bytes = (int64_t)bm[t] * bn[t] * 4;
@@ -171,6 +182,10 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_sma
             }
         }
     }
+    if (best.tile == fg::TILE_256x256 && allow_k32 && !forced_plain) {
+        const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256) * batches;
+        if (force_k32 || tiles >= kNumCU) best.tile = fg::TILE_256x256_K32;
+    }
     return best;
 }
 
@@ -193,7 +208,7 @@ const fg::KernelEntry *select_kernel(const Problem &q, Plan *plan_out = nullptr)
         return &(q.dual ? fg::kernel_table_dual() : fg::kernel_table_cplx())[t * 4 + v];
     }
     const bool may_split = plan_out && !q.a_diag && !q.b_diag && !q.cd16;   // the reduction pass writes FP32
-    const Plan plan = choose_plan(q.M, q.N, q.K, may_split, true, 1, !q.a_diag && !q.b_diag);
+    const Plan plan = choose_plan(q.M, q.N, q.K, may_split, true, 1, !q.a_diag && !q.b_diag, !q.a_diag && !q.b_diag && !q.ab_add);
     const int tile = plan.tile;
     if (plan_out) *plan_out = plan;
     if (q.a_diag) return &fg::kernel_table_diag()[tile * 4 + (q.b_kc ? 0 : 1)];

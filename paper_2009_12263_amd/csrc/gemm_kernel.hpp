@@ -103,14 +103,24 @@ __device__ __forceinline__ int tile_row(int pos, int rows, int z_count) {
 // B column-major) rather than M/N-contiguous.  STAGES LDS buffers per operand form a ring over K.
 template <int BM_, int BN_, int BK_, int STAGES_, int WGM_, int WGN_, bool A_KC_, bool B_KC_, bool STRIDED_,
           int DIAG_ = 0, int CPLX_ = 0, bool SPREAD_ = false, bool BF16_ = false, bool XFORM_ = false, bool ILV_ = false,
-          bool CSTREAM_ = false, bool CD16_ = false>
+          bool CSTREAM_ = false, bool CD16_ = false, bool M16_ = false>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_;
-    static constexpr int KSTEPS = BK / 16;                          // MFMA k-slices per tile
+    // M16: the product is made of v_mfma_f32_16x16x32 instructions (16x16 results, 32 k per
+    // instruction) instead of v_mfma_f32_32x32x16.  Same flops per cycle; on operand data that
+    // keeps the chip at its power limit the 16x16x32 stream sustains a markedly higher rate.
+    static constexpr bool M16 = M16_;
+    static constexpr int KSLICE = M16_ ? 32 : 16;                   // k per matrix instruction
+    static constexpr int KSTEPS = BK / KSLICE;                      // MFMA k-slices per tile
     static constexpr int WGM = WGM_, WGN = WGN_;
     static constexpr int NWAVES = WGM * WGN, NTHREADS = 64 * NWAVES;
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;
-    static constexpr int TI = WTM / 32, TJ = WTN / 32;
+    static constexpr int TI = WTM / 32, TJ = WTN / 32;             // 32x32 blocks of results per wave (epilogue)
+    static constexpr int FI = M16_ ? 2 * TI : TI, FJ = M16_ ? 2 * TJ : TJ;   // operand fragments per wave and k-slice
+    // Epilogue view of the results: 32x32 blocks of 16 registers; register r of lane l holds row
+    // l % 32 and column acc_col(r) + ACC_LH * (l / 32) of its block (see gather_blocks for M16).
+    static constexpr int ACC_LH = M16_ ? 8 : 4;
+    static constexpr int acc_col(int r) { return M16_ ? 16 * (r >> 3) + 4 * ((r >> 2) & 1) + (r & 3) : 8 * (r >> 2) + (r & 3); }
     static constexpr bool A_KC = A_KC_, B_KC = B_KC_, STRIDED = STRIDED_;
     // 0: real; 1: complex (i^2 = -1), 2: dual (eps^2 = 0) numbers in planar-split storage
     static constexpr int CPLX = CPLX_;
@@ -156,7 +166,8 @@ struct TileCfg {
     static_assert(DIAG != 1 || A_KC, "a diagonal A is synthesised K-contiguous");
     static_assert(DIAG != 2 || B_KC, "a diagonal B is synthesised K-contiguous");
     static_assert(!(CPLX && (DIAG || STRIDED)), "complex products take plain matrices");
-    static_assert(!SPREAD || STAGES >= 4 || KSTEPS >= 4, "spread refills need slack before the tile is needed");
+    static_assert(!SPREAD || STAGES >= 4 || BK >= 64, "spread refills need slack before the tile is needed");
+    static_assert(!M16 || (CPLX == 0 && DIAG == 0 && !ILV && BK == 64), "16x16x32 products: real, non-diagonal operands, two k-slices per tile");
     static_assert(!XFORM || (DIAG == 0 && CPLX == 0 && !BF16 && !STRIDED), "element-wise addition on A and B: plain real FP16 matrices");
     static_assert(!CSTREAM || STRIDED, "the streaming variant is a contraction kernel");
     static_assert(!CD16 || (CPLX == 0 && DIAG == 0 && !STRIDED && !ILV), "binary16 C and D: plain real matrix kernels");
@@ -175,6 +186,10 @@ __device__ __forceinline__ int kc_swz(int row) { return (row / (128 / BK)) & (BK
 
 // M/N-contiguous tile: k-rows of R halves.  The 64-byte chunk index of a k-row is XORed with
 // (krow & 3) so that the four k-rows one transposing read touches fall into different banks.
+// With 16-row fragments (TileCfg::M16) half a wave reads 16 rows of eight k-rows, krow = 0..3 and
+// 8..11 (+4 for the second half of the fragment): k-rows whose bit 3 is set therefore also have
+// the two 32-byte halves of every 64-byte chunk swapped, which puts the eight 32-byte pieces into
+// eight different bank groups.
 template <int R>
 __device__ __forceinline__ int mc_swz(int krow) { return krow & ((R / 32 - 1) < 3 ? (R / 32 - 1) : 3); }
 
@@ -258,9 +273,11 @@ __device__ __forceinline__ T load_param(unsigned offset) {
 // layout).  Such a tile cannot be copied by direct loads, which cannot separate the parts: it is
 // fetched into registers (fetch), split, and written into the two planes of the planar LDS
 // layout (commit), the conversion the paper places in the global-to-shared copy.
-template <int R, int BK, bool KC, int SLABS, bool STRIDED, int ES = 1>
+// FLIP (M/N-contiguous tiles read as 16-row fragments, TileCfg::M16): see mc_swz.
+template <int R, int BK, bool KC, int SLABS, bool STRIDED, int ES = 1, bool FLIP = false>
 struct TileLoader {
     static_assert(ES == 1 || (ES == 2 && !STRIDED), "interleaved elements: plain matrices only");
+    static_assert(!FLIP || ES == 1, "");
     uint32_t voff[SLABS];    // per-lane byte offset from the moving base (per slab)
     u32x4 stage[ES == 2 ? SLABS : 1][2];   // ES == 2: the 32 fetched bytes of each slab's chunk
     const char *base;        // uniform: start of this block's panel at the current K step
@@ -320,6 +337,7 @@ struct TileLoader {
                 if constexpr (STRIDED) kchunk[s] = kr;             // k offset of this lane's k-row inside the tile
                 int p = lane % CH;                                  // physical chunk
                 int c = p ^ (mc_swz<R>(kr) << 2);                   // 64-byte granular XOR
+                if constexpr (FLIP) c ^= ((kr >> 3) & 1) << 1;      // and the 32-byte halves of k-rows 8..15 mod 16 swapped
                 if constexpr (!STRIDED) off = (int64_t)kr * ks + c * 8;
                 else off = group_offset(rg, row0 + c * 8) + (int64_t)kr * kgrp.stride[0];
                 if constexpr (STRIDED) {
@@ -492,23 +510,35 @@ struct DiagLoader {
 };
 
 // ---- LDS -> register fragment reads -----------------------------------------------------------
-// Fragment of 32 rows x 16 k for v_mfma_f32_32x32x16_f16: lane l holds row l%32, k = 8*(l/32)+0..7.
-template <int R, int BK, bool KC, int NT>
+// Fragment of 32 rows x 16 k for v_mfma_f32_32x32x16_f16: lane l holds row l%32, k = 8*(l/32)+0..7;
+// M16: 16 rows x 32 k for v_mfma_f32_16x16x32_f16: lane l holds row l%16, k = 8*(l/16)+0..7.
+template <int R, int BK, bool KC, int NT, bool M16 = false>
 struct FragReader {
-    // KC: one address per 16-wide k slice (the swizzle mixes the slice index into the chunk);
-    //     sub-tiles are 32 rows apart.
-    // MC: one address per 32-row sub-tile; k slices are 16 k-rows apart, the two halves of a
-    //     fragment 4 k-rows apart.
-    static constexpr int KSTEPS = BK / 16;
+    // KC: one address per k slice (the swizzle mixes the slice index into the chunk); sub-tiles
+    //     are ROWS rows apart.
+    // MC: one address per sub-tile; k slices are KW k-rows apart, the two halves of a fragment 4
+    //     k-rows apart.
+    static constexpr int KW = M16 ? 32 : 16, ROWS = M16 ? 16 : 32;
+    static constexpr int KSTEPS = BK / KW;
     uint32_t addr[KC ? KSTEPS : NT];
 
     __device__ __forceinline__ void init(int row_base, int lane, int perm_z = 1) {
         if constexpr (KC) {
-            int r = row_base + (lane & 31);
+            int r = row_base + (lane & (ROWS - 1));
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) {
-                int c = (2 * ks + (lane >> 5)) ^ kc_swz<BK>(r);
+                int c = ((KW / 8) * ks + lane / ROWS) ^ kc_swz<BK>(r);
                 addr[ks] = r * (BK * 2) + c * 16;
+            }
+        } else if constexpr (M16) {
+            // a group of 16 lanes transposes 4 k-rows x 16 rows; group g takes k-rows 8g .. 8g+3
+            int g = lane >> 4, i16 = lane & 15;
+            int kr = 8 * g + (i16 >> 2);                           // + 32*ks + 4*t
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                int m = tile_row(row_base + 16 * t + 4 * (i16 & 3), R, perm_z);   // 4 rows per address
+                int c64 = (m >> 5) ^ mc_swz<R>(kr);
+                addr[t] = kr * (R * 2) + c64 * 64 + ((m & 31) ^ (16 * (g & 1))) * 2;
             }
         } else {
             int g = lane >> 4, i16 = lane & 15;
@@ -524,9 +554,9 @@ struct FragReader {
 
     __device__ __forceinline__ half8 read(FG_LDS const char *tile, int t, int ks) const {
         if constexpr (KC) {
-            return *(FG_LDS const half8 *)(tile + addr[ks] + t * (32 * BK * 2));
+            return *(FG_LDS const half8 *)(tile + addr[ks] + t * (ROWS * BK * 2));
         } else {
-            FG_LDS const char *p = tile + addr[t] + ks * 16 * (R * 2);
+            FG_LDS const char *p = tile + addr[t] + ks * KW * (R * 2);
             short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FG_LDS short4v *)(p));
             short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((FG_LDS short4v *)(p + 4 * (R * 2)));
             return __builtin_bit_cast(half8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -601,8 +631,8 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
         // them, the rest is a scalar offset.
         constexpr bool H = Cfg::CD16;
         constexpr int ES = H ? 2 : 4;                                    // bytes per element of C and D
-        const int voff_c = (lm + 4 * lh * (int)p.ldc) * ES;
-        const int voff_d = (lm + 4 * lh * (int)p.ldd) * ES;
+        const int voff_c = (lm + Cfg::ACC_LH * lh * (int)p.ldc) * ES;
+        const int voff_d = (lm + Cfg::ACC_LH * lh * (int)p.ldd) * ES;
         const int ldc4 = (int)p.ldc * ES, ldd4 = (int)p.ldd * ES;
         const char *Cb = (const char *)Cp, *Db = (const char *)Dp;
         __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
@@ -627,9 +657,9 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                 const int ip = b / (2 * Cfg::TJ), j = (b >> 1) % Cfg::TJ, h = b & 1;
 #pragma unroll
                 for (int r8 = 0; r8 < 8; ++r8) {
-                    const int r = 8 * h + r8, col = 32 * j + 8 * (r >> 2) + (r & 3);
+                    const int r = 8 * h + r8, col = 32 * j + Cfg::acc_col(r);
                     dst[2 * r8] = load_cd<H, kStream>(rc, voff_p, 64 * ES * ip + col * ldc4);
-                    dst[2 * r8 + 1] = load_cd<H, kStream>(rc, voff_p, 64 * ES * ip + (col + 4) * ldc4);
+                    dst[2 * r8 + 1] = load_cd<H, kStream>(rc, voff_p, 64 * ES * ip + (col + Cfg::ACC_LH) * ldc4);
                 }
             };
             auto exchange = [](float &x, float &y) {
@@ -661,7 +691,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
 #pragma unroll
                     for (int r8 = 0; r8 < 8; ++r8) {
                         const int r = 8 * h + r8;
-                        b0[r8] = b1[r8] = p.bias[n_base + 32 * j + 8 * (r >> 2) + 4 * lh + (r & 3)];
+                        b0[r8] = b1[r8] = p.bias[n_base + 32 * j + Cfg::acc_col(r) + Cfg::ACC_LH * lh];
                     }
                 }
                 float y[16];
@@ -684,9 +714,9 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                 }
 #pragma unroll
                 for (int r8 = 0; r8 < 8; ++r8) {
-                    const int r = 8 * h + r8, col = 32 * j + 8 * (r >> 2) + (r & 3);
+                    const int r = 8 * h + r8, col = 32 * j + Cfg::acc_col(r);
                     store_cd<H, kStream>(y[2 * r8], rd, voff_p, 64 * ES * ip + col * ldd4);
-                    store_cd<H, kStream>(y[2 * r8 + 1], rd, voff_p, 64 * ES * ip + (col + 4) * ldd4);
+                    store_cd<H, kStream>(y[2 * r8 + 1], rd, voff_p, 64 * ES * ip + (col + Cfg::ACC_LH) * ldd4);
                 }
             }
             return;
@@ -706,7 +736,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                 const int i = b / Cfg::TJ, j = b % Cfg::TJ;
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    dst[r] = load_cd<H, kStream>(rc, voff_c, 32 * ES * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4);
+                    dst[r] = load_cd<H, kStream>(rc, voff_c, 32 * ES * i + (32 * j + Cfg::acc_col(r)) * ldc4);
             };
             float bias_m[Cfg::TI];
 #pragma unroll
@@ -726,7 +756,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                 for (int r = 0; r < 16; ++r) bv[r] = bias_m[i];
                 if (bias_n_on) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) bv[r] = p.bias[n_base + 32 * j + 8 * (r >> 2) + 4 * lh + (r & 3)];
+                    for (int r = 0; r < 16; ++r) bv[r] = p.bias[n_base + 32 * j + Cfg::acc_col(r) + Cfg::ACC_LH * lh];
                 }
                 float y[16];
 #pragma unroll
@@ -740,7 +770,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                 }
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    store_cd<H, kStream>(y[r], rd, voff_d, 32 * ES * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4);
+                    store_cd<H, kStream>(y[r], rd, voff_d, 32 * ES * i + (32 * j + Cfg::acc_col(r)) * ldd4);
             }
         } else {
             // a tile that hangs over the edge of D: rows m >= M are masked per lane (their offset is
@@ -762,21 +792,21 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
 #pragma unroll
                             for (int r8 = 0; r8 < 8; ++r8) {
                                 const int r = 8 * h + r8;
-                                const int ncol = n_base + 32 * j + 8 * (r >> 2) + (r & 3) + 4 * lh;
+                                const int ncol = n_base + 32 * j + Cfg::acc_col(r) + Cfg::ACC_LH * lh;
                                 const bool n_ok = ncol < p.N;
                                 if constexpr (BIAS_N) bv[r8] = p.bias[n_ok ? ncol : p.N - 1];
                                 else bv[r8] = bias_mi;
                                 if constexpr (HAS_C)
-                                    cv[r8] = load_cd<H, kStream>(rc, n_ok ? vc : kOutOfRange, 32 * ES * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldc4);
+                                    cv[r8] = load_cd<H, kStream>(rc, n_ok ? vc : kOutOfRange, 32 * ES * i + (32 * j + Cfg::acc_col(r)) * ldc4);
                             }
 #pragma unroll
                             for (int r8 = 0; r8 < 8; ++r8) {
                                 const int r = 8 * h + r8;
-                                const bool n_ok = n_base + 32 * j + 8 * (r >> 2) + (r & 3) + 4 * lh < p.N;
+                                const bool n_ok = n_base + 32 * j + Cfg::acc_col(r) + Cfg::ACC_LH * lh < p.N;
                                 float y = p.alpha * acc[i][j][r] + bv[r8];
                                 if constexpr (HAS_C) y += p.beta * (cv[r8] > floor_c ? cv[r8] : floor_c);
                                 y = y > floor_v ? y : floor_v;
-                                store_cd<H, kStream>(y, rd, n_ok ? vd : kOutOfRange, 32 * ES * i + (32 * j + 8 * (r >> 2) + (r & 3)) * ldd4);
+                                store_cd<H, kStream>(y, rd, n_ok ? vd : kOutOfRange, 32 * ES * i + (32 * j + Cfg::acc_col(r)) * ldd4);
                             }
                         }
                     }
@@ -815,7 +845,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
             uint32_t col4[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                col4[r] = (uint32_t)__builtin_amdgcn_ds_bpermute((8 * (r >> 2) + (r & 3) + 4 * lh) * 4, (int)col_of_lane);
+                col4[r] = (uint32_t)__builtin_amdgcn_ds_bpermute((Cfg::acc_col(r) + Cfg::ACC_LH * lh) * 4, (int)col_of_lane);
             // both parts are below 2^31 when in range; if either is out of range the sum must not
             // wrap back into range (formed again for the store rather than kept: registers are short here)
             auto offset = [&](int i, int r) { return ((row4[i] | col4[r]) & kOutOfRange) ? kOutOfRange : row4[i] + col4[r]; };
@@ -947,11 +977,45 @@ __device__ __forceinline__ floatx16 mfma(half8 a, half8 b, floatx16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+template <bool BF16>
+__device__ __forceinline__ floatx4 mfma(half8 a, half8 b, floatx4 c) {
+    if constexpr (BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// M16: the 16x16 results of a wave, regrouped into the 32x32 blocks the epilogues work on.  In
+// the 16x16 result (i, j) register r of lane l holds row 16 i + l % 16 and column 16 j +
+// 4 (l / 16) + r.  Exchanging the odd 16-lane rows of (2i, j)'s register with the even ones of
+// (2i+1, j)'s gives one register with rows 32 i + l % 32 at column 16 j + r + 8 (l / 32) and one
+// with the same rows four columns further: the layout TileCfg::acc_col / ACC_LH describe, in
+// which a store instruction again covers two whole 128-byte lines of a column-major result.
+template <class Cfg>
+__device__ __forceinline__ void gather_blocks(const floatx4 (&a16)[Cfg::FI][Cfg::FJ], floatx16 (&acc)[Cfg::TI][Cfg::TJ]) {
+#pragma unroll
+    for (int i = 0; i < Cfg::TI; ++i)
+#pragma unroll
+        for (int j = 0; j < Cfg::TJ; ++j)
+#pragma unroll
+            for (int nj = 0; nj < 2; ++nj)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float x = a16[2 * i][2 * j + nj][r], y = a16[2 * i + 1][2 * j + nj][r];
+                    const auto s = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
+                    const unsigned s0 = s[0], s1 = s[1];      // (copied out before the bit cast: see the binary16 epilogue)
+                    acc[i][j][8 * nj + r] = __builtin_bit_cast(float, s0);
+                    acc[i][j][8 * nj + 4 + r] = __builtin_bit_cast(float, s1);
+                }
+}
+
 template <class Cfg>
 __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p) {
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     FG_LDS char *smem = (FG_LDS char *)smem_generic;
-    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, TI = Cfg::TI, TJ = Cfg::TJ;
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK;
+    constexpr int TI = Cfg::FI, TJ = Cfg::FJ;           // operand fragments (and matrix-instruction results) per wave
     constexpr int S = Cfg::STAGES, KS = Cfg::KSTEPS, L = Cfg::LOADS_PER_TILE, P = Cfg::PLANES;
 
     const int lane = threadIdx.x & 63;
@@ -964,15 +1028,15 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
     FG_LDS char *lds_a = smem;
     FG_LDS char *lds_b = smem + Cfg::A_BYTES;
 
-    using PlainA = TileLoader<BM, BK, Cfg::A_KC, Cfg::A_SLABS, Cfg::STRIDED, Cfg::ILV ? 2 : 1>;
-    using PlainB = TileLoader<BN, BK, Cfg::B_KC, Cfg::B_SLABS, Cfg::STRIDED, Cfg::ILV ? 2 : 1>;
+    using PlainA = TileLoader<BM, BK, Cfg::A_KC, Cfg::A_SLABS, Cfg::STRIDED, Cfg::ILV ? 2 : 1, Cfg::M16>;
+    using PlainB = TileLoader<BN, BK, Cfg::B_KC, Cfg::B_SLABS, Cfg::STRIDED, Cfg::ILV ? 2 : 1, Cfg::M16>;
     constexpr int NLOADERS = Cfg::ILV ? 1 : P;      // an interleaved operand is one array, not one per plane
     using LoaderA = typename std::conditional<Cfg::DIAG == 1, DiagLoader<BM, BK, Cfg::A_SLABS>, PlainA>::type;
     using LoaderB = typename std::conditional<Cfg::DIAG == 2, DiagLoader<BN, BK, Cfg::B_SLABS>, PlainB>::type;
     LoaderA la[P];
     LoaderB lb[P];
-    FragReader<BM, BK, Cfg::A_KC, TI> fa;
-    FragReader<BN, BK, Cfg::B_KC, TJ> fb;
+    FragReader<BM, BK, Cfg::A_KC, TI, Cfg::M16> fa;
+    FragReader<BN, BK, Cfg::B_KC, TJ, Cfg::M16> fb;
     if constexpr (Cfg::STRIDED && !Cfg::A_KC) fa.init(wm * Cfg::WTM, lane, p.perm_z);
     else fa.init(wm * Cfg::WTM, lane);
     fb.init(wn * Cfg::WTN, lane);
@@ -1053,7 +1117,8 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
 
     while (true) {
         const int m_base = m0 + wm * Cfg::WTM, n_base = n0 + wn * Cfg::WTN;
-        floatx16 acc[P][TI][TJ];
+        using AccT = typename std::conditional<Cfg::M16, floatx4, floatx16>::type;
+        AccT acc[P][TI][TJ];
 #pragma unroll
         for (int q = 0; q < P; ++q)
 #pragma unroll
@@ -1061,7 +1126,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
 #pragma unroll
                 for (int j = 0; j < TJ; ++j)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[q][i][j][r] = 0.f;
+                    for (int r = 0; r < (Cfg::M16 ? 4 : 16); ++r) acc[q][i][j][r] = 0.f;
 
         if (nkt > 0) {
             if (nkt >= S) wait_tile<(S - 1) * L>(); else wait_tile<0>();
@@ -1070,11 +1135,15 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
             // A fragments are reloaded in place (the registers of sub-tile i are free once its
             // MFMAs of this slice are issued); B fragments, used by every sub-tile row, are double
             // buffered.  Complex operands carry a second set for the imaginary planes.
-            half8 af[P][TI], bf[P][2][TJ];
+            // M16 (a slice is 32 k: twice the fragment registers per row or column): A's fragments
+            // pass through a window of AW registers, the one of row i being replaced by row i+AW's
+            // as soon as row i's instructions are issued.
+            constexpr int AW = Cfg::M16 ? (TI < 4 ? TI : 4) : TI;
+            half8 af[P][AW], bf[P][2][TJ];
 #pragma unroll
             for (int q = 0; q < P; ++q) {
 #pragma unroll
-                for (int i = 0; i < TI; ++i) af[q][i] = fa.read(lds_a + q * Cfg::A_PLANE_BYTES, i, 0);
+                for (int i = 0; i < AW; ++i) af[q][i] = fa.read(lds_a + q * Cfg::A_PLANE_BYTES, i, 0);
 #pragma unroll
                 for (int j = 0; j < TJ; ++j) bf[q][0][j] = fb.read(lds_b + q * Cfg::B_PLANE_BYTES, j, 0);
             }
@@ -1098,6 +1167,86 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                 FG_LDS const char *tb = lds_b + cur * Cfg::B_TILE_BYTES;
                 FG_LDS const char *na = lds_a + nxt * Cfg::A_TILE_BYTES;
                 FG_LDS const char *nb = lds_b + nxt * Cfg::B_TILE_BYTES;
+                if constexpr (Cfg::M16) {
+                    // Two slices of 32 k, each TI rows of TJ matrix instructions.  The barrier that
+                    // publishes tile kt+1 and retires tile kt sits in front of row BAR_I of the last
+                    // slice, the first row after which a fragment of tile kt+1 is read (three
+                    // quarters through the tile for the 128-row wave tile).
+                    static_assert(KS == 2, "");
+                    constexpr int BAR_I = TI - AW;
+                    const int prev = (kt - 1) & (S - 1);
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        const int rb = ks & 1, wb = rb ^ 1;
+                        const bool last = (ks + 1 == KS);
+                        bool refill_a = false, refill_b = false;
+                        if constexpr (Cfg::SPREAD) {
+                            if (ks == 0 && RB) {
+                                refill_b = true;
+                                lb[0].begin();
+                            }
+                        }
+                        if (!last) {
+#pragma unroll
+                            for (int j = 0; j < TJ; ++j) bf[0][wb][j] = fb.read(tb, j, ks + 1);
+                        }
+                        uint32_t add_a = 0, add_b = 0;          // two packed halves each
+                        if constexpr (Cfg::XFORM) {
+                            const bool in_k = (kt0 + kt) * BK + ks * 32 + 8 * (lane >> 4) < xf_k;
+                            add_a = in_k ? xf_a : 0u;
+                            add_b = in_k ? xf_b : 0u;
+#pragma unroll
+                            for (int j = 0; j < TJ; ++j) bf[0][rb][j] = add8(bf[0][rb][j], add_b);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int i = 0; i < TI; ++i) {
+                            const int slot = i % AW;
+                            if (last && MORE && i == BAR_I) {
+                                if (RA) wait_tile<(S - 2) * L>(); else wait_tile<0>();
+                                __builtin_amdgcn_s_barrier();
+                                if (RA) {
+                                    if constexpr (Cfg::SPREAD) {
+                                        refill_a = true;
+                                        la[0].begin();
+                                    } else {
+                                        la[0].issue(lds_a + cur * Cfg::A_TILE_BYTES, wave);
+                                        lb[0].issue(lds_b + cur * Cfg::B_TILE_BYTES, wave);
+                                    }
+                                }
+                            }
+                            if constexpr (Cfg::XFORM) af[0][slot] = add8(af[0][slot], add_a);
+#pragma unroll
+                            for (int j = 0; j < TJ; ++j) acc[0][i][j] = mfma<Cfg::BF16>(bf[0][rb][j], af[0][slot], acc[0][i][j]);
+                            // the window moves on
+                            if (i + AW < TI) af[0][slot] = fa.read(ta, i + AW, ks);
+                            else if (!last) af[0][slot] = fa.read(ta, i + AW - TI, ks + 1);
+                            else if (MORE) af[0][slot] = fa.read(na, i + AW - TI, 0);
+                            // B's first fragments of tile kt+1, over the rows after the barrier
+                            // (measured against reading them all right after the barrier, and the
+                            // second slice's over the rows of the first: 7 % faster on 8192^3)
+                            if (last && MORE && i >= BAR_I) {
+#pragma unroll
+                                for (int j = 0; j < TJ; ++j)
+                                    if (j * AW / TJ == i - BAR_I) bf[0][wb][j] = fb.read(nb, j, 0);
+                            }
+                            if constexpr (Cfg::SPREAD) {
+                                // A's refill over the rows after the barrier, B's over the first slice
+#pragma unroll
+                                for (int n = 0; n < Cfg::A_SLABS; ++n)
+                                    if (refill_a && i == BAR_I + n * AW / Cfg::A_SLABS) la[0].issue_slab(lds_a + cur * Cfg::A_TILE_BYTES, wave, n);
+#pragma unroll
+                                for (int n = 0; n < Cfg::B_SLABS; ++n)
+                                    if (refill_b && i == n * TI / Cfg::B_SLABS) lb[0].issue_slab(lds_b + prev * Cfg::B_TILE_BYTES, wave, n);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        if constexpr (Cfg::SPREAD) {
+                            if (refill_a) la[0].advance();
+                            if (refill_b) lb[0].advance();
+                        }
+                    }
+                } else
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     const int rb = ks & 1, wb = rb ^ 1;     // KS is even: slice 0 always uses buffer 0
@@ -1161,7 +1310,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                     // addend is zero (a lane's eight values share one k chunk, K is a multiple of 8).
                     uint32_t add_a = 0, add_b = 0;          // two packed halves each
                     if constexpr (Cfg::XFORM) {
-                        const bool in_k = (kt0 + kt) * BK + ks * 16 + 8 * (lane >> 5) < xf_k;
+                        const bool in_k = (kt0 + kt) * BK + ks * Cfg::KSLICE + 8 * (lane / (Cfg::M16 ? 16 : 32)) < xf_k;
                         add_a = in_k ? xf_a : 0u;
                         add_b = in_k ? xf_b : 0u;
 #pragma unroll
@@ -1280,6 +1429,12 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                 ep.D += c_off;
                 if (ep.has_c) ep.C += c_off;
             }
+            if constexpr (Cfg::M16) {
+                floatx16 blocks[Cfg::TI][Cfg::TJ];
+                gather_blocks<Cfg>(acc[0], blocks);
+                if (ep.has_c) epilogue<Cfg, true>(ep, ep.C, ep.D, blocks, mb, nb, lane);
+                else epilogue<Cfg, false>(ep, ep.C, ep.D, blocks, mb, nb, lane);
+            } else {
             if constexpr (Cfg::ILV) {
                 if (ep.has_c) epilogue_interleaved<Cfg, true>(ep, acc[0], acc[1], m_base, n_base, lane);
                 else epilogue_interleaved<Cfg, false>(ep, acc[0], acc[1], m_base, n_base, lane);
@@ -1290,6 +1445,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
             if constexpr (Cfg::CPLX && !Cfg::ILV) {
                 if (ep.has_c) epilogue<Cfg, true>(ep, ep.C_im, ep.D_im, acc[1], m_base, n_base, lane);
                 else epilogue<Cfg, false>(ep, ep.C_im, ep.D_im, acc[1], m_base, n_base, lane);
+            }
             }
         }
 

@@ -8,8 +8,12 @@ namespace fg {
 // TILE_128x128_DEEP: the 128x128 tile with a ring of four buffers (128 KB of LDS, one workgroup per
 // compute unit), for outputs of at most one such tile per unit: a lone 4-wave workgroup turns a K
 // tile over in 512 cycles, too fast for a two-buffer ring to cover the memory latency.
-enum TileId { TILE_256x256 = 0, TILE_256x128 = 1, TILE_128x128 = 2, TILE_64x64 = 3, TILE_128x128_DEEP = 4, TILE_COUNT = 5,
-              DIAG_TILE_COUNT = 4 };
+// TILE_256x256_K32: the 256x256 tile computed with 16x16x32 matrix instructions (TileCfg::M16), for
+// products that fill the GPU: there the chip runs at its power limit and that instruction shape
+// sustains a higher rate on the same data; on a partly filled GPU the 32x32x16 kernels are faster.
+// Plain, BF16 and binary16-result matrix kernels only (other tables leave the entry empty).
+enum TileId { TILE_256x256 = 0, TILE_256x128 = 1, TILE_128x128 = 2, TILE_64x64 = 3, TILE_128x128_DEEP = 4,
+              TILE_256x256_K32 = 5, TILE_COUNT = 6, DIAG_TILE_COUNT = 4 };
 
 struct KernelEntry {
     void (*fn)(const GemmParams);
@@ -81,6 +85,13 @@ inline int entry_index(int tile, int variant) { return tile * VARIANT_COUNT + va
 
 // real kernels with BK = 64: ring refills are spread between the MFMAs (TileCfg::SPREAD)
 #define FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR) TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR, 0, 0, true>
+#define FG_EMPTY_ENTRY { nullptr, nullptr, 0, 0, 0, 0 }
+// the same with 16x16x32 matrix instructions (TileCfg::M16); BF: bfloat16 inputs, H: binary16 C and D
+#define FG_CFG_K32(BM, BN, BK, ST, WGM, WGN, AKC, BKC, BF, H) TileCfg<BM, BN, BK, ST, WGM, WGN, AKC, BKC, false, 0, 0, true, BF, false, false, false, H, true>
+#define FG_ENTRY_K32(BM, BN, BK, ST, WGM, WGN, AKC, BKC, BF, H, NAME)                              \
+    { gemm_kernel<FG_CFG_K32(BM, BN, BK, ST, WGM, WGN, AKC, BKC, BF, H)>, NAME, BM, BN,            \
+      FG_CFG_K32(BM, BN, BK, ST, WGM, WGN, AKC, BKC, BF, H)::NTHREADS,                             \
+      FG_CFG_K32(BM, BN, BK, ST, WGM, WGN, AKC, BKC, BF, H)::LDS_BYTES }
 #define FG_ENTRY(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR, NAME)                                    \
     { gemm_kernel<FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)>, NAME, BM, BN,                  \
       FG_CFG(BM, BN, BK, ST, WGM, WGN, AKC, BKC, STR)::NTHREADS,                                   \
@@ -107,6 +118,7 @@ inline int entry_index(int tile, int variant) { return tile * VARIANT_COUNT + va
             FG_ENTRY_BF16(128, 128, 64, 2, 2, 2, AKC, BKC, "gemm_bf16_" TAG "_128x128x64"),        \
             FG_ENTRY_BF16(64, 64, 64, 2, 2, 2, AKC, BKC, "gemm_bf16_" TAG "_64x64x64"),            \
             FG_ENTRY_BF16(128, 128, 64, 4, 2, 2, AKC, BKC, "gemm_bf16_" TAG "_128x128x64_deep"),   \
+            FG_ENTRY_K32(256, 256, 64, 2, 2, 4, AKC, BKC, true, false, "gemm_bf16_" TAG "_256x256x64_k32"), \
         };                                                                                         \
         return t;                                                                                  \
     }
@@ -125,6 +137,7 @@ inline int entry_index(int tile, int variant) { return tile * VARIANT_COUNT + va
             FG_ENTRY_H16(128, 128, 64, 2, 2, 2, AKC, BKC, "gemm_h16_" TAG "_128x128x64"),          \
             FG_ENTRY_H16(64, 64, 64, 2, 2, 2, AKC, BKC, "gemm_h16_" TAG "_64x64x64"),              \
             FG_ENTRY_H16(128, 128, 64, 4, 2, 2, AKC, BKC, "gemm_h16_" TAG "_128x128x64_deep"),     \
+            FG_ENTRY_K32(256, 256, 64, 2, 2, 4, AKC, BKC, false, true, "gemm_h16_" TAG "_256x256x64_k32"), \
         };                                                                                         \
         return t;                                                                                  \
     }
@@ -143,6 +156,7 @@ inline int entry_index(int tile, int variant) { return tile * VARIANT_COUNT + va
             FG_ENTRY_XF(128, 128, 64, 2, 2, 2, AKC, BKC, "gemm_abadd_" TAG "_128x128x64"),         \
             FG_ENTRY_XF(64, 64, 64, 2, 2, 2, AKC, BKC, "gemm_abadd_" TAG "_64x64x64"),             \
             FG_ENTRY_XF(128, 128, 64, 4, 2, 2, AKC, BKC, "gemm_abadd_" TAG "_128x128x64_deep"),    \
+            FG_EMPTY_ENTRY,                                                                        \
         };                                                                                         \
         return t;                                                                                  \
     }
@@ -174,7 +188,9 @@ inline int entry_index(int tile, int variant) { return tile * VARIANT_COUNT + va
             FG_ENTRY(64, 64, 64, 2, 2, 2, AKC, BKC, true, "gett_" TAG "_64x64x64"),                \
             FG_ENTRY_GS(64, 64, 64, 2, 2, 2, AKC, BKC, "gett_stream_" TAG "_64x64x64"),            \
             FG_ENTRY(128, 128, 64, 4, 2, 2, AKC, BKC, false, "gemm_" TAG "_128x128x64_deep"),      \
-            /* no contraction variants of the deep tile (measured: no faster there): entries stay empty */ \
+            /* no contraction variants of the deep tile (measured: no faster there) nor of the k32 one */ \
+            FG_EMPTY_ENTRY, FG_EMPTY_ENTRY,                                                        \
+            FG_ENTRY_K32(256, 256, 64, 2, 2, 4, AKC, BKC, false, false, "gemm_" TAG "_256x256x64_k32"), \
         };                                                                                         \
         return t;                                                                                  \
     }

@@ -49,7 +49,7 @@ def test_header_is_plain_c_and_links_against_the_library(tmp_path):
     out = subprocess.run([str(exe)], capture_output=True, text=True)
     assert out.returncode == 0, out
     plan, err = out.stdout.strip().split("|")
-    assert plan == "gemm_nn_256x256x64" and "A is NULL" in err
+    assert plan == "gemm_nn_256x256x64_k32" and "A is NULL" in err
 
 
 class FakeTensor:
@@ -128,8 +128,8 @@ def test_binary16_c_and_d_rules():
     im = lambda m: fg.Matrix(m.re, m.layout, m.ld, im=m.re)
     assert status(256, 256, 256, 1.0, im(A), im(B), 0.0, None, im(Dh)) == fg.FG_ERR_UNSUPPORTED
     assert status(256, 256, 256, 1.0, A, B, 0.0, None, Dh, a_add=0.5) == fg.FG_ERR_UNSUPPORTED
-    assert fg.fg_gemm_plan(8192, 8192, 8192, variant=fg.FG_PLAN_REAL_F16_CD) == "gemm_h16_nn_256x256x64"
-    assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_ROW, fg.FG_ROW, fg.FG_ROW, variant=fg.FG_PLAN_REAL_F16_CD) == "gemm_h16_nn_256x256x64"
+    assert fg.fg_gemm_plan(8192, 8192, 8192, variant=fg.FG_PLAN_REAL_F16_CD) == "gemm_h16_nn_256x256x64_k32"
+    assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_ROW, fg.FG_ROW, fg.FG_ROW, variant=fg.FG_PLAN_REAL_F16_CD) == "gemm_h16_nn_256x256x64_k32"
     assert "+" not in fg.fg_gemm_plan(512, 512, 8192, variant=fg.FG_PLAN_REAL_F16_CD)
     assert "+" not in fg.fg_gemm_plan(4100, 4100, 4096, variant=fg.FG_PLAN_REAL_F16_CD)
     with pytest.raises(fg.FlexGemmError):
@@ -142,7 +142,10 @@ def test_empty_problem_is_ok_without_a_gpu():
 
 
 def test_plan_names_follow_sizes_and_layouts():
-    assert fg.fg_gemm_plan(8192, 8192, 8192) == "gemm_nn_256x256x64"
+    # outputs with at least one 256x256 tile per compute unit: the kernel built on 16x16x32 matrix
+    # instructions (k32), which holds a higher rate once the whole chip is busy
+    assert fg.fg_gemm_plan(8192, 8192, 8192) == "gemm_nn_256x256x64_k32"
+    assert fg.fg_gemm_plan(8192, 8192, 8192, fg.FG_ROW, fg.FG_ROW) == "gemm_tt_256x256x64_k32"
     assert fg.fg_gemm_plan(8192, 1024, 4096) == "gemm_nn_256x128x64"
     # 2048^2 outputs: 256 medium tiles, one per compute unit, with the ring of four buffers that a
     # workgroup alone on its unit needs to cover the memory latency
@@ -150,13 +153,13 @@ def test_plan_names_follow_sizes_and_layouts():
     assert fg.fg_gemm_plan(1024, 1024, 1024) == "gemm_nn_64x64x64"
     assert fg.fg_gemm_plan(4096, 2048, 2048) == "gemm_nn_256x128x64"        # 512 medium tiles would share units: two buffers
     # 4100^2: 289 big tiles are one full round of 256 plus 33 leftover tiles, which are split over K
-    assert fg.fg_gemm_plan(4100, 4100, 4096) == "gemm_nn_256x256x64+tailsplitk4"
+    assert fg.fg_gemm_plan(4100, 4100, 4096) == "gemm_nn_256x256x64_k32+tailsplitk4"
     assert fg.fg_gemm_plan(256, 256, 256, fg.FG_COL, fg.FG_ROW) == "gemm_nt_64x64x64"
     # a row-major D is computed as the transposed problem: the operands swap roles
-    assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_ROW, fg.FG_ROW, fg.FG_ROW) == "gemm_nn_256x256x64"
+    assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_ROW, fg.FG_ROW, fg.FG_ROW) == "gemm_nn_256x256x64_k32"
     # sizes need not be multiples of the tile: edge tiles are predicated
     assert fg.fg_gemm_plan(100, 72, 64) == "gemm_nn_64x64x64"
-    assert fg.fg_gemm_plan(5000, 3000, 1000) == "gemm_nn_256x256x64"     # 240 tiles: one round
+    assert fg.fg_gemm_plan(5000, 3000, 1000) == "gemm_nn_256x256x64"     # 240 tiles: one round, not every unit busy: the 32x32x16 kernel
     assert fg.fg_gemm_plan(128, 64, 60) == "gemm_general_64x64x32"       # K % 8 != 0: the general kernel
     with pytest.raises(fg.FlexGemmError):
         fg.fg_gemm_plan(128, 64, 60, variant=fg.FG_PLAN_COMPLEX)
@@ -179,7 +182,7 @@ def test_planner_splits_k_only_for_small_outputs_with_long_k(monkeypatch):
     assert "+splitk" not in fg.fg_gemm_plan(256, 256, 65536, fg.FG_DIAG, fg.FG_COL)
     assert fg.fg_gemm_plan(4096, 4096, 4096, variant=fg.FG_PLAN_COMPLEX_INTERLEAVED) == "cgemm_il_nn_256x128x32"
     assert fg.fg_gemm_plan(4096, 4096, 4096, variant=fg.FG_PLAN_DUAL) == "dgemm_nn_256x128x32"
-    assert fg.fg_gemm_plan(8192, 8192, 8192, variant=fg.FG_PLAN_REAL_BF16) == "gemm_bf16_nn_256x256x64"
+    assert fg.fg_gemm_plan(8192, 8192, 8192, variant=fg.FG_PLAN_REAL_BF16) == "gemm_bf16_nn_256x256x64_k32"
 
 
 def contract_status(mA, sA, mB, sB, mC, sC, ext, pa=0x1000, pb=0x2000, pc=0x3000):

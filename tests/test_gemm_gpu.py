@@ -300,11 +300,12 @@ def test_binary16_c_and_d_whole_line_stores(monkeypatch):
 
 
 def test_every_tile_shape_in_every_kernel_family(monkeypatch):
-    """Each of the five block tiles (256x256, 256x128, 128x128, 64x64 and the 128x128 tile with a
-    ring of four buffers) forced in turn on one ragged problem, for the plain, BF16, A/B-addition
-    and binary16-result kernels and all four layout pairs: integer data, every entry exact.  The
-    deep-ring tile is also run over a K that is shorter than its ring and with K split."""
-    for tile in range(5):
+    """Each of the block tiles (256x256, 256x128, 128x128, 64x64, the 128x128 tile with a ring of
+    four buffers, and the 256x256 tile on 16x16x32 matrix instructions) forced in turn on one
+    ragged problem, for the plain, BF16, A/B-addition and binary16-result kernels and all four
+    layout pairs: integer data, every entry exact.  The deep-ring tile is also run over a K that
+    is shorter than its ring and with K split, the 16x16x32 kernel over short K and with K split."""
+    for tile in range(6):
         monkeypatch.setenv("FG_FORCE_TILE", str(tile))
         for la, lb in itertools.product((fg.FG_COL, fg.FG_ROW), repeat=2):
             say("tile %d layouts A=%d B=%d: plain, bf16, ab_add, f16 C,D" % (tile, la, lb))
@@ -317,6 +318,15 @@ def test_every_tile_shape_in_every_kernel_family(monkeypatch):
         say("deep ring, K = %d" % K); run_gemm_case(256, 384, K, ints=True)
     monkeypatch.setenv("FG_FORCE_SPLIT", "3")
     say("deep ring, K split in 3"); run_gemm_case(384, 256, 1536, fg.FG_ROW, fg.FG_COL, ints=True, bias_dim=1, act=fg.FG_ACT_RELU)
+    monkeypatch.delenv("FG_FORCE_SPLIT")
+    monkeypatch.setenv("FG_FORCE_TILE", "5")
+    for K in (8, 64, 72, 128, 192, 520):
+        say("16x16x32 kernel, K = %d" % K); run_gemm_case(300, 520, K, fg.FG_COL, fg.FG_ROW, ints=True, pad=8)
+    say("16x16x32 kernel, A/B layouts x row-major D, bias along N, ReLU")
+    for la, lb in itertools.product((fg.FG_COL, fg.FG_ROW), repeat=2):
+        run_gemm_case(520, 300, 200, la, lb, ld_layout=fg.FG_ROW, ints=True, bias_dim=1, act=fg.FG_ACT_RELU, beta=-2.0)
+    monkeypatch.setenv("FG_FORCE_SPLIT", "3")
+    say("16x16x32 kernel, K split in 3"); run_gemm_case(512, 256, 1536, fg.FG_ROW, fg.FG_COL, ints=True, bias_dim=0)
     monkeypatch.delenv("FG_FORCE_SPLIT")
     monkeypatch.delenv("FG_FORCE_TILE")
     say("planner's own choice of the deep ring, floats"); assert "deep" in fg.fg_gemm_plan(2048, 2048, 2048)
