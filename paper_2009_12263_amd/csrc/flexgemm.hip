@@ -102,12 +102,13 @@ const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
 // share a unit and one for a workgroup that has a unit to itself.  Edge tiles are predicated, so
 // a tile need not divide the problem.  K is split only when the output has too few tiles to fill
 // the GPU and K is long (may_split: plain real products).
-// allow_k32: the kernel family has the 256x256 tile with 16x16x32 matrix instructions
-// (TILE_256x256_K32).  It is not a candidate of its own: it replaces the 256x256 tile when that
-// one is chosen and the output has at least one such tile per compute unit (measured 0 to +5 %
-// there, K from 1024 to 8192; -3 to -8 % when fewer units are busy).
+// k32: the kernel family has the 256x256 tile with 16x16x32 matrix instructions
+// (TILE_256x256_K32).  It is not a candidate of its own.  k32 == 2: it replaces the 256x256 tile
+// when that one is chosen and the output has at least one such tile per compute unit (measured 0
+// to +5 % there, K from 1024 to 8192; -3 to -8 % when fewer units are busy).  k32 == 1: only when
+// forced (A and B both M/N-contiguous: measured 0 to -5 %).
 Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_smallest = true, int64_t batches = 1,
-                 bool allow_deep = true, bool allow_k32 = false) {
+                 bool allow_deep = true, int k32 = 0) {
     static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64, 128, 256};
     static const int bn[fg::TILE_COUNT] = {256, 128, 128, 64, 128, 256};
     static const int per_cu[fg::TILE_COUNT] = {1, 1, 2, 4, 1, 1};
@@ -182,9 +183,9 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_sma
             }
         }
     }
-    if (best.tile == fg::TILE_256x256 && allow_k32 && !forced_plain) {
+    if (best.tile == fg::TILE_256x256 && k32 > 0 && !forced_plain) {
         const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256) * batches;
-        if (force_k32 || tiles >= kNumCU) best.tile = fg::TILE_256x256_K32;
+        if (force_k32 || (k32 == 2 && tiles >= kNumCU)) best.tile = fg::TILE_256x256_K32;
     }
     return best;
 }
@@ -208,7 +209,8 @@ const fg::KernelEntry *select_kernel(const Problem &q, Plan *plan_out = nullptr)
         return &(q.dual ? fg::kernel_table_dual() : fg::kernel_table_cplx())[t * 4 + v];
     }
     const bool may_split = plan_out && !q.a_diag && !q.b_diag && !q.cd16;   // the reduction pass writes FP32
-    const Plan plan = choose_plan(q.M, q.N, q.K, may_split, true, 1, !q.a_diag && !q.b_diag, !q.a_diag && !q.b_diag && !q.ab_add);
+    const int k32 = (q.a_diag || q.b_diag || q.ab_add) ? 0 : ((q.a_kc || q.b_kc) ? 2 : 1);
+    const Plan plan = choose_plan(q.M, q.N, q.K, may_split, true, 1, !q.a_diag && !q.b_diag, k32);
     const int tile = plan.tile;
     if (plan_out) *plan_out = plan;
     if (q.a_diag) return &fg::kernel_table_diag()[tile * 4 + (q.b_kc ? 0 : 1)];

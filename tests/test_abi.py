@@ -146,6 +146,7 @@ def test_plan_names_follow_sizes_and_layouts():
     # instructions (k32), which holds a higher rate once the whole chip is busy
     assert fg.fg_gemm_plan(8192, 8192, 8192) == "gemm_nn_256x256x64_k32"
     assert fg.fg_gemm_plan(8192, 8192, 8192, fg.FG_ROW, fg.FG_ROW) == "gemm_tt_256x256x64_k32"
+    assert fg.fg_gemm_plan(8192, 8192, 8192, fg.FG_COL, fg.FG_ROW) == "gemm_nt_256x256x64"     # neither operand K-contiguous: measured no faster
     assert fg.fg_gemm_plan(8192, 1024, 4096) == "gemm_nn_256x128x64"
     # 2048^2 outputs: 256 medium tiles, one per compute unit, with the ring of four buffers that a
     # workgroup alone on its unit needs to cover the memory latency
