@@ -7,9 +7,10 @@
 //     tile of step k+1 streams in while step k is multiplied;
 //   * LDS tiles are XOR-swizzled (the paper pads instead and names swizzling as the missing
 //     optimisation, Section 5.1);
-//   * fragments are read in the lane layout v_mfma_f32_32x32x16_f16 wants: a K-contiguous
-//     operand with one ds_read_b128 per fragment, an M/N-contiguous operand with the
-//     transposing ds_read_b64_tr_b16;
+//   * fragments are read in the lane layout the matrix instruction wants (v_mfma_f32_32x32x16_f16,
+//     or v_mfma_f32_16x16x32_f16 in the kernels of TileCfg::M16): a K-contiguous operand with
+//     one ds_read_b128 per fragment, an M/N-contiguous operand with the transposing
+//     ds_read_b64_tr_b16;
 //   * C is read and D written straight from/to the accumulator registers with the epilogue
 //     (alpha, beta, bias, activation; Sections 4.2.3, 4.2.5, 5.3) fused into that store, so
 //     the paper's stages 1, 2, 4 and 5 (C and D through shared memory) do not exist here.
@@ -99,7 +100,7 @@ __device__ __forceinline__ int tile_row(int pos, int rows, int z_count) {
 
 // ---- tile configuration ---------------------------------------------------------------------
 // BM x BN x BK block tile, WGM x WGN waves, each wave owns a (32*TI) x (32*TJ) sub-tile made of
-// 32x32 MFMA accumulators.  A_KC / B_KC: operand is K-contiguous in memory (A row-major,
+// 32x32 MFMA accumulators (of four 16x16 ones each with M16, regrouped for the epilogue).  A_KC / B_KC: operand is K-contiguous in memory (A row-major,
 // B column-major) rather than M/N-contiguous.  STAGES LDS buffers per operand form a ring over K.
 template <int BM_, int BN_, int BK_, int STAGES_, int WGM_, int WGN_, bool A_KC_, bool B_KC_, bool STRIDED_,
           int DIAG_ = 0, int CPLX_ = 0, bool SPREAD_ = false, bool BF16_ = false, bool XFORM_ = false, bool ILV_ = false,
