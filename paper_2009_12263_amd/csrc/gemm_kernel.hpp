@@ -1140,6 +1140,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
             // pass through a window of AW registers, the one of row i being replaced by row i+AW's
             // as soon as row i's instructions are issued.
             constexpr int AW = Cfg::M16 ? (TI < 4 ? TI : 4) : TI;
+            static_assert(TI % AW == 0, "row i of every slice must find its fragment in register i % AW");
             half8 af[P][AW], bf[P][2][TJ];
 #pragma unroll
             for (int q = 0; q < P; ++q) {
