@@ -228,7 +228,11 @@ fg_status fg_init(void);
  * Name of the kernel variant and block tile that fg_gemm would use for this problem, written as
  * a NUL-terminated string into `buf` (at most `buf_len` bytes), followed by "+splitk<n>" when K
  * is split into n ranges for every tile, or "+tailsplitk<n>" when only the tiles of the last round
- * are split.  This is the "params" choice of Section 4.2.1, made here by an estimate
+ * are split.  A name ending in "_k32" is the kernel built on 16x16x32 matrix instructions, used for
+ * outputs of at least one 256x256 tile per compute unit; the others use 32x32x16 instructions.  Both
+ * accumulate the same FP16 products in FP32, in a different order: results agree within the stated
+ * tolerance and are bit-identical on integer-valued data.
+ * This is the "params" choice of Section 4.2.1, made here by an estimate
  * of the run time of every tile shape and split.  `variant` (fg_plan_variant) names the operator: real FP16, planar complex, dual, real BF16,
  * interleaved complex, or real FP16 with C and D stored as binary16.
  * Returns FG_OK, or the status fg_gemm would return for these sizes and layouts.
