@@ -169,6 +169,7 @@ struct TileCfg {
     static_assert(!(CPLX && (DIAG || STRIDED)), "complex products take plain matrices");
     static_assert(!SPREAD || STAGES >= 4 || BK >= 64, "spread refills need slack before the tile is needed");
     static_assert(!M16 || (CPLX == 0 && DIAG == 0 && !ILV && BK == 64), "16x16x32 products: real, non-diagonal operands, two k-slices per tile");
+    static_assert(!M16 || !STRIDED, "16x16x32 products: matrix kernels (the contraction kernels measured slower with them and are not built)");
     static_assert(!XFORM || (DIAG == 0 && CPLX == 0 && !BF16 && !STRIDED), "element-wise addition on A and B: plain real FP16 matrices");
     static_assert(!CSTREAM || STRIDED, "the streaming variant is a contraction kernel");
     static_assert(!CD16 || (CPLX == 0 && DIAG == 0 && !STRIDED && !ILV), "binary16 C and D: plain real matrix kernels");
