@@ -229,7 +229,7 @@ fg_status fg_init(void);
  * a NUL-terminated string into `buf` (at most `buf_len` bytes), followed by "+splitk<n>" when K
  * is split into n ranges for every tile, or "+tailsplitk<n>" when only the tiles of the last round
  * are split.  A name ending in "_k32" is the kernel built on 16x16x32 matrix instructions, used for
- * outputs of at least one 256x256 tile per compute unit; the others use 32x32x16 instructions.  Both
+ * outputs with a 256x256 tile for at least three quarters of the compute units; the others use 32x32x16 instructions.  Both
  * accumulate the same FP16 products in FP32, in a different order: results agree within the stated
  * tolerance and are bit-identical on integer-valued data.
  * This is the "params" choice of Section 4.2.1, made here by an estimate

@@ -104,9 +104,10 @@ const fg::KernelEntry *table_for(bool a_kc, bool b_kc) {
 // the GPU and K is long (may_split: plain real products).
 // k32: the kernel family has the 256x256 tile with 16x16x32 matrix instructions
 // (TILE_256x256_K32).  It is not a candidate of its own.  k32 == 2: it replaces the 256x256 tile
-// when that one is chosen and the output has at least one such tile per compute unit (measured 0
-// to +5 % there, K from 1024 to 8192; -3 to -8 % when fewer units are busy).  k32 == 1: only when
-// forced (A and B both M/N-contiguous: measured 0 to -5 %).
+// when that one is chosen and the output has such a tile for at least three quarters of the
+// compute units (measured +1 to +5 % from 192 tiles up, K from 1024 to 8192; equal at 176 tiles,
+// -1 to -6 % at 160 and fewer: a partly busy chip is not at its power limit).  k32 == 1: only
+// when forced (A and B both M/N-contiguous: measured 0 to -5 %).
 Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_smallest = true, int64_t batches = 1,
                  bool allow_deep = true, int k32 = 0) {
     static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64, 128, 256};
@@ -185,7 +186,7 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_sma
     }
     if (best.tile == fg::TILE_256x256 && k32 > 0 && !forced_plain) {
         const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256) * batches;
-        if (force_k32 || (k32 == 2 && tiles >= kNumCU)) best.tile = fg::TILE_256x256_K32;
+        if (force_k32 || (k32 == 2 && tiles >= kNumCU * 3 / 4)) best.tile = fg::TILE_256x256_K32;
     }
     return best;
 }

@@ -9,7 +9,7 @@ namespace fg {
 // compute unit), for outputs of at most one such tile per unit: a lone 4-wave workgroup turns a K
 // tile over in 512 cycles, too fast for a two-buffer ring to cover the memory latency.
 // TILE_256x256_K32: the 256x256 tile computed with 16x16x32 matrix instructions (TileCfg::M16), for
-// products that fill the GPU: there the chip runs at its power limit and that instruction shape
+// products that fill (most of) the GPU: there the chip runs at its power limit and that instruction shape
 // sustains a higher rate on the same data; on a partly filled GPU the 32x32x16 kernels are faster.
 // Plain, BF16 and binary16-result matrix kernels only (other tables leave the entry empty).
 enum TileId { TILE_256x256 = 0, TILE_256x128 = 1, TILE_128x128 = 2, TILE_64x64 = 3, TILE_128x128_DEEP = 4,

@@ -142,8 +142,8 @@ def test_empty_problem_is_ok_without_a_gpu():
 
 
 def test_plan_names_follow_sizes_and_layouts():
-    # outputs with at least one 256x256 tile per compute unit: the kernel built on 16x16x32 matrix
-    # instructions (k32), which holds a higher rate once the whole chip is busy
+    # outputs with a 256x256 tile for at least three quarters of the compute units: the kernel built on
+    # 16x16x32 matrix instructions (k32), which holds a higher rate once the chip is at its power limit
     assert fg.fg_gemm_plan(8192, 8192, 8192) == "gemm_nn_256x256x64_k32"
     assert fg.fg_gemm_plan(8192, 8192, 8192, fg.FG_ROW, fg.FG_ROW) == "gemm_tt_256x256x64_k32"
     assert fg.fg_gemm_plan(8192, 8192, 8192, fg.FG_COL, fg.FG_ROW) == "gemm_nt_256x256x64"     # neither operand K-contiguous: measured no faster
@@ -160,7 +160,8 @@ def test_plan_names_follow_sizes_and_layouts():
     assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_ROW, fg.FG_ROW, fg.FG_ROW) == "gemm_nn_256x256x64_k32"
     # sizes need not be multiples of the tile: edge tiles are predicated
     assert fg.fg_gemm_plan(100, 72, 64) == "gemm_nn_64x64x64"
-    assert fg.fg_gemm_plan(5000, 3000, 1000) == "gemm_nn_256x256x64"     # 240 tiles: one round, not every unit busy: the 32x32x16 kernel
+    assert fg.fg_gemm_plan(5000, 3000, 1000) == "gemm_nn_256x256x64_k32"  # 240 tiles: one round
+    assert fg.fg_gemm_plan(3072, 3072, 3072) == "gemm_nn_256x256x64"      # 144 tiles, under three quarters of the units: the 32x32x16 kernel
     assert fg.fg_gemm_plan(128, 64, 60) == "gemm_general_64x64x32"       # K % 8 != 0: the general kernel
     with pytest.raises(fg.FlexGemmError):
         fg.fg_gemm_plan(128, 64, 60, variant=fg.FG_PLAN_COMPLEX)
