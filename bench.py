@@ -69,8 +69,8 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True):
     res = {}
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
-    def timed(fn, reps=10):
-        for _ in range(3):
+    def timed(fn, reps=20):
+        for _ in range(20):         # enough for the clock to settle after the change of kernel
             fn()
         e0.record(stream)
         for _ in range(reps):
