@@ -254,6 +254,14 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
  */
 fg_status fg_probe_mfma(const void *fp16_operands, int32_t iters, int64_t *flops_out, void *hip_stream);
 
+/*
+ * The same measurement with v_mfma_f32_16x16x32_f16, the instruction of the "_k32" kernels
+ * (iters * 64 per wave: the same number of floating-point operations per iteration, same
+ * arguments, same return values).  On operand data that keeps the chip at its power limit the two
+ * shapes sustain different rates.
+ */
+fg_status fg_probe_mfma_k32(const void *fp16_operands, int32_t iters, int64_t *flops_out, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ FG_F16, FG_BF16, FG_F32, FG_CF16, FG_CF32 = 0, 1, 2, 3, 4
 FG_COL, FG_ROW, FG_DIAG, FG_ZERO = 0, 1, 2, 3
 FG_ACT_NONE, FG_ACT_RELU = 0, 1
 
-EXPORTS = ("fg_init", "fg_gemm", "fg_gemm_ex", "fg_gemm_dual", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan", "fg_probe_mfma")
+EXPORTS = ("fg_init", "fg_gemm", "fg_gemm_ex", "fg_gemm_dual", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan", "fg_probe_mfma", "fg_probe_mfma_k32")
 FG_PLAN_REAL, FG_PLAN_COMPLEX, FG_PLAN_DUAL, FG_PLAN_REAL_BF16, FG_PLAN_COMPLEX_INTERLEAVED, FG_PLAN_REAL_F16_CD = 0, 1, 2, 3, 4, 5
 
 
@@ -78,6 +78,8 @@ def load_library() -> C.CDLL:
         lib.fg_gemm_plan.argtypes = [i64, i64, i64, i32, i32, i32, i32, C.c_char_p, i32]
         lib.fg_probe_mfma.restype = C.c_int
         lib.fg_probe_mfma.argtypes = [vp, i32, C.POINTER(C.c_int64), vp]
+        lib.fg_probe_mfma_k32.restype = C.c_int
+        lib.fg_probe_mfma_k32.argtypes = [vp, i32, C.POINTER(C.c_int64), vp]
         _lib = lib
     return _lib
 
@@ -194,10 +196,12 @@ def fg_contract(modesA: Sequence[int], stridesA: Sequence[int], A: torch.Tensor,
     return _check(st, raise_on_error)
 
 
-def fg_probe_mfma(fp16_operands: torch.Tensor, iters: int, stream=None) -> int:
+def fg_probe_mfma(fp16_operands: torch.Tensor, iters: int, stream=None, k32: bool = False) -> int:
     """Launch the MFMA-only measurement kernel on operands from ``fp16_operands``; returns the
-    number of floating-point operations of the launch (see fg_probe_mfma in include/flexgemm.h)."""
+    number of floating-point operations of the launch (see fg_probe_mfma and fg_probe_mfma_k32 in
+    include/flexgemm.h; ``k32`` selects the 16x16x32 instruction)."""
     flops = C.c_int64(0)
-    st = load_library().fg_probe_mfma(fp16_operands.data_ptr(), iters, C.byref(flops), _stream_handle(stream))
+    fn = load_library().fg_probe_mfma_k32 if k32 else load_library().fg_probe_mfma
+    st = fn(fp16_operands.data_ptr(), iters, C.byref(flops), _stream_handle(stream))
     _check(st, True)
     return int(flops.value)

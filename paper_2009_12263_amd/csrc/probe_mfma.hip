@@ -1,9 +1,11 @@
 // Measurement aid: the rate at which the matrix units of the chip retire
-// v_mfma_f32_32x32x16_f16 when nothing else runs, for operands taken from a caller's buffer.
+// v_mfma_f32_32x32x16_f16 (fg_probe_mfma) or v_mfma_f32_16x16x32_f16 (fg_probe_mfma_k32) when
+// nothing else runs, for operands taken from a caller's buffer.
 // The engine clock of this GPU is power-managed, and dense MFMA power depends on how many operand
 // bits toggle: the same instruction stream measured 2.3-2.45 PFLOP/s on zeros or smooth values and
-// 1.7 PFLOP/s on uniform random FP16 operands.  The benchmark reports this figure next to the GEMM
-// so that the fraction of the *sustainable* MFMA rate for the workload's data can be read off.
+// 1.7 PFLOP/s on uniform random FP16 operands, and the 16x16x32 shape 2.0 PFLOP/s on those.  The
+// benchmark reports these figures next to the GEMM so that the fraction of the *sustainable* MFMA
+// rate for the workload's data can be read off.
 #include "../../include/flexgemm.h"
 
 #include <hip/hip_runtime.h>
@@ -46,16 +48,58 @@ __global__ __launch_bounds__(512) void mfma_only(const half8 *src, float *sink, 
     if (s == 12345.678f && sink) sink[0] = s;   // keeps the accumulators live; never true in practice
 }
 
-}  // namespace
+// The same operand registers as 16-row fragments of 32 k: 8 + 4 fragments (the second half repeats
+// the first) and 32 accumulators of 16x16; iters * 64 MFMAs per wave, the same flops per iteration.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(512) void mfma_only_k32(const half8 *src, float *sink, int iters) {
+    half8 a[8], b[4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = src[threadIdx.x + 512 * (i % 4)];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) b[j] = src[threadIdx.x + 512 * (4 + j % 2)];
+    floatx4 c[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) c[i][j][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) c[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(b[j], a[i], c[i][j], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s += c[i][j][r];
+    if (s == 12345.678f && sink) sink[0] = s;
+}
 
-extern "C" fg_status fg_probe_mfma(const void *fp16_operands, int32_t iters, int64_t *flops_out, void *hip_stream) {
+fg_status probe(bool k32, const void *fp16_operands, int32_t iters, int64_t *flops_out, void *hip_stream) {
     if (!fp16_operands || !flops_out) return FG_ERR_NULL;
     if (iters < 1 || iters > (1 << 20)) return FG_ERR_SHAPE;
     if (reinterpret_cast<uintptr_t>(fp16_operands) & 15u) return FG_ERR_ALIGN;
     const int blocks = 256;   // one workgroup of 8 waves per compute unit: 2 waves per SIMD
-    hipLaunchKernelGGL(mfma_only, dim3(blocks), dim3(512), 0, (hipStream_t)hip_stream, (const half8 *)fp16_operands,
-                       (float *)nullptr, iters);
+    hipLaunchKernelGGL(k32 ? mfma_only_k32 : mfma_only, dim3(blocks), dim3(512), 0, (hipStream_t)hip_stream,
+                       (const half8 *)fp16_operands, (float *)nullptr, iters);
     if (hipGetLastError() != hipSuccess) return FG_ERR_LAUNCH;
-    *flops_out = (int64_t)blocks * 8 * iters * 32 * 32768;
+    *flops_out = (int64_t)blocks * 8 * iters * 32 * 32768;      // 32 x 32768 = 64 x 16384 flop per wave and iteration
     return FG_OK;
+}
+
+}  // namespace
+
+extern "C" fg_status fg_probe_mfma_k32(const void *fp16_operands, int32_t iters, int64_t *flops_out, void *hip_stream) {
+    return probe(true, fp16_operands, iters, flops_out, hip_stream);
+}
+
+extern "C" fg_status fg_probe_mfma(const void *fp16_operands, int32_t iters, int64_t *flops_out, void *hip_stream) {
+    return probe(false, fp16_operands, iters, flops_out, hip_stream);
 }

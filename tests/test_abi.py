@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "flexgemm.h")).read()
-    declared = set(re.findall(r"\b(fg_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(fg_[a-z0-9_]+)\s*\(", header))
     assert declared == set(fg.EXPORTS)
     lib = fg.load_library()
     for name in declared:

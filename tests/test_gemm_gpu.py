@@ -412,3 +412,17 @@ def test_general_kernel_is_only_for_plain_real_products():
     assert fg.fg_gemm(64, 64, 64, 1.0, fg.Matrix(H, fg.FG_DIAG, 0), m(H), 0.0, None, m(F), **kw) == fg.FG_ERR_ALIGN
     assert fg.fg_gemm(64, 64, 60, 1.0, fg.Matrix(H, fg.FG_DIAG, 0), fg.Matrix(H, fg.FG_COL, 64), 0.0, None, fg.Matrix(F, fg.FG_COL, 64), **kw) == fg.FG_ERR_UNSUPPORTED
     torch.cuda.synchronize()
+
+
+def test_mfma_only_probes():
+    """The two measurement kernels (32x32x16 and 16x16x32 instruction streams) run on a caller's
+    buffer, report the same operation count per iteration, and reject bad arguments."""
+    buf = torch.zeros(48 * 1024, dtype=torch.float16, device="cuda")
+    for k32 in (False, True):
+        assert fg.fg_probe_mfma(buf, 10, k32=k32) == 256 * 8 * 10 * 32 * 32768
+    torch.cuda.synchronize()
+    with pytest.raises(fg.FlexGemmError):
+        fg.fg_probe_mfma(buf, 0, k32=True)
+    with pytest.raises(fg.FlexGemmError):
+        fg.fg_probe_mfma(buf[1:], 10, k32=True)       # not 16-byte aligned
+
