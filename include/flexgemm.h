@@ -21,10 +21,15 @@
  *     partial products of split-K calls (outputs with too few tiles to fill the GPU and a long K,
  *     or the leftover tiles of the last, partly filled round of a larger output, are computed as
  *     partial products over ranges of K plus a reduction pass, the cross-workgroup reduction
- *     use of the epilogue in Section 4.2.5).  All such calls on one GPU share
- *     it: calls on one stream are ordered and safe; split-K calls on different streams of one GPU
- *     must not overlap in time.  The partial products are added in a fixed order, so results do
- *     not depend on scheduling.
+ *     use of the epilogue in Section 4.2.5).  fg_gemm_plan() tells whether a problem is computed
+ *     that way ("+splitk<n>" / "+tailsplitk<n>" in the plan name).  All such calls on one GPU share
+ *     the workspace: calls on one stream are ordered anyway, and a call on another stream than the
+ *     previous user's is made to wait on the device (an event recorded after that user's reduction
+ *     pass) until the workspace is free, so calls on different streams may be issued freely; they
+ *     are serialised, not run side by side.  The exception is a stream under graph capture: the
+ *     caller orders captured split-K calls against other users of the workspace, and the workspace
+ *     must exist before the capture begins (fg_init(); FG_ERR_UNSUPPORTED otherwise).  The partial
+ *     products are added in a fixed order, so results do not depend on scheduling.
  *   - Every descriptor pointer (fg_matrix, fg_epilogue, mode/extent/stride arrays) is a HOST
  *     pointer, read only during the call.
  *   - Work is enqueued on `hip_stream` (a hipStream_t, NULL = the default stream) and the call
@@ -50,7 +55,12 @@
  *     (A row-major, B column-major), below 2^24 for the other layouts of A and B, below 2^21
  *     for C and D; half of each for interleaved complex matrices.  M, N and K are at most 2^30.
  *   - D may alias C exactly (same pointer, layout and ld: the in-place BLAS form).  A and B
- *     must not overlap D.
+ *     must not overlap D.  With beta == 0 the C term is absent and C (Cin) is never read, so it may
+ *     hold anything, NaN included (the BLAS convention).
+ *   - Non-finite values: NaN and infinities in A, B, C or bias propagate into D as IEEE arithmetic
+ *     produces them; with FG_ACT_RELU a NaN becomes 0 (relu(y) is the comparison y > 0 ? y : 0).
+ *     Memory outside the described matrices (the padding between ld and the extent, the bytes
+ *     after the last element) may hold anything: it never influences a result.
  */
 #ifndef FLEXGEMM_H
 #define FLEXGEMM_H
@@ -191,14 +201,22 @@ fg_status fg_gemm_dual(int64_t M, int64_t N, int64_t K, float alpha,
  * only or listed twice in a tensor).  A, B are FP16 device tensors, Cin (NULL iff beta term
  * absent) and Cout FP32; Cout may equal Cin.  The tensors are never transposed in memory: the
  * mode-to-tile mapping happens while tiles are loaded and while the result is stored.
- * Requirements of this version (else FG_ERR_UNSUPPORTED): in each of A and B some mode that is
- * not a batch mode has stride 1 and an extent that is a multiple of 8; at most 4 modes of extent
- * above 1 per group; A, B and C each span less than 2 GiB; at most 2^20 batch indices; no
- * negative strides.  (The summed mode that is walked fastest -- A's unit-stride mode if it is
- * summed, else B's, else the first summed mode of A -- is covered in steps of 64; an extent that
- * is not a multiple of 64 costs the zero-filled remainder of the last step.)  The row and
- * column extents are otherwise arbitrary: tiles that hang over the merged row or column extent
- * are predicated like the edge tiles of fg_gemm.
+ * Fast path (the tiled matrix-unit kernels): in each of A and B some mode that is not a batch mode
+ * has stride 1 and an extent that is a multiple of 8; every other stride of A and B is a multiple
+ * of 8 elements and the base pointers are 16-byte aligned (so that 16-byte pieces along the
+ * contiguous mode stay aligned); if both A and B are contiguous along a summed mode it is the same
+ * one; there is a summed mode; A, B and C each span less than 2 GiB.  (The summed mode that is
+ * walked fastest -- A's unit-stride mode if it is summed, else B's, else the first summed mode of A
+ * -- is covered in steps of 64; an extent that is not a multiple of 64 costs the zero-filled
+ * remainder of the last step.)  The row and column extents are otherwise arbitrary: tiles that
+ * hang over the merged row or column extent are predicated like the edge tiles of fg_gemm.
+ * A description that misses any of these is computed by a general kernel: the same mode mapping
+ * with element-wise loads and 64-bit offsets, any strides, any extents, element-aligned pointers,
+ * tensors of any size, outer products; much slower.  fg_contract_plan() tells which one serves a
+ * description, and why.
+ * Limits of both (FG_ERR_UNSUPPORTED): at most 4 modes of extent above 1 per group (rows, columns,
+ * summed, batch); merged extents up to 2^30 and at most 2^20 batch indices; no negative strides.
+ * Base pointers must be aligned to an element (FG_ERR_ALIGN).
  */
 fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA, const void *A,
                       int32_t nB, const int32_t *modesB, const int64_t *stridesB, const void *B,
@@ -207,12 +225,35 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
                       int32_t n_modes, const int32_t *mode_labels, const int64_t *mode_extents,
                       float alpha, float beta, void *hip_stream);
 
+/*
+ * Name of the kernel fg_contract would use for this description (same descriptor arguments; the
+ * data pointers are only inspected for alignment), as a NUL-terminated string in `buf`:
+ * "gett_<layouts>_<tile>" or "gett_stream_..." for the tiled kernels (the latter when whole
+ * lines of the result stream past the L2), or "gett_general_64x64x32 (<reason>)" with the first
+ * requirement of the tiled kernels that the description misses.  Returns what fg_contract would
+ * return for the description.
+ */
+fg_status fg_contract_plan(int32_t nA, const int32_t *modesA, const int64_t *stridesA, const void *A,
+                           int32_t nB, const int32_t *modesB, const int64_t *stridesB, const void *B,
+                           int32_t nC, const int32_t *modesC, const int64_t *stridesC,
+                           const float *Cin, float *Cout,
+                           int32_t n_modes, const int32_t *mode_labels, const int64_t *mode_extents,
+                           char *buf, int32_t buf_len);
+
 /* Message for the most recent failing call on this thread ("" if none).  The pointer refers to
  * thread-local static storage: valid until the next library call on the same thread. */
 const char *fg_last_error(void);
 
 /* Library version: major * 10000 + minor * 100 + patch. */
 int32_t fg_version(void);
+
+/*
+ * Tuning aid, not part of the method: the planner's overrides FG_FORCE_TILE (0..5: tile shape),
+ * FG_FORCE_SPLIT (n: K ranges for every tile) and FG_FORCE_TAIL (n: K ranges for the tiles of the
+ * last round; 1: never) are environment variables read once, when the library is loaded.  This
+ * call reads them again (for a process that changes its environment afterwards).
+ */
+void fg_reload_tuning(void);
 
 /*
  * Optional: prepare every kernel variant on the current device (raise its LDS limit, query its
@@ -245,14 +286,15 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
 /*
  * Measurement aid, not part of the method: launches a kernel that only issues
  * v_mfma_f32_32x32x16_f16 (iters * 32 per wave, 8 waves on each of the 256 compute units) on
- * operand fragments read from `fp16_operands` (device pointer, 16-byte aligned, at least 48 KiB of
- * FP16 values, e.g. the A matrix of a workload) and writes the number of floating-point
+ * operand fragments read from the first 48 KiB of `fp16_operands` (device pointer, 16-byte aligned,
+ * `operand_bytes` bytes of FP16 values, at least 48 KiB, FG_ERR_SHAPE otherwise; e.g. the A matrix
+ * of a workload) and writes the number of floating-point
  * operations of the launch to *flops_out (host).  Timed by the caller, it gives the MFMA rate the
  * chip sustains for that operand data: the engine clock is power-managed and dense MFMA power
  * depends on the operand values.  Returns FG_ERR_NULL / FG_ERR_SHAPE (iters outside 1..2^20) /
  * FG_ERR_ALIGN / FG_ERR_LAUNCH.
  */
-fg_status fg_probe_mfma(const void *fp16_operands, int32_t iters, int64_t *flops_out, void *hip_stream);
+fg_status fg_probe_mfma(const void *fp16_operands, int64_t operand_bytes, int32_t iters, int64_t *flops_out, void *hip_stream);
 
 /*
  * The same measurement with v_mfma_f32_16x16x32_f16, the instruction of the "_k32" kernels
@@ -260,7 +302,7 @@ fg_status fg_probe_mfma(const void *fp16_operands, int32_t iters, int64_t *flops
  * arguments, same return values).  On operand data that keeps the chip at its power limit the two
  * shapes sustain different rates.
  */
-fg_status fg_probe_mfma_k32(const void *fp16_operands, int32_t iters, int64_t *flops_out, void *hip_stream);
+fg_status fg_probe_mfma_k32(const void *fp16_operands, int64_t operand_bytes, int32_t iters, int64_t *flops_out, void *hip_stream);
 
 #ifdef __cplusplus
 }

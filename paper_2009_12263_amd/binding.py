@@ -22,7 +22,8 @@ FG_F16, FG_BF16, FG_F32, FG_CF16, FG_CF32 = 0, 1, 2, 3, 4
 FG_COL, FG_ROW, FG_DIAG, FG_ZERO = 0, 1, 2, 3
 FG_ACT_NONE, FG_ACT_RELU = 0, 1
 
-EXPORTS = ("fg_init", "fg_gemm", "fg_gemm_ex", "fg_gemm_dual", "fg_contract", "fg_last_error", "fg_version", "fg_gemm_plan", "fg_probe_mfma", "fg_probe_mfma_k32")
+EXPORTS = ("fg_init", "fg_gemm", "fg_gemm_ex", "fg_gemm_dual", "fg_contract", "fg_contract_plan", "fg_last_error", "fg_version",
+           "fg_reload_tuning", "fg_gemm_plan", "fg_probe_mfma", "fg_probe_mfma_k32")
 FG_PLAN_REAL, FG_PLAN_COMPLEX, FG_PLAN_DUAL, FG_PLAN_REAL_BF16, FG_PLAN_COMPLEX_INTERLEAVED, FG_PLAN_REAL_F16_CD = 0, 1, 2, 3, 4, 5
 
 
@@ -63,11 +64,15 @@ def load_library() -> C.CDLL:
         lib.fg_gemm_ex.argtypes = [i64, i64, i64, f32, C.POINTER(fg_matrix), C.POINTER(fg_matrix), f32,
                                    C.POINTER(fg_matrix), C.POINTER(fg_matrix), C.POINTER(fg_epilogue),
                                    C.POINTER(fg_load_transforms), vp]
+        lib.fg_reload_tuning.restype = None
+        lib.fg_reload_tuning.argtypes = []
         lib.fg_gemm_dual.restype = C.c_int
         lib.fg_gemm_dual.argtypes = [i64, i64, i64, f32, C.POINTER(fg_matrix), C.POINTER(fg_matrix), f32,
                                      C.POINTER(fg_matrix), C.POINTER(fg_matrix), vp]
         lib.fg_contract.restype = C.c_int
         lib.fg_contract.argtypes = [i32, vp, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, f32, f32, vp]
+        lib.fg_contract_plan.restype = C.c_int
+        lib.fg_contract_plan.argtypes = [i32, vp, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, vp, i32, vp, vp, C.c_char_p, i32]
         lib.fg_last_error.restype = C.c_char_p
         lib.fg_last_error.argtypes = []
         lib.fg_version.restype = i32
@@ -77,9 +82,9 @@ def load_library() -> C.CDLL:
         lib.fg_gemm_plan.restype = C.c_int
         lib.fg_gemm_plan.argtypes = [i64, i64, i64, i32, i32, i32, i32, C.c_char_p, i32]
         lib.fg_probe_mfma.restype = C.c_int
-        lib.fg_probe_mfma.argtypes = [vp, i32, C.POINTER(C.c_int64), vp]
+        lib.fg_probe_mfma.argtypes = [vp, i64, i32, C.POINTER(C.c_int64), vp]
         lib.fg_probe_mfma_k32.restype = C.c_int
-        lib.fg_probe_mfma_k32.argtypes = [vp, i32, C.POINTER(C.c_int64), vp]
+        lib.fg_probe_mfma_k32.argtypes = [vp, i64, i32, C.POINTER(C.c_int64), vp]
         _lib = lib
     return _lib
 
@@ -125,6 +130,11 @@ def fg_version() -> int:
 def fg_init(raise_on_error: bool = True) -> int:
     """Prepare every kernel variant on the current device; see fg_init in include/flexgemm.h."""
     return _check(load_library().fg_init(), raise_on_error)
+
+
+def fg_reload_tuning() -> None:
+    """Re-read the FG_FORCE_* tuning overrides from the environment (read once at load otherwise)."""
+    load_library().fg_reload_tuning()
 
 
 def _check(status: int, raise_on_error: bool) -> int:
@@ -196,12 +206,28 @@ def fg_contract(modesA: Sequence[int], stridesA: Sequence[int], A: torch.Tensor,
     return _check(st, raise_on_error)
 
 
+def fg_contract_plan(modesA: Sequence[int], stridesA: Sequence[int], A, modesB: Sequence[int], stridesB: Sequence[int], B,
+                     modesC: Sequence[int], stridesC: Sequence[int], Cin, Cout, extents: dict) -> str:
+    """Name of the kernel fg_contract would use; see fg_contract_plan in include/flexgemm.h."""
+    lib = load_library()
+    i32 = lambda xs: (C.c_int32 * len(xs))(*[int(x) for x in xs])
+    i64 = lambda xs: (C.c_int64 * len(xs))(*[int(x) for x in xs])
+    mA, sA, mB, sB, mC, sC = i32(modesA), i64(stridesA), i32(modesB), i64(stridesB), i32(modesC), i64(stridesC)
+    labels, exts = i32(list(extents.keys())), i64([extents[k] for k in extents])
+    ptr = lambda t: t.data_ptr() if t is not None else None
+    buf = C.create_string_buffer(256)
+    st = lib.fg_contract_plan(len(mA), mA, sA, ptr(A), len(mB), mB, sB, ptr(B), len(mC), mC, sC, ptr(Cin), ptr(Cout),
+                              len(labels), labels, exts, buf, 256)
+    _check(st, True)
+    return buf.value.decode()
+
+
 def fg_probe_mfma(fp16_operands: torch.Tensor, iters: int, stream=None, k32: bool = False) -> int:
     """Launch the MFMA-only measurement kernel on operands from ``fp16_operands``; returns the
     number of floating-point operations of the launch (see fg_probe_mfma and fg_probe_mfma_k32 in
     include/flexgemm.h; ``k32`` selects the 16x16x32 instruction)."""
     flops = C.c_int64(0)
     fn = load_library().fg_probe_mfma_k32 if k32 else load_library().fg_probe_mfma
-    st = fn(fp16_operands.data_ptr(), iters, C.byref(flops), _stream_handle(stream))
+    st = fn(fp16_operands.data_ptr(), fp16_operands.numel() * fp16_operands.element_size(), iters, C.byref(flops), _stream_handle(stream))
     _check(st, True)
     return int(flops.value)

@@ -47,6 +47,20 @@ void note_relaxed(fg_status st, const char *fmt, ...) {
 
 constexpr int kNumCU = 256;   // MI355X: 8 XCDs x 32 compute units
 
+// Tuning overrides of the planner, from the environment: FG_FORCE_TILE=0..5 picks a tile shape
+// (5: the 256x256 tile with the k32 kernel where the family has one), FG_FORCE_SPLIT=n a split of K
+// for every tile, FG_FORCE_TAIL=n a split of K for the tiles of the last round (1: never).  Read
+// when the library is loaded and again by fg_reload_tuning(), not on every call.
+std::atomic<int> g_force_tile{-1}, g_force_split{0}, g_force_tail{0};
+
+void read_tuning_from_environment() {
+    const char *t = getenv("FG_FORCE_TILE"), *s = getenv("FG_FORCE_SPLIT"), *l = getenv("FG_FORCE_TAIL");
+    g_force_tile.store(t ? atoi(t) : -1);
+    g_force_split.store(s ? atoi(s) : 0);
+    g_force_tail.store(l ? atoi(l) : 0);
+}
+struct TuningAtLoad { TuningAtLoad() { read_tuning_from_environment(); } } g_tuning_at_load;
+
 // ---- description of one GEMM after normalisation to "column-major D" ------------------------
 struct Problem {
     int64_t M, N, K;
@@ -117,18 +131,16 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_sma
     static const double rate_alone[fg::TILE_COUNT] = {1.0, 0.8, 0.43, 0.17, 0.51, 1.0};
     static const int split_options[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
     constexpr double cu_flops = 4.7e12, round_fixed = 2e-6, cu_cd_bw = 25e9, reduce_launch = 6e-6, reduce_bw = 3e12;
-    // tuning aids: FG_FORCE_TILE=0..5 picks a tile shape (5: the 256x256 tile, k32 kernel where there is one), FG_FORCE_SPLIT=n a split of K for every
-    // tile, FG_FORCE_TAIL=n a split of K for the tiles of the last round (1: never)
-    int force_tile = -1, force_split = 0, force_tail = 0;
+    // tuning overrides (see read_tuning_from_environment)
+    int force_tile = -1;
+    const int force_split = g_force_split.load(std::memory_order_relaxed), force_tail = g_force_tail.load(std::memory_order_relaxed);
     bool force_k32 = false, forced_plain = false;
-    if (const char *f = getenv("FG_FORCE_TILE")) {
-        int t = atoi(f);
+    {
+        int t = g_force_tile.load(std::memory_order_relaxed);
         if (t == fg::TILE_256x256_K32) { t = fg::TILE_256x256; force_k32 = true; }
         else forced_plain = (t == fg::TILE_256x256);
         if (t >= 0 && t < fg::TILE_COUNT) force_tile = t;
     }
-    if (const char *f = getenv("FG_FORCE_SPLIT")) force_split = atoi(f);
-    if (const char *f = getenv("FG_FORCE_TAIL")) force_tail = atoi(f);
     const int64_t nk = (K + 63) / 64;                       // K tiles (every real kernel has BK = 64)
     Plan best{0, 1, 1};
     double best_cost = -1;
@@ -252,19 +264,43 @@ fg_status prepare(const fg::KernelEntry &k, int dev, int &per_cu) {
 
 // Split-K workspace: one allocation of kWorkspaceBytes per device, made by fg_init() or by the
 // first call that splits K, and kept until the process ends.  Every split-K call on a device
-// uses it, so such calls must not overlap in time (calls on one stream never do).
-fg_status workspace(int dev, float **ws) {
-    static std::mutex m;
-    static float *per_dev[64];
+// uses it.  Calls on one stream are ordered anyway; a call on another stream than the previous
+// user's first waits (on the device, not on the host) for the event that user recorded after its
+// reduction pass, so that calls on different streams cannot overwrite each other's partial
+// products.  A stream that is being captured into a graph takes no part in this (events recorded
+// into a graph order nothing outside it): captured split-K calls must be ordered by the caller,
+// and the workspace must exist before the capture starts (fg_init()).
+struct Workspace {
+    float *ptr = nullptr;
+    hipEvent_t last_use = nullptr;       // recorded after the most recent split-K call's reduction pass
+    hipStream_t last_stream = nullptr;
+    bool used = false;
+};
+std::mutex g_ws_mutex;
+Workspace g_ws[64];
+
+bool stream_is_capturing(hipStream_t stream) {
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &st) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return st != hipStreamCaptureStatusNone;
+}
+
+// Must be called with g_ws_mutex held.
+fg_status workspace_locked(int dev, hipStream_t stream, bool may_allocate, Workspace **out) {
     if (dev < 0 || dev >= 64) return fail(FG_ERR_LAUNCH, "device index %d out of range", dev);
-    std::lock_guard<std::mutex> lock(m);
-    if (!per_dev[dev]) {
+    Workspace &w = g_ws[dev];
+    if (!w.ptr) {
+        if (!may_allocate || stream_is_capturing(stream))
+            return fail(FG_ERR_UNSUPPORTED, "this call splits K and needs the library's workspace, which cannot be allocated while the "
+                                            "stream is being captured: call fg_init() on this device before the capture");
         void *ptr = nullptr;
         hipError_t e = hipMalloc(&ptr, (size_t)kWorkspaceBytes);
         if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "hipMalloc of the split-K workspace failed: %s", hipGetErrorString(e));
-        per_dev[dev] = (float *)ptr;
+        e = hipEventCreateWithFlags(&w.last_use, hipEventDisableTiming);
+        if (e != hipSuccess) { (void)hipFree(ptr); return fail(FG_ERR_LAUNCH, "hipEventCreate for the split-K workspace failed: %s", hipGetErrorString(e)); }
+        w.ptr = (float *)ptr;
     }
-    *ws = per_dev[dev];
+    *out = &w;
     return FG_OK;
 }
 
@@ -414,10 +450,13 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
     q.dual = dual;
     q.bf16 = bf16;
     q.alpha = alpha;
-    q.beta = has_c ? beta : 0.f;
-    q.C = has_c ? (const float *)C->re : nullptr;
-    q.C_im = has_c ? (const float *)C->im : nullptr;
-    q.ldc = has_c ? C->ld : 0;
+    // beta == 0: C is validated but never read (the BLAS convention), so that D may alias an
+    // uninitialised C without its NaNs or infinities reaching the result as 0 * x
+    const bool use_c = has_c && beta != 0.f;
+    q.beta = use_c ? beta : 0.f;
+    q.C = use_c ? (const float *)C->re : nullptr;
+    q.C_im = use_c ? (const float *)C->im : nullptr;
+    q.ldc = use_c ? C->ld : 0;
     q.D = (float *)D->re;
     q.D_im = (float *)D->im;
     q.ldd = D->ld;
@@ -453,6 +492,8 @@ fg_status normalise(int64_t M, int64_t N, int64_t K, float alpha, const fg_matri
 // (the (ba) -> m convention of the paper's layout listing).  No data moves: the kernel computes
 // element offsets from these groups while it loads tiles and stores results.
 struct Contraction {
+    bool general;            // a requirement of the tiled kernels is missed: use the general kernel
+    char why_general[160];
     int64_t M, N, K, batches;
     fg::ModeGroup a_b, b_b, c_b;
     const void *A, *B;
@@ -503,9 +544,17 @@ fg_status plan_contraction(int32_t nA, const int32_t *modesA, const int64_t *str
         if (extents[i] == 0) any_zero = true;
     }
     c.M = c.N = 0; c.K = 0; c.batches = 1;
+    c.general = false; c.why_general[0] = 0;
     if (any_zero) return FG_OK;               // an empty tensor: nothing to compute
     if (!A || !B || !Cout) return fail(FG_ERR_NULL, "A, B or Cout is NULL");
-    if (!aligned16(A) || !aligned16(B) || !aligned16(Cout) || (Cin && !aligned16(Cin))) return fail(FG_ERR_ALIGN, "tensor base pointers must be 16-byte aligned");
+    if (!aligned_to(A, 2) || !aligned_to(B, 2) || !aligned_to(Cout, 4) || (Cin && !aligned_to(Cin, 4)))
+        return fail(FG_ERR_ALIGN, "tensor base pointers must be aligned to an element");
+    // A description that misses a requirement of the tiled kernels is computed by the general
+    // kernel; the first reason is kept for fg_contract_plan.
+    auto need_general = [&](const char *fmt, int x = 0, int y = 0) {
+        if (!c.general) { c.general = true; snprintf(c.why_general, sizeof c.why_general, fmt, x, y); }
+    };
+    if (!aligned16(A) || !aligned16(B) || !aligned16(Cout) || (Cin && !aligned16(Cin))) need_general("a tensor base pointer is not 16-byte aligned");
 
     // Lanes of the result run along GEMM rows, so C's unit-stride mode should be a row mode:
     // exchange the roles of A and B when it belongs to B only.
@@ -529,20 +578,21 @@ fg_status plan_contraction(int32_t nA, const int32_t *modesA, const int64_t *str
         }
         return best;
     };
-    const int ua = unit_mode(ta), ub = unit_mode(tb);
-    if (ua < 0 || ub < 0) return fail(FG_ERR_UNSUPPORTED, "A and B each need a row, column or summed mode with stride 1 and an extent that is a multiple of 8");
-    c.a_kc = is_sum(ua);                      // A's contiguous mode is summed over
-    c.b_kc = is_sum(ub);
-    if (c.a_kc && c.b_kc && ua != ub) return fail(FG_ERR_UNSUPPORTED, "A and B are contiguous along different summed modes (%d and %d)", ua, ub);
+    int ua = unit_mode(ta), ub = unit_mode(tb);
+    if (ua < 0 || ub < 0) need_general("A or B has no row, column or summed mode with stride 1 and an extent that is a multiple of 8");
+    c.a_kc = ua >= 0 && is_sum(ua);           // A's contiguous mode is summed over
+    c.b_kc = ub >= 0 && is_sum(ub);
+    if (c.a_kc && c.b_kc && ua != ub) need_general("A and B are contiguous along different summed modes (%d and %d)", ua, ub);
+    if (c.general) { ua = ub = -1; c.a_kc = c.b_kc = false; }   // the merged indices then follow the tensors' own mode order
 
     // order of the modes inside each merged index
     int32_t m_modes[16], n_modes_[16], k_modes[16], b_modes[16];
     int nm = 0, nn = 0, nkk = 0, nb = 0;
     auto push_unique = [](int32_t *arr, int &n, int32_t label) { for (int i = 0; i < n; ++i) if (arr[i] == label) return; arr[n++] = label; };
-    if (!c.a_kc) push_unique(m_modes, nm, ua);
+    if (!c.a_kc && ua >= 0) push_unique(m_modes, nm, ua);
     else if (c_unit >= 0 && is_row(c_unit)) push_unique(m_modes, nm, c_unit);
     for (int i = 0; i < tc.n; ++i) if (is_row(tc.modes[i])) push_unique(m_modes, nm, tc.modes[i]);
-    if (!c.b_kc) push_unique(n_modes_, nn, ub);
+    if (!c.b_kc && ub >= 0) push_unique(n_modes_, nn, ub);
     for (int i = 0; i < tc.n; ++i) if (is_col(tc.modes[i])) push_unique(n_modes_, nn, tc.modes[i]);
     if (c.a_kc) push_unique(k_modes, nkk, ua);
     else if (c.b_kc) push_unique(k_modes, nkk, ub);
@@ -550,7 +600,7 @@ fg_status plan_contraction(int32_t nA, const int32_t *modesA, const int64_t *str
     for (int i = 0; i < tc.n; ++i) if (is_batch(tc.modes[i])) push_unique(b_modes, nb, tc.modes[i]);
     if (nm > fg::kMaxGroupModes || nn > fg::kMaxGroupModes || nkk > fg::kMaxGroupModes || nb > fg::kMaxGroupModes)
         return fail(FG_ERR_UNSUPPORTED, "at most %d modes per merged index", fg::kMaxGroupModes);
-    if (nkk == 0) return fail(FG_ERR_UNSUPPORTED, "an outer product (no summed mode) is not supported");
+    if (nkk == 0) need_general("no summed mode (an outer product)");
 
     // Modes of extent 1 carry no index and are dropped.  For the others the kernel divides by the
     // extent with a multiply-high: with 2^s < e <= 2^(s+1) and magic = floor(2^(32+s)/e) + 1,
@@ -580,31 +630,45 @@ fg_status plan_contraction(int32_t nA, const int32_t *modesA, const int64_t *str
     if (nm == 0) c.M = 1;
     if (nn == 0) c.N = 1;
 
-    // K steps of 64 walk the leading summed mode; when its extent is not a multiple of 64 the
-    // last step of each pass is zero-filled, so the kernel sees that extent rounded up
-    if ((c.a_kc || c.b_kc) && c.a_k.extent[0] % 8) return fail(FG_ERR_UNSUPPORTED, "the leading summed mode (%d) is contiguous in A or B and must have an extent that is a multiple of 8", k_modes[0]);
-    if (c.a_k.n == 0) {
-        // every summed mode has extent 1: one K step whose k = 0 alone is loaded
-        c.a_k.n = c.b_k.n = 1;
-        c.a_k.extent[0] = c.b_k.extent[0] = 1;
-        c.a_k.stride[0] = c.b_k.stride[0] = 0;
-    }
-    c.K = c.K / c.a_k.extent[0] * ((c.a_k.extent[0] + 63) / 64 * 64);
-    if (c.a_kc && c.a_k.stride[0] != 1) return fail(FG_ERR_UNSUPPORTED, "internal: leading summed mode is not contiguous in A");
-    if (c.b_kc && c.b_k.stride[0] != 1) return fail(FG_ERR_UNSUPPORTED, "leading summed mode %d is contiguous in A but not in B", k_modes[0]);
-    if (!c.a_kc && (c.a_m.stride[0] != 1 || c.a_m.extent[0] % 8)) return fail(FG_ERR_UNSUPPORTED, "A's contiguous row mode must have an extent that is a multiple of 8");
-    if (!c.b_kc && (c.b_n.stride[0] != 1 || c.b_n.extent[0] % 8)) return fail(FG_ERR_UNSUPPORTED, "B's contiguous column mode must have an extent that is a multiple of 8");
-    // the kernel addresses A and B with 32-bit byte offsets inside a 2 GiB window
-    auto span = [&](const TensorView &t) {
-        int64_t sp = 1;
-        for (int i = 0; i < t.n; ++i) { int64_t e; extent_of(t.modes[i], e); int64_t st = t.strides[i] < 0 ? -t.strides[i] : t.strides[i]; sp += (e - 1) * st; }
-        return sp;
-    };
     for (int i = 0; i < ta.n; ++i) if (ta.strides[i] < 0) return fail(FG_ERR_UNSUPPORTED, "negative strides are not supported");
     for (int i = 0; i < tb.n; ++i) if (tb.strides[i] < 0) return fail(FG_ERR_UNSUPPORTED, "negative strides are not supported");
     for (int i = 0; i < tc.n; ++i) if (tc.strides[i] < 0) return fail(FG_ERR_UNSUPPORTED, "negative strides are not supported");
-    if (span(ta) * 2 >= (1ll << 31) || span(tb) * 2 >= (1ll << 31) || span(tc) * 4 >= (1ll << 31))
-        return fail(FG_ERR_UNSUPPORTED, "A, B and C must each span less than 2 GiB");
+    if (!c.general) {
+        if ((c.a_kc || c.b_kc) && c.a_k.n > 0 && c.a_k.extent[0] % 8) need_general("the leading summed mode (%d) is contiguous in A or B and its extent is not a multiple of 8", k_modes[0]);
+        if (c.a_kc && c.a_k.n > 0 && c.a_k.stride[0] != 1) need_general("the leading summed mode is not contiguous in A");
+        if (c.b_kc && c.b_k.n > 0 && c.b_k.stride[0] != 1) need_general("the leading summed mode (%d) is contiguous in A but not in B", k_modes[0]);
+        if ((c.a_kc || c.b_kc) && c.a_k.n == 0) need_general("the contiguous summed mode has extent 1");
+        if (!c.a_kc && (c.a_m.n == 0 || c.a_m.stride[0] != 1 || c.a_m.extent[0] % 8)) need_general("A's contiguous row mode must have an extent that is a multiple of 8");
+        if (!c.b_kc && (c.b_n.n == 0 || c.b_n.stride[0] != 1 || c.b_n.extent[0] % 8)) need_general("B's contiguous column mode must have an extent that is a multiple of 8");
+        // The tiled kernels fetch 16-byte pieces along the contiguous mode: every other stride of A
+        // and B must keep those pieces 16-byte aligned.
+        auto strides_ok = [](const fg::ModeGroup &g, int first) {
+            for (int t = first; t < g.n; ++t) if (g.stride[t] % 8) return false;
+            return true;
+        };
+        if (!strides_ok(c.a_m, c.a_kc ? 0 : 1) || !strides_ok(c.a_k, c.a_kc ? 1 : 0) || !strides_ok(c.a_b, 0))
+            need_general("a stride of A other than its contiguous mode's is not a multiple of 8 elements");
+        if (!strides_ok(c.b_n, c.b_kc ? 0 : 1) || !strides_ok(c.b_k, c.b_kc ? 1 : 0) || !strides_ok(c.b_b, 0))
+            need_general("a stride of B other than its contiguous mode's is not a multiple of 8 elements");
+        // the tiled kernels address A, B and C with 32-bit byte offsets inside a 2 GiB window
+        auto span = [&](const TensorView &t) {
+            int64_t sp = 1;
+            for (int i = 0; i < t.n; ++i) { int64_t e; extent_of(t.modes[i], e); sp += (e - 1) * t.strides[i]; }
+            return sp;
+        };
+        if (span(ta) * 2 >= (1ll << 31) || span(tb) * 2 >= (1ll << 31) || span(tc) * 4 >= (1ll << 31)) need_general("A, B or C spans 2 GiB or more");
+    }
+    if (!c.general) {
+        if (c.a_k.n == 0) {
+            // every summed mode has extent 1: one K step whose k = 0 alone is loaded
+            c.a_k.n = c.b_k.n = 1;
+            c.a_k.extent[0] = c.b_k.extent[0] = 1;
+            c.a_k.stride[0] = c.b_k.stride[0] = 0;
+        }
+        // K steps of 64 walk the leading summed mode; when its extent is not a multiple of 64 the
+        // last step of each pass is zero-filled, so the tiled kernels see that extent rounded up
+        c.K = c.K / c.a_k.extent[0] * ((c.a_k.extent[0] + 63) / 64 * 64);
+    }
     if (c.M > (1 << 30) || c.N > (1 << 30) || c.K > (1 << 30) || c.batches > (1 << 20)) return fail(FG_ERR_UNSUPPORTED, "merged extents above 2^30 (2^20 for batch modes) are not supported");
     return FG_OK;
 }
@@ -639,8 +703,9 @@ fg_status fg_init(void) {
             if (!tb.t[i].fn) continue;          // a variant that is not built for this tile
             if (fg_status st = prepare(tb.t[i], dev, per_cu)) return st;
         }
-    float *ws = nullptr;
-    return workspace(dev, &ws);
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    Workspace *w = nullptr;
+    return workspace_locked(dev, nullptr, true, &w);
 }
 
 static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
@@ -706,21 +771,29 @@ static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const f
     // workspace, then the reduction pass that also applies alpha, beta.C, bias and the activations.
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return fail(FG_ERR_LAUNCH, "no HIP device is current");
-    float *ws = nullptr;
-    if (fg_status st = workspace(dev, &ws)) return st;
     int S = plan.splits, first = 0, count = tiles;
     if (plan.tail_splits > 1) {
         int per_cu = 0;
         if (fg_status st = prepare(k, dev, per_cu)) return st;
         const int slots = per_cu * kNumCU;
         first = tiles / slots * slots; count = tiles - first; S = plan.tail_splits;
-        if (first == 0 || count == 0 || (int64_t)count * S * k.bm * k.bn * 4 > kWorkspaceBytes) { S = 1; }
-        else {
-            fg::GemmParams head = p;
-            head.tile_count = first;
-            if (fg_status st = launch(k, head, stream)) return st;
-        }
-        if (S == 1) return launch(k, p, stream);
+        if (first == 0 || count == 0 || (int64_t)count * S * k.bm * k.bn * 4 > kWorkspaceBytes) S = 1;
+    }
+    if (S == 1) return launch(k, p, stream);
+    float *ws = nullptr;
+    Workspace *guard = nullptr;
+    std::lock_guard<std::mutex> ws_lock(g_ws_mutex);
+    if (fg_status st = workspace_locked(dev, stream, true, &guard)) return st;
+    ws = guard->ptr;
+    if (stream_is_capturing(stream)) guard = nullptr;      // a captured call is ordered by its graph's caller
+    else if (guard->used && guard->last_stream != stream) {
+        hipError_t e = hipStreamWaitEvent(stream, guard->last_use, 0);
+        if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "hipStreamWaitEvent on the workspace's last use failed: %s", hipGetErrorString(e));
+    }
+    if (first > 0) {
+        fg::GemmParams head = p;
+        head.tile_count = first;
+        if (fg_status st = launch(k, head, stream)) return st;
     }
     const int64_t nk = (q.K + 63) / 64;
     fg::GemmParams part = p;
@@ -733,6 +806,12 @@ static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const f
     hipError_t e = fg::launch_splitk_reduce(ws, S, first, count, k.bm, k.bn, p.tiles_m, p.tiles_n, (int)q.M, (int)q.N, q.alpha, q.beta,
                                             q.C, q.ldc, q.D, q.ldd, q.bias, q.bias_dim, q.act, q.c_act, stream);
     if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "launch of the split-K reduction failed: %s", hipGetErrorString(e));
+    if (guard) {
+        e = hipEventRecord(guard->last_use, stream);
+        if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "hipEventRecord after the split-K reduction failed: %s", hipGetErrorString(e));
+        guard->last_stream = stream;
+        guard->used = true;
+    }
     return FG_OK;
 }
 
@@ -746,6 +825,8 @@ fg_status fg_gemm_ex(int64_t M, int64_t N, int64_t K, float alpha, const fg_matr
                      const fg_load_transforms *lt, void *hip_stream) {
     return gemm_impl(M, N, K, alpha, A, B, beta, C, D, ep, false, lt, hip_stream);
 }
+
+void fg_reload_tuning(void) { read_tuning_from_environment(); }
 
 fg_status fg_gemm_dual(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
                        float beta, const fg_matrix *C, const fg_matrix *D, void *hip_stream) {
@@ -797,16 +878,8 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
     return FG_OK;
 }
 
-fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA, const void *A,
-                      int32_t nB, const int32_t *modesB, const int64_t *stridesB, const void *B,
-                      int32_t nC, const int32_t *modesC, const int64_t *stridesC, const float *Cin, float *Cout,
-                      int32_t n_modes, const int32_t *mode_labels, const int64_t *mode_extents,
-                      float alpha, float beta, void *hip_stream) {
-    Contraction c;
-    if (fg_status st = plan_contraction(nA, modesA, stridesA, A, nB, modesB, stridesB, B, nC, modesC, stridesC,
-                                        Cin, Cout, n_modes, mode_labels, mode_extents, c))
-        return st;
-    if (c.M == 0 || c.N == 0) return FG_OK;
+// Kernel for a planned contraction (tiled kernels only): tile shape, streaming variant, row order.
+static const fg::KernelEntry *select_contract_kernel(const Contraction &c, const float *Cin, const float *Cout, int *perm_z_out) {
     // A result that is not contiguous along the leading row mode is stored in short pieces; the
     // smallest tile makes them shorter still (measured on the paper's D_abc = A_bda B_dc).
     const bool rows_contiguous = c.c_m.n == 0 || c.c_m.stride[0] == 1;
@@ -822,27 +895,81 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
                           whole_lines(c.c_n, 0) && whole_lines(c.c_b, 0) && (uintptr_t)Cout % 128 == 0 &&
                           (!Cin || (uintptr_t)Cin % 128 == 0);
     const fg::KernelEntry &k = table_for(c.a_kc, c.b_kc)[fg::entry_index(tile, c_stream ? fg::VARIANT_CONTRACT_STREAM : fg::VARIANT_CONTRACT)];
-    if (!k.fn) return fail(FG_ERR_UNSUPPORTED, "internal: no contraction kernel for tile %d", tile);
+    // Row order inside a tile (tile_row in the kernel): when A is contiguous along its leading row
+    // mode but C along the next one, and the leading mode is short enough that a tile spans at
+    // least four values of the next, let every accumulator hold 8 x 4 of (leading, next).
+    *perm_z_out = 1;
+    if (k.fn && !c.a_kc && c.c_m.n >= 2 && c.c_m.stride[1] == 1) {
+        const int e0 = c.a_m.extent[0];
+        if (e0 % 8 == 0 && k.bm % e0 == 0 && k.bm / e0 >= 4) *perm_z_out = k.bm / e0;
+    }
+    return k.fn ? &k : nullptr;
+}
+
+fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA, const void *A,
+                      int32_t nB, const int32_t *modesB, const int64_t *stridesB, const void *B,
+                      int32_t nC, const int32_t *modesC, const int64_t *stridesC, const float *Cin, float *Cout,
+                      int32_t n_modes, const int32_t *mode_labels, const int64_t *mode_extents,
+                      float alpha, float beta, void *hip_stream) {
+    Contraction c;
+    if (fg_status st = plan_contraction(nA, modesA, stridesA, A, nB, modesB, stridesB, B, nC, modesC, stridesC,
+                                        Cin, Cout, n_modes, mode_labels, mode_extents, c))
+        return st;
+    if (c.M == 0 || c.N == 0) return FG_OK;
+    const bool use_c = Cin != nullptr && beta != 0.f;        // beta == 0: Cin is never read
+    if (c.general) {
+        fg::ContractFallbackParams f;
+        memset(&f, 0, sizeof f);
+        f.M = (int32_t)c.M; f.N = (int32_t)c.N; f.K = (int32_t)c.K; f.batches = (int32_t)c.batches;
+        f.A = (const _Float16 *)c.A; f.B = (const _Float16 *)c.B;
+        f.C = use_c ? Cin : nullptr; f.D = Cout;
+        f.a_m = c.a_m; f.a_k = c.a_k; f.b_n = c.b_n; f.b_k = c.b_k; f.c_m = c.c_m; f.c_n = c.c_n;
+        f.a_b = c.a_b; f.b_b = c.b_b; f.c_b = c.c_b;
+        f.alpha = alpha; f.beta = use_c ? beta : 0.f;
+        f.a_kfast = c.a_k.n > 0 && c.a_k.stride[0] == 1;
+        f.b_kfast = c.b_k.n > 0 && c.b_k.stride[0] == 1;
+        if (((c.M + 63) / 64) * ((c.N + 63) / 64) * c.batches >= (1ll << 31)) return fail(FG_ERR_UNSUPPORTED, "too many tiles");
+        hipError_t e = fg::launch_contract_fallback(f, (hipStream_t)hip_stream);
+        if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "launch of the general contraction kernel failed: %s", hipGetErrorString(e));
+        return FG_OK;
+    }
+    int perm_z = 1;
+    const fg::KernelEntry *kp = select_contract_kernel(c, Cin, Cout, &perm_z);
+    if (!kp) return fail(FG_ERR_UNSUPPORTED, "internal: no contraction kernel for this tile");
+    const fg::KernelEntry &k = *kp;
     fg::GemmParams p;
     memset(&p, 0, sizeof p);
     p.M = (int32_t)c.M; p.N = (int32_t)c.N; p.K = (int32_t)c.K;
     p.tiles_m = (int32_t)((c.M + k.bm - 1) / k.bm); p.tiles_n = (int32_t)((c.N + k.bn - 1) / k.bn);
     p.A = (const _Float16 *)c.A; p.B = (const _Float16 *)c.B;
-    p.C = Cin; p.D = Cout;
-    p.has_c = (Cin != nullptr);
-    p.alpha = alpha; p.beta = Cin ? beta : 0.f;
+    p.C = use_c ? Cin : nullptr; p.D = Cout;
+    p.has_c = use_c;
+    p.alpha = alpha; p.beta = use_c ? beta : 0.f;
     p.a_m = c.a_m; p.a_k = c.a_k; p.b_n = c.b_n; p.b_k = c.b_k; p.c_m = c.c_m; p.c_n = c.c_n;
     p.a_b = c.a_b; p.b_b = c.b_b; p.c_b = c.c_b; p.batches = (int32_t)c.batches;
     if ((int64_t)p.tiles_m * p.tiles_n * c.batches >= (1ll << 31)) return fail(FG_ERR_UNSUPPORTED, "too many tiles");
-    // Row order inside a tile (tile_row in the kernel): when A is contiguous along its leading row
-    // mode but C along the next one, and the leading mode is short enough that a tile spans at
-    // least four values of the next, let every accumulator hold 8 x 4 of (leading, next).
-    p.perm_z = 1;
-    if (!c.a_kc && c.c_m.n >= 2 && c.c_m.stride[1] == 1) {
-        const int e0 = c.a_m.extent[0];
-        if (e0 % 8 == 0 && k.bm % e0 == 0 && k.bm / e0 >= 4) p.perm_z = k.bm / e0;
-    }
+    p.perm_z = perm_z;
     return launch(k, p, (hipStream_t)hip_stream);
+}
+
+fg_status fg_contract_plan(int32_t nA, const int32_t *modesA, const int64_t *stridesA, const void *A,
+                           int32_t nB, const int32_t *modesB, const int64_t *stridesB, const void *B,
+                           int32_t nC, const int32_t *modesC, const int64_t *stridesC, const float *Cin, float *Cout,
+                           int32_t n_modes, const int32_t *mode_labels, const int64_t *mode_extents,
+                           char *buf, int32_t buf_len) {
+    if (!buf || buf_len <= 0) return fail(FG_ERR_NULL, "buf is NULL or empty");
+    buf[0] = 0;
+    Contraction c;
+    if (fg_status st = plan_contraction(nA, modesA, stridesA, A, nB, modesB, stridesB, B, nC, modesC, stridesC,
+                                        Cin, Cout, n_modes, mode_labels, mode_extents, c))
+        return st;
+    if (c.M == 0 || c.N == 0) { snprintf(buf, (size_t)buf_len, "nothing to compute"); return FG_OK; }
+    if (c.general) { snprintf(buf, (size_t)buf_len, "gett_general_64x64x32 (%s)", c.why_general); return FG_OK; }
+    int perm_z = 1;
+    const fg::KernelEntry *k = select_contract_kernel(c, Cin, Cout, &perm_z);
+    if (!k) return fail(FG_ERR_UNSUPPORTED, "internal: no contraction kernel for this tile");
+    snprintf(buf, (size_t)buf_len, "%s", k->name);
+    return FG_OK;
 }
 
 }  // extern "C"

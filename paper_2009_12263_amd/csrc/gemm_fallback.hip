@@ -55,6 +55,7 @@ __global__ __launch_bounds__(256) void gemm_fallback(FallbackParams p) {
     }
     const float floor_v = p.act == 1 ? 0.f : -__builtin_inff();
     const float floor_c = p.c_act == 1 ? 0.f : -__builtin_inff();
+    const bool act_none = p.act != 1, c_act_none = p.c_act != 1;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int n = n0 + 4 * ty + j;
@@ -66,10 +67,10 @@ __global__ __launch_bounds__(256) void gemm_fallback(FallbackParams p) {
             float y = p.alpha * acc[i][j];
             if (p.C) {
                 const float c = p.C[m + (int64_t)n * p.ldc];
-                y += p.beta * (c > floor_c ? c : floor_c);
+                y += p.beta * act_clamp(c, floor_c, c_act_none);
             }
             if (p.bias) y += p.bias[p.bias_dim == 0 ? m : n];
-            y = y > floor_v ? y : floor_v;
+            y = act_clamp(y, floor_v, act_none);
             p.D[m + (int64_t)n * p.ldd] = y;
         }
     }

@@ -617,6 +617,12 @@ __device__ __forceinline__ void store_cd(float y, __amdgpu_buffer_rsrc_t r, uint
     }
 }
 
+// The activation as the comparison that defines it, relu(v) = v > 0 ? v : 0 (a NaN becomes 0); with
+// no activation (`pass`, uniform) the value goes through untouched, so that NaN and infinities in
+// the operands reach D as IEEE arithmetic produces them.  Written with a floor so that both cases
+// are one compare and one select; the uniform flag is merged into the compare's lane mask.
+__device__ __forceinline__ float act_clamp(float v, float floor_v, bool pass) { return ((v > floor_v) | pass) ? v : floor_v; }
+
 template <class Cfg>
 constexpr int stream_policy() { return (Cfg::DIAG == 0 && (!Cfg::STRIDED || Cfg::CSTREAM)) ? 2 : 0; }   // gfx950 cache policy: bit 1 = nt
 template <class Cfg, bool HAS_C>
@@ -627,6 +633,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
     const bool bias_m_on = p.bias && p.bias_dim == 0, bias_n_on = p.bias && p.bias_dim != 0;
     const float floor_v = p.act == 1 ? 0.f : -__builtin_inff();
     const float floor_c = p.c_act == 1 ? 0.f : -__builtin_inff();       // activation on loaded C
+    const bool pass_v = p.act != 1, pass_c = p.c_act != 1;              // no activation: NaN and -inf pass through
     if constexpr (!Cfg::STRIDED) {
         // (m, n) at m + n*ld.  All accesses are buffer operations on a descriptor whose base is this
         // wave's corner of the tile: the per-lane part of the address is one register for all of
@@ -705,11 +712,11 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                     if constexpr (HAS_C) {
                         float c0 = cv[b % (AHEAD + 1)][2 * r8], c1 = cv[b % (AHEAD + 1)][2 * r8 + 1];
                         exchange(c0, c1);
-                        v0 += p.beta * (c0 > floor_c ? c0 : floor_c);
-                        v1 += p.beta * (c1 > floor_c ? c1 : floor_c);
+                        v0 += p.beta * act_clamp(c0, floor_c, pass_c);
+                        v1 += p.beta * act_clamp(c1, floor_c, pass_c);
                     }
-                    v0 = v0 > floor_v ? v0 : floor_v;
-                    v1 = v1 > floor_v ? v1 : floor_v;
+                    v0 = act_clamp(v0, floor_v, pass_v);
+                    v1 = act_clamp(v1, floor_v, pass_v);
                     exchange(v0, v1);
                     y[2 * r8] = v0;
                     y[2 * r8 + 1] = v1;
@@ -766,9 +773,9 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                     float v = p.alpha * acc[i][j][r] + bv[r];
                     if constexpr (HAS_C) {
                         const float c = cv[b % (AHEAD + 1)][r];
-                        v += p.beta * (c > floor_c ? c : floor_c);
+                        v += p.beta * act_clamp(c, floor_c, pass_c);
                     }
-                    y[r] = v > floor_v ? v : floor_v;
+                    y[r] = act_clamp(v, floor_v, pass_v);
                 }
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
@@ -806,8 +813,8 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                                 const int r = 8 * h + r8;
                                 const bool n_ok = n_base + 32 * j + Cfg::acc_col(r) + Cfg::ACC_LH * lh < p.N;
                                 float y = p.alpha * acc[i][j][r] + bv[r8];
-                                if constexpr (HAS_C) y += p.beta * (cv[r8] > floor_c ? cv[r8] : floor_c);
-                                y = y > floor_v ? y : floor_v;
+                                if constexpr (HAS_C) y += p.beta * act_clamp(cv[r8], floor_c, pass_c);
+                                y = act_clamp(y, floor_v, pass_v);
                                 store_cd<H, kStream>(y, rd, n_ok ? vd : kOutOfRange, 32 * ES * i + (32 * j + Cfg::acc_col(r)) * ldd4);
                             }
                         }
@@ -876,7 +883,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                 for (int r = 0; r < 16; ++r) {
                     float v = p.alpha * acc[i][j][r];
                     if constexpr (HAS_C) v += p.beta * cv[i % (AHEAD + 1)][r];
-                    y[r] = v > floor_v ? v : floor_v;
+                    y[r] = act_clamp(v, floor_v, pass_v);
                 }
 #pragma unroll
                 for (int r = 0; r < 16; ++r)

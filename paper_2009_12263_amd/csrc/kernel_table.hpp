@@ -79,6 +79,19 @@ struct FallbackParams {
 };
 hipError_t launch_gemm_fallback(const FallbackParams &p, hipStream_t stream);
 
+// General kernel for contractions the tiled kernels cannot take (contract_fallback.hip): same
+// mode groups as GemmParams, 64-bit element offsets.
+struct ContractFallbackParams {
+    int32_t M, N, K, batches;
+    const _Float16 *A, *B;
+    const float *C;
+    float *D;
+    ModeGroup a_m, a_k, b_n, b_k, c_m, c_n, a_b, b_b, c_b;
+    float alpha, beta;
+    int32_t a_kfast, b_kfast;    // the operand's leading summed mode has stride 1: load with lanes along k
+};
+hipError_t launch_contract_fallback(const ContractFallbackParams &p, hipStream_t stream);
+
 // Entry index inside one table of real kernels: three variants per tile.
 enum Variant { VARIANT_MATRIX = 0, VARIANT_CONTRACT = 1, VARIANT_CONTRACT_STREAM = 2, VARIANT_COUNT = 3 };
 inline int entry_index(int tile, int variant) { return tile * VARIANT_COUNT + variant; }

@@ -82,9 +82,10 @@ __global__ __launch_bounds__(512) void mfma_only_k32(const half8 *src, float *si
     if (s == 12345.678f && sink) sink[0] = s;
 }
 
-fg_status probe(bool k32, const void *fp16_operands, int32_t iters, int64_t *flops_out, void *hip_stream) {
+fg_status probe(bool k32, const void *fp16_operands, int64_t operand_bytes, int32_t iters, int64_t *flops_out, void *hip_stream) {
     if (!fp16_operands || !flops_out) return FG_ERR_NULL;
     if (iters < 1 || iters > (1 << 20)) return FG_ERR_SHAPE;
+    if (operand_bytes < 48 * 1024) return FG_ERR_SHAPE;      // the kernels read the first 48 KiB
     if (reinterpret_cast<uintptr_t>(fp16_operands) & 15u) return FG_ERR_ALIGN;
     const int blocks = 256;   // one workgroup of 8 waves per compute unit: 2 waves per SIMD
     hipLaunchKernelGGL(k32 ? mfma_only_k32 : mfma_only, dim3(blocks), dim3(512), 0, (hipStream_t)hip_stream,
@@ -96,10 +97,10 @@ fg_status probe(bool k32, const void *fp16_operands, int32_t iters, int64_t *flo
 
 }  // namespace
 
-extern "C" fg_status fg_probe_mfma_k32(const void *fp16_operands, int32_t iters, int64_t *flops_out, void *hip_stream) {
-    return probe(true, fp16_operands, iters, flops_out, hip_stream);
+extern "C" fg_status fg_probe_mfma_k32(const void *fp16_operands, int64_t operand_bytes, int32_t iters, int64_t *flops_out, void *hip_stream) {
+    return probe(true, fp16_operands, operand_bytes, iters, flops_out, hip_stream);
 }
 
-extern "C" fg_status fg_probe_mfma(const void *fp16_operands, int32_t iters, int64_t *flops_out, void *hip_stream) {
-    return probe(false, fp16_operands, iters, flops_out, hip_stream);
+extern "C" fg_status fg_probe_mfma(const void *fp16_operands, int64_t operand_bytes, int32_t iters, int64_t *flops_out, void *hip_stream) {
+    return probe(false, fp16_operands, operand_bytes, iters, flops_out, hip_stream);
 }

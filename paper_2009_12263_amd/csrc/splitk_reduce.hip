@@ -35,14 +35,15 @@ __global__ __launch_bounds__(256) void splitk_reduce(const float *W, int splits,
     }
     const float floor_v = act == 1 ? 0.f : -__builtin_inff();
     const float floor_c = c_act == 1 ? 0.f : -__builtin_inff();
+    const bool act_none = act != 1, c_act_none = c_act != 1;
     for (int q = 0; q < valid; ++q) {
         float y = alpha * sum[q];
         if (C) {
             const float c = C[m + q + (int64_t)n * ldc];
-            y += beta * (c > floor_c ? c : floor_c);
+            y += beta * act_clamp(c, floor_c, c_act_none);
         }
         if (bias) y += bias[bias_dim == 0 ? m + q : n];
-        y = y > floor_v ? y : floor_v;
+        y = act_clamp(y, floor_v, act_none);
         D[m + q + (int64_t)n * ldd] = y;
     }
 }

@@ -27,8 +27,27 @@ from paper_2009_12263_amd import workloads as W
 OFFICIAL_RTOL = 2e-3
 
 
+def setenv(monkeypatch, name: str, value: str):
+    """Set one of the library's FG_FORCE_* tuning variables and make the library read it (it reads
+    its environment once, at load); tests/conftest.py re-reads after the test has restored it."""
+    monkeypatch.setenv(name, value)
+    fg.fg_reload_tuning()
+
+
+def delenv(monkeypatch, name: str, raising: bool = True):
+    monkeypatch.delenv(name, raising=raising)
+    fg.fg_reload_tuning()
+
+
+def poison_padding(t: torch.Tensor, lead: int, ld: int, other: int):
+    """NaN into every element between the extent and the leading dimension: memory the library may
+    read (inside 16-byte chunks and edge tiles) but must never let influence a result."""
+    if ld > lead and other > 0:
+        t[:ld * other].view(other, ld)[:, lead:] = float("nan")
+
+
 def make_operand(rows: int, cols: int, layout: int, stream: int, device, ints: bool, pad: int = 0, seed=W.DEFAULT_SEED,
-                 dtype=torch.float16):
+                 dtype=torch.float16, poison: bool = False):
     """A stored rows x cols FP16 (or BF16) operand in FG_COL / FG_ROW layout with ld = extent + pad.
     Returns (device tensor, ld)."""
     lead = rows if layout == fg.FG_COL else cols
@@ -36,6 +55,8 @@ def make_operand(rows: int, cols: int, layout: int, stream: int, device, ints: b
     ld = (lead + 7) // 8 * 8 + pad          # leading dimensions of FP16 operands are multiples of 8
     gen = W.small_ints if ints else W.uniform_pm1
     t = gen(ld * other, stream, seed=seed, device=device, dtype=dtype)
+    if poison:
+        poison_padding(t, lead, ld, other)
     return t, ld
 
 
@@ -96,13 +117,14 @@ def compare(got: np.ndarray, ref: np.ndarray, G: np.ndarray, K: int, exact: bool
 def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alpha=1.0, beta=1.0, with_c=True,
                   bias_dim=None, act=fg.FG_ACT_NONE, ints=False, pad=0, config=1, samples: Optional[int] = None,
                   inplace=False, device="cuda", seed=W.DEFAULT_SEED, bf16=False, ab_add=None, c_act=fg.FG_ACT_NONE,
-                  cd16=False):
+                  cd16=False, poison=False):
     """Run fg_gemm on seeded inputs and compare with the oracle.  ``samples`` None: every entry.
-    ``cd16``: C and D are stored as binary16 (any leading dimension)."""
+    ``cd16``: C and D are stored as binary16 (any leading dimension).  ``poison``: the padding of
+    A, B and C (everything between an extent and its leading dimension) holds NaN."""
     dt = torch.bfloat16 if bf16 else torch.float16
     odt = O.BF16 if bf16 else O.F16
-    A, lda = make_operand(M, K, la, W.stream_id(config, "A"), device, ints, pad, seed, dt)
-    B, ldb = make_operand(K, N, lb, W.stream_id(config, "B"), device, ints, pad, seed, dt)
+    A, lda = make_operand(M, K, la, W.stream_id(config, "A"), device, ints, pad, seed, dt, poison)
+    B, ldb = make_operand(K, N, lb, W.stream_id(config, "B"), device, ints, pad, seed, dt, poison)
     lead, other = (M, N) if ld_layout == fg.FG_COL else (N, M)
     ldc = (lead + 3) // 4 * 4 + (4 if pad else 0)   # leading dimensions of FP32 operands are multiples of 4
     cd_dtype = torch.float32
@@ -111,6 +133,8 @@ def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alph
         cd_dtype = torch.float16
     gen_cd = W.small_ints if ints else W.uniform_pm1
     Cbuf = gen_cd(ldc * other, W.stream_id(config, "C"), seed=seed, device=device, dtype=cd_dtype) if with_c else None
+    if poison and with_c:
+        poison_padding(Cbuf, lead, ldc, other)
     bias = None
     if bias_dim is not None:
         bias = make_f32(M if bias_dim == 0 else N, W.stream_id(config, "bias"), device, ints, seed)
@@ -124,7 +148,7 @@ def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alph
     D_host = np16(Dbuf)
     # padding of D must be untouched
     Dm = D_host.reshape(other, ldc)
-    if ldc > lead and not inplace:
+    if ldc > lead and (not inplace or poison):
         assert np.isnan(Dm[:, lead:]).all(), "padding of D was written"
     Dlog = Dm[:, :lead].T if ld_layout == fg.FG_COL else Dm[:, :lead]       # logical M x N view
     at = None
@@ -178,8 +202,9 @@ def run_unaligned_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG
 
 def run_contract_case(extents, modesA, modesB, modesC, alpha=1.0, beta=0.0, ints=False, samples: Optional[int] = None,
                       stridesA=None, stridesB=None, stridesC=None, inplace=False, config=5, device="cuda",
-                      seed=W.DEFAULT_SEED, B_override=None):
-    """Run fg_contract on seeded dense (or explicitly strided) tensors and compare with the oracle."""
+                      seed=W.DEFAULT_SEED, B_override=None, poison=False):
+    """Run fg_contract on seeded dense (or explicitly strided) tensors and compare with the oracle.
+    ``poison``: every position of A, B and Cin that the strided tensors do not reach holds NaN."""
     ext = lambda ms: [extents[m] for m in ms]
     sA = list(stridesA) if stridesA else list(W.col_major_strides(tuple(ext(modesA))))
     sB = list(stridesB) if stridesB else list(W.col_major_strides(tuple(ext(modesB))))
@@ -192,6 +217,18 @@ def run_contract_case(extents, modesA, modesB, modesC, alpha=1.0, beta=0.0, ints
         B = B_override.to(device)
     nC = span(modesC, sC)
     Cin = gen(nC, W.stream_id(config, "C"), seed=seed, device=device, dtype=torch.float32) if beta != 0.0 else None
+    if poison:
+        def reached_mask(modes, strides, n):
+            idx = torch.zeros(1, dtype=torch.int64)
+            for m, st in zip(modes, strides):
+                idx = (idx[:, None] + torch.arange(extents[m], dtype=torch.int64)[None, :] * st).reshape(-1)
+            mask = torch.zeros(n, dtype=torch.bool)
+            mask[idx] = True
+            return mask.to(device)
+        A[~reached_mask(modesA, sA, A.numel())] = float("nan")
+        B[~reached_mask(modesB, sB, B.numel())] = float("nan")
+        if Cin is not None:
+            Cin[~reached_mask(modesC, sC, nC)] = float("nan")
     Cout = Cin if (inplace and Cin is not None) else torch.full((nC,), float("nan"), dtype=torch.float32, device=device)
     Cin_host = np16(Cin).copy() if Cin is not None else None
     fg.fg_contract(modesA, sA, A, modesB, sB, B, modesC, sC, Cin, Cout, extents, alpha=alpha, beta=beta)
@@ -253,18 +290,21 @@ def run_diag_case(M, N, K, side="A", other_layout=fg.FG_COL, ld_layout=fg.FG_COL
 
 def run_cgemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alpha=1.0, beta=1.0, with_c=True,
                    ints=False, pad=0, config=4, samples: Optional[int] = None, device="cuda", seed=W.DEFAULT_SEED,
-                   dual=False, interleaved=False):
+                   dual=False, interleaved=False, poison=False):
     """Planar-split complex (or, with ``dual``, dual-number) D = alpha A B + beta C; the two planes
     are separate arrays.  ``interleaved``: the same numbers stored with real and imaginary parts
-    adjacent (FG_CF16 inputs, FG_CF32 C and D)."""
-    Ar, lda = make_operand(M, K, la, W.stream_id(config, "A"), device, ints, pad, seed)
-    Ai, _ = make_operand(M, K, la, W.stream_id(config, "A_im"), device, ints, pad, seed)
-    Br, ldb = make_operand(K, N, lb, W.stream_id(config, "B"), device, ints, pad, seed)
-    Bi, _ = make_operand(K, N, lb, W.stream_id(config, "B_im"), device, ints, pad, seed)
+    adjacent (FG_CF16 inputs, FG_CF32 C and D).  ``poison``: NaN in the padding of A, B and C."""
+    Ar, lda = make_operand(M, K, la, W.stream_id(config, "A"), device, ints, pad, seed, poison=poison)
+    Ai, _ = make_operand(M, K, la, W.stream_id(config, "A_im"), device, ints, pad, seed, poison=poison)
+    Br, ldb = make_operand(K, N, lb, W.stream_id(config, "B"), device, ints, pad, seed, poison=poison)
+    Bi, _ = make_operand(K, N, lb, W.stream_id(config, "B_im"), device, ints, pad, seed, poison=poison)
     lead, other = (M, N) if ld_layout == fg.FG_COL else (N, M)
     ldc = (lead + 3) // 4 * 4 + (4 if pad else 0)
     Cr = make_f32(ldc * other, W.stream_id(config, "C"), device, ints, seed) if with_c else None
     Ci = make_f32(ldc * other, W.stream_id(config, "C_im"), device, ints, seed) if with_c else None
+    if poison and with_c:
+        poison_padding(Cr, lead, ldc, other)
+        poison_padding(Ci, lead, ldc, other)
     Dr = torch.full((ldc * other,), float("nan"), dtype=torch.float32, device=device)
     Di = torch.full((ldc * other,), float("nan"), dtype=torch.float32, device=device)
     if interleaved:

@@ -8,6 +8,16 @@ import pytest
 
 from paper_2009_12263_amd import binding as fg
 
+
+def delenv(monkeypatch, name, raising=True):
+    monkeypatch.delenv(name, raising=raising)
+    fg.fg_reload_tuning()
+
+
+def setenv(monkeypatch, name, value):
+    monkeypatch.setenv(name, value)
+    fg.fg_reload_tuning()
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
@@ -168,9 +178,9 @@ def test_plan_names_follow_sizes_and_layouts():
 
 
 def test_planner_splits_k_only_for_small_outputs_with_long_k(monkeypatch):
-    monkeypatch.delenv("FG_FORCE_SPLIT", raising=False)
-    monkeypatch.delenv("FG_FORCE_TILE", raising=False)
-    monkeypatch.delenv("FG_FORCE_TAIL", raising=False)
+    delenv(monkeypatch, "FG_FORCE_SPLIT", raising=False)
+    delenv(monkeypatch, "FG_FORCE_TILE", raising=False)
+    delenv(monkeypatch, "FG_FORCE_TAIL", raising=False)
     for shape in [(8192, 8192, 8192), (4096, 4096, 4096), (2048, 2048, 2048), (1024, 1024, 1024), (65536, 256, 256), (256, 256, 256)]:
         assert "+splitk" not in fg.fg_gemm_plan(*shape), shape
     for shape in [(512, 512, 8192), (256, 256, 65536), (64, 64, 32768), (1024, 1024, 8192), (128, 4096, 16384)]:
@@ -193,6 +203,40 @@ def contract_status(mA, sA, mB, sB, mC, sC, ext, pa=0x1000, pb=0x2000, pc=0x3000
                           FakeTensor(pc, torch.float32), ext, raise_on_error=False)
 
 
+def contract_plan(mA, sA, mB, sB, mC, sC, ext, pa=0x1000, pb=0x2000, pc=0x3000):
+    import torch
+    return fg.fg_contract_plan(mA, sA, FakeTensor(pa, torch.float16), mB, sB, FakeTensor(pb, torch.float16), mC, sC, None,
+                               FakeTensor(pc, torch.float32), ext)
+
+
+def test_contraction_descriptions_the_tiled_kernels_cannot_take_go_to_the_general_kernel():
+    a, b, c, d, e = 0, 1, 2, 3, 4
+    ext = {a: 64, b: 64, c: 64, d: 64}
+    dense3 = [1, 64, 4096]
+    assert contract_plan([a, d, c], dense3, [d, b], [1, 64], [a, b, c], dense3, ext).startswith("gett_")
+    assert "general" not in contract_plan([a, d, c], dense3, [d, b], [1, 64], [a, b, c], dense3, ext)
+    general = lambda *args, **kw: contract_plan(*args, **kw).startswith("gett_general_64x64x32 (")
+    # no unit-stride mode in A
+    assert general([a, d, c], [2, 128, 8192], [d, b], [1, 64], [a, b, c], dense3, ext)
+    # B is contiguous along the summed mode, whose extent is not a multiple of 8
+    ext2 = {a: 64, b: 64, c: 64, d: 36}
+    assert general([a, d, c], [1, 64, 2304], [d, b], [1, 36], [a, b, c], dense3, ext2)
+    # base pointer aligned to an element only
+    assert general([a, d, c], dense3, [d, b], [1, 64], [a, b, c], dense3, ext, pa=0x1002)
+    assert general([a, d, c], dense3, [d, b], [1, 64], [a, b, c], dense3, ext, pc=0x3004)
+    # a stride of A that would put 16-byte pieces at 2-byte alignment (padded tensor)
+    assert general([a, d, c], [1, 65, 65 * 64], [d, b], [1, 64], [a, b, c], dense3, ext)
+    assert not general([a, d, c], [1, 72, 72 * 64], [d, b], [1, 64], [a, b, c], dense3, ext)
+    # A and B contiguous along different summed modes
+    ext5 = {a: 64, b: 64, d: 64, e: 64}
+    assert general([d, e, a], dense3, [e, d, b], dense3, [a, b], [1, 64], ext5)
+    # an outer product
+    assert general([a], [1], [b], [1], [a, b], [1, 64], {a: 64, b: 64})
+    # a tensor of 2 GiB
+    big = {a: 1 << 15, b: 64, d: 1 << 15}
+    assert general([a, d], [1, 1 << 15], [d, b], [1, 1 << 15], [a, b], [1, 1 << 15], big)
+
+
 def test_contract_argument_errors():
     a, b, c, d = 0, 1, 2, 3
     ext = {a: 64, b: 64, c: 64, d: 64}
@@ -203,13 +247,13 @@ def test_contract_argument_errors():
     assert contract_status([a, d, 9], dense3, [d, b], [1, 64], [a, b, 9], dense3, ext) == fg.FG_ERR_MODES
     # repeated mode inside one tensor
     assert contract_status([a, a, d], dense3, [d, b], [1, 64], [a, b], [1, 64], ext) == fg.FG_ERR_MODES
-    # no unit-stride mode in A
-    assert contract_status([a, d, c], [2, 128, 8192], [d, b], [1, 64], [a, b, c], dense3, ext) == fg.FG_ERR_UNSUPPORTED
-    # B is contiguous along the summed mode, whose extent is not a multiple of 8
-    ext2 = {a: 64, b: 64, c: 64, d: 36}
-    assert contract_status([a, d, c], [1, 64, 2304], [d, b], [1, 36], [a, b, c], dense3, ext2) == fg.FG_ERR_UNSUPPORTED
-    # misaligned base pointer
-    assert contract_status([a, d, c], dense3, [d, b], [1, 64], [a, b, c], dense3, ext, pa=0x1002) == fg.FG_ERR_ALIGN
+    # a base pointer that is not aligned to an element
+    assert contract_status([a, d, c], dense3, [d, b], [1, 64], [a, b, c], dense3, ext, pa=0x1001) == fg.FG_ERR_ALIGN
+    assert contract_status([a, d, c], dense3, [d, b], [1, 64], [a, b, c], dense3, ext, pc=0x3002) == fg.FG_ERR_ALIGN
+    # negative stride; more than four modes in a group
+    assert contract_status([a, d, c], [1, -64, 4096], [d, b], [1, 64], [a, b, c], dense3, ext) == fg.FG_ERR_UNSUPPORTED
+    many = {i: 2 for i in range(7)}
+    assert contract_status([0, 1, 2, 3, 4, 5], [1, 2, 4, 8, 16, 32], [5, 6], [1, 2], [0, 1, 2, 3, 4, 6], [1, 2, 4, 8, 16, 32], many) == fg.FG_ERR_UNSUPPORTED
     # an empty mode: nothing to do, OK without a GPU
     ext3 = {a: 64, b: 0, c: 64, d: 64}
     assert contract_status([a, d, c], dense3, [d, b], [1, 64], [a, b, c], [1, 64, 0], ext3) == fg.FG_OK

@@ -4,7 +4,8 @@ import pytest
 import torch
 
 from paper_2009_12263_amd import binding as fg
-from tests.parity import run_contract_case
+from paper_2009_12263_amd import workloads as W
+from tests.parity import delenv, run_contract_case, setenv
 
 pytestmark = pytest.mark.gpu
 a, b, c, d, e, f = 0, 1, 2, 3, 4, 5
@@ -56,12 +57,12 @@ def test_every_tile_shape_in_the_contraction_kernels(monkeypatch):
     contiguous result (streaming stores), a permuted one, batch modes and a C operand: integer
     data, every entry exact."""
     for tile in range(4):
-        monkeypatch.setenv("FG_FORCE_TILE", str(tile))
+        setenv(monkeypatch, "FG_FORCE_TILE", str(tile))
         say("tile %d" % tile)
         run_contract_case({a: 64, b: 72, c: 5, d: 192}, [a, d, c], [d, b], [a, b, c], ints=True)
         run_contract_case({a: 12, b: 16, c: 40, d: 320}, [b, d, a], [d, c], [a, b, c], ints=True, beta=1.0)
         run_contract_case({a: 40, b: 24, c: 3, d: 128, e: 2}, [a, d, c, e], [d, e, b], [a, e, b, c], ints=True, alpha=2.0, beta=-1.0)
-    monkeypatch.delenv("FG_FORCE_TILE")
+    delenv(monkeypatch, "FG_FORCE_TILE")
 
 
 def test_ragged_extents_every_entry():
@@ -126,6 +127,41 @@ def test_padded_strides():
     run_contract_case(ext, [a, d, c], [d, b], [a, b, c], ints=True, stridesA=[1, 72, 72 * 64 + 8], stridesB=[1, 80], stridesC=[1, 68, 68 * 64 + 4])
 
 
+def test_poisoned_gaps_of_strided_tensors():
+    """The gaps that padded strides leave in A, B and Cin hold NaN: the result must not see them
+    (integer-exact), also with ragged extents whose edge tiles read past the extents."""
+    ext = {a: 64, b: 64, c: 2, d: 64}
+    run_contract_case(ext, [a, d, c], [d, b], [a, b, c], ints=True, stridesA=[1, 72, 72 * 64 + 8], stridesB=[1, 80], stridesC=[1, 68, 68 * 64 + 4], poison=True)
+    run_contract_case(ext, [a, d, c], [d, b], [a, b, c], ints=True, beta=2.0, stridesA=[1, 72, 72 * 64 + 8], stridesB=[1, 80], stridesC=[1, 68, 68 * 64 + 4], poison=True)
+    ext = {a: 40, b: 24, c: 3, d: 72}
+    run_contract_case(ext, [a, d, c], [d, b], [a, b, c], ints=True, beta=-1.0, stridesA=[1, 48, 48 * 72 + 16], stridesB=[1, 80], stridesC=[1, 44, 44 * 24 + 8], poison=True)
+    # A contiguous along the summed mode
+    run_contract_case(ext, [d, a, c], [d, b], [a, b, c], ints=True, stridesA=[1, 80, 80 * 40 + 8], stridesB=[1, 88], stridesC=[1, 44, 44 * 24 + 8], poison=True)
+
+
+def test_descriptions_only_the_general_kernel_takes():
+    """Contractions that miss a requirement of the tiled kernels: strides that are not multiples of
+    8 elements, no contiguous mode at all, A and B contiguous along different summed modes, odd
+    extents everywhere, an outer product, and a tensor of 2 GiB.  Integer-exact, every entry
+    (sampled for the large one); gaps between strided elements hold NaN."""
+    ext = {a: 64, b: 64, c: 2, d: 64}
+    general = lambda *args: "general" in fg.fg_contract_plan(*args)
+    t16, t32 = torch.empty(64, dtype=torch.float16, device="cuda"), torch.empty(64, dtype=torch.float32, device="cuda")
+    sA, sB, sC = [1, 65, 65 * 64 + 3], [1, 67], [1, 65, 65 * 64 + 1]
+    assert general([a, d, c], sA, t16, [d, b], sB, t16, [a, b, c], sC, None, t32, ext)
+    say("general: odd strides"); run_contract_case(ext, [a, d, c], [d, b], [a, b, c], ints=True, beta=2.0, stridesA=sA, stridesB=sB, stridesC=sC, poison=True)
+    say("general: no unit stride"); run_contract_case(ext, [a, d, c], [d, b], [a, b, c], ints=True, stridesA=[2, 130, 130 * 64], stridesB=[3, 200], stridesC=[2, 130, 130 * 64], poison=True)
+    ext5 = {a: 40, b: 24, d: 16, e: 8}
+    assert general([d, e, a], [1, 16, 128], t16, [e, d, b], [1, 8, 128], t16, [a, b], [1, 40], None, t32, ext5)
+    say("general: different contiguous summed modes"); run_contract_case(ext5, [d, e, a], [e, d, b], [a, b], ints=True)
+    say("general: odd extents, batch mode"); run_contract_case({a: 13, b: 7, c: 3, d: 29, e: 5}, [d, a, c, e], [b, d, e, c], [b, a, c], ints=True, beta=-1.0)
+    say("general: outer product"); run_contract_case({a: 70, b: 33}, [a], [b], [a, b], ints=True)
+    say("general: floats"); run_contract_case({a: 100, b: 50, d: 333}, [d, a], [b, d], [b, a], alpha=0.5, beta=1.5)
+    say("general: A of 2 GiB, sampled")
+    big = {a: 1 << 15, b: 24, d: 1 << 15}
+    run_contract_case(big, [a, d], [d, b], [a, b], ints=True, samples=2000)
+
+
 def test_delta_gives_mode_permutation():
     n = 64
     ext = {a: n, b: n, c: n, d: n}
@@ -135,13 +171,15 @@ def test_delta_gives_mode_permutation():
 
 
 def test_seeded_random_contraction_sweep():
-    """Thirty seeded random contractions: one or two row, column and summed modes, sometimes a
-    batch mode, random order of the modes inside each tensor, random extents; the first mode of A
-    and of B is given an extent that is a multiple of 8 (the library's requirement for the
-    contiguous mode).  Integer-valued, every entry compared."""
+    """Sixty seeded random contractions: one or two row, column and summed modes, sometimes a
+    batch mode, random order of the modes inside each tensor, random extents, nothing adjusted to
+    the tiled kernels' requirements: descriptions they cannot take (no 8-aligned contiguous mode,
+    A and B contiguous along different summed modes) run on the general kernel, and both kinds
+    must occur.  Integer-valued, every entry compared."""
     import random
     rng = random.Random(5)
-    for case in range(30):
+    kinds = {"tiled": 0, "general": 0}
+    for case in range(60):
         labels = iter(range(100))
         rows = [next(labels) for _ in range(rng.randint(1, 2))]
         cols = [next(labels) for _ in range(rng.randint(1, 2))]
@@ -158,16 +196,22 @@ def test_seeded_random_contraction_sweep():
         mB = cols + sums + batch
         mC = rows + cols + batch
         rng.shuffle(mA); rng.shuffle(mB); rng.shuffle(mC)
-        # the contiguous (first) mode of A and B must not be a batch mode and needs an extent % 8 == 0
-        for modes in (mA, mB):
-            free = [m for m in modes if m not in batch]
-            first = rng.choice(free)
-            modes.remove(first); modes.insert(0, first)
-        for first in (mA[0], mB[0]):
-            if ext[first] % 8:
-                ext[first] = rng.choice([8, 16, 24, 40])
-        if mA[0] in sums and mB[0] in sums and mA[0] != mB[0]:
-            mB.remove(mA[0]); mB.insert(0, mA[0])          # contiguous along different summed modes is unsupported
+        if case % 2 == 0:
+            # make the description one the tiled kernels take: a non-batch first mode with an extent % 8 == 0
+            for modes in (mA, mB):
+                free = [m for m in modes if m not in batch]
+                first = rng.choice(free)
+                modes.remove(first); modes.insert(0, first)
+            for first in (mA[0], mB[0]):
+                if ext[first] % 8:
+                    ext[first] = rng.choice([8, 16, 24, 40])
+            if mA[0] in sums and mB[0] in sums and mA[0] != mB[0]:
+                mB.remove(mA[0]); mB.insert(0, mA[0])
+        dense = lambda ms: list(W.col_major_strides(tuple(ext[m] for m in ms)))
+        fake = lambda dt: torch.empty(64, dtype=dt, device="cuda")      # only the alignment of the pointers matters
+        plan = fg.fg_contract_plan(mA, dense(mA), fake(torch.float16), mB, dense(mB), fake(torch.float16), mC, dense(mC), None, fake(torch.float32), ext)
+        kinds["general" if "general" in plan else "tiled"] += 1
         beta = rng.choice([0.0, 1.0, -0.5])
-        say("sweep %d: A%s B%s C%s ext=%s beta=%g" % (case, mA, mB, mC, ext, beta))
+        say("sweep %d: A%s B%s C%s ext=%s beta=%g plan=%s" % (case, mA, mB, mC, ext, beta, plan))
         run_contract_case(ext, mA, mB, mC, alpha=rng.choice([1.0, 2.0, -1.0]), beta=beta, ints=True, seed=2000 + case)
+    assert kinds["tiled"] >= 15 and kinds["general"] >= 15, kinds

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 from paper_2009_12263_amd import binding as fg
-from tests.parity import run_gemm_case, run_unaligned_gemm_case
+from tests.parity import delenv, run_gemm_case, run_unaligned_gemm_case, setenv
 
 pytestmark = pytest.mark.gpu
 
@@ -69,6 +69,26 @@ def test_full_size_8192_sampled(la, lb):
     run_gemm_case(8192, 8192, 8192, la, lb, config=2, samples=4096)
 
 
+@pytest.mark.parametrize("la,lb", list(itertools.product(LAYOUTS, LAYOUTS)))
+def test_full_size_16384_sampled(la, lb):
+    """The largest point of the config-2 sweep (3.2 GB of operands, 4096 block tiles = 16 rounds of
+    the persistent grid, the largest ld * n offsets of the sweep): sampled entries and every kind
+    of tile seam, floats in all four layout pairs, integer-exact in NN and TT."""
+    say("16384^3 la=%d lb=%d floats sampled" % (la, lb))
+    run_gemm_case(16384, 16384, 16384, la, lb, config=2, samples=4096)
+    if la == lb:
+        say("16384^3 la=%d lb=%d ints sampled" % (la, lb))
+        run_gemm_case(16384, 16384, 16384, la, lb, config=2, samples=4096, ints=True)
+
+
+@pytest.mark.parametrize("n", [2048, 4096])
+@pytest.mark.parametrize("la,lb", list(itertools.product(LAYOUTS, LAYOUTS)))
+def test_full_size_2048_4096_sampled_all_layouts(n, la, lb):
+    """The middle points of the config-2 sweep in every layout pair: floats and integers."""
+    say("%d^3 la=%d lb=%d floats sampled" % (n, la, lb)); run_gemm_case(n, n, n, la, lb, config=2, samples=4096)
+    say("%d^3 la=%d lb=%d ints sampled" % (n, la, lb)); run_gemm_case(n, n, n, la, lb, config=2, samples=4096, ints=True)
+
+
 def test_full_size_4096_ints_sampled():
     say("4096^3 ints sampled"); run_gemm_case(4096, 4096, 4096, ints=True, config=2, samples=8192)
 
@@ -90,6 +110,71 @@ def test_arbitrary_sizes_edge_tiles(la, lb, ldl):
     say("edge floats + bias + relu")
     run_gemm_case(333, 1111, 248, la, lb, ldl, alpha=0.5, beta=-1.0, bias_dim=0, act=fg.FG_ACT_RELU, pad=8, config=3)
     run_gemm_case(333, 1111, 248, la, lb, ldl, with_c=False, bias_dim=1, pad=8, config=3)
+
+
+@pytest.mark.parametrize("la,lb", list(itertools.product(LAYOUTS, LAYOUTS)))
+def test_poisoned_padding_never_reaches_a_result(la, lb):
+    """Everything between an extent and its leading dimension in A, B and C holds NaN (that covers
+    the rest of the last 16-byte chunk of a column or row, and the rows and columns an edge tile
+    reads beyond the matrix).  The kernels read some of it by design; no stored entry may depend on
+    it: results stay finite and, on integers, bit-exact; D's own padding stays untouched."""
+    for (M, N, K) in [(100, 260, 200), (257, 129, 264), (300, 520, 136), (777, 1031, 520), (250, 250, 72)]:
+        for ldl in LAYOUTS:
+            say("poison ints M=%d N=%d K=%d la=%d lb=%d D=%d" % (M, N, K, la, lb, ldl))
+            run_gemm_case(M, N, K, la, lb, ldl, ints=True, pad=8, config=2, poison=True)
+    say("poison floats bias relu"); run_gemm_case(333, 1111, 248, la, lb, alpha=0.5, beta=-1.0, bias_dim=0, act=fg.FG_ACT_RELU, pad=8, config=3, poison=True)
+    say("poison in place"); run_gemm_case(259, 131, 200, la, lb, ints=True, pad=8, inplace=True, poison=True)
+    say("poison split-K 300x200x4096"); run_gemm_case(300, 200, 4096, la, lb, ints=True, pad=8, bias_dim=0, act=fg.FG_ACT_RELU, c_act=fg.FG_ACT_RELU, poison=True)
+    say("poison split-K with K tail 250x120x4104"); run_gemm_case(250, 120, 4104, la, lb, ints=True, pad=8, poison=True)
+    say("poison tail split 4100x4100x1032"); run_gemm_case(4100, 4100, 1032, la, lb, ints=True, pad=8, samples=6000, poison=True)
+    say("poison addition on A and B"); run_gemm_case(257, 129, 264, la, lb, ints=True, pad=8, ab_add=(1.0, -2.0), poison=True)
+    say("poison bf16"); run_gemm_case(257, 129, 264, la, lb, ints=True, pad=8, bf16=True, poison=True)
+    say("poison binary16 C and D"); run_gemm_case(257, 129, 264, la, lb, ints=True, pad=8, cd16=True, poison=True)
+
+
+def test_poisoned_padding_complex_dual_diagonal():
+    from tests.parity import run_cgemm_case, run_diag_case
+    for la, lb in itertools.product(LAYOUTS, LAYOUTS):
+        say("poison complex la=%d lb=%d" % (la, lb)); run_cgemm_case(130, 200, 72, la, lb, ints=True, pad=8, poison=True)
+    say("poison dual"); run_cgemm_case(130, 200, 72, ints=True, pad=8, dual=True, poison=True)
+    say("poison interleaved complex"); run_cgemm_case(130, 200, 72, fg.FG_ROW, fg.FG_COL, ints=True, pad=8, interleaved=True, poison=True)
+
+
+def test_non_finite_values_propagate_like_the_definition():
+    """NaN and infinities in A, B and C reach D exactly where the definition puts them (the oracle
+    evaluates the same IEEE expression in FP64): without activation they pass through, with ReLU
+    the comparison y > 0 turns NaN into 0.  With beta == 0, C is never read: a NaN-filled C (the
+    in-place call on uninitialised memory) leaves the product untouched."""
+    import numpy as np
+    from oracle import cpu_oracle as O
+    from paper_2009_12263_amd import workloads as W
+    from tests.parity import np16
+    for (M, N, K, force) in [(300, 260, 136, None), (300, 200, 4096, None), (70, 50, 27, None)]:
+        for act in (fg.FG_ACT_NONE, fg.FG_ACT_RELU):
+            say("non-finite M=%d N=%d K=%d act=%d" % (M, N, K, act))
+            lda, ldb, ldc = (M + 7) // 8 * 8, (K + 7) // 8 * 8, (M + 3) // 4 * 4
+            A = W.small_ints(lda * K, 1, device="cuda"); B = W.small_ints(ldb * N, 2, device="cuda")
+            Cm = W.small_ints(ldc * N, 3, device="cuda", dtype=torch.float32)
+            A.view(K, lda)[5, 17] = float("nan"); A.view(K, lda)[K - 1, 3] = float("inf")
+            B.view(N, ldb)[7, 2] = float("-inf")
+            Cm.view(N, ldc)[9, 40] = float("nan"); Cm.view(N, ldc)[11, 41] = float("-inf")
+            D = torch.full_like(Cm, 7.0)
+            fg.fg_gemm(M, N, K, 1.0, fg.Matrix(A, fg.FG_COL, lda), fg.Matrix(B, fg.FG_COL, ldb), 1.0, fg.Matrix(Cm, fg.FG_COL, ldc),
+                       fg.Matrix(D, fg.FG_COL, ldc), act=act)
+            torch.cuda.synchronize()
+            with np.errstate(invalid="ignore"):
+                r = O.gemm(M, N, K, 1.0, O.Operand(np16(A), O.COL, lda), O.Operand(np16(B), O.COL, ldb), 1.0, np16(Cm), None, O.COL, ldc, act=act)
+            got = np16(D).reshape(N, ldc)[:, :M].T.astype(np.float64)
+            assert np.isnan(r["D"]).any() or act == fg.FG_ACT_RELU
+            assert np.array_equal(got, r["D"], equal_nan=True), "non-finite entries differ from the definition"
+    say("beta == 0 with a NaN-filled C, in place")
+    M = N = 256; K = 128
+    A = W.small_ints(M * K, 1, device="cuda"); B = W.small_ints(K * N, 2, device="cuda")
+    D = torch.full((M * N,), float("nan"), dtype=torch.float32, device="cuda")
+    fg.fg_gemm(M, N, K, 1.0, fg.Matrix(A, fg.FG_COL, M), fg.Matrix(B, fg.FG_COL, K), 0.0, fg.Matrix(D, fg.FG_COL, M), fg.Matrix(D, fg.FG_COL, M))
+    torch.cuda.synchronize()
+    r = O.gemm(M, N, K, 1.0, O.Operand(np16(A), O.COL, M), O.Operand(np16(B), O.COL, K), 0.0, None, None, O.COL, M)
+    assert np.array_equal(np16(D).reshape(N, M).T.astype(np.float64), r["D"])
 
 
 def test_arbitrary_sizes_large():
@@ -250,10 +335,10 @@ def test_forced_split_counts(monkeypatch):
     """Every split count the planner can choose, forced on one ragged multi-tile problem, gives the
     same exact result (FG_FORCE_SPLIT is the library's tuning override)."""
     for S in (2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64):
-        monkeypatch.setenv("FG_FORCE_SPLIT", str(S))
+        setenv(monkeypatch, "FG_FORCE_SPLIT", str(S))
         assert ("+splitk%d" % S) in fg.fg_gemm_plan(200, 136, 4160)
         say("forced split %d" % S); run_gemm_case(200, 136, 4160, ints=True, bias_dim=1, act=fg.FG_ACT_RELU)
-    monkeypatch.setenv("FG_FORCE_SPLIT", "1")
+    setenv(monkeypatch, "FG_FORCE_SPLIT", "1")
     assert "+splitk" not in fg.fg_gemm_plan(512, 512, 8192)
     run_gemm_case(512, 512, 8192, ints=True)
 
@@ -289,14 +374,14 @@ def test_binary16_c_and_d_whole_line_stores(monkeypatch):
     on that path, on each such tile, with interior and edge waves in one launch.  Integer data:
     every entry must equal the exact result rounded once."""
     for tile in (0, 1, 2, 4):
-        monkeypatch.setenv("FG_FORCE_TILE", str(tile))
+        setenv(monkeypatch, "FG_FORCE_TILE", str(tile))
         say("tile %d: bias along N, ReLU, ReLU on C, beta = -3, in place" % tile)
         run_gemm_case(600, 520, 128, ints=True, cd16=True, bias_dim=1, act=fg.FG_ACT_RELU, c_act=fg.FG_ACT_RELU, beta=-3.0, inplace=True)
         say("tile %d: bias along M, no C, row-major D" % tile)
         run_gemm_case(520, 600, 192, fg.FG_ROW, fg.FG_ROW, ld_layout=fg.FG_ROW, ints=True, cd16=True, bias_dim=0, with_c=False, pad=8)
         say("tile %d: alpha = -2, beta = 1, separate C" % tile)
         run_gemm_case(512, 512, 64, fg.FG_COL, fg.FG_ROW, ints=True, cd16=True, alpha=-2.0)
-    monkeypatch.delenv("FG_FORCE_TILE")
+    delenv(monkeypatch, "FG_FORCE_TILE")
 
 
 def test_every_tile_shape_in_every_kernel_family(monkeypatch):
@@ -306,29 +391,29 @@ def test_every_tile_shape_in_every_kernel_family(monkeypatch):
     layout pairs: integer data, every entry exact.  The deep-ring tile is also run over a K that
     is shorter than its ring and with K split, the 16x16x32 kernel over short K and with K split."""
     for tile in range(6):
-        monkeypatch.setenv("FG_FORCE_TILE", str(tile))
+        setenv(monkeypatch, "FG_FORCE_TILE", str(tile))
         for la, lb in itertools.product((fg.FG_COL, fg.FG_ROW), repeat=2):
             say("tile %d layouts A=%d B=%d: plain, bf16, ab_add, f16 C,D" % (tile, la, lb))
             run_gemm_case(300, 264, 448, la, lb, ints=True, bias_dim=0)
             run_gemm_case(300, 264, 448, la, lb, ints=True, bf16=True)
             run_gemm_case(300, 264, 192, la, lb, ints=True, ab_add=(1.0, -2.0), c_act=fg.FG_ACT_RELU)
             run_gemm_case(300, 264, 448, la, lb, ints=True, cd16=True, act=fg.FG_ACT_RELU)
-    monkeypatch.setenv("FG_FORCE_TILE", "4")
+    setenv(monkeypatch, "FG_FORCE_TILE", "4")
     for K in (64, 128, 192, 256, 320):
         say("deep ring, K = %d" % K); run_gemm_case(256, 384, K, ints=True)
-    monkeypatch.setenv("FG_FORCE_SPLIT", "3")
+    setenv(monkeypatch, "FG_FORCE_SPLIT", "3")
     say("deep ring, K split in 3"); run_gemm_case(384, 256, 1536, fg.FG_ROW, fg.FG_COL, ints=True, bias_dim=1, act=fg.FG_ACT_RELU)
-    monkeypatch.delenv("FG_FORCE_SPLIT")
-    monkeypatch.setenv("FG_FORCE_TILE", "5")
+    delenv(monkeypatch, "FG_FORCE_SPLIT")
+    setenv(monkeypatch, "FG_FORCE_TILE", "5")
     for K in (8, 64, 72, 128, 192, 520):
         say("16x16x32 kernel, K = %d" % K); run_gemm_case(300, 520, K, fg.FG_COL, fg.FG_ROW, ints=True, pad=8)
     say("16x16x32 kernel, A/B layouts x row-major D, bias along N, ReLU")
     for la, lb in itertools.product((fg.FG_COL, fg.FG_ROW), repeat=2):
         run_gemm_case(520, 300, 200, la, lb, ld_layout=fg.FG_ROW, ints=True, bias_dim=1, act=fg.FG_ACT_RELU, beta=-2.0)
-    monkeypatch.setenv("FG_FORCE_SPLIT", "3")
+    setenv(monkeypatch, "FG_FORCE_SPLIT", "3")
     say("16x16x32 kernel, K split in 3"); run_gemm_case(512, 256, 1536, fg.FG_ROW, fg.FG_COL, ints=True, bias_dim=0)
-    monkeypatch.delenv("FG_FORCE_SPLIT")
-    monkeypatch.delenv("FG_FORCE_TILE")
+    delenv(monkeypatch, "FG_FORCE_SPLIT")
+    delenv(monkeypatch, "FG_FORCE_TILE")
     say("planner's own choice of the deep ring, floats"); assert "deep" in fg.fg_gemm_plan(2048, 2048, 2048)
     run_gemm_case(2048, 2048, 2048, samples=4000)
 
@@ -358,32 +443,63 @@ def test_split_k_results_do_not_depend_on_arrival_order(monkeypatch):
              (384, 256, 4096, 4, 6), (2100, 2112, 640, 3, 3), (128, 128, 576, 3, 4)]
     for rep in range(4):
         for (m, n, k, tile, S) in cases:
-            monkeypatch.setenv("FG_FORCE_TILE", str(tile))
-            monkeypatch.setenv("FG_FORCE_SPLIT", str(S))
+            setenv(monkeypatch, "FG_FORCE_TILE", str(tile))
+            setenv(monkeypatch, "FG_FORCE_SPLIT", str(S))
             assert ("+splitk%d" % S) in fg.fg_gemm_plan(m, n, k)
             say("launch %d: %dx%dx%d tile %d split %d" % (rep, m, n, k, tile, S))
             run_gemm_case(m, n, k, fg.FG_COL if rep % 2 else fg.FG_ROW, fg.FG_COL, ints=True, seed=1000 + 17 * rep + S,
                           bias_dim=rep % 2, act=fg.FG_ACT_RELU if rep & 2 else fg.FG_ACT_NONE, beta=1.0 if rep % 3 else -2.0)
-    monkeypatch.delenv("FG_FORCE_TILE")
-    monkeypatch.delenv("FG_FORCE_SPLIT")
+    delenv(monkeypatch, "FG_FORCE_TILE")
+    delenv(monkeypatch, "FG_FORCE_SPLIT")
     for rep in range(6):
         say("planner's split, launch %d" % rep); run_gemm_case(512, 512, 8192, ints=True, seed=50 + rep)
+
+
+def test_split_k_calls_on_two_streams_do_not_disturb_each_other():
+    """All split-K calls of a GPU share one workspace.  The library orders a call against the
+    previous user on another stream with an event, so two streams may issue such calls freely:
+    forty launches alternating between two streams, each into its own output, must all equal the
+    results of the same calls made one after the other."""
+    from paper_2009_12263_amd import workloads as W
+    shapes = [(512, 512, 8192), (384, 256, 8192)]
+    for (M, N, K) in shapes:
+        assert "+splitk" in fg.fg_gemm_plan(M, N, K)
+    ops = []
+    for i, (M, N, K) in enumerate(shapes):
+        A = W.small_ints(M * K, 10 + i, device="cuda"); B = W.small_ints(K * N, 20 + i, device="cuda")
+        ref = torch.empty(M * N, dtype=torch.float32, device="cuda")
+        fg.fg_gemm(M, N, K, 1.0, fg.Matrix(A, fg.FG_COL, M), fg.Matrix(B, fg.FG_COL, K), 0.0, None, fg.Matrix(ref, fg.FG_COL, M))
+        ops.append((M, N, K, A, B, ref))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = []
+    for rep in range(20):
+        for i, (M, N, K, A, B, ref) in enumerate(ops):
+            D = torch.full_like(ref, float("nan"))
+            outs.append((i, D))
+    torch.cuda.synchronize()
+    for n, (i, D) in enumerate(outs):
+        M, N, K, A, B, ref = ops[i]
+        fg.fg_gemm(M, N, K, 1.0, fg.Matrix(A, fg.FG_COL, M), fg.Matrix(B, fg.FG_COL, K), 0.0, None, fg.Matrix(D, fg.FG_COL, M), stream=streams[i])
+    torch.cuda.synchronize()
+    for n, (i, D) in enumerate(outs):
+        assert torch.equal(D, ops[i][5]), "launch %d on stream %d differs from the serial result" % (n, i)
 
 
 def test_tail_round_split(monkeypatch):
     """More tiles than the persistent grid holds at once, with a small remainder: the full rounds
     run as one pass and only the leftover tiles are split over K (plus the reduction pass).  Forced
     on small tiles so that the oracle can check every entry, then the planner's own choice."""
-    monkeypatch.setenv("FG_FORCE_TILE", "3")                      # 64x64 tiles: 1024 workgroups resident
+    setenv(monkeypatch, "FG_FORCE_TILE", "3")                      # 64x64 tiles: 1024 workgroups resident
     for S in (2, 3, 7):
-        monkeypatch.setenv("FG_FORCE_TAIL", str(S))
+        setenv(monkeypatch, "FG_FORCE_TAIL", str(S))
         assert ("+tailsplitk%d" % S) in fg.fg_gemm_plan(2100, 2112, 512)
         say("tail split %d on 33x33 tiles of 64x64, ragged edge" % S)
         run_gemm_case(2100, 2112, 512, ints=True, bias_dim=0, act=fg.FG_ACT_RELU)
     say("tail split, row-major operands and result, C with ReLU on C")
     run_gemm_case(2112, 2100, 456, fg.FG_ROW, fg.FG_ROW, ld_layout=fg.FG_ROW, ints=True, c_act=fg.FG_ACT_RELU, alpha=2.0, beta=-1.0)
-    monkeypatch.delenv("FG_FORCE_TILE")
-    monkeypatch.delenv("FG_FORCE_TAIL")
+    delenv(monkeypatch, "FG_FORCE_TILE")
+    delenv(monkeypatch, "FG_FORCE_TAIL")
     assert "+tailsplitk" in fg.fg_gemm_plan(4100, 4100, 4096)
     say("planner's choice: 4100x4100x4096 floats sampled"); run_gemm_case(4100, 4100, 4096, samples=6000)
     say("planner's choice: 4100x4100x4096 ints sampled"); run_gemm_case(4100, 4100, 4096, ints=True, samples=6000, bias_dim=1)

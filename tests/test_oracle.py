@@ -455,6 +455,25 @@ def test_ab_add_and_relu_on_c_by_brute_force():
             acc = sum(A2[i, k] * B2[k, j] for k in range(K))
             want[i, j] = max(1.5 * acc - 0.5 * max(float(Cm[i, j]), 0.0) + float(bias[j]), 0.0)
     assert np.allclose(r["D"], want, rtol=0, atol=1e-12)
+    # the tolerance denominator under the transforms: |alpha| sum_k |A'_ik| |B'_kj| + |beta| |relu(C_ij)|,
+    # with the transformed elements (the bias is not part of it)
+    want_g = np.zeros((M, N))
+    for i in range(M):
+        for j in range(N):
+            want_g[i, j] = 1.5 * sum(abs(A2[i, k]) * abs(B2[k, j]) for k in range(K)) + 0.5 * max(float(Cm[i, j]), 0.0)
+    assert np.allclose(r["G"], want_g, rtol=0, atol=1e-12)
+    # ... and it must differ from the denominator of the untransformed product (so that a G that
+    # ignored the transforms would fail here): negative C entries exist, and the addends change |A'||B'|
+    r_plain = O.gemm(M, N, K, 1.5, Operand(A, ROW, lda), Operand(B, ROW, ldb), -0.5, Cm.T.copy().reshape(-1), None, COL, M,
+                     bias=bias, bias_dim=1, act=ACT_RELU)
+    assert (Cm < 0).any() and not np.allclose(r_plain["G"], want_g, rtol=1e-3, atol=0)
+    # each transform alone
+    r_c = O.gemm(M, N, K, 1.5, Operand(A, ROW, lda), Operand(B, ROW, ldb), -0.5, Cm.T.copy().reshape(-1), None, COL, M, c_act=ACT_RELU)
+    g_c = 1.5 * np.abs(Ah.astype(np.float64)) @ np.abs(Bh.astype(np.float64)) + 0.5 * np.maximum(Cm.astype(np.float64), 0.0)
+    assert np.allclose(r_c["G"], g_c, rtol=0, atol=1e-12)
+    r_ab = O.gemm(M, N, K, 1.5, Operand(A, ROW, lda), Operand(B, ROW, ldb), -0.5, Cm.T.copy().reshape(-1), None, COL, M, ab_add=(a_add, b_add))
+    g_ab = 1.5 * np.abs(A2) @ np.abs(B2) + 0.5 * np.abs(Cm.astype(np.float64))
+    assert np.allclose(r_ab["G"], g_ab, rtol=0, atol=1e-12)
     # a zero addend and no activation on C give back the plain product
     r0 = O.gemm(M, N, K, 1.5, Operand(A, ROW, lda), Operand(B, ROW, ldb), -0.5, Cm.T.copy().reshape(-1), None, COL, M, ab_add=(0.0, 0.0))
     r1 = O.gemm(M, N, K, 1.5, Operand(A, ROW, lda), Operand(B, ROW, ldb), -0.5, Cm.T.copy().reshape(-1), None, COL, M)
