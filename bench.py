@@ -27,15 +27,20 @@ if ROOT not in sys.path:
 
 METRIC = "TFLOP/s and % of FP16 MFMA peak, mixed-precision GEMM N=8192 and GETT"
 MFMA_FP16_PEAK_TFLOPS = 2500.0     # MI355X dense FP16 MFMA, published (2.5 PFLOP/s)
-# Bytes per launch of the 8192^3 kernel that crossed the L2 <-> memory-side boundary, from two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for a
-# plain copy kernel of known size (factors 2.0 and 1.0): profiles/gemm_nn_8192_pmc.md.  Only
-# meaningful for the default workload.
-MEASURED_HBM_TRAFFIC_BYTES = 2.175e9
+# Bytes per launch of the 8192^3 kernel that crossed the L2 <-> memory-side boundary.  NOT measured
+# by this program: a constant from two rocprofv3 --pmc runs of this command (FETCH_SIZE, WRITE_SIZE),
+# each scaled by what the same counter reads for a plain copy kernel of known size (factors 2.0 and
+# 1.0), recorded in the file named below.  It is reported only when the kernel that is timed is the
+# one that was profiled (same plan name), and the JSON line names the source.
+PROFILED_TRAFFIC = {"kernel": "gemm_nn_256x256x64_k32", "bytes": 2.175e9, "source": "profiles/gemm_nn_8192_pmc.md"}
 
 
-def cpu_baseline(M, N, K, A, lda, B, ldb, C, ldc, budget_s=15.0):
-    """Time the oracle on a sample of output entries of the same workload, sized to ~budget_s."""
+def cpu_baseline(M, N, K, A, lda, B, ldb, C, ldc, budget_s=12.0):
+    """The oracle as it stands, timed on this machine's host cores.  `value` comes from a bounded sample
+    of output entries of the timed workload itself (each a full K-long FP64 dot product) and is
+    what the full problem would run at: `projected_seconds_full_problem` is a projection from it,
+    not a measurement.  `legs` are problems the oracle computes in full: config 1 (256^3), the
+    1024^3 point of config 2 and contraction 5a."""
     import numpy as np
     from oracle import cpu_oracle as O
     threads = O.default_threads()
@@ -53,12 +58,32 @@ def cpu_baseline(M, N, K, A, lda, B, ldb, C, ldc, budget_s=15.0):
     count = int(min(max(probe, probe * budget_s / max(t, 1e-6)), 4_000_000))
     t = run(count)
     flops = 2.0 * K * count
-    return {"value": flops / t * 1e-12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+    rate = flops / t
+    legs = []
+
+    def leg(name, fl, fn):
+        t0 = time.perf_counter()
+        fn()
+        dt = time.perf_counter() - t0
+        legs.append({"workload": name, "computed": "in full", "seconds": dt, "GFLOPs": fl / dt * 1e-9})
+
+    for n, cfg in ((256, "configs[0]"), (1024, "configs[1] at N=1024")):
+        if n <= min(M, N, K) and lda >= n and ldb >= n:
+            a, b, c = A[:n * n], B[:n * n], C[:n * n]
+            leg("%s: D = A.B + C, M=N=K=%d" % (cfg, n), 2.0 * n ** 3,
+                lambda: O.gemm(n, n, n, 1.0, O.Operand(a, O.COL, n), O.Operand(b, O.COL, n), 1.0, c, None, O.COL, n, threads=threads))
+    e = 256
+    if A.size >= e ** 3 and B.size >= e * e:
+        st3, st2 = [1, e, e * e], [1, e]
+        leg("configs[4] 5a: C[a,b,c] = sum_d A[a,d,c] B[d,b], extents 256", 2.0 * e ** 4,
+            lambda: O.contract({0: e, 1: e, 2: e, 3: e}, [0, 3, 2], st3, A[:e ** 3], [3, 1], st2, B[:e * e], [0, 1, 2], st3, threads=threads))
+    return {"value": rate * 1e-12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
             "sample": "%d of %d output entries of the same %dx%dx%d problem, each a full K=%d FP64 dot product; %.1f s"
-                      % (count, M * N, M, N, K, K, t)}
+                      % (count, M * N, M, N, K, K, t),
+            "projected_seconds_full_problem": 2.0 * M * N * K / rate, "legs": legs}
 
 
-def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True):
+def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True, sweep16k=True):
     """Other rows of the hot-path table, outside the timed region: the remaining layout pairs at
     the same size, the fused-epilogue and layout-adapter configurations and the contractions.
     Each figure is flops (or algorithmic bytes) over the mean of 10 launches timed with HIP events;
@@ -70,7 +95,7 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True):
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
     def timed(fn, reps=20):
-        for _ in range(20):         # enough for the clock to settle after the change of kernel
+        for _ in range(min(20, reps)):         # enough for the clock to settle after the change of kernel
             fn()
         e0.record(stream)
         for _ in range(reps):
@@ -122,9 +147,34 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True):
     guard("mfma_only_rate_16x16x32_on_this_data_TFLOPs", mfma_ceiling_k32)
 
     flops = 2.0 * n ** 3
-    for name, la, lb in (("NT", fg.FG_COL, fg.FG_ROW), ("TN", fg.FG_ROW, fg.FG_COL), ("TT", fg.FG_ROW, fg.FG_ROW)):
-        a2, b2 = fg.Matrix(A, la, n), fg.Matrix(B, lb, n)
-        guard("gemm_%s_%d_TFLOPs" % (name, n), lambda: flops / timed(lambda: fg.fg_gemm(n, n, n, 1.0, a2, b2, 1.0, mC, mD, stream=stream)) * 1e-12)
+    # The whole config-2 sweep, operands left in the caches by the previous launch ("hot"): every
+    # size in every layout pair, plus config 1 (256^3 NN).  The sizes below the timed one use the
+    # leading part of the same buffers; 16384 gets buffers of its own, released afterwards.
+    pairs = (("NN", fg.FG_COL, fg.FG_COL), ("NT", fg.FG_COL, fg.FG_ROW), ("TN", fg.FG_ROW, fg.FG_COL), ("TT", fg.FG_ROW, fg.FG_ROW))
+
+    def sweep_point(sz, a_buf, b_buf, c_buf, d_buf, layouts):
+        for name, la, lb in layouts:
+            if sz == n and name == "NN":
+                continue                         # the timed workload itself
+            a2, b2 = fg.Matrix(a_buf, la, sz), fg.Matrix(b_buf, lb, sz)
+            c2, d2 = fg.Matrix(c_buf, fg.FG_COL, sz), fg.Matrix(d_buf, fg.FG_COL, sz)
+            guard("gemm_%s_%d_TFLOPs" % (name, sz), lambda: 2.0 * sz ** 3 / timed(
+                lambda: fg.fg_gemm(sz, sz, sz, 1.0, a2, b2, 1.0, c2, d2, stream=stream), reps=10 if sz > 8192 else 20) * 1e-12)
+    sweep_point(256, A, B, mC.re, mD.re, pairs[:1])
+    for sz in (1024, 2048, 4096, 8192):
+        if sz <= n:
+            sweep_point(sz, A, B, mC.re, mD.re, pairs)
+    if n == 8192 and sweep16k:
+        def big():
+            sz = 16384
+            a16 = W.uniform_pm1(sz * sz, W.stream_id(2, "A"), device=A.device)
+            b16 = W.uniform_pm1(sz * sz, W.stream_id(2, "B"), device=A.device)
+            c16 = W.uniform_pm1(sz * sz, W.stream_id(2, "C"), device=A.device, dtype=torch.float32)
+            d16 = torch.empty_like(c16)
+            sweep_point(sz, a16, b16, c16, d16, pairs)
+            return "done"
+        guard("sweep_16384", big)
+        torch.cuda.empty_cache()
 
     m = 4096
     dev = A.device
@@ -227,6 +277,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed-region extras (other layouts and configs)")
     ap.add_argument("--no-cold", action="store_true",
                     help="skip the cache-cold extras (keeps one group of launches per workload in a profile)")
+    ap.add_argument("--no-16384", action="store_true", help="skip the 16384^3 points of the sweep (3.2 GB of extra operands)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain elementwise copy kernel (D = -C: 4 M N bytes read, 4 M N written), "
                          "so a counter profile of this command can be scaled")
@@ -282,23 +333,26 @@ def main():
     torch.cuda.synchronize()
     per_launch = sorted(b.elapsed_time(e) for b, e in evs)
 
+    plan_name = fg.fg_gemm_plan(M, N, K)
     out = {
         "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16 in / f32 accumulate", "data": "synthetic",
         "config": {"workload": "configs[1]: square mixed-precision GEMM D = A.B + C, M=N=K=%d, A,B FP16 column-major (NN), "
                                "C,D FP32, uniform[-1,1), alpha=beta=1" % n,
-                   "kernel": fg.fg_gemm_plan(M, N, K)},
+                   "kernel": plan_name},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_FP16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_FP16_PEAK_TFLOPS,
-                     "traffic": MEASURED_HBM_TRAFFIC_BYTES if n == 8192 else None,
+                     "traffic": PROFILED_TRAFFIC["bytes"] if (n == 8192 and plan_name == PROFILED_TRAFFIC["kernel"]) else None,
+                     "traffic_source": (PROFILED_TRAFFIC["source"] + " (rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE of this command, not measured in this run)")
+                                       if (n == 8192 and plan_name == PROFILED_TRAFFIC["kernel"]) else None,
                      "kernel_ms": kern_ms,
                      "per_launch_ms_min": per_launch[0], "per_launch_ms_median": per_launch[len(per_launch) // 2],
                      "frac_of_mfma_only_rate_on_this_data": None},
     }
 
     if not args.no_extras:
-        out["extras"] = extras(fg, W, torch, n, A, B, mC, mD, stream, cold=not args.no_cold)
+        out["extras"] = extras(fg, W, torch, n, A, B, mC, mD, stream, cold=not args.no_cold, sweep16k=not args.no_16384)
         # the MFMA-only rate in the instruction shape the timed kernel uses
         key = "mfma_only_rate_16x16x32_on_this_data_TFLOPs" if out["config"]["kernel"].endswith("_k32") else "mfma_only_rate_on_this_data_TFLOPs"
         sustained = out["extras"].get(key)
