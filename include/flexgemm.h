@@ -176,6 +176,27 @@ fg_status fg_gemm_ex(int64_t M, int64_t N, int64_t K, float alpha,
                      const fg_load_transforms *lt, void *hip_stream);
 
 /*
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): fg_gemm_ex with the same arguments, results and errors,
+ * except that the partial products of a K split go to a 16 MiB array that is part of the library's
+ * device image (one copy per GPU, held until the process ends) instead of the 64 MiB workspace.
+ * The call makes the same plan as fg_gemm_ex, so its result is bit-identical; when that plan's
+ * partial products need more than 16 MiB (tiles to split x K ranges x tile bytes, e.g. a 2048 x 2048
+ * output split three ways) it returns FG_ERR_UNSUPPORTED and launches nothing.  It never calls
+ * hipMalloc, hipFree or any allocating routine; for that to cover the runtime's own first-use
+ * work (loading the kernels, looking up the array's address) call fg_init() once per device
+ * beforehand.  Nothing in the array needs clearing between calls (every partial tile is written
+ * whole before the reduction pass reads it).  All calls on one GPU share the array and are NOT
+ * ordered against each other by the library: calls on one stream are safe, calls that overlap in
+ * time on different streams of one GPU race.
+ */
+fg_status fg_gemm_noalloc(int64_t M, int64_t N, int64_t K, float alpha,
+                          const fg_matrix *A, const fg_matrix *B,
+                          float beta, const fg_matrix *C,
+                          const fg_matrix *D, const fg_epilogue *ep,
+                          const fg_load_transforms *lt, void *hip_stream);
+
+/*
  * Dual-number product (Section 5.4): every element is x + eps.x' with eps^2 = 0, stored like the
  * planar complex matrices (value plane at `re`, dual plane at `im`), so
  *     D.re = alpha * A.re.B.re + beta * C.re
@@ -257,7 +278,7 @@ void fg_reload_tuning(void);
 
 /*
  * Optional: prepare every kernel variant on the current device (raise its LDS limit, query its
- * occupancy) and allocate the split-K workspace.  Without it each variant is prepared by the first
+ * occupancy), allocate the split-K workspace and look up the static scratch array of fg_gemm_noalloc.  Without it each variant is prepared by the first
  * call that uses it, and the workspace is allocated by the first call that splits K.  After
  * fg_init() on a device, fg_gemm / fg_gemm_ex / fg_gemm_dual / fg_contract on that device do
  * nothing but enqueue one kernel (two or three when K is split) on the given stream, so they may be recorded into a HIP graph

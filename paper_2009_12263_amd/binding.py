@@ -22,7 +22,7 @@ FG_F16, FG_BF16, FG_F32, FG_CF16, FG_CF32 = 0, 1, 2, 3, 4
 FG_COL, FG_ROW, FG_DIAG, FG_ZERO = 0, 1, 2, 3
 FG_ACT_NONE, FG_ACT_RELU = 0, 1
 
-EXPORTS = ("fg_init", "fg_gemm", "fg_gemm_ex", "fg_gemm_dual", "fg_contract", "fg_contract_plan", "fg_last_error", "fg_version",
+EXPORTS = ("fg_init", "fg_gemm", "fg_gemm_ex", "fg_gemm_noalloc", "fg_gemm_dual", "fg_contract", "fg_contract_plan", "fg_last_error", "fg_version",
            "fg_reload_tuning", "fg_gemm_plan", "fg_probe_mfma", "fg_probe_mfma_k32")
 FG_PLAN_REAL, FG_PLAN_COMPLEX, FG_PLAN_DUAL, FG_PLAN_REAL_BF16, FG_PLAN_COMPLEX_INTERLEAVED, FG_PLAN_REAL_F16_CD = 0, 1, 2, 3, 4, 5
 
@@ -64,6 +64,8 @@ def load_library() -> C.CDLL:
         lib.fg_gemm_ex.argtypes = [i64, i64, i64, f32, C.POINTER(fg_matrix), C.POINTER(fg_matrix), f32,
                                    C.POINTER(fg_matrix), C.POINTER(fg_matrix), C.POINTER(fg_epilogue),
                                    C.POINTER(fg_load_transforms), vp]
+        lib.fg_gemm_noalloc.restype = C.c_int
+        lib.fg_gemm_noalloc.argtypes = lib.fg_gemm_ex.argtypes
         lib.fg_reload_tuning.restype = None
         lib.fg_reload_tuning.argtypes = []
         lib.fg_gemm_dual.restype = C.c_int
@@ -146,9 +148,10 @@ def _check(status: int, raise_on_error: bool) -> int:
 def fg_gemm(M: int, N: int, K: int, alpha: float, A: Optional[Matrix], B: Optional[Matrix], beta: float,
             C_: Optional[Matrix], D: Optional[Matrix], bias: Optional[torch.Tensor] = None, bias_dim: int = 0,
             act: int = FG_ACT_NONE, stream=None, raise_on_error: bool = True,
-            a_add: float = 0.0, b_add: float = 0.0, c_act: int = FG_ACT_NONE) -> int:
+            a_add: float = 0.0, b_add: float = 0.0, c_act: int = FG_ACT_NONE, noalloc: bool = False) -> int:
     """D = act(alpha * op(A) * op(B) + beta * C + bias); see fg_gemm in include/flexgemm.h.
-    With ``a_add``, ``b_add`` or ``c_act`` the call goes to fg_gemm_ex (transforms on loaded elements)."""
+    With ``a_add``, ``b_add`` or ``c_act`` the call goes to fg_gemm_ex (transforms on loaded elements);
+    with ``noalloc`` to fg_gemm_noalloc (same arguments as fg_gemm_ex)."""
     lib = load_library()
     sa = A._struct() if A is not None else None
     sb = B._struct() if B is not None else None
@@ -160,7 +163,10 @@ def fg_gemm(M: int, N: int, K: int, alpha: float, A: Optional[Matrix], B: Option
         ep.bias = bias.data_ptr() if bias is not None else None
         ep.bias_dim, ep.act = bias_dim, act
     ref = lambda s: C.byref(s) if s is not None else None
-    if a_add != 0.0 or b_add != 0.0 or c_act != FG_ACT_NONE:
+    if noalloc:
+        lt = fg_load_transforms(a_add, b_add, c_act)
+        st = lib.fg_gemm_noalloc(M, N, K, alpha, ref(sa), ref(sb), beta, ref(sc), ref(sd), ref(ep), C.byref(lt), _stream_handle(stream))
+    elif a_add != 0.0 or b_add != 0.0 or c_act != FG_ACT_NONE:
         lt = fg_load_transforms(a_add, b_add, c_act)
         st = lib.fg_gemm_ex(M, N, K, alpha, ref(sa), ref(sb), beta, ref(sc), ref(sd), ref(ep), C.byref(lt), _stream_handle(stream))
     else:

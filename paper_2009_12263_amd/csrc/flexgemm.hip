@@ -304,6 +304,28 @@ fg_status workspace_locked(int dev, hipStream_t stream, bool may_allocate, Works
     return FG_OK;
 }
 
+// The allocation-free entry point keeps its partial products in this array instead: part of the
+// library's device image, so each GPU the library runs on holds one copy until the process ends.
+// Host code never uses the symbol itself as an address: g_static_scratch[dev] is the array's
+// device address on GPU `dev`, asked for once per device with that device current.
+constexpr int64_t kStaticScratchBytes = 16ll << 20;
+static __device__ __align__(256) float scratch[kStaticScratchBytes / 4];
+float *g_static_scratch[64];
+
+fg_status static_scratch(int dev, float **out) {
+    static std::mutex m;
+    if (dev < 0 || dev >= 64) return fail(FG_ERR_LAUNCH, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(m);
+    if (!g_static_scratch[dev]) {
+        float *ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return fail(FG_ERR_LAUNCH, "hipGetSymbolAddress of the static scratch array failed: %s", hipGetErrorString(e));
+        g_static_scratch[dev] = ptr;
+    }
+    *out = g_static_scratch[dev];
+    return FG_OK;
+}
+
 fg_status launch(const fg::KernelEntry &k, const fg::GemmParams &p, hipStream_t stream) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return fail(FG_ERR_LAUNCH, "no HIP device is current");
@@ -703,14 +725,19 @@ fg_status fg_init(void) {
             if (!tb.t[i].fn) continue;          // a variant that is not built for this tile
             if (fg_status st = prepare(tb.t[i], dev, per_cu)) return st;
         }
+    float *st = nullptr;
+    if (fg_status s2 = static_scratch(dev, &st)) return s2;
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     Workspace *w = nullptr;
     return workspace_locked(dev, nullptr, true, &w);
 }
 
+// static_only: the allocation-free entry point.  Same plan as the ordinary call; partial products
+// of a K split go to the static scratch array (FG_ERR_UNSUPPORTED if they do not fit), and nothing
+// on this path allocates, frees or creates anything.
 static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
                            float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep, bool dual,
-                           const fg_load_transforms *lt, void *hip_stream) {
+                           const fg_load_transforms *lt, void *hip_stream, bool static_only = false) {
     Problem q;
     if (fg_status st = normalise(M, N, K, alpha, A, B, beta, C, D, ep, dual, lt, q)) return st;
     if (q.M == 0 || q.N == 0) return FG_OK;
@@ -780,15 +807,25 @@ static fg_status gemm_impl(int64_t M, int64_t N, int64_t K, float alpha, const f
         if (first == 0 || count == 0 || (int64_t)count * S * k.bm * k.bn * 4 > kWorkspaceBytes) S = 1;
     }
     if (S == 1) return launch(k, p, stream);
+    const int64_t need = (int64_t)count * S * k.bm * k.bn * 4;
     float *ws = nullptr;
     Workspace *guard = nullptr;
-    std::lock_guard<std::mutex> ws_lock(g_ws_mutex);
-    if (fg_status st = workspace_locked(dev, stream, true, &guard)) return st;
-    ws = guard->ptr;
-    if (stream_is_capturing(stream)) guard = nullptr;      // a captured call is ordered by its graph's caller
-    else if (guard->used && guard->last_stream != stream) {
-        hipError_t e = hipStreamWaitEvent(stream, guard->last_use, 0);
-        if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "hipStreamWaitEvent on the workspace's last use failed: %s", hipGetErrorString(e));
+    std::unique_lock<std::mutex> ws_lock(g_ws_mutex, std::defer_lock);
+    if (static_only) {
+        if (need > kStaticScratchBytes)
+            return fail(FG_ERR_UNSUPPORTED, "this problem is computed as %d partial products over K, which need %lld bytes of scratch memory; the "
+                                            "static scratch array of the allocation-free entry point holds %lld (use fg_gemm_ex)",
+                        S, (long long)need, (long long)kStaticScratchBytes);
+        if (fg_status st = static_scratch(dev, &ws)) return st;
+    } else {
+        ws_lock.lock();
+        if (fg_status st = workspace_locked(dev, stream, true, &guard)) return st;
+        ws = guard->ptr;
+        if (stream_is_capturing(stream)) guard = nullptr;      // a captured call is ordered by its graph's caller
+        else if (guard->used && guard->last_stream != stream) {
+            hipError_t e = hipStreamWaitEvent(stream, guard->last_use, 0);
+            if (e != hipSuccess) return fail(FG_ERR_LAUNCH, "hipStreamWaitEvent on the workspace's last use failed: %s", hipGetErrorString(e));
+        }
     }
     if (first > 0) {
         fg::GemmParams head = p;
@@ -824,6 +861,12 @@ fg_status fg_gemm_ex(int64_t M, int64_t N, int64_t K, float alpha, const fg_matr
                      float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep,
                      const fg_load_transforms *lt, void *hip_stream) {
     return gemm_impl(M, N, K, alpha, A, B, beta, C, D, ep, false, lt, hip_stream);
+}
+
+fg_status fg_gemm_noalloc(int64_t M, int64_t N, int64_t K, float alpha, const fg_matrix *A, const fg_matrix *B,
+                          float beta, const fg_matrix *C, const fg_matrix *D, const fg_epilogue *ep,
+                          const fg_load_transforms *lt, void *hip_stream) {
+    return gemm_impl(M, N, K, alpha, A, B, beta, C, D, ep, false, lt, hip_stream, true);
 }
 
 void fg_reload_tuning(void) { read_tuning_from_environment(); }

@@ -117,7 +117,7 @@ def compare(got: np.ndarray, ref: np.ndarray, G: np.ndarray, K: int, exact: bool
 def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alpha=1.0, beta=1.0, with_c=True,
                   bias_dim=None, act=fg.FG_ACT_NONE, ints=False, pad=0, config=1, samples: Optional[int] = None,
                   inplace=False, device="cuda", seed=W.DEFAULT_SEED, bf16=False, ab_add=None, c_act=fg.FG_ACT_NONE,
-                  cd16=False, poison=False):
+                  cd16=False, poison=False, noalloc=False):
     """Run fg_gemm on seeded inputs and compare with the oracle.  ``samples`` None: every entry.
     ``cd16``: C and D are stored as binary16 (any leading dimension).  ``poison``: the padding of
     A, B and C (everything between an extent and its leading dimension) holds NaN."""
@@ -143,7 +143,7 @@ def run_gemm_case(M, N, K, la=fg.FG_COL, lb=fg.FG_COL, ld_layout=fg.FG_COL, alph
     fg.fg_gemm(M, N, K, alpha, fg.Matrix(A, la, lda), fg.Matrix(B, lb, ldb), beta,
                fg.Matrix(Cbuf, ld_layout, ldc) if with_c else None, fg.Matrix(Dbuf, ld_layout, ldc),
                bias=bias, bias_dim=bias_dim or 0, act=act,
-               a_add=ab_add[0] if ab_add else 0.0, b_add=ab_add[1] if ab_add else 0.0, c_act=c_act)
+               a_add=ab_add[0] if ab_add else 0.0, b_add=ab_add[1] if ab_add else 0.0, c_act=c_act, noalloc=noalloc)
     torch.cuda.synchronize()
     D_host = np16(Dbuf)
     # padding of D must be untouched
