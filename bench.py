@@ -146,6 +146,17 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True, sweep16k=True):
         return fl[0] / t * 1e-12
     guard("mfma_only_rate_16x16x32_on_this_data_TFLOPs", mfma_ceiling_k32)
 
+    def kloop_mix():
+        fl = [0]
+
+        def run():
+            fl[0] = fg.fg_probe_mfma(A, 1000, stream=stream, kloop_mix=True)
+        t = timed(run, reps=5)
+        return fl[0] / t * 1e-12
+    # 16x16x32 matrix instructions + the LDS fragment reads and direct loads of the 256x256x64 K loop
+    # in its proportions, nothing depending on anything: the bound of that K loop on this data
+    guard("kloop_instruction_mix_rate_on_this_data_TFLOPs", kloop_mix)
+
     flops = 2.0 * n ** 3
     # The whole config-2 sweep, operands left in the caches by the previous launch ("hot"): every
     # size in every layout pair, plus config 1 (256^3 NN).  The sizes below the timed one use the
@@ -273,6 +284,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--size", type=int, default=8192, help="M = N = K of the timed GEMM")
+    ap.add_argument("--settle-ms", type=float, default=300.0,
+                    help="untimed: run the step for this long before the warm-up steps so that the engine clock has settled")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed-region extras (other layouts and configs)")
     ap.add_argument("--no-cold", action="store_true",
@@ -308,6 +321,16 @@ def main():
 
     if args.copy_calibration:
         torch.neg(C, out=D)      # one elementwise kernel: reads 4 M N bytes, writes 4 M N bytes
+    # Untimed, before the W warm-up steps: keep the GPU busy with the same call until the engine
+    # clock has settled.  In a fresh process the clock dips after the first few launches and takes
+    # about 0.1 s of continuous work to come back (launch durations 0.91, 0.98, 1.08, 1.08, 1.02 ...
+    # 0.89 ms by the 25th launch, 0.85 from the 100th on); a run with few warm-up steps would time
+    # that transient instead of the rate a job sees.  Not counted in `warmup` or `steps`.
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -338,6 +361,7 @@ def main():
         "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16 in / f32 accumulate", "data": "synthetic",
+        "settle_ms": args.settle_ms,
         "config": {"workload": "configs[1]: square mixed-precision GEMM D = A.B + C, M=N=K=%d, A,B FP16 column-major (NN), "
                                "C,D FP32, uniform[-1,1), alpha=beta=1" % n,
                    "kernel": plan_name},
@@ -358,6 +382,10 @@ def main():
         sustained = out["extras"].get(key)
         if isinstance(sustained, float) and sustained > 0:
             out["roofline"]["frac_of_mfma_only_rate_on_this_data"] = achieved / sustained
+        mix = out["extras"].get("kloop_instruction_mix_rate_on_this_data_TFLOPs")
+        if isinstance(mix, float) and mix > 0 and out["config"]["kernel"].endswith("_k32"):
+            # whole kernel (K loops + epilogues) against the rate of the K loop's bare instruction mix
+            out["roofline"]["frac_of_kloop_instruction_mix_rate"] = achieved / mix
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(M, N, K, A.cpu().numpy(), M, B.cpu().numpy(), K, C.cpu().numpy(), M)

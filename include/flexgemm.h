@@ -325,6 +325,17 @@ fg_status fg_probe_mfma(const void *fp16_operands, int64_t operand_bytes, int32_
  */
 fg_status fg_probe_mfma_k32(const void *fp16_operands, int64_t operand_bytes, int32_t iters, int64_t *flops_out, void *hip_stream);
 
+/*
+ * Measurement aid: the matrix-instruction stream of fg_probe_mfma_k32 together with the other
+ * instructions of the 256x256x64 kernel's K loop in its proportions -- per 64 matrix instructions
+ * 24 fragment reads of 1 KB from LDS and 8 direct-to-LDS loads of 1 KB (from a window of at most
+ * 4 MiB of `fp16_operands`, which needs at least 128 KiB) -- with no dependence between them, no
+ * barrier and no epilogue.  Its rate is what the compute units sustain for that instruction mix on
+ * that data, i.e. the bound of a K loop with this tile shape however it is scheduled.  Same
+ * arguments and return values as fg_probe_mfma.
+ */
+fg_status fg_probe_kloop_mix(const void *fp16_operands, int64_t operand_bytes, int32_t iters, int64_t *flops_out, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

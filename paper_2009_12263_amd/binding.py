@@ -23,7 +23,7 @@ FG_COL, FG_ROW, FG_DIAG, FG_ZERO = 0, 1, 2, 3
 FG_ACT_NONE, FG_ACT_RELU = 0, 1
 
 EXPORTS = ("fg_init", "fg_gemm", "fg_gemm_ex", "fg_gemm_noalloc", "fg_gemm_dual", "fg_contract", "fg_contract_plan", "fg_last_error", "fg_version",
-           "fg_reload_tuning", "fg_gemm_plan", "fg_probe_mfma", "fg_probe_mfma_k32")
+           "fg_reload_tuning", "fg_gemm_plan", "fg_probe_mfma", "fg_probe_mfma_k32", "fg_probe_kloop_mix")
 FG_PLAN_REAL, FG_PLAN_COMPLEX, FG_PLAN_DUAL, FG_PLAN_REAL_BF16, FG_PLAN_COMPLEX_INTERLEAVED, FG_PLAN_REAL_F16_CD = 0, 1, 2, 3, 4, 5
 
 
@@ -87,6 +87,8 @@ def load_library() -> C.CDLL:
         lib.fg_probe_mfma.argtypes = [vp, i64, i32, C.POINTER(C.c_int64), vp]
         lib.fg_probe_mfma_k32.restype = C.c_int
         lib.fg_probe_mfma_k32.argtypes = [vp, i64, i32, C.POINTER(C.c_int64), vp]
+        lib.fg_probe_kloop_mix.restype = C.c_int
+        lib.fg_probe_kloop_mix.argtypes = [vp, i64, i32, C.POINTER(C.c_int64), vp]
         _lib = lib
     return _lib
 
@@ -228,12 +230,14 @@ def fg_contract_plan(modesA: Sequence[int], stridesA: Sequence[int], A, modesB: 
     return buf.value.decode()
 
 
-def fg_probe_mfma(fp16_operands: torch.Tensor, iters: int, stream=None, k32: bool = False) -> int:
+def fg_probe_mfma(fp16_operands: torch.Tensor, iters: int, stream=None, k32: bool = False, kloop_mix: bool = False) -> int:
     """Launch the MFMA-only measurement kernel on operands from ``fp16_operands``; returns the
-    number of floating-point operations of the launch (see fg_probe_mfma and fg_probe_mfma_k32 in
-    include/flexgemm.h; ``k32`` selects the 16x16x32 instruction)."""
+    number of floating-point operations of the launch (see fg_probe_mfma, fg_probe_mfma_k32 and
+    fg_probe_kloop_mix in include/flexgemm.h; ``k32`` selects the 16x16x32 instruction,
+    ``kloop_mix`` that instruction together with the K loop's LDS reads and direct loads)."""
     flops = C.c_int64(0)
-    fn = load_library().fg_probe_mfma_k32 if k32 else load_library().fg_probe_mfma
+    lib = load_library()
+    fn = lib.fg_probe_kloop_mix if kloop_mix else lib.fg_probe_mfma_k32 if k32 else lib.fg_probe_mfma
     st = fn(fp16_operands.data_ptr(), fp16_operands.numel() * fp16_operands.element_size(), iters, C.byref(flops), _stream_handle(stream))
     _check(st, True)
     return int(flops.value)

@@ -625,8 +625,9 @@ __device__ __forceinline__ float act_clamp(float v, float floor_v, bool pass) { 
 
 template <class Cfg>
 constexpr int stream_policy() { return (Cfg::DIAG == 0 && (!Cfg::STRIDED || Cfg::CSTREAM)) ? 2 : 0; }   // gfx950 cache policy: bit 1 = nt
-template <class Cfg, bool HAS_C>
-__device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, float *Dp, floatx16 (&acc)[Cfg::TI][Cfg::TJ],
+// `block(i, j)` returns the 32x32 block (i, j) of the wave's results as sixteen registers.
+template <class Cfg, bool HAS_C, class Blocks>
+__device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, float *Dp, const Blocks &block,
                                          int m_base, int n_base, int lane) {
     constexpr int kStream = stream_policy<Cfg>();
     const int lm = lane & 31, lh = lane >> 5;
@@ -704,11 +705,12 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                     }
                 }
                 float y[16];
+                const floatx16 acc0 = block(2 * ip, j), acc1 = block(2 * ip + 1, j);
 #pragma unroll
                 for (int r8 = 0; r8 < 8; ++r8) {
                     const int r = 8 * h + r8;
-                    float v0 = p.alpha * acc[2 * ip][j][r] + b0[r8];
-                    float v1 = p.alpha * acc[2 * ip + 1][j][r] + b1[r8];
+                    float v0 = p.alpha * acc0[r] + b0[r8];
+                    float v1 = p.alpha * acc1[r] + b1[r8];
                     if constexpr (HAS_C) {
                         float c0 = cv[b % (AHEAD + 1)][2 * r8], c1 = cv[b % (AHEAD + 1)][2 * r8 + 1];
                         exchange(c0, c1);
@@ -768,9 +770,10 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                     for (int r = 0; r < 16; ++r) bv[r] = p.bias[n_base + 32 * j + Cfg::acc_col(r) + Cfg::ACC_LH * lh];
                 }
                 float y[16];
+                const floatx16 acc_ij = block(i, j);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    float v = p.alpha * acc[i][j][r] + bv[r];
+                    float v = p.alpha * acc_ij[r] + bv[r];
                     if constexpr (HAS_C) {
                         const float c = cv[b % (AHEAD + 1)][r];
                         v += p.beta * act_clamp(c, floor_c, pass_c);
@@ -795,6 +798,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                     const float bias_mi = (bias_m_on && m_ok) ? p.bias[m] : 0.f;
 #pragma unroll
                     for (int j = 0; j < Cfg::TJ; ++j) {
+                        const floatx16 acc_ij = block(i, j);
 #pragma unroll
                         for (int h = 0; h < 2; ++h) {
                             float cv[8], bv[8];
@@ -812,7 +816,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                             for (int r8 = 0; r8 < 8; ++r8) {
                                 const int r = 8 * h + r8;
                                 const bool n_ok = n_base + 32 * j + Cfg::acc_col(r) + Cfg::ACC_LH * lh < p.N;
-                                float y = p.alpha * acc[i][j][r] + bv[r8];
+                                float y = p.alpha * acc_ij[r] + bv[r8];
                                 if constexpr (HAS_C) y += p.beta * act_clamp(cv[r8], floor_c, pass_c);
                                 y = act_clamp(y, floor_v, pass_v);
                                 store_cd<H, kStream>(y, rd, n_ok ? vd : kOutOfRange, 32 * ES * i + (32 * j + Cfg::acc_col(r)) * ldd4);
@@ -879,9 +883,10 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, f
                     load_c(i);
                 }
                 float y[16];
+                const floatx16 acc_ij = block(i, j);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    float v = p.alpha * acc[i][j][r];
+                    float v = p.alpha * acc_ij[r];
                     if constexpr (HAS_C) v += p.beta * cv[i % (AHEAD + 1)][r];
                     y[r] = act_clamp(v, floor_v, pass_v);
                 }
@@ -1001,22 +1006,22 @@ __device__ __forceinline__ floatx4 mfma(half8 a, half8 b, floatx4 c) {
 // (2i+1, j)'s gives one register with rows 32 i + l % 32 at column 16 j + r + 8 (l / 32) and one
 // with the same rows four columns further: the layout TileCfg::acc_col / ACC_LH describe, in
 // which a store instruction again covers two whole 128-byte lines of a column-major result.
+// One block (i, j) at a time, formed when the epilogue reaches it, so that the other results stay
+// where they are until then.
 template <class Cfg>
-__device__ __forceinline__ void gather_blocks(const floatx4 (&a16)[Cfg::FI][Cfg::FJ], floatx16 (&acc)[Cfg::TI][Cfg::TJ]) {
+__device__ __forceinline__ floatx16 gather_block(const floatx4 (&a16)[Cfg::FI][Cfg::FJ], int i, int j) {
+    floatx16 out;
 #pragma unroll
-    for (int i = 0; i < Cfg::TI; ++i)
+    for (int nj = 0; nj < 2; ++nj)
 #pragma unroll
-        for (int j = 0; j < Cfg::TJ; ++j)
-#pragma unroll
-            for (int nj = 0; nj < 2; ++nj)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float x = a16[2 * i][2 * j + nj][r], y = a16[2 * i + 1][2 * j + nj][r];
-                    const auto s = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
-                    const unsigned s0 = s[0], s1 = s[1];      // (copied out before the bit cast: see the binary16 epilogue)
-                    acc[i][j][8 * nj + r] = __builtin_bit_cast(float, s0);
-                    acc[i][j][8 * nj + 4 + r] = __builtin_bit_cast(float, s1);
-                }
+        for (int r = 0; r < 4; ++r) {
+            const float x = a16[2 * i][2 * j + nj][r], y = a16[2 * i + 1][2 * j + nj][r];
+            const auto s = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
+            const unsigned s0 = s[0], s1 = s[1];
+            out[8 * nj + r] = __builtin_bit_cast(float, s0);
+            out[8 * nj + 4 + r] = __builtin_bit_cast(float, s1);
+        }
+    return out;
 }
 
 template <class Cfg>
@@ -1440,22 +1445,23 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                 if (ep.has_c) ep.C += c_off;
             }
             if constexpr (Cfg::M16) {
-                floatx16 blocks[Cfg::TI][Cfg::TJ];
-                gather_blocks<Cfg>(acc[0], blocks);
+                auto blocks = [&](int i, int j) { return gather_block<Cfg>(acc[0], i, j); };
                 if (ep.has_c) epilogue<Cfg, true>(ep, ep.C, ep.D, blocks, mb, nb, lane);
                 else epilogue<Cfg, false>(ep, ep.C, ep.D, blocks, mb, nb, lane);
             } else {
-            if constexpr (Cfg::ILV) {
-                if (ep.has_c) epilogue_interleaved<Cfg, true>(ep, acc[0], acc[1], m_base, n_base, lane);
-                else epilogue_interleaved<Cfg, false>(ep, acc[0], acc[1], m_base, n_base, lane);
-            } else {
-            if (ep.has_c) epilogue<Cfg, true>(ep, ep.C, ep.D, acc[0], mb, nb, lane);
-            else epilogue<Cfg, false>(ep, ep.C, ep.D, acc[0], mb, nb, lane);
-            }
-            if constexpr (Cfg::CPLX && !Cfg::ILV) {
-                if (ep.has_c) epilogue<Cfg, true>(ep, ep.C_im, ep.D_im, acc[1], m_base, n_base, lane);
-                else epilogue<Cfg, false>(ep, ep.C_im, ep.D_im, acc[1], m_base, n_base, lane);
-            }
+                if constexpr (Cfg::ILV) {
+                    if (ep.has_c) epilogue_interleaved<Cfg, true>(ep, acc[0], acc[1], m_base, n_base, lane);
+                    else epilogue_interleaved<Cfg, false>(ep, acc[0], acc[1], m_base, n_base, lane);
+                } else {
+                    auto blocks = [&](int i, int j) -> floatx16 { return acc[0][i][j]; };
+                    if (ep.has_c) epilogue<Cfg, true>(ep, ep.C, ep.D, blocks, mb, nb, lane);
+                    else epilogue<Cfg, false>(ep, ep.C, ep.D, blocks, mb, nb, lane);
+                }
+                if constexpr (Cfg::CPLX && !Cfg::ILV) {
+                    auto blocks_im = [&](int i, int j) -> floatx16 { return acc[1][i][j]; };
+                    if (ep.has_c) epilogue<Cfg, true>(ep, ep.C_im, ep.D_im, blocks_im, m_base, n_base, lane);
+                    else epilogue<Cfg, false>(ep, ep.C_im, ep.D_im, blocks_im, m_base, n_base, lane);
+                }
             }
         }
 

@@ -82,6 +82,65 @@ __global__ __launch_bounds__(512) void mfma_only_k32(const half8 *src, float *si
     if (s == 12345.678f && sink) sink[0] = s;
 }
 
+// The instruction mix of the 256x256x64 kernel's K loop without its dependences: per K tile a
+// wave issues 64 matrix instructions (16x16x32), 24 fragment reads of 1 KB from LDS and 8
+// direct-to-LDS loads of 1 KB from global memory (a window of the caller's buffer that stays in
+// the L2).  The matrix instructions use fixed operand registers, nothing waits for the data that
+// is loaded, and there is no barrier: what remains is what the compute unit's issue logic, LDS
+// and vector-memory path (and the power they draw) leave of the matrix-instruction rate.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(512) void kloop_mix(const half8 *src, uint32_t window_bytes, float *sink, int iters) {
+    __shared__ half8 lds[8192];     // 128 KB, the size of the GEMM's tile ring
+    for (int i = threadIdx.x; i < 8192; i += 512) lds[i] = src[i];
+    __syncthreads();
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    u32x4 rsrc;
+    {
+        const uint64_t a = (uint64_t)src;
+        rsrc[0] = (uint32_t)a; rsrc[1] = (uint32_t)(a >> 32) & 0xffffu; rsrc[2] = window_bytes; rsrc[3] = 0x00020000u;
+    }
+    const uint32_t slabs = window_bytes / 1024u;        // a power of two (checked by the host)
+    half8 a[8], b[4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = src[threadIdx.x + 512 * (i % 4)];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) b[j] = src[threadIdx.x + 512 * (4 + j % 2)];
+    floatx4 c[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) c[i][j][r] = 0.f;
+    const uint32_t lane_lds = (uint32_t)(uintptr_t)(lds + threadIdx.x);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < 64; ++r) {
+            // written as assembly so that the order below is the order issued
+            asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(c[(r >> 2) & 7][r & 3]) : "v"(b[r & 3]), "v"(a[(r >> 2) & 7]));
+            if ((r * 24) / 64 != ((r + 1) * 24) / 64) {
+                half8 frag;
+                asm volatile("ds_read_b128 %0, %1" : "=v"(frag) : "v"(lane_lds + 8192u * (r & 7)));
+            }
+            if ((r * 8) / 64 != ((r + 1) * 8) / 64) {
+                const uint32_t dst = (uint32_t)(uintptr_t)lds + wave * 1024u + (r & 7) * 8192u;
+                const uint32_t voff = ((((uint32_t)it * 64u + r) * 8u + wave) & (slabs - 1)) * 1024u + (threadIdx.x & 63) * 16u;
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(dst), "v"(voff), "s"(rsrc) : "memory", "m0");
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s += c[i][j][r];
+    if (s == 12345.678f && sink) sink[0] = s;
+}
+
 fg_status probe(bool k32, const void *fp16_operands, int64_t operand_bytes, int32_t iters, int64_t *flops_out, void *hip_stream) {
     if (!fp16_operands || !flops_out) return FG_ERR_NULL;
     if (iters < 1 || iters > (1 << 20)) return FG_ERR_SHAPE;
@@ -96,6 +155,21 @@ fg_status probe(bool k32, const void *fp16_operands, int64_t operand_bytes, int3
 }
 
 }  // namespace
+
+extern "C" fg_status fg_probe_kloop_mix(const void *fp16_operands, int64_t operand_bytes, int32_t iters, int64_t *flops_out, void *hip_stream) {
+    if (!fp16_operands || !flops_out) return FG_ERR_NULL;
+    if (iters < 1 || iters > (1 << 20)) return FG_ERR_SHAPE;
+    if (operand_bytes < 128 * 1024) return FG_ERR_SHAPE;      // the LDS fill reads the first 128 KiB
+    if (reinterpret_cast<uintptr_t>(fp16_operands) & 15u) return FG_ERR_ALIGN;
+    // the direct loads walk the largest power-of-two window of the buffer, at most 4 MiB (one L2)
+    uint32_t window = 128 * 1024;
+    while (window < (4u << 20) && (int64_t)window * 2 <= operand_bytes) window *= 2;
+    const int blocks = 256;
+    hipLaunchKernelGGL(kloop_mix, dim3(blocks), dim3(512), 0, (hipStream_t)hip_stream, (const half8 *)fp16_operands, window, (float *)nullptr, iters);
+    if (hipGetLastError() != hipSuccess) return FG_ERR_LAUNCH;
+    *flops_out = (int64_t)blocks * 8 * iters * 64 * 16384;
+    return FG_OK;
+}
 
 extern "C" fg_status fg_probe_mfma_k32(const void *fp16_operands, int64_t operand_bytes, int32_t iters, int64_t *flops_out, void *hip_stream) {
     return probe(true, fp16_operands, operand_bytes, iters, flops_out, hip_stream);

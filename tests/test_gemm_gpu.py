@@ -541,4 +541,13 @@ def test_mfma_only_probes():
         fg.fg_probe_mfma(buf, 0, k32=True)
     with pytest.raises(fg.FlexGemmError):
         fg.fg_probe_mfma(buf[1:], 10, k32=True)       # not 16-byte aligned
+    with pytest.raises(fg.FlexGemmError):
+        fg.fg_probe_mfma(buf[:1024], 10)              # fewer than the 48 KiB the kernels read
+    # the K loop's instruction mix: needs 128 KiB, walks a power-of-two window of the buffer (here 256 KiB
+    # of a 300 KiB buffer whose tail is never touched), same operation count per iteration
+    mix = torch.zeros(150 * 1024, dtype=torch.float16, device="cuda")
+    assert fg.fg_probe_mfma(mix, 10, kloop_mix=True) == 256 * 8 * 10 * 32 * 32768
+    torch.cuda.synchronize()
+    with pytest.raises(fg.FlexGemmError):
+        fg.fg_probe_mfma(buf, 10, kloop_mix=True)
 
