@@ -275,7 +275,24 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True, sweep16k=True):
     return res
 
 
+def markdown_table(path):
+    """The current-numbers table of the design doc, from a JSON line this program wrote earlier."""
+    d = json.load(open(path))
+    ex = d.get("extras", {})
+    peak = MFMA_FP16_PEAK_TFLOPS
+    rows = [("headline: " + d["config"]["kernel"] + " (timed region)", d["roofline"]["achieved"], "TFLOP/s")]
+    rows += [(k[:-7], v, "TFLOP/s") for k, v in ex.items() if k.endswith("_TFLOPs") and isinstance(v, float)]
+    rows += [(k[:-5], v, "GB/s") for k, v in ex.items() if k.endswith("_GBps") and isinstance(v, float)]
+    print("| bench.py key | measured | of the roof |")
+    print("|---|---|---|")
+    for name, v, unit in rows:
+        roof = "%.1f %% of 2.5 PFLOP/s" % (100 * v / peak) if unit == "TFLOP/s" else "%.1f %% of 8 TB/s" % (100 * v / 8000.0)
+        print("| %s | %.0f %s | %s |" % (name, v, unit, roof))
+
+
 def main():
+    if len(sys.argv) == 3 and sys.argv[1] == "--table":
+        return markdown_table(sys.argv[2])
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     # Defaults: the engine clock dips after the first few launches of a fresh process and takes about
