@@ -193,7 +193,18 @@ __device__ __forceinline__ int kc_swz(int row) { return (row / (128 / BK)) & (BK
 // the two 32-byte halves of every 64-byte chunk swapped, which puts the eight 32-byte pieces into
 // eight different bank groups.
 template <int R>
-__device__ __forceinline__ int mc_swz(int krow) { return krow & ((R / 32 - 1) < 3 ? (R / 32 - 1) : 3); }
+__device__ __forceinline__ int mc_swz(int krow) { return R == 64 ? (krow >> 1) & 1 : krow & ((R / 32 - 1) < 3 ? (R / 32 - 1) : 3); }
+// Tiles read as 32-row fragments (every kernel but TileCfg::M16) also XOR the position of a
+// 16-byte piece inside its 64-byte chunk with the k-row.  The LDS serves a transposing read 32
+// lanes at a time: four k-rows times 32 rows, 8 bytes per lane, i.e. every bank once if the four
+// k-rows' pieces are spread out.  In the tile's own row order the 32 rows of a k-row are one
+// chunk and the XOR above suffices; when a contraction permutes the rows of a tile (tile_row) the
+// 32 rows are 16-byte pieces of several chunks at the same position inside each, and the XOR
+// above alone maps the four k-rows onto the same banks.  Tiles of 64 rows have two chunks per
+// k-row and k-rows two apart share their banks, hence their own pattern.  (Found by enumerating
+// the XOR patterns against a model of the bank use; SQ_LDS_BANK_CONFLICT confirms.)
+template <int R>
+__device__ __forceinline__ int mc_piece(int krow) { return R == 64 ? 3 * ((krow >> 1) & 1) : krow & 3; }
 
 // ---- buffer resources and direct-to-LDS loads ------------------------------------------------
 // Raw buffer descriptor over `bytes` bytes starting at p (p is workgroup-uniform, so the four
@@ -340,6 +351,7 @@ struct TileLoader {
                 int p = lane % CH;                                  // physical chunk
                 int c = p ^ (mc_swz<R>(kr) << 2);                   // 64-byte granular XOR
                 if constexpr (FLIP) c ^= ((kr >> 3) & 1) << 1;      // and the 32-byte halves of k-rows 8..15 mod 16 swapped
+                else c ^= mc_piece<R>(kr);                          // 32-row fragments: see mc_piece
                 if constexpr (!STRIDED) off = (int64_t)kr * ks + c * 8;
                 else off = group_offset(rg, row0 + c * 8) + (int64_t)kr * kgrp.stride[0];
                 if constexpr (STRIDED) {
@@ -549,7 +561,7 @@ struct FragReader {
             for (int t = 0; t < NT; ++t) {
                 int m = tile_row(row_base + 32 * t + 16 * (g & 1) + 4 * (i16 & 3), R, perm_z);   // 4 rows per address
                 int c64 = (m >> 5) ^ mc_swz<R>(kr);
-                addr[t] = kr * (R * 2) + c64 * 64 + (m & 31) * 2;
+                addr[t] = kr * (R * 2) + c64 * 64 + ((((m & 31) >> 3) ^ mc_piece<R>(kr)) << 4) + (m & 7) * 2;
             }
         }
     }
