@@ -310,6 +310,43 @@ def test_calls_can_be_captured_in_a_hip_graph():
         assert torch.equal(D1, want1) and torch.equal(D2, want2), "replay %d differs from the eager result" % rep
 
 
+@pytest.mark.parametrize("noalloc", [False, True])
+def test_split_k_calls_can_be_captured_in_a_hip_graph(noalloc):
+    """A call that splits K enqueues two kernels (partial products, reduction pass) and, outside a
+    capture, orders itself against the workspace's previous user with an event; under capture it
+    must record nothing but its kernels.  Captured through fg_gemm (library workspace, which exists
+    after fg_init) and through the allocation-free entry point; every replay is checked."""
+    from paper_2009_12263_amd import workloads as W
+    M, N, K = 384, 256, 8192
+    assert "+splitk" in fg.fg_gemm_plan(M, N, K)
+    A = W.small_ints(M * K, 1, device="cuda"); B = W.small_ints(K * N, 2, device="cuda")
+    Cm = W.small_ints(M * N, 3, device="cuda", dtype=torch.float32)
+    D = torch.empty_like(Cm)
+    fg.fg_init()
+    call = lambda stream=None: fg.fg_gemm(M, N, K, 1.0, fg.Matrix(A, fg.FG_COL, M), fg.Matrix(B, fg.FG_COL, K), -1.0, fg.Matrix(Cm, fg.FG_COL, M),
+                                          fg.Matrix(D, fg.FG_COL, M), stream=stream, noalloc=noalloc)
+    call()
+    torch.cuda.synchronize()
+    want = D.clone()
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        D.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=s):
+            call(stream=s)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        D.fill_(float("nan"))
+        call_other = torch.empty_like(D)
+        fg.fg_gemm(M, N, K, 2.0, fg.Matrix(A, fg.FG_COL, M), fg.Matrix(B, fg.FG_COL, K), 0.0, None, fg.Matrix(call_other, fg.FG_COL, M))   # eager split-K work in between
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        say("split-K graph replay %d noalloc=%s" % (rep, noalloc))
+        assert torch.equal(D, want), "replay %d differs from the eager result" % rep
+
+
 def test_split_k_small_outputs_long_k():
     """Outputs with too few tiles to fill the GPU and a long K are computed as partial products
     over K ranges plus a reduction pass (the cross-workgroup reduction use of the epilogue,
