@@ -257,3 +257,28 @@ def test_contract_argument_errors():
     # an empty mode: nothing to do, OK without a GPU
     ext3 = {a: 64, b: 0, c: 64, d: 64}
     assert contract_status([a, d, c], dense3, [d, b], [1, 64], [a, b, c], [1, 64, 0], ext3) == fg.FG_OK
+
+
+def test_planner_over_random_shapes_never_fails_and_its_splits_fit_the_workspace():
+    """Seeded random M, N, K over six orders of magnitude, every layout pair and variant: the plan
+    query succeeds, names a kernel, and a split plan's partial products (tiles x K ranges x tile
+    bytes) fit the 64 MiB workspace."""
+    import random
+    rng = random.Random(7)
+    for _ in range(400):
+        M = rng.choice([1, 7, 64, 100, 256, 300, 1000, 1024, 2048, 4100, 8192, 20000])
+        N = rng.choice([1, 5, 64, 128, 200, 512, 1111, 4096, 8192, 16384])
+        K = 8 * rng.choice([1, 2, 8, 33, 64, 128, 513, 1024, 4096, 8192, 65536])
+        la, lb, ld = rng.choice([0, 1]), rng.choice([0, 1]), rng.choice([0, 1])
+        variant = rng.choice([fg.FG_PLAN_REAL, fg.FG_PLAN_REAL, fg.FG_PLAN_REAL_BF16, fg.FG_PLAN_COMPLEX, fg.FG_PLAN_DUAL,
+                              fg.FG_PLAN_COMPLEX_INTERLEAVED, fg.FG_PLAN_REAL_F16_CD])
+        plan = fg.fg_gemm_plan(M, N, K, la, lb, ld, variant)
+        m = re.match(r"^[a-z0-9_]+_(\d+)x(\d+)x(\d+)(?:_[a-z0-9]+)?(?:\+(tail)?splitk(\d+))?$", plan)
+        assert m, plan
+        bm, bn = int(m.group(1)), int(m.group(2))
+        if m.group(5) and not m.group(4):
+            S = int(m.group(5))
+            Mn, Nn = (M, N) if ld == 0 else (N, M)
+            tiles = -(-Mn // bm) * -(-Nn // bn)
+            assert 2 <= S <= 64 and tiles * S * bm * bn * 4 <= 64 << 20, (plan, M, N, K)
+            assert variant in (fg.FG_PLAN_REAL, fg.FG_PLAN_REAL_BF16), plan     # the reduction pass writes FP32 real results
