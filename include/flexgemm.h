@@ -296,11 +296,12 @@ fg_status fg_init(void);
  * tolerance and are bit-identical on integer-valued data.
  * This is the "params" choice of Section 4.2.1, made here by an estimate
  * of the run time of every tile shape and split.  `variant` (fg_plan_variant) names the operator: real FP16, planar complex, dual, real BF16,
- * interleaved complex, or real FP16 with C and D stored as binary16.
+ * interleaved complex, real FP16 with C and D stored as binary16, or real FP16 with a constant added to the
+ * loaded A and B values (fg_gemm_ex with a_add or b_add).
  * Returns FG_OK, or the status fg_gemm would return for these sizes and layouts.
  */
 typedef enum { FG_PLAN_REAL = 0, FG_PLAN_COMPLEX = 1, FG_PLAN_DUAL = 2, FG_PLAN_REAL_BF16 = 3,
-               FG_PLAN_COMPLEX_INTERLEAVED = 4, FG_PLAN_REAL_F16_CD = 5 } fg_plan_variant;
+               FG_PLAN_COMPLEX_INTERLEAVED = 4, FG_PLAN_REAL_F16_CD = 5, FG_PLAN_REAL_AB_ADD = 6 } fg_plan_variant;
 fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t layoutB,
                        int32_t layoutD, int32_t variant, char *buf, int32_t buf_len);
 

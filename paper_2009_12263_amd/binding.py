@@ -25,6 +25,7 @@ FG_ACT_NONE, FG_ACT_RELU = 0, 1
 EXPORTS = ("fg_init", "fg_gemm", "fg_gemm_ex", "fg_gemm_noalloc", "fg_gemm_dual", "fg_contract", "fg_contract_plan", "fg_last_error", "fg_version",
            "fg_reload_tuning", "fg_gemm_plan", "fg_probe_mfma", "fg_probe_mfma_k32", "fg_probe_kloop_mix")
 FG_PLAN_REAL, FG_PLAN_COMPLEX, FG_PLAN_DUAL, FG_PLAN_REAL_BF16, FG_PLAN_COMPLEX_INTERLEAVED, FG_PLAN_REAL_F16_CD = 0, 1, 2, 3, 4, 5
+FG_PLAN_REAL_AB_ADD = 6
 
 
 class fg_matrix(C.Structure):

@@ -222,7 +222,7 @@ const fg::KernelEntry *select_kernel(const Problem &q, Plan *plan_out = nullptr)
         return &(q.dual ? fg::kernel_table_dual() : fg::kernel_table_cplx())[t * 4 + v];
     }
     const bool may_split = plan_out && !q.a_diag && !q.b_diag && !q.cd16;   // the reduction pass writes FP32
-    const int k32 = (q.a_diag || q.b_diag || q.ab_add) ? 0 : ((q.a_kc || q.b_kc) ? 2 : 1);
+    const int k32 = (q.a_diag || q.b_diag) ? 0 : q.ab_add ? (q.a_kc != q.b_kc ? 2 : 0) : ((q.a_kc || q.b_kc) ? 2 : 1);
     const Plan plan = choose_plan(q.M, q.N, q.K, may_split, true, 1, !q.a_diag && !q.b_diag, k32);
     const int tile = plan.tile;
     if (plan_out) *plan_out = plan;
@@ -886,7 +886,7 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
     if (!ok_in(layoutA) || !ok_in(layoutB) || (layoutD != FG_COL && layoutD != FG_ROW))
         return fail(FG_ERR_LAYOUT, "plan query: A, B take FG_COL / FG_ROW / FG_DIAG, D takes FG_COL / FG_ROW");
     if (layoutA == FG_DIAG && layoutB == FG_DIAG) return fail(FG_ERR_UNSUPPORTED, "at most one of A and B may be diagonal");
-    if (variant < FG_PLAN_REAL || variant > FG_PLAN_REAL_F16_CD) return fail(FG_ERR_LAYOUT, "plan query: unknown variant %d", variant);
+    if (variant < FG_PLAN_REAL || variant > FG_PLAN_REAL_AB_ADD) return fail(FG_ERR_LAYOUT, "plan query: unknown variant %d", variant);
     if (variant != FG_PLAN_REAL && (layoutA == FG_DIAG || layoutB == FG_DIAG))
         return fail(FG_ERR_UNSUPPORTED, "diagonal operands are supported for real FG_F16 products only");
     Problem q;
@@ -896,6 +896,7 @@ fg_status fg_gemm_plan(int64_t M, int64_t N, int64_t K, int32_t layoutA, int32_t
     q.dual = variant == FG_PLAN_DUAL;
     q.bf16 = variant == FG_PLAN_REAL_BF16;
     q.cd16 = variant == FG_PLAN_REAL_F16_CD;
+    q.ab_add = variant == FG_PLAN_REAL_AB_ADD;
     if (layoutD == FG_COL) {
         q.M = M; q.N = N;
         q.a_diag = layoutA == FG_DIAG; q.b_diag = layoutB == FG_DIAG;

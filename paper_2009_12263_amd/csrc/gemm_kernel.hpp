@@ -1219,7 +1219,9 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                         }
                         uint32_t add_a = 0, add_b = 0;          // two packed halves each
                         if constexpr (Cfg::XFORM) {
-                            const bool in_k = (kt0 + kt) * BK + ks * 32 + 8 * (lane >> 4) < xf_k;
+                            // only the last K tile can reach beyond K: before it the addends are
+                            // the same in every lane and stay in scalar registers
+                            const bool in_k = MORE || (kt0 + kt) * BK + ks * 32 + 8 * (lane >> 4) < xf_k;
                             add_a = in_k ? xf_a : 0u;
                             add_b = in_k ? xf_b : 0u;
 #pragma unroll
@@ -1337,7 +1339,7 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                     // addend is zero (a lane's eight values share one k chunk, K is a multiple of 8).
                     uint32_t add_a = 0, add_b = 0;          // two packed halves each
                     if constexpr (Cfg::XFORM) {
-                        const bool in_k = (kt0 + kt) * BK + ks * Cfg::KSLICE + 8 * (lane / (Cfg::M16 ? 16 : 32)) < xf_k;
+                        const bool in_k = MORE || (kt0 + kt) * BK + ks * Cfg::KSLICE + 8 * (lane / (Cfg::M16 ? 16 : 32)) < xf_k;
                         add_a = in_k ? xf_a : 0u;
                         add_b = in_k ? xf_b : 0u;
 #pragma unroll

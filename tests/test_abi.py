@@ -195,6 +195,12 @@ def test_planner_splits_k_only_for_small_outputs_with_long_k(monkeypatch):
     assert fg.fg_gemm_plan(4096, 4096, 4096, variant=fg.FG_PLAN_COMPLEX_INTERLEAVED) == "cgemm_il_nn_256x128x32"
     assert fg.fg_gemm_plan(4096, 4096, 4096, variant=fg.FG_PLAN_DUAL) == "dgemm_nn_256x128x32"
     assert fg.fg_gemm_plan(8192, 8192, 8192, variant=fg.FG_PLAN_REAL_BF16) == "gemm_bf16_nn_256x256x64_k32"
+    # addition on A and B: the 16x16x32 kernel for the two layout pairs that have one
+    assert fg.fg_gemm_plan(4096, 4096, 4096, variant=fg.FG_PLAN_REAL_AB_ADD) == "gemm_abadd_nn_256x256x64_k32"
+    assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_ROW, fg.FG_ROW, variant=fg.FG_PLAN_REAL_AB_ADD) == "gemm_abadd_tt_256x256x64_k32"
+    assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_COL, fg.FG_ROW, variant=fg.FG_PLAN_REAL_AB_ADD) == "gemm_abadd_nt_256x256x64"
+    assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_ROW, fg.FG_COL, variant=fg.FG_PLAN_REAL_AB_ADD) == "gemm_abadd_tn_256x256x64"
+    assert fg.fg_gemm_plan(2048, 2048, 2048, variant=fg.FG_PLAN_REAL_AB_ADD) == "gemm_abadd_nn_128x128x64_deep"
 
 
 def contract_status(mA, sA, mB, sB, mC, sC, ext, pa=0x1000, pb=0x2000, pc=0x3000):
@@ -271,7 +277,7 @@ def test_planner_over_random_shapes_never_fails_and_its_splits_fit_the_workspace
         K = 8 * rng.choice([1, 2, 8, 33, 64, 128, 513, 1024, 4096, 8192, 65536])
         la, lb, ld = rng.choice([0, 1]), rng.choice([0, 1]), rng.choice([0, 1])
         variant = rng.choice([fg.FG_PLAN_REAL, fg.FG_PLAN_REAL, fg.FG_PLAN_REAL_BF16, fg.FG_PLAN_COMPLEX, fg.FG_PLAN_DUAL,
-                              fg.FG_PLAN_COMPLEX_INTERLEAVED, fg.FG_PLAN_REAL_F16_CD])
+                              fg.FG_PLAN_COMPLEX_INTERLEAVED, fg.FG_PLAN_REAL_F16_CD, fg.FG_PLAN_REAL_AB_ADD])
         plan = fg.fg_gemm_plan(M, N, K, la, lb, ld, variant)
         m = re.match(r"^[a-z0-9_]+_(\d+)x(\d+)x(\d+)(?:_[a-z0-9]+)?(?:\+(tail)?splitk(\d+))?$", plan)
         assert m, plan
@@ -281,4 +287,4 @@ def test_planner_over_random_shapes_never_fails_and_its_splits_fit_the_workspace
             Mn, Nn = (M, N) if ld == 0 else (N, M)
             tiles = -(-Mn // bm) * -(-Nn // bn)
             assert 2 <= S <= 64 and tiles * S * bm * bn * 4 <= 64 << 20, (plan, M, N, K)
-            assert variant in (fg.FG_PLAN_REAL, fg.FG_PLAN_REAL_BF16), plan     # the reduction pass writes FP32 real results
+            assert variant in (fg.FG_PLAN_REAL, fg.FG_PLAN_REAL_BF16, fg.FG_PLAN_REAL_AB_ADD), plan     # the reduction pass writes FP32 real results

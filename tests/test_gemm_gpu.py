@@ -447,8 +447,13 @@ def test_every_tile_shape_in_every_kernel_family(monkeypatch):
     say("16x16x32 kernel, A/B layouts x row-major D, bias along N, ReLU")
     for la, lb in itertools.product((fg.FG_COL, fg.FG_ROW), repeat=2):
         run_gemm_case(520, 300, 200, la, lb, ld_layout=fg.FG_ROW, ints=True, bias_dim=1, act=fg.FG_ACT_RELU, beta=-2.0)
+    for la, lb in ((fg.FG_COL, fg.FG_COL), (fg.FG_ROW, fg.FG_ROW)):
+        for K in (8, 72, 520, 1000):
+            say("16x16x32 kernel with addition on A and B, layouts %d %d, K = %d" % (la, lb, K))
+            run_gemm_case(300, 520, K, la, lb, ints=True, pad=8, ab_add=(3.0, -1.0), c_act=fg.FG_ACT_RELU)
     setenv(monkeypatch, "FG_FORCE_SPLIT", "3")
     say("16x16x32 kernel, K split in 3"); run_gemm_case(512, 256, 1536, fg.FG_ROW, fg.FG_COL, ints=True, bias_dim=0)
+    say("16x16x32 kernel with addition on A and B, K split in 3"); run_gemm_case(512, 256, 1544, ints=True, ab_add=(1.0, 2.0))
     delenv(monkeypatch, "FG_FORCE_SPLIT")
     delenv(monkeypatch, "FG_FORCE_TILE")
     say("planner's own choice of the deep ring, floats"); assert "deep" in fg.fg_gemm_plan(2048, 2048, 2048)
