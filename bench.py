@@ -95,8 +95,19 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True, sweep16k=True):
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
     def timed(fn, reps=20):
-        for _ in range(min(20, reps)):         # enough for the clock to settle after the change of kernel
+        # After a change of kernel the engine clock needs some tens of milliseconds to settle
+        # (a 4096^3 product measured 12 % slower over launches 21-40 than in the steady state), so
+        # warm-up and timed region are sized by time: at least 20 launches and 60 ms of warm-up,
+        # at least `reps` launches and 40 ms timed.
+        e0.record(stream)
+        for _ in range(5):
             fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        per_launch_ms = max(e0.elapsed_time(e1) / 5, 1e-3)
+        for _ in range(max(15, min(4000, int(60.0 / per_launch_ms)))):
+            fn()
+        reps = max(reps, min(4000, int(40.0 / per_launch_ms)))
         e0.record(stream)
         for _ in range(reps):
             fn()
