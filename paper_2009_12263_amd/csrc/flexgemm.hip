@@ -127,8 +127,8 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_sma
     static const int bm[fg::TILE_COUNT] = {256, 256, 128, 64, 128, 256};
     static const int bn[fg::TILE_COUNT] = {256, 128, 128, 64, 128, 256};
     static const int per_cu[fg::TILE_COUNT] = {1, 1, 2, 4, 1, 1};
-    static const double rate_shared[fg::TILE_COUNT] = {1.0, 0.8, 0.73, 0.45, 0.51, 1.0};
-    static const double rate_alone[fg::TILE_COUNT] = {1.0, 0.8, 0.43, 0.17, 0.51, 1.0};
+    static const double rate_shared[fg::TILE_COUNT] = {1.0, 0.8, 0.73, 0.45, 0.57, 1.0};
+    static const double rate_alone[fg::TILE_COUNT] = {1.0, 0.8, 0.43, 0.17, 0.57, 1.0};
     static const int split_options[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
     constexpr double cu_flops = 4.7e12, round_fixed = 2e-6, cu_cd_bw = 25e9, reduce_launch = 6e-6, reduce_bw = 3e12;
     // tuning overrides (see read_tuning_from_environment)
