@@ -250,7 +250,8 @@ fg_status fg_contract(int32_t nA, const int32_t *modesA, const int64_t *stridesA
  * Name of the kernel fg_contract would use for this description (same descriptor arguments; the
  * data pointers are only inspected for alignment), as a NUL-terminated string in `buf`:
  * "gett_<layouts>_<tile>" or "gett_stream_..." for the tiled kernels (the latter when whole
- * lines of the result stream past the L2), or "gett_general_64x64x32 (<reason>)" with the first
+ * lines of the result stream past the L2; a tile name ending in "_deep" is the 128x128 tile with a
+ * ring of four buffers, for results of at most one such tile per compute unit), or "gett_general_64x64x32 (<reason>)" with the first
  * requirement of the tiled kernels that the description misses.  Returns what fg_contract would
  * return for the description.
  */

@@ -927,7 +927,7 @@ static const fg::KernelEntry *select_contract_kernel(const Contraction &c, const
     // A result that is not contiguous along the leading row mode is stored in short pieces; the
     // smallest tile makes them shorter still (measured on the paper's D_abc = A_bda B_dc).
     const bool rows_contiguous = c.c_m.n == 0 || c.c_m.stride[0] == 1;
-    const int tile = choose_plan(c.M, c.N, c.K, false, rows_contiguous || c.M < 128 || c.N < 128, c.batches, false).tile;
+    const int tile = choose_plan(c.M, c.N, c.K, false, rows_contiguous || c.M < 128 || c.N < 128, c.batches, true).tile;
     // The result streams past the L2 only if every store of 32 consecutive rows is one whole,
     // aligned 128-byte line: leading row mode contiguous with an extent that is a multiple of 32,
     // every other stride of C and its base a multiple of 32 elements.

@@ -9,7 +9,8 @@ namespace fg {
 // compute unit) and eight waves of 32x64 (two per SIMD, so that one wave's LDS and barrier latencies
 // are covered by the other's matrix instructions), for outputs of at most one such tile per unit: a
 // lone workgroup turns a K tile over too fast for a two-buffer ring to cover the memory latency.
-// (2048^3: 26.5 us against 28.8 us with four waves of 64x64 and the same ring.)
+// (2048^3: 26.5 us against 28.8 us with four waves of 64x64 and the same ring.)  Matrix and
+// contraction kernels; no 16x16x32 form.
 // TILE_256x256_K32: the 256x256 tile computed with 16x16x32 matrix instructions (TileCfg::M16), for
 // products that fill (most of) the GPU: there the chip runs at its power limit and that instruction shape
 // sustains a higher rate on the same data; on a partly filled GPU the 32x32x16 kernels are faster.
@@ -217,8 +218,8 @@ inline KernelEntry xf_k32_entry(const char *name) {
             FG_ENTRY(64, 64, 64, 2, 2, 2, AKC, BKC, true, "gett_" TAG "_64x64x64"),                \
             FG_ENTRY_GS(64, 64, 64, 2, 2, 2, AKC, BKC, "gett_stream_" TAG "_64x64x64"),            \
             FG_ENTRY(128, 128, 64, 4, 4, 2, AKC, BKC, false, "gemm_" TAG "_128x128x64_deep"),      \
-            /* no contraction variants of the deep tile (measured: no faster there) nor of the k32 one */ \
-            FG_EMPTY_ENTRY, FG_EMPTY_ENTRY,                                                        \
+            FG_ENTRY(128, 128, 64, 4, 4, 2, AKC, BKC, true, "gett_" TAG "_128x128x64_deep"),       \
+            FG_ENTRY_GS(128, 128, 64, 4, 4, 2, AKC, BKC, "gett_stream_" TAG "_128x128x64_deep"),   \
             FG_ENTRY_K32(256, 256, 64, 2, 2, 4, AKC, BKC, false, false, "gemm_" TAG "_256x256x64_k32"), \
         };                                                                                         \
         return t;                                                                                  \

@@ -35,6 +35,10 @@ def test_paper_contraction_full_size():
     ext = {a: 64, b: 32, c: 2048, d: 2048}
     say("paper contraction ints sampled"); run_contract_case(ext, [b, d, a], [d, c], [a, b, c], ints=True, samples=8192)
     say("paper contraction floats sampled"); run_contract_case(ext, [b, d, a], [d, c], [a, b, c], samples=8192)
+    dummy = torch.zeros(64, dtype=torch.float16, device="cuda"); out = torch.zeros(64, dtype=torch.float32, device="cuda")
+    plan = fg.fg_contract_plan([b, d, a], W.col_major_strides((32, 2048, 64)), dummy, [d, c], W.col_major_strides((2048, 2048)), dummy,
+                               [a, b, c], W.col_major_strides((64, 32, 2048)), None, out, ext)
+    assert plan == "gett_nn_128x128x64_deep", plan
 
 
 def test_result_contiguous_along_the_second_row_mode():
@@ -53,15 +57,24 @@ def test_result_contiguous_along_the_second_row_mode():
 
 
 def test_every_tile_shape_in_the_contraction_kernels(monkeypatch):
-    """The four block tiles of the contraction kernels forced in turn on contractions with a
-    contiguous result (streaming stores), a permuted one, batch modes and a C operand: integer
-    data, every entry exact."""
-    for tile in range(4):
+    """The five block tiles of the contraction kernels (the last one the 128x128 tile with a ring of
+    four buffers) forced in turn on contractions with a contiguous result (streaming stores), a
+    permuted one, batch modes and a C operand: integer data, every entry exact.  The deep ring also
+    over summed extents shorter than the ring and in all four layout pairs."""
+    for tile in range(5):
         setenv(monkeypatch, "FG_FORCE_TILE", str(tile))
         say("tile %d" % tile)
         run_contract_case({a: 64, b: 72, c: 5, d: 192}, [a, d, c], [d, b], [a, b, c], ints=True)
         run_contract_case({a: 12, b: 16, c: 40, d: 320}, [b, d, a], [d, c], [a, b, c], ints=True, beta=1.0)
         run_contract_case({a: 40, b: 24, c: 3, d: 128, e: 2}, [a, d, c, e], [d, e, b], [a, e, b, c], ints=True, alpha=2.0, beta=-1.0)
+    setenv(monkeypatch, "FG_FORCE_TILE", "4")
+    for K in (8, 64, 136, 256, 520):
+        say("deep ring, summed extent %d" % K)
+        run_contract_case({a: 136, b: 24, c: 7, d: K}, [a, d, c], [d, b], [a, b, c], ints=True)
+    say("deep ring, A and B contiguous along the summed mode / along the rows and columns")
+    run_contract_case({a: 40, b: 136, c: 3, d: 320}, [d, a, c], [d, b], [a, b, c], ints=True, beta=1.0)
+    run_contract_case({a: 40, b: 136, c: 3, d: 320}, [d, a, c], [b, d], [a, b, c], ints=True)
+    run_contract_case({a: 40, b: 136, c: 3, d: 320}, [a, d, c], [b, d], [a, b, c], ints=True)
     delenv(monkeypatch, "FG_FORCE_TILE")
 
 
