@@ -83,7 +83,7 @@ def cpu_baseline(M, N, K, A, lda, B, ldb, C, ldc, budget_s=12.0):
             "projected_seconds_full_problem": 2.0 * M * N * K / rate, "legs": legs}
 
 
-def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True, sweep16k=True):
+def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True, sweep16k=True, fixed_launches=0):
     """Other rows of the hot-path table, outside the timed region: the remaining layout pairs at
     the same size, the fused-epilogue and layout-adapter configurations and the contractions.
     Each figure is flops (or algorithmic bytes) over the mean of 10 launches timed with HIP events;
@@ -99,6 +99,15 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True, sweep16k=True):
         # (a 4096^3 product measured 12 % slower over launches 21-40 than in the steady state), so
         # warm-up and timed region are sized by time: at least 20 launches and 60 ms of warm-up,
         # at least `reps` launches and 40 ms timed.
+        if fixed_launches:                      # profiler runs: a fixed, small number of dispatches per row
+            for _ in range(fixed_launches):
+                fn()
+            e0.record(stream)
+            for _ in range(fixed_launches):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / fixed_launches * 1e-3
         e0.record(stream)
         for _ in range(5):
             fn()
@@ -318,6 +327,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed-region extras (other layouts and configs)")
     ap.add_argument("--no-cold", action="store_true",
                     help="skip the cache-cold extras (keeps one group of launches per workload in a profile)")
+    ap.add_argument("--extras-launches", type=int, default=0,
+                    help="extras: this many warm-up and this many timed launches per row instead of sizing both by time (for profiler runs)")
     ap.add_argument("--no-16384", action="store_true", help="skip the 16384^3 points of the sweep (3.2 GB of extra operands)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain elementwise copy kernel (D = -C: 4 M N bytes read, 4 M N written), "
@@ -404,7 +415,8 @@ def main():
     }
 
     if not args.no_extras:
-        out["extras"] = extras(fg, W, torch, n, A, B, mC, mD, stream, cold=not args.no_cold, sweep16k=not args.no_16384)
+        out["extras"] = extras(fg, W, torch, n, A, B, mC, mD, stream, cold=not args.no_cold, sweep16k=not args.no_16384,
+                               fixed_launches=args.extras_launches)
         # the MFMA-only rate in the instruction shape the timed kernel uses
         key = "mfma_only_rate_16x16x32_on_this_data_TFLOPs" if out["config"]["kernel"].endswith("_k32") else "mfma_only_rate_on_this_data_TFLOPs"
         sustained = out["extras"].get(key)
