@@ -32,7 +32,7 @@ MFMA_FP16_PEAK_TFLOPS = 2500.0     # MI355X dense FP16 MFMA, published (2.5 PFLO
 # each scaled by what the same counter reads for a plain copy kernel of known size (factors 2.0 and
 # 1.0), recorded in the file named below.  It is reported only when the kernel that is timed is the
 # one that was profiled (same plan name), and the JSON line names the source.
-PROFILED_TRAFFIC = {"kernel": "gemm_nn_256x256x64_k32", "bytes": 2.158e9, "source": "profiles/gemm_nn_8192_pmc.md"}
+PROFILED_TRAFFIC = {"kernel": "gemm_nn_256x256x64_k32", "bytes": 2.168e9, "source": "profiles/gemm_nn_8192_pmc.md"}
 
 
 def cpu_baseline(M, N, K, A, lda, B, ldb, C, ldc, budget_s=12.0):
