@@ -296,7 +296,7 @@ def extras(fg, W, torch, n, A, B, mC, mD, stream, cold=True, sweep16k=True, fixe
 
 
 def markdown_table(path):
-    """The current-numbers table of the design doc, from a JSON line this program wrote earlier."""
+    """A table of the current numbers (markdown), from a JSON line this program wrote earlier."""
     d = json.load(open(path))
     ex = d.get("extras", {})
     peak = MFMA_FP16_PEAK_TFLOPS
