@@ -224,8 +224,16 @@ const fg::KernelEntry *select_kernel(const Problem &q, Plan *plan_out = nullptr)
     const bool may_split = plan_out && !q.a_diag && !q.b_diag && !q.cd16;   // the reduction pass writes FP32
     const int k32 = (q.a_diag || q.b_diag) ? 0 : q.ab_add ? (q.a_kc != q.b_kc ? 2 : 0) : ((q.a_kc || q.b_kc) ? 2 : 1);
     const Plan plan = choose_plan(q.M, q.N, q.K, may_split, true, 1, !q.a_diag && !q.b_diag, k32);
-    const int tile = plan.tile;
-    if (plan_out) *plan_out = plan;
+    int tile = plan.tile;
+    // A product with a diagonal operand is bound by its memory traffic (one pass over the dense
+    // operand, C and D; a tile row only meets the K tiles on the diagonal).  While all of it fits the
+    // 256 MB memory-side cache, the smallest tile, four workgroups per unit at different points
+    // between their loads and their stores, measured fastest (4096^2: 26.6 us against 29.6 us with
+    // the 256x256 tile, 8192 x 1024: 14.8 against 17.0); beyond that size its short pieces cost
+    // more in memory than they gain (8192^2: 180 us against 135 us), and the estimate above decides.
+    if ((q.a_diag || q.b_diag) && g_force_tile.load(std::memory_order_relaxed) < 0 && q.M * q.N * 10 <= (256ll << 20))
+        tile = fg::TILE_64x64;
+    if (plan_out) { *plan_out = plan; plan_out->tile = tile; }
     if (q.a_diag) return &fg::kernel_table_diag()[tile * 4 + (q.b_kc ? 0 : 1)];
     if (q.b_diag) return &fg::kernel_table_diag()[tile * 4 + (q.a_kc ? 2 : 3)];
     if (q.ab_add) {
