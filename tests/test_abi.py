@@ -195,6 +195,9 @@ def test_planner_splits_k_only_for_small_outputs_with_long_k(monkeypatch):
     assert fg.fg_gemm_plan(4096, 4096, 4096, variant=fg.FG_PLAN_COMPLEX_INTERLEAVED) == "cgemm_il_nn_256x128x32"
     assert fg.fg_gemm_plan(4096, 4096, 4096, variant=fg.FG_PLAN_DUAL) == "dgemm_nn_256x128x32"
     assert fg.fg_gemm_plan(8192, 8192, 8192, variant=fg.FG_PLAN_REAL_BF16) == "gemm_bf16_nn_256x256x64_k32"
+    # a short K (a pass over C and D): the 256x128 tile instead of the 256x256 one
+    assert fg.fg_gemm_plan(8192, 8192, 256) == "gemm_nn_256x128x64"
+    assert fg.fg_gemm_plan(8192, 8192, 320) == "gemm_nn_256x256x64_k32"
     # a diagonal operand: the smallest tile while the product's traffic fits the memory-side cache
     assert fg.fg_gemm_plan(4096, 4096, 4096, fg.FG_DIAG, fg.FG_COL) == "gemm_diagA_n_64x64x64"
     assert fg.fg_gemm_plan(8192, 8192, 8192, fg.FG_DIAG, fg.FG_COL) == "gemm_diagA_n_256x256x64"
