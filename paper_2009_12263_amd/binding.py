@@ -118,6 +118,31 @@ class Matrix:
         return m
 
 
+def _check_extent(m: Optional["Matrix"], rows: int, cols: int, name: str) -> None:
+    """The library sees pointers only and cannot know how much memory is behind them: before a call
+    that will launch kernels, check here that every device tensor holds the matrix it is said to
+    hold (a matrix larger than its tensor would be read or written out of bounds on the GPU).
+    Descriptions the library rejects by itself (a leading dimension that is too small, ...) are
+    left to it."""
+    if m is None or rows <= 0 or cols <= 0:
+        return
+    for t in (m.re, m.im):
+        if t is None or not getattr(t, "is_cuda", False):     # only real device tensors are checked
+            continue
+        per_entry = 2 if (m.dtype in (FG_CF16, FG_CF32) and not t.is_complex()) else 1
+        if m.layout == FG_DIAG:
+            need = min(rows, cols)
+        elif m.layout == FG_COL:
+            need = (cols - 1) * m.ld + rows if m.ld >= rows else 0
+        elif m.layout == FG_ROW:
+            need = (rows - 1) * m.ld + cols if m.ld >= cols else 0
+        else:
+            need = 0
+        if need * per_entry > t.numel():
+            raise ValueError("%s: a %d x %d matrix with leading dimension %d needs %d elements, the tensor has %d"
+                             % (name, rows, cols, m.ld, need * per_entry, t.numel()))
+
+
 def _stream_handle(stream) -> Optional[int]:
     if stream is None:
         return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
@@ -156,6 +181,8 @@ def fg_gemm(M: int, N: int, K: int, alpha: float, A: Optional[Matrix], B: Option
     With ``a_add``, ``b_add`` or ``c_act`` the call goes to fg_gemm_ex (transforms on loaded elements);
     with ``noalloc`` to fg_gemm_noalloc (same arguments as fg_gemm_ex)."""
     lib = load_library()
+    if M > 0 and N > 0:          # an empty result launches nothing
+        _check_extent(A, M, K, "A"); _check_extent(B, K, N, "B"); _check_extent(C_, M, N, "C"); _check_extent(D, M, N, "D")
     sa = A._struct() if A is not None else None
     sb = B._struct() if B is not None else None
     sc = C_._struct() if C_ is not None else None
@@ -181,6 +208,8 @@ def fg_gemm_dual(M: int, N: int, K: int, alpha: float, A: Optional[Matrix], B: O
                  C_: Optional[Matrix], D: Optional[Matrix], stream=None, raise_on_error: bool = True) -> int:
     """Dual-number product on planar (value, dual part) matrices; see fg_gemm_dual in include/flexgemm.h."""
     lib = load_library()
+    if M > 0 and N > 0:          # an empty result launches nothing
+        _check_extent(A, M, K, "A"); _check_extent(B, K, N, "B"); _check_extent(C_, M, N, "C"); _check_extent(D, M, N, "D")
     sa = A._struct() if A is not None else None
     sb = B._struct() if B is not None else None
     sc = C_._struct() if C_ is not None else None
@@ -205,6 +234,14 @@ def fg_contract(modesA: Sequence[int], stridesA: Sequence[int], A: torch.Tensor,
     """Cout = alpha * contraction(A, B) + beta * Cin; see fg_contract in include/flexgemm.h.
     ``extents`` maps each integer mode label to its extent."""
     lib = load_library()
+    for name, t, modes, strides in (("A", A, modesA, stridesA), ("B", B, modesB, stridesB), ("Cin", Cin, modesC, stridesC),
+                                    ("Cout", Cout, modesC, stridesC)):
+        # the same protection as _check_extent: the last element the description reaches must exist
+        if t is not None and getattr(t, "is_cuda", False) and all(int(v) > 0 for v in extents.values()) and len(modes) == len(strides) and all(m in extents and extents[m] > 0 for m in modes) \
+                and all(int(x) >= 0 for x in strides):
+            need = 1 + sum((int(extents[m]) - 1) * int(x) for m, x in zip(modes, strides))
+            if need > t.numel():
+                raise ValueError("%s: the modes and strides reach element %d, the tensor has %d" % (name, need - 1, t.numel()))
     i32 = lambda xs: (C.c_int32 * len(xs))(*[int(x) for x in xs])
     i64 = lambda xs: (C.c_int64 * len(xs))(*[int(x) for x in xs])
     mA, sA, mB, sB, mC, sC = i32(modesA), i64(stridesA), i32(modesB), i64(stridesB), i32(modesC), i64(stridesC)

@@ -233,6 +233,30 @@ def test_transforms_fusion_table_4096():
     run_gemm_case(4096, 4096, 4096, bias_dim=0, act=fg.FG_ACT_RELU, ab_add=(1.0, -2.0), c_act=fg.FG_ACT_RELU, samples=4096, config=3, ints=True)
 
 
+def test_binding_refuses_tensors_smaller_than_the_matrix():
+    """The library sees pointers only; the Python binding checks that every device tensor holds the
+    matrix it is said to hold and raises before anything is launched."""
+    A = torch.zeros(64 * 64, dtype=torch.float16, device="cuda")
+    D = torch.full((64 * 64,), 7.0, dtype=torch.float32, device="cuda")
+    m = lambda t, ld=64, lay=fg.FG_COL: fg.Matrix(t, lay, ld)
+    short = D[:64 * 64 - 1]
+    with pytest.raises(ValueError):
+        fg.fg_gemm(64, 64, 64, 1.0, m(A), m(A), 0.0, None, m(short))
+    with pytest.raises(ValueError):
+        fg.fg_gemm(64, 64, 64, 1.0, m(A, 72), m(A), 0.0, None, m(D))          # 63 * 72 + 64 > 4096
+    with pytest.raises(ValueError):
+        fg.fg_gemm(64, 64, 64, 1.0, m(A), m(A[:100], 64, fg.FG_ROW), 0.0, None, m(D))
+    with pytest.raises(ValueError):
+        fg.fg_gemm(64, 64, 64, 1.0, m(A), m(A), 1.0, m(short), m(D))
+    with pytest.raises(ValueError):
+        fg.fg_contract([0, 1], [1, 64], A, [1, 2], [1, 64], A, [0, 2], [1, 64], None, short, {0: 64, 1: 64, 2: 64})
+    torch.cuda.synchronize()
+    assert bool((D == 7.0).all())
+    assert fg.fg_gemm(64, 64, 64, 1.0, m(A), m(A), 0.0, None, m(D)) == fg.FG_OK     # exactly large enough
+    torch.cuda.synchronize()
+    assert bool((D == 0.0).all())
+
+
 def test_transforms_are_rejected_where_unsupported():
     H = torch.zeros(64 * 64, dtype=torch.float16, device="cuda")
     Bf = torch.zeros(64 * 64, dtype=torch.bfloat16, device="cuda")
