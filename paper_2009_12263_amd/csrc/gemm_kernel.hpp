@@ -81,6 +81,9 @@ struct GemmParams {
     // Contractions with an M-contiguous A: order in which the matrix unit sees the rows of a block
     // tile (tile_row below).  1: the order in which they are loaded.
     int32_t perm_z;
+    // Matrix kernels: C and D are accessed with the default cache policy instead of the streaming
+    // one (set by the host when the whole problem fits the memory-side cache; see stream_policy).
+    int32_t cd_cached;
 };
 
 // Row permutation inside a block tile of a contraction (A contiguous along its leading row mode).
@@ -638,10 +641,10 @@ __device__ __forceinline__ float act_clamp(float v, float floor_v, bool pass) { 
 template <class Cfg>
 constexpr int stream_policy() { return (Cfg::DIAG == 0 && (!Cfg::STRIDED || Cfg::CSTREAM)) ? 2 : 0; }   // gfx950 cache policy: bit 1 = nt
 // `block(i, j)` returns the 32x32 block (i, j) of the wave's results as sixteen registers.
-template <class Cfg, bool HAS_C, class Blocks>
+template <class Cfg, bool HAS_C, class Blocks, bool CACHED = false>
 __device__ __forceinline__ void epilogue(const GemmParams &p, const float *Cp, float *Dp, const Blocks &block,
                                          int m_base, int n_base, int lane) {
-    constexpr int kStream = stream_policy<Cfg>();
+    constexpr int kStream = CACHED ? 0 : stream_policy<Cfg>();
     const int lm = lane & 31, lh = lane >> 5;
     const bool bias_m_on = p.bias && p.bias_dim == 0, bias_n_on = p.bias && p.bias_dim != 0;
     const float floor_v = p.act == 1 ? 0.f : -__builtin_inff();
@@ -1458,8 +1461,14 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                 ep.D += c_off;
                 if (ep.has_c) ep.C += c_off;
             }
+            // the matrix kernels that stream C and D have a second copy of the epilogue without the hint
+            constexpr bool TWO_POLICIES = !Cfg::STRIDED && Cfg::DIAG == 0 && Cfg::CPLX == 0 && !Cfg::ILV;
             if constexpr (Cfg::M16) {
                 auto blocks = [&](int i, int j) { return gather_block<Cfg>(acc[0], i, j); };
+                if (TWO_POLICIES && ep.cd_cached) {
+                    if (ep.has_c) epilogue<Cfg, true, decltype(blocks), true>(ep, ep.C, ep.D, blocks, mb, nb, lane);
+                    else epilogue<Cfg, false, decltype(blocks), true>(ep, ep.C, ep.D, blocks, mb, nb, lane);
+                } else
                 if (ep.has_c) epilogue<Cfg, true>(ep, ep.C, ep.D, blocks, mb, nb, lane);
                 else epilogue<Cfg, false>(ep, ep.C, ep.D, blocks, mb, nb, lane);
             } else {
@@ -1468,6 +1477,10 @@ __global__ __launch_bounds__(Cfg::NTHREADS) void gemm_kernel(const GemmParams p)
                     else epilogue_interleaved<Cfg, false>(ep, acc[0], acc[1], m_base, n_base, lane);
                 } else {
                     auto blocks = [&](int i, int j) -> floatx16 { return acc[0][i][j]; };
+                    if (TWO_POLICIES && ep.cd_cached) {
+                        if (ep.has_c) epilogue<Cfg, true, decltype(blocks), true>(ep, ep.C, ep.D, blocks, mb, nb, lane);
+                        else epilogue<Cfg, false, decltype(blocks), true>(ep, ep.C, ep.D, blocks, mb, nb, lane);
+                    } else
                     if (ep.has_c) epilogue<Cfg, true>(ep, ep.C, ep.D, blocks, mb, nb, lane);
                     else epilogue<Cfg, false>(ep, ep.C, ep.D, blocks, mb, nb, lane);
                 }
