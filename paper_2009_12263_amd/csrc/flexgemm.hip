@@ -210,12 +210,37 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, bool may_split, bool allow_sma
     return best;
 }
 
+// Tile of the complex and dual kernels (256x128, 128x128 with two workgroups per unit, 64x64 with
+// four): the one with the smallest estimated time.  Whole rounds run with every slot of a unit
+// taken, the workgroups of the last, partly filled round share a unit with fewer others; a
+// workgroup's rate is a measured fraction of what a unit sustains with the 256x128 tile (4096^3:
+// 455 / 515 / 629 us with the three tiles; alone on a unit: 1024^3 51 / 35 / 18 us).  The estimate
+// reproduces the fastest tile of every measured case but one near-tie (2560^3: 131 us against 156 us
+// for the tile the former rule, "the largest tile with 256 tiles", picked; 3072^3: 276 against 301).
 int choose_ctile(int64_t M, int64_t N) {
     static const int bm[fg::CTILE_COUNT] = {256, 128, 64};
     static const int bn[fg::CTILE_COUNT] = {128, 128, 64};
-    for (int t = 0; t < fg::CTILE_COUNT; ++t)
-        if (((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]) >= kNumCU) return t;
-    return fg::CTILE_COUNT - 1;
+    static const int per_cu[fg::CTILE_COUNT] = {1, 2, 4};
+    static const double rate_shared[fg::CTILE_COUNT] = {1.0, 0.883, 0.72};
+    static const double rate_alone[fg::CTILE_COUNT] = {1.0, 0.74, 0.45};
+    const int forced = g_force_tile.load(std::memory_order_relaxed);      // tuning override, 0..2 here
+    if (forced >= 0 && forced < fg::CTILE_COUNT) return forced;
+    int best = 0;
+    double best_cost = -1;
+    for (int t = 0; t < fg::CTILE_COUNT; ++t) {
+        const int64_t tiles = ((M + bm[t] - 1) / bm[t]) * ((N + bn[t] - 1) / bn[t]);
+        const int64_t slots = (int64_t)kNumCU * per_cu[t];
+        auto tile_time = [&](int64_t sharing) {     // one tile, `sharing` workgroups on its unit
+            const double unit = per_cu[t] == 1 ? rate_alone[t]
+                              : rate_alone[t] + (rate_shared[t] - rate_alone[t]) * (double)(sharing - 1) / (per_cu[t] - 1);
+            return (double)bm[t] * bn[t] * (double)sharing / unit;
+        };
+        const int64_t full = tiles / slots, rest = tiles - full * slots;
+        double cost = (double)full * tile_time(per_cu[t]);
+        if (rest > 0) cost += tile_time((rest + kNumCU - 1) / kNumCU);
+        if (best_cost < 0 || cost < best_cost) { best = t; best_cost = cost; }
+    }
+    return best;
 }
 
 // Kernel variant for a normalised problem.

@@ -194,6 +194,10 @@ def test_planner_splits_k_only_for_small_outputs_with_long_k(monkeypatch):
     assert "+splitk" not in fg.fg_gemm_plan(256, 256, 65536, fg.FG_DIAG, fg.FG_COL)
     assert fg.fg_gemm_plan(4096, 4096, 4096, variant=fg.FG_PLAN_COMPLEX_INTERLEAVED) == "cgemm_il_nn_256x128x32"
     assert fg.fg_gemm_plan(4096, 4096, 4096, variant=fg.FG_PLAN_DUAL) == "dgemm_nn_256x128x32"
+    # complex tiles by estimated time: one partly filled round of the large tile beats two of a smaller one
+    assert fg.fg_gemm_plan(2560, 2560, 2560, variant=fg.FG_PLAN_COMPLEX) == "cgemm_nn_256x128x32"
+    assert fg.fg_gemm_plan(2048, 2048, 2048, variant=fg.FG_PLAN_COMPLEX) == "cgemm_nn_128x128x32"
+    assert fg.fg_gemm_plan(1024, 1024, 1024, variant=fg.FG_PLAN_DUAL) == "dgemm_nn_64x64x32"
     assert fg.fg_gemm_plan(8192, 8192, 8192, variant=fg.FG_PLAN_REAL_BF16) == "gemm_bf16_nn_256x256x64_k32"
     # a short K (a pass over C and D): the 256x128 tile instead of the 256x256 one
     assert fg.fg_gemm_plan(8192, 8192, 256) == "gemm_nn_256x128x64"
