@@ -270,7 +270,8 @@ const char *fg_last_error(void);
 int32_t fg_version(void);
 
 /*
- * Tuning aid, not part of the method: the planner's overrides FG_FORCE_TILE (0..5: tile shape),
+ * Tuning aid, not part of the method: the planner's overrides FG_FORCE_TILE (0..5: tile shape; 0..2 for complex and
+ * dual products, whose kernels have three),
  * FG_FORCE_SPLIT (n: K ranges for every tile) and FG_FORCE_TAIL (n: K ranges for the tiles of the
  * last round; 1: never) are environment variables read once, when the library is loaded.  This
  * call reads them again (for a process that changes its environment afterwards).

@@ -47,7 +47,8 @@ void note_relaxed(fg_status st, const char *fmt, ...) {
 
 constexpr int kNumCU = 256;   // MI355X: 8 XCDs x 32 compute units
 
-// Tuning overrides of the planner, from the environment: FG_FORCE_TILE=0..5 picks a tile shape
+// Tuning overrides of the planner, from the environment: FG_FORCE_TILE=0..5 picks a tile shape (0..2
+// for the three tiles of the complex and dual kernels)
 // (5: the 256x256 tile with the k32 kernel where the family has one), FG_FORCE_SPLIT=n a split of K
 // for every tile, FG_FORCE_TAIL=n a split of K for the tiles of the last round (1: never).  Read
 // when the library is loaded and again by fg_reload_tuning(), not on every call.
